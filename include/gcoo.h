@@ -1,0 +1,156 @@
+/*
+ * gcoo.h - C ABI of the grouped-COO (GCOO) sparse x dense multiplication library for
+ * AMD Instinct MI355X (gfx950).
+ *
+ * The library computes C = A x B in fp32 (Equation 1 of the paper, Section 2), with
+ * A (m x k, sparse) held on the device in the GCOO layout of Section 3.1 and B (k x N), C (m x N)
+ * dense and row-major.  All compute runs in HIP kernels on the device that is current when a
+ * function is called; there is no CPU path.
+ *
+ * Layout conventions.  A is cut into g = (m + p - 1) / p groups of p consecutive rows
+ * (Algorithm 1 derives the group count from the height of A; the last group holds
+ * m - (g-1)p rows).  Each group is a COO list ordered by column, then row, then position in
+ * the input; the lists are concatenated into values[nnz] (fp32), rows[nnz], cols[nnz] (int32,
+ * 0-based, absolute coordinates).  gIdxes[q] is the position of the first entry of group q,
+ * with one extra entry gIdxes[g] = nnz; nnzPerGroup[q] is the number of entries of group q.
+ *
+ * Memory ownership.  The library never allocates or frees device memory.  The caller
+ * allocates one device buffer of gcoo_device_bytes() bytes (256-byte aligned), hands it to a
+ * gcoo_from_* call and keeps it alive, unmodified, until gcoo_free() of the handle and until
+ * every gcoo_spdm() launched on it has finished.  The handle itself is a small host object owned
+ * by the library.
+ *
+ * Streams.  `stream` arguments are hipStream_t values passed as void* (NULL = the default
+ * stream).  Kernels are launched on that stream and the call returns without waiting, except
+ * where a function says that it synchronises.
+ *
+ * Errors.  Every function returning int returns GCOO_OK (0) or a negative gcoo_status.  On error
+ * no handle is produced and C is not written by the failing call.  No C++ exception crosses
+ * this boundary.  Functions are safe to call from several host threads on distinct handles;
+ * one handle may be read by concurrent gcoo_spdm() calls.
+ */
+#ifndef GCOO_H
+#define GCOO_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum gcoo_status {
+    GCOO_OK = 0,
+    GCOO_EINVAL = -1,   /* null pointer, negative size, p outside [1, GCOO_MAX_P], ld < N, misaligned buffer,
+                           nnz or a dimension above INT32_MAX, unknown variant */
+    GCOO_EBOUNDS = -2,  /* host-side validation: row_ptr not non-decreasing from 0, or a column outside [0, k) */
+    GCOO_ENOMEM = -3,   /* dev_buf smaller than gcoo_device_bytes() for this input */
+    GCOO_EHIP = -4      /* a HIP runtime call failed; gcoo_last_hip_error() holds its text */
+} gcoo_status;
+
+/* Largest supported group height p (rows per group). */
+#define GCOO_MAX_P 256
+
+/* Opaque host-side handle of one converted matrix. */
+typedef struct gcoo_matrix gcoo_matrix;
+
+/*
+ * Device bytes a gcoo_from_csr() / gcoo_from_dense() call needs in dev_buf for an m x k matrix
+ * with nnz stored entries and group height p: the five arrays of Section 3.1 (Table 1:
+ * 3*nnz + 2*g elements, plus one sentinel) and the scratch space the conversion kernels use.
+ * Returns 0 for invalid arguments.  Pure host arithmetic.
+ */
+size_t gcoo_device_bytes(int64_t m, int64_t k, int64_t nnz, int32_t p);
+
+/*
+ * Section 3.1 / Algorithm 1 for a CSR input: convert an m x k CSR matrix to GCOO on the device.
+ *   row_ptr[m+1]  0-based, non-decreasing, row_ptr[0] = 0, nnz = row_ptr[m]
+ *   col_idx[nnz]  each in [0, k); columns of a row may be unsorted and may repeat
+ *   vals[nnz]     fp32; every stored entry is kept, explicit zeros included (nnz is preserved)
+ *   src_on_device 0: the three arrays are host pointers (validated, then copied to the device);
+ *                 1: device pointers (not validated; row_ptr[m] is read back, which synchronises
+ *                    `stream`)
+ *   p             rows per group, 1..GCOO_MAX_P
+ *   dev_buf       caller-owned device memory, 256-byte aligned, >= gcoo_device_bytes(m,k,nnz,p)
+ * The conversion kernels (group index from row_ptr, then a stable per-group radix sort on the
+ * column) run on `stream`.  With host input the call returns after the input has been copied
+ * (the copies synchronise); the kernels may still be running.  *out receives the handle.
+ * Degenerate shapes (m = 0, nnz = 0) succeed.
+ */
+int gcoo_from_csr(int64_t m, int64_t k,
+                  const int32_t* row_ptr, const int32_t* col_idx, const float* vals,
+                  int src_on_device, int32_t p,
+                  void* dev_buf, size_t dev_buf_bytes, void* stream,
+                  gcoo_matrix** out);
+
+/*
+ * Algorithm 1, step 1: count the entries of a dense device matrix A_dev (m x k, row-major,
+ * leading dimension lda >= k) that are not equal to zero.  Writes the count to *nnz (host).
+ * Synchronises `stream`.  Used to size dev_buf before gcoo_from_dense().
+ */
+int gcoo_dense_nnz(int64_t m, int64_t k, const float* A_dev, int64_t lda, void* stream, int64_t* nnz);
+
+/*
+ * Algorithm 1 (both steps) for a dense device matrix: count per group, prefix sum, then fill
+ * values/rows/cols.  An entry is stored when it is != 0.0f (so +0 and -0 are dropped, NaN is
+ * kept).  Synchronises `stream` once, between the two steps, to learn nnz and check that
+ * dev_buf is large enough (GCOO_ENOMEM otherwise).
+ */
+int gcoo_from_dense(int64_t m, int64_t k, const float* A_dev, int64_t lda, int32_t p,
+                    void* dev_buf, size_t dev_buf_bytes, void* stream,
+                    gcoo_matrix** out);
+
+/*
+ * Algorithm 2 (GCOOSpDM): C = A x B, alpha = 1, beta = 0; every element of C (m x N) is
+ * overwritten, rows of empty groups with +0.
+ *   B_dev  k x N row-major device matrix, leading dimension ldb >= N
+ *   C_dev  m x N row-major device matrix, leading dimension ldc >= N; must not overlap B_dev
+ * Entries that A does not store are skipped, never multiplied (a non-finite value in a row of B
+ * that no stored entry touches does not reach C).  The summation order inside one element of C
+ * is by ascending column of A; results are deterministic from run to run.
+ * Asynchronous on `stream`; allocates nothing; N = 0 or m = 0 is a no-op success.
+ */
+int gcoo_spdm(const gcoo_matrix* A, const float* B_dev, int64_t ldb, int64_t N,
+              float* C_dev, int64_t ldc, void* stream);
+
+/*
+ * gcoo_spdm() with the kernel chosen by the caller instead of the built-in heuristic
+ * (Section 5 of the paper leaves the choice of launch parameters to a tuner).
+ *   variant  GCOO_VARIANT_AUTO, or one of the GCOO_VARIANT_* below.  A variant that does not
+ *            support this matrix/shape returns GCOO_EINVAL.
+ */
+#define GCOO_VARIANT_AUTO      0
+#define GCOO_VARIANT_LDS       1  /* accumulators in LDS; any p, any alignment */
+#define GCOO_VARIANT_REG       2  /* accumulators in VGPRs, B value reused along a run of equal columns */
+#define GCOO_VARIANT_REG_NORUN 3  /* accumulators in VGPRs, one B load per entry (for run length ~ 1) */
+int gcoo_spdm_variant(const gcoo_matrix* A, const float* B_dev, int64_t ldb, int64_t N,
+                      float* C_dev, int64_t ldc, void* stream, int variant);
+
+/* Variant gcoo_spdm() would pick for this matrix and these operand shapes (one of GCOO_VARIANT_* > 0). */
+int gcoo_spdm_pick(const gcoo_matrix* A, const float* B_dev, int64_t ldb, int64_t N,
+                   const float* C_dev, int64_t ldc);
+
+/* Release the host handle.  The device buffer stays the caller's.  NULL is accepted. */
+int gcoo_free(gcoo_matrix* A);
+
+/* Shape of a handle: any output pointer may be NULL. */
+int gcoo_info(const gcoo_matrix* A, int64_t* m, int64_t* k, int64_t* nnz, int32_t* p, int64_t* g);
+
+/*
+ * Copy the five arrays of Section 3.1 to HOST buffers: values[nnz], rows[nnz], cols[nnz],
+ * gIdxes[g+1] (widened to int64), nnzPerGroup[g].  Any pointer may be NULL to skip that array.
+ * Waits for the conversion kernels on `stream` first (synchronises).
+ */
+int gcoo_export(const gcoo_matrix* A, float* values, int32_t* rows, int32_t* cols,
+                int64_t* gIdxes, int32_t* nnzPerGroup, void* stream);
+
+/* Static text for a status code. */
+const char* gcoo_strerror(int status);
+
+/* Text of the last HIP error seen by the calling thread inside this library ("" if none). */
+const char* gcoo_last_hip_error(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* GCOO_H */

@@ -1,0 +1,212 @@
+"""ctypes binding of include/gcoo.h: argument marshalling only.
+
+Every step of the path (conversion to GCOO and the product) runs in the HIP kernels of
+libgcoo.so.  torch is used for device memory and for the current stream, nothing else.  If
+the library has not been built, loading it raises: there is no fallback.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+
+import numpy as np
+import torch
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libgcoo.so")
+
+GCOO_OK, GCOO_EINVAL, GCOO_EBOUNDS, GCOO_ENOMEM, GCOO_EHIP = 0, -1, -2, -3, -4
+GCOO_MAX_P = 256
+VARIANT_AUTO, VARIANT_LDS, VARIANT_REG, VARIANT_REG_NORUN = 0, 1, 2, 3
+
+# every symbol include/gcoo.h declares
+SYMBOLS = ["gcoo_device_bytes", "gcoo_from_csr", "gcoo_dense_nnz", "gcoo_from_dense", "gcoo_spdm",
+           "gcoo_spdm_variant", "gcoo_spdm_pick", "gcoo_free", "gcoo_info", "gcoo_export",
+           "gcoo_strerror", "gcoo_last_hip_error"]
+
+_lib = None
+
+
+class GcooError(RuntimeError):
+    def __init__(self, status: int, where: str):
+        L = lib()
+        msg = L.gcoo_strerror(status).decode()
+        if status == GCOO_EHIP:
+            msg += ": " + L.gcoo_last_hip_error().decode()
+        super().__init__(f"{where}: {msg} ({status})")
+        self.status = status
+
+
+def lib():
+    """Load libgcoo.so (built in-tree by paper_2005_14469_amd/build.py)."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            raise FileNotFoundError(
+                f"{LIB_PATH} is missing: build it with `python -m paper_2005_14469_amd.build` "
+                "(there is no CPU fallback)")
+        L = C.CDLL(LIB_PATH)
+        i64, i32, vp, sz = C.c_int64, C.c_int32, C.c_void_p, C.c_size_t
+        L.gcoo_device_bytes.restype = sz
+        L.gcoo_device_bytes.argtypes = [i64, i64, i64, i32]
+        L.gcoo_from_csr.restype = C.c_int
+        L.gcoo_from_csr.argtypes = [i64, i64, vp, vp, vp, C.c_int, i32, vp, sz, vp, C.POINTER(vp)]
+        L.gcoo_dense_nnz.restype = C.c_int
+        L.gcoo_dense_nnz.argtypes = [i64, i64, vp, i64, vp, C.POINTER(i64)]
+        L.gcoo_from_dense.restype = C.c_int
+        L.gcoo_from_dense.argtypes = [i64, i64, vp, i64, i32, vp, sz, vp, C.POINTER(vp)]
+        L.gcoo_spdm.restype = C.c_int
+        L.gcoo_spdm.argtypes = [vp, vp, i64, i64, vp, i64, vp]
+        L.gcoo_spdm_variant.restype = C.c_int
+        L.gcoo_spdm_variant.argtypes = [vp, vp, i64, i64, vp, i64, vp, C.c_int]
+        L.gcoo_spdm_pick.restype = C.c_int
+        L.gcoo_spdm_pick.argtypes = [vp, vp, i64, i64, vp, i64]
+        L.gcoo_free.restype = C.c_int
+        L.gcoo_free.argtypes = [vp]
+        L.gcoo_info.restype = C.c_int
+        L.gcoo_info.argtypes = [vp, C.POINTER(i64), C.POINTER(i64), C.POINTER(i64), C.POINTER(i32), C.POINTER(i64)]
+        L.gcoo_export.restype = C.c_int
+        L.gcoo_export.argtypes = [vp, vp, vp, vp, vp, vp, vp]
+        L.gcoo_strerror.restype = C.c_char_p
+        L.gcoo_strerror.argtypes = [C.c_int]
+        L.gcoo_last_hip_error.restype = C.c_char_p
+        L.gcoo_last_hip_error.argtypes = []
+        _lib = L
+    return _lib
+
+
+def _check(status: int, where: str):
+    if status != GCOO_OK:
+        raise GcooError(status, where)
+
+
+def _stream_ptr(stream=None):
+    s = stream if stream is not None else torch.cuda.current_stream()
+    return C.c_void_p(s.cuda_stream)
+
+
+def gcoo_device_bytes(m: int, k: int, nnz: int, p: int) -> int:
+    return int(lib().gcoo_device_bytes(m, k, nnz, p))
+
+
+class GcooMatrix:
+    """Owner of one handle and of the torch buffer behind it."""
+
+    def __init__(self, handle, buf: torch.Tensor):
+        self._h = C.c_void_p(handle)
+        self.buf = buf
+
+    @property
+    def handle(self):
+        if self._h is None:
+            raise ValueError("handle already freed")
+        return self._h
+
+    def info(self):
+        m, k, nnz, g = C.c_int64(), C.c_int64(), C.c_int64(), C.c_int64()
+        p = C.c_int32()
+        _check(lib().gcoo_info(self.handle, C.byref(m), C.byref(k), C.byref(nnz), C.byref(p), C.byref(g)), "gcoo_info")
+        return dict(m=m.value, k=k.value, nnz=nnz.value, p=p.value, g=g.value)
+
+    def export(self, stream=None):
+        """The five arrays as numpy arrays on the host (gIdxes has g+1 int64 entries)."""
+        i = self.info()
+        v = np.empty(i["nnz"], np.float32)
+        r = np.empty(i["nnz"], np.int32)
+        c = np.empty(i["nnz"], np.int32)
+        gi = np.empty(i["g"] + 1, np.int64)
+        npg = np.empty(i["g"], np.int32)
+        _check(lib().gcoo_export(self.handle, v.ctypes.data, r.ctypes.data, c.ctypes.data, gi.ctypes.data,
+                                 npg.ctypes.data, _stream_ptr(stream)), "gcoo_export")
+        return dict(values=v, rows=r, cols=c, gIdxes=gi, nnzPerGroup=npg)
+
+    def free(self):
+        if self._h is not None:
+            lib().gcoo_free(self._h)
+            self._h = None
+            self.buf = None
+
+    def __del__(self):
+        try:
+            self.free()
+        except Exception:
+            pass
+
+
+def _alloc(nbytes: int, device) -> torch.Tensor:
+    buf = torch.empty(max(nbytes, 256), dtype=torch.uint8, device=device)
+    assert buf.data_ptr() % 256 == 0
+    return buf
+
+
+def gcoo_from_csr(m: int, k: int, row_ptr, col_idx, vals, p: int, device="cuda:0", stream=None) -> GcooMatrix:
+    """row_ptr/col_idx/vals: numpy arrays (host input) or torch device tensors (device input)."""
+    on_dev = isinstance(row_ptr, torch.Tensor)
+    if on_dev:
+        assert row_ptr.is_cuda and row_ptr.dtype == torch.int32 and row_ptr.is_contiguous()
+        assert col_idx.dtype == torch.int32 and vals.dtype == torch.float32
+        nnz = int(col_idx.numel())
+        ptrs = (row_ptr.data_ptr(), col_idx.data_ptr(), vals.data_ptr())
+        device = row_ptr.device
+    else:
+        row_ptr = np.ascontiguousarray(row_ptr, dtype=np.int32)
+        col_idx = np.ascontiguousarray(col_idx, dtype=np.int32)
+        vals = np.ascontiguousarray(vals, dtype=np.float32)
+        nnz = int(col_idx.shape[0])
+        ptrs = (row_ptr.ctypes.data, col_idx.ctypes.data, vals.ctypes.data)
+    need = gcoo_device_bytes(m, k, nnz, p)
+    if need == 0:
+        raise GcooError(GCOO_EINVAL, "gcoo_device_bytes")
+    with torch.cuda.device(device):
+        buf = _alloc(need, device)
+        out = C.c_void_p()
+        _check(lib().gcoo_from_csr(m, k, ptrs[0], ptrs[1], ptrs[2], 1 if on_dev else 0, p, buf.data_ptr(),
+                                   buf.numel(), _stream_ptr(stream), C.byref(out)), "gcoo_from_csr")
+    return GcooMatrix(out.value, buf)
+
+
+def gcoo_dense_nnz(A: torch.Tensor, stream=None) -> int:
+    assert A.is_cuda and A.dtype == torch.float32 and A.dim() == 2 and A.stride(1) == 1
+    n = C.c_int64()
+    with torch.cuda.device(A.device):
+        _check(lib().gcoo_dense_nnz(A.shape[0], A.shape[1], A.data_ptr(), A.stride(0), _stream_ptr(stream), C.byref(n)),
+               "gcoo_dense_nnz")
+    return n.value
+
+
+def gcoo_from_dense(A: torch.Tensor, p: int, stream=None) -> GcooMatrix:
+    """Algorithm 1 as the paper runs it: count, allocate by the count, fill."""
+    assert A.is_cuda and A.dtype == torch.float32 and A.dim() == 2 and A.stride(1) == 1
+    m, k = A.shape
+    nnz = gcoo_dense_nnz(A, stream)
+    need = gcoo_device_bytes(m, k, nnz, p)
+    if need == 0:
+        raise GcooError(GCOO_EINVAL, "gcoo_device_bytes")
+    with torch.cuda.device(A.device):
+        buf = _alloc(need, A.device)
+        out = C.c_void_p()
+        _check(lib().gcoo_from_dense(m, k, A.data_ptr(), A.stride(0), p, buf.data_ptr(), buf.numel(),
+                                     _stream_ptr(stream), C.byref(out)), "gcoo_from_dense")
+    return GcooMatrix(out.value, buf)
+
+
+def gcoo_spdm(A: GcooMatrix, B: torch.Tensor, C_out: torch.Tensor | None = None, variant: int = VARIANT_AUTO,
+              stream=None) -> torch.Tensor:
+    """C = A x B on the current stream.  B: [k, N] fp32 device tensor with unit column stride."""
+    assert B.is_cuda and B.dtype == torch.float32 and B.dim() == 2 and (B.stride(1) == 1 or B.shape[1] <= 1)
+    i = A.info()
+    assert B.shape[0] == i["k"]
+    N = B.shape[1]
+    if C_out is None:
+        C_out = torch.empty((i["m"], N), dtype=torch.float32, device=B.device)
+    assert C_out.is_cuda and C_out.dtype == torch.float32 and C_out.shape == (i["m"], N)
+    ldb = B.stride(0) if B.shape[0] > 1 else max(N, 1)
+    ldc = C_out.stride(0) if C_out.shape[0] > 1 else max(N, 1)
+    with torch.cuda.device(B.device):
+        _check(lib().gcoo_spdm_variant(A.handle, B.data_ptr(), ldb, N, C_out.data_ptr(), ldc, _stream_ptr(stream),
+                                       variant), "gcoo_spdm")
+    return C_out
+
+
+def gcoo_spdm_pick(A: GcooMatrix, B: torch.Tensor, C_out: torch.Tensor) -> int:
+    return int(lib().gcoo_spdm_pick(A.handle, B.data_ptr(), B.stride(0), B.shape[1], C_out.data_ptr(), C_out.stride(0)))

@@ -1,0 +1,456 @@
+// Host side of the C ABI declared in include/gcoo.h: argument checks, device-buffer layout,
+// kernel selection and launches.  No compute happens on the host.
+#include "gcoo.h"
+
+#include <hip/hip_runtime.h>
+
+#include <cmath>
+#include <cstdio>
+#include <cstring>
+#include <new>
+#include <string>
+
+#include "gcoo_build_kernels.hpp"
+#include "gcoo_spdm_launch.hpp"
+#include "gcoo_spdm_lds_kernel.hpp"
+
+namespace {
+
+thread_local std::string g_hip_error;
+
+int hip_fail(hipError_t e, const char* what)
+{
+    g_hip_error = std::string(what) + ": " + hipGetErrorString(e);
+    return GCOO_EHIP;
+}
+
+#define HIP_TRY(expr)                                  \
+    do {                                               \
+        hipError_t e_ = (expr);                        \
+        if (e_ != hipSuccess) return hip_fail(e_, #expr); \
+    } while (0)
+
+constexpr size_t kAlign = 256;
+size_t al(size_t bytes) { return (bytes + kAlign - 1) / kAlign * kAlign; }
+
+// 8 bytes of device memory for gcoo_dense_nnz(), which is handed no device buffer: one copy per
+// device, addressed through hipGetSymbolAddress; calls on one device serialise on it.
+__device__ unsigned long long g_dense_total;
+
+// Carve-up of the caller's device buffer.  Offsets depend on (m, nnz, g) only.
+struct Layout {
+    size_t values, rows, cols, gIdxes, nnzPerGroup, ctl;   // kept for the life of the handle
+    size_t tmp_cols, tmp_rows, tmp_vals;                   // conversion scratch (second sort buffer)
+    size_t in_row_ptr, in_cols, in_vals;                   // staging of a host CSR input
+    size_t counter;                                        // 8-byte device counter
+    size_t total;
+};
+
+Layout make_layout(int64_t m, int64_t nnz, int64_t g)
+{
+    Layout L{};
+    size_t at = 0;
+    auto take = [&](size_t bytes) { size_t o = at; at += al(bytes ? bytes : 1); return o; };
+    const size_t n4 = (size_t)nnz * 4;
+    // the arrays whose size does not depend on nnz come first, so that a dense input can be
+    // counted into them before nnz is known
+    L.gIdxes = take((size_t)(g + 1) * 4);
+    L.nnzPerGroup = take((size_t)g * 4);
+    L.counter = take(8);
+    L.values = take(n4);
+    L.rows = take(n4);
+    L.cols = take(n4);
+    L.ctl = take(n4);
+    L.tmp_cols = take(n4);
+    L.tmp_rows = take(n4);
+    L.tmp_vals = take(n4);
+    L.in_row_ptr = take((size_t)(m + 1) * 4);
+    L.in_cols = take(n4);
+    L.in_vals = take(n4);
+    L.total = at;
+    return L;
+}
+
+bool dims_ok(int64_t m, int64_t k, int64_t nnz, int32_t p)
+{
+    return m >= 0 && k >= 0 && nnz >= 0 && p >= 1 && p <= GCOO_MAX_P && m <= INT32_MAX && k <= INT32_MAX &&
+           nnz <= INT32_MAX;
+}
+
+int radix_passes(int64_t k)
+{
+    int bits = 0;
+    while (bits < 31 && ((int64_t)1 << bits) < k) ++bits;   // column indices fit in `bits` bits
+    int passes = (bits + 7) / 8;
+    return passes < 1 ? 1 : passes;
+}
+
+}  // namespace
+
+struct gcoo_matrix {
+    int64_t m, k, nnz, g;
+    int32_t p;
+    int device;
+    char* base;
+    Layout L;
+    float* values() const { return reinterpret_cast<float*>(base + L.values); }
+    int32_t* rows() const { return reinterpret_cast<int32_t*>(base + L.rows); }
+    int32_t* cols() const { return reinterpret_cast<int32_t*>(base + L.cols); }
+    int32_t* gIdxes() const { return reinterpret_cast<int32_t*>(base + L.gIdxes); }
+    int32_t* nnzPerGroup() const { return reinterpret_cast<int32_t*>(base + L.nnzPerGroup); }
+    uint32_t* ctl() const { return reinterpret_cast<uint32_t*>(base + L.ctl); }
+};
+
+namespace {
+
+int new_handle(int64_t m, int64_t k, int64_t nnz, int32_t p, void* dev_buf, gcoo_matrix** out)
+{
+    gcoo_matrix* h = new (std::nothrow) gcoo_matrix;
+    if (!h) return GCOO_ENOMEM;
+    h->m = m; h->k = k; h->nnz = nnz; h->p = p;
+    h->g = (m + p - 1) / p;
+    h->base = static_cast<char*>(dev_buf);
+    h->L = make_layout(m, nnz, h->g);
+    if (hipGetDevice(&h->device) != hipSuccess) h->device = -1;
+    *out = h;
+    return GCOO_OK;
+}
+
+int launch_mark_runs(const gcoo_matrix* h, hipStream_t s)
+{
+    if (h->g > 0 && h->nnz > 0) {
+        gcoo::mark_runs<<<dim3((unsigned)h->g), dim3(256), 0, s>>>(h->gIdxes(), h->rows(), h->cols(), h->p, h->g, h->ctl());
+        HIP_TRY(hipGetLastError());
+    }
+    return GCOO_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+size_t gcoo_device_bytes(int64_t m, int64_t k, int64_t nnz, int32_t p)
+{
+    if (!dims_ok(m, k, nnz, p)) return 0;
+    return make_layout(m, nnz, (m + p - 1) / p).total;
+}
+
+int gcoo_from_csr(int64_t m, int64_t k, const int32_t* row_ptr, const int32_t* col_idx, const float* vals,
+                  int src_on_device, int32_t p, void* dev_buf, size_t dev_buf_bytes, void* stream, gcoo_matrix** out)
+{
+    if (!out) return GCOO_EINVAL;
+    *out = nullptr;
+    if (!row_ptr || !dev_buf || !dims_ok(m, k, 0, p)) return GCOO_EINVAL;
+    if (reinterpret_cast<uintptr_t>(dev_buf) % kAlign) return GCOO_EINVAL;
+    hipStream_t s = static_cast<hipStream_t>(stream);
+
+    int64_t nnz;
+    if (src_on_device) {
+        int32_t last = 0;
+        HIP_TRY(hipMemcpyAsync(&last, row_ptr + m, sizeof(int32_t), hipMemcpyDeviceToHost, s));
+        HIP_TRY(hipStreamSynchronize(s));
+        nnz = last;
+        if (nnz < 0) return GCOO_EBOUNDS;
+    } else {
+        if (row_ptr[0] != 0) return GCOO_EBOUNDS;
+        for (int64_t i = 0; i < m; ++i)
+            if (row_ptr[i + 1] < row_ptr[i]) return GCOO_EBOUNDS;
+        nnz = row_ptr[m];
+        if (nnz > 0 && (!col_idx || !vals)) return GCOO_EINVAL;
+        for (int64_t e = 0; e < nnz; ++e)
+            if (col_idx[e] < 0 || col_idx[e] >= k) return GCOO_EBOUNDS;
+    }
+    if (nnz > 0 && (!col_idx || !vals)) return GCOO_EINVAL;
+    const int64_t g = (m + p - 1) / p;
+    const Layout L = make_layout(m, nnz, g);
+    if (dev_buf_bytes < L.total) return GCOO_ENOMEM;
+
+    gcoo_matrix* h = nullptr;
+    int rc = new_handle(m, k, nnz, p, dev_buf, &h);
+    if (rc != GCOO_OK) return rc;
+    char* base = h->base;
+
+    const int32_t* d_row_ptr = row_ptr;
+    const int32_t* d_cols = col_idx;
+    const float* d_vals = vals;
+    if (!src_on_device) {
+        int32_t* sp = reinterpret_cast<int32_t*>(base + L.in_row_ptr);
+        int32_t* sc = reinterpret_cast<int32_t*>(base + L.in_cols);
+        float* sv = reinterpret_cast<float*>(base + L.in_vals);
+        hipError_t e = hipMemcpyAsync(sp, row_ptr, (size_t)(m + 1) * 4, hipMemcpyHostToDevice, s);
+        if (e == hipSuccess && nnz > 0) e = hipMemcpyAsync(sc, col_idx, (size_t)nnz * 4, hipMemcpyHostToDevice, s);
+        if (e == hipSuccess && nnz > 0) e = hipMemcpyAsync(sv, vals, (size_t)nnz * 4, hipMemcpyHostToDevice, s);
+        if (e != hipSuccess) { delete h; return hip_fail(e, "hipMemcpyAsync(CSR input)"); }
+        d_row_ptr = sp; d_cols = sc; d_vals = sv;
+    }
+
+    // Algorithm 1, step 1: group index and counts straight from row_ptr (also writes the sentinel).
+    {
+        const unsigned blocks = (unsigned)((g + 1 + 255) / 256);
+        gcoo::group_index_from_row_ptr<<<dim3(blocks), dim3(256), 0, s>>>(d_row_ptr, m, p, g, h->gIdxes(), h->nnzPerGroup());
+        hipError_t e = hipGetLastError();
+        if (e != hipSuccess) { delete h; return hip_fail(e, "group_index_from_row_ptr"); }
+    }
+    // Algorithm 1, step 2: stable per-group radix sort on the column, 8 bits per pass, ping-pong
+    // between the scratch triple and the final arrays so that the last pass lands in the latter.
+    if (g > 0 && nnz > 0) {
+        const int passes = radix_passes(k);
+        int32_t* fin_c = h->cols(); int32_t* fin_r = h->rows(); float* fin_v = h->values();
+        int32_t* tmp_c = reinterpret_cast<int32_t*>(base + L.tmp_cols);
+        int32_t* tmp_r = reinterpret_cast<int32_t*>(base + L.tmp_rows);
+        float* tmp_v = reinterpret_cast<float*>(base + L.tmp_vals);
+        const int32_t* src_c = d_cols; const int32_t* src_r = nullptr; const float* src_v = d_vals;
+        for (int pass = 0; pass < passes; ++pass) {
+            const bool to_final = ((passes - 1 - pass) % 2) == 0;
+            int32_t* dc = to_final ? fin_c : tmp_c;
+            int32_t* dr = to_final ? fin_r : tmp_r;
+            float* dv = to_final ? fin_v : tmp_v;
+            if (pass == 0)
+                gcoo::sort_groups_by_col_digit<true><<<dim3((unsigned)g), dim3(64), 0, s>>>(
+                    h->gIdxes(), d_row_ptr, m, p, src_c, src_r, src_v, dc, dr, dv, 8 * pass);
+            else
+                gcoo::sort_groups_by_col_digit<false><<<dim3((unsigned)g), dim3(64), 0, s>>>(
+                    h->gIdxes(), d_row_ptr, m, p, src_c, src_r, src_v, dc, dr, dv, 8 * pass);
+            hipError_t e = hipGetLastError();
+            if (e != hipSuccess) { delete h; return hip_fail(e, "sort_groups_by_col_digit"); }
+            src_c = dc; src_r = dr; src_v = dv;
+        }
+    }
+    rc = launch_mark_runs(h, s);
+    if (rc != GCOO_OK) { delete h; return rc; }
+    *out = h;
+    return GCOO_OK;
+}
+
+int gcoo_dense_nnz(int64_t m, int64_t k, const float* A_dev, int64_t lda, void* stream, int64_t* nnz)
+{
+    if (!nnz || m < 0 || k < 0 || lda < k || (m > 0 && k > 0 && !A_dev)) return GCOO_EINVAL;
+    *nnz = 0;
+    if (m == 0 || k == 0) return GCOO_OK;
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    unsigned long long* dptr = nullptr;
+    HIP_TRY(hipGetSymbolAddress(reinterpret_cast<void**>(&dptr), HIP_SYMBOL(g_dense_total)));
+    unsigned long long got = 0;
+    HIP_TRY(hipMemsetAsync(dptr, 0, 8, s));
+    const unsigned blocks = (unsigned)(m < 2048 ? m : 2048);
+    gcoo::count_dense_total<<<dim3(blocks), dim3(256), 0, s>>>(A_dev, lda, m, k, dptr);
+    HIP_TRY(hipGetLastError());
+    HIP_TRY(hipMemcpyAsync(&got, dptr, 8, hipMemcpyDeviceToHost, s));
+    HIP_TRY(hipStreamSynchronize(s));
+    *nnz = (int64_t)got;
+    return GCOO_OK;
+}
+
+int gcoo_from_dense(int64_t m, int64_t k, const float* A_dev, int64_t lda, int32_t p, void* dev_buf, size_t dev_buf_bytes,
+                    void* stream, gcoo_matrix** out)
+{
+    if (!out) return GCOO_EINVAL;
+    *out = nullptr;
+    if (!dev_buf || !dims_ok(m, k, 0, p) || lda < k || (m > 0 && k > 0 && !A_dev)) return GCOO_EINVAL;
+    if (reinterpret_cast<uintptr_t>(dev_buf) % kAlign) return GCOO_EINVAL;
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    const int64_t g = (m + p - 1) / p;
+    // gIdxes / nnzPerGroup / counter sit at the front of the buffer at offsets that do not
+    // depend on nnz, so step 1 can run before the buffer size for this nnz is checked.
+    const Layout L0 = make_layout(m, 0, g);
+    if (dev_buf_bytes < L0.total) return GCOO_ENOMEM;
+    char* base = static_cast<char*>(dev_buf);
+    int32_t* cnt = reinterpret_cast<int32_t*>(base + L0.nnzPerGroup);
+    int32_t* idx = reinterpret_cast<int32_t*>(base + L0.gIdxes);
+    unsigned long long* tot = reinterpret_cast<unsigned long long*>(base + L0.counter);
+    unsigned long long total = 0;
+    if (g > 0) {
+        gcoo::count_dense_per_group<<<dim3((unsigned)g), dim3(256), 0, s>>>(A_dev, lda, m, k, p, cnt);
+        HIP_TRY(hipGetLastError());
+        gcoo::scan_group_counts<<<dim3(1), dim3(256), 0, s>>>(cnt, g, idx, tot);
+        HIP_TRY(hipGetLastError());
+        HIP_TRY(hipMemcpyAsync(&total, tot, 8, hipMemcpyDeviceToHost, s));
+        HIP_TRY(hipStreamSynchronize(s));
+    } else {
+        HIP_TRY(hipMemsetAsync(idx, 0, 4, s));          // only the sentinel exists
+    }
+    if (total > (unsigned long long)INT32_MAX) return GCOO_EINVAL;
+    const int64_t nnz = (int64_t)total;
+    const Layout L = make_layout(m, nnz, g);
+    if (dev_buf_bytes < L.total) return GCOO_ENOMEM;
+    gcoo_matrix* h = nullptr;
+    int rc = new_handle(m, k, nnz, p, dev_buf, &h);
+    if (rc != GCOO_OK) return rc;
+    if (g > 0 && nnz > 0) {
+        gcoo::fill_from_dense<<<dim3((unsigned)g), dim3(64), 0, s>>>(A_dev, lda, m, k, p, h->gIdxes(), h->values(),
+                                                                     h->rows(), h->cols());
+        hipError_t e = hipGetLastError();
+        if (e != hipSuccess) { delete h; return hip_fail(e, "fill_from_dense"); }
+    }
+    rc = launch_mark_runs(h, s);
+    if (rc != GCOO_OK) { delete h; return rc; }
+    *out = h;
+    return GCOO_OK;
+}
+
+}  // extern "C"
+
+namespace {
+
+struct Shape {
+    bool al4, al2;
+};
+
+Shape shape_of(const float* B, int64_t ldb, int64_t N, const float* C, int64_t ldc)
+{
+    const uintptr_t pb = reinterpret_cast<uintptr_t>(B), pc = reinterpret_cast<uintptr_t>(C);
+    Shape s;
+    s.al4 = (N % 4 == 0) && (ldb % 4 == 0) && (ldc % 4 == 0) && (pb % 16 == 0) && (pc % 16 == 0);
+    s.al2 = (N % 2 == 0) && (ldb % 2 == 0) && (ldc % 2 == 0) && (pb % 8 == 0) && (pc % 8 == 0);
+    return s;
+}
+
+// Expected run length under uniform sparsity: a column of a p-row band holds Binomial(p, d)
+// entries, so runs average p*d / (1 - (1-d)^p) entries (Section 3.3 cut down to one band).
+double expected_run_length(const gcoo_matrix* A)
+{
+    if (A->nnz == 0 || A->m == 0 || A->k == 0) return 1.0;
+    const double d = (double)A->nnz / ((double)A->m * (double)A->k);
+    const double pe = (double)(A->p < A->m ? A->p : A->m);
+    const double none = std::pow(1.0 - d, pe);
+    return none >= 1.0 ? 1.0 : pe * d / (1.0 - none);
+}
+
+// Which (P, V) instance of spdm_reg serves this p and alignment; V = 0 if none.
+void reg_config(int32_t p, const Shape& sh, int* P, int* V)
+{
+    *P = 0; *V = 0;
+    if (p <= 32 && sh.al4) { *P = p <= 8 ? 8 : (p <= 16 ? 16 : 32); *V = 4; }
+    else if (p <= 64 && sh.al2) { *P = 64; *V = 2; }
+    else if (p <= 128) { *P = 128; *V = 1; }
+}
+
+}  // namespace
+
+namespace gcoo {
+hipError_t launch_spdm_reg(int P, int V, bool reuse, const SpdmArgs& a, hipStream_t s)
+{
+    if (V == 4 && P == 8) return launch_spdm_reg_p8_v4(reuse, a, s);
+    if (V == 4 && P == 16) return launch_spdm_reg_p16_v4(reuse, a, s);
+    if (V == 4 && P == 32) return launch_spdm_reg_p32_v4(reuse, a, s);
+    if (V == 2 && P == 64) return launch_spdm_reg_p64_v2(reuse, a, s);
+    if (V == 1 && P == 128) return launch_spdm_reg_p128_v1(reuse, a, s);
+    return hipErrorInvalidValue;
+}
+}  // namespace gcoo
+
+namespace {
+
+int check_spdm_args(const gcoo_matrix* A, const float* B, int64_t ldb, int64_t N, const float* C, int64_t ldc)
+{
+    if (!A || N < 0 || ldb < N || ldc < N || N > INT32_MAX) return GCOO_EINVAL;
+    if (N > 0 && A->m > 0 && !C) return GCOO_EINVAL;
+    if (N > 0 && A->nnz > 0 && !B) return GCOO_EINVAL;
+    return GCOO_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+int gcoo_spdm_pick(const gcoo_matrix* A, const float* B_dev, int64_t ldb, int64_t N, const float* C_dev, int64_t ldc)
+{
+    int rc = check_spdm_args(A, B_dev, ldb, N, C_dev, ldc);
+    if (rc != GCOO_OK) return rc;
+    int P, V;
+    reg_config(A->p, shape_of(B_dev, ldb, N, C_dev, ldc), &P, &V);
+    if (V == 0) return GCOO_VARIANT_LDS;
+    return expected_run_length(A) >= 1.25 ? GCOO_VARIANT_REG : GCOO_VARIANT_REG_NORUN;
+}
+
+int gcoo_spdm_variant(const gcoo_matrix* A, const float* B_dev, int64_t ldb, int64_t N, float* C_dev, int64_t ldc,
+                      void* stream, int variant)
+{
+    int rc = check_spdm_args(A, B_dev, ldb, N, C_dev, ldc);
+    if (rc != GCOO_OK) return rc;
+    if (variant < GCOO_VARIANT_AUTO || variant > GCOO_VARIANT_REG_NORUN) return GCOO_EINVAL;
+    if (variant == GCOO_VARIANT_AUTO) variant = gcoo_spdm_pick(A, B_dev, ldb, N, C_dev, ldc);
+    if (A->m == 0 || N == 0) return GCOO_OK;
+    hipStream_t s = static_cast<hipStream_t>(stream);
+
+    if (variant == GCOO_VARIANT_LDS) {
+        const int64_t tiles = (N + 63) / 64;
+        const int64_t total = A->g * tiles;
+        if (total > 0x7fffffffLL) return GCOO_EINVAL;
+        const size_t smem = (size_t)A->p * 64 * sizeof(float);
+        gcoo::spdm_lds<<<dim3((unsigned)total), dim3(64), smem, s>>>(A->values(), A->rows(), A->cols(), A->gIdxes(), A->m,
+                                                                     A->p, B_dev, ldb, N, C_dev, ldc, A->g);
+        HIP_TRY(hipGetLastError());
+        return GCOO_OK;
+    }
+    int P, V;
+    reg_config(A->p, shape_of(B_dev, ldb, N, C_dev, ldc), &P, &V);
+    if (V == 0) return GCOO_EINVAL;
+    gcoo::SpdmArgs a{A->values(), A->cols(), A->ctl(), A->gIdxes(), A->m, A->p, A->g, B_dev, ldb, N, C_dev, ldc};
+    hipError_t e = gcoo::launch_spdm_reg(P, V, variant == GCOO_VARIANT_REG, a, s);
+    if (e != hipSuccess) return hip_fail(e, "spdm_reg launch");
+    return GCOO_OK;
+}
+
+int gcoo_spdm(const gcoo_matrix* A, const float* B_dev, int64_t ldb, int64_t N, float* C_dev, int64_t ldc, void* stream)
+{
+    return gcoo_spdm_variant(A, B_dev, ldb, N, C_dev, ldc, stream, GCOO_VARIANT_AUTO);
+}
+
+int gcoo_free(gcoo_matrix* A)
+{
+    delete A;
+    return GCOO_OK;
+}
+
+int gcoo_info(const gcoo_matrix* A, int64_t* m, int64_t* k, int64_t* nnz, int32_t* p, int64_t* g)
+{
+    if (!A) return GCOO_EINVAL;
+    if (m) *m = A->m;
+    if (k) *k = A->k;
+    if (nnz) *nnz = A->nnz;
+    if (p) *p = A->p;
+    if (g) *g = A->g;
+    return GCOO_OK;
+}
+
+int gcoo_export(const gcoo_matrix* A, float* values, int32_t* rows, int32_t* cols, int64_t* gIdxes, int32_t* nnzPerGroup,
+                void* stream)
+{
+    if (!A) return GCOO_EINVAL;
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    const size_t n4 = (size_t)A->nnz * 4;
+    if (values && n4) HIP_TRY(hipMemcpyAsync(values, A->values(), n4, hipMemcpyDeviceToHost, s));
+    if (rows && n4) HIP_TRY(hipMemcpyAsync(rows, A->rows(), n4, hipMemcpyDeviceToHost, s));
+    if (cols && n4) HIP_TRY(hipMemcpyAsync(cols, A->cols(), n4, hipMemcpyDeviceToHost, s));
+    if (nnzPerGroup && A->g) HIP_TRY(hipMemcpyAsync(nnzPerGroup, A->nnzPerGroup(), (size_t)A->g * 4, hipMemcpyDeviceToHost, s));
+    int32_t* narrow = nullptr;
+    if (gIdxes) {
+        narrow = new (std::nothrow) int32_t[(size_t)A->g + 1];
+        if (!narrow) return GCOO_ENOMEM;
+        hipError_t e = hipMemcpyAsync(narrow, A->gIdxes(), (size_t)(A->g + 1) * 4, hipMemcpyDeviceToHost, s);
+        if (e != hipSuccess) { delete[] narrow; return hip_fail(e, "hipMemcpyAsync(gIdxes)"); }
+    }
+    hipError_t e = hipStreamSynchronize(s);
+    if (gIdxes && e == hipSuccess)
+        for (int64_t i = 0; i <= A->g; ++i) gIdxes[i] = narrow[i];
+    delete[] narrow;
+    if (e != hipSuccess) return hip_fail(e, "hipStreamSynchronize");
+    return GCOO_OK;
+}
+
+const char* gcoo_strerror(int status)
+{
+    switch (status) {
+        case GCOO_OK: return "ok";
+        case GCOO_EINVAL: return "invalid argument";
+        case GCOO_EBOUNDS: return "malformed CSR input (row_ptr not non-decreasing from 0, or column out of range)";
+        case GCOO_ENOMEM: return "device buffer too small (see gcoo_device_bytes) or host allocation failed";
+        case GCOO_EHIP: return "HIP runtime error (see gcoo_last_hip_error)";
+        default: return "unknown status";
+    }
+}
+
+const char* gcoo_last_hip_error(void) { return g_hip_error.c_str(); }
+
+}  // extern "C"

@@ -1,0 +1,84 @@
+"""Host-only checks of the C ABI: the library loads, exports every symbol the header declares,
+and the argument checks that need no device behave as the header says.  No kernel is launched."""
+import ctypes as C
+import os
+import re
+
+import numpy as np
+import pytest
+
+from paper_2005_14469_amd import binding, build
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+@pytest.fixture(scope="module")
+def L():
+    if not os.path.exists(binding.LIB_PATH):
+        build.build()
+    return binding.lib()
+
+
+def test_header_symbols_are_exported(L):
+    text = open(os.path.join(ROOT, "include", "gcoo.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    declared = set(re.findall(r"\b(gcoo_[a-z_]+)\s*\(", text))
+    assert declared == set(binding.SYMBOLS)
+    for name in declared:
+        assert hasattr(L, name), name
+
+
+def test_device_bytes_covers_table_1_footprint(L):
+    for m, k, nnz, p in [(4, 4, 6, 2), (8000, 8000, 6400000, 32), (1, 1, 0, 1), (16384, 16384, 868447, 64)]:
+        b = L.gcoo_device_bytes(m, k, nnz, p)
+        g = (m + p - 1) // p
+        assert b >= 4 * (3 * nnz + 2 * g + 1) and b % 256 == 0
+    assert L.gcoo_device_bytes(-1, 4, 0, 2) == 0
+    assert L.gcoo_device_bytes(4, 4, 0, 0) == 0
+    assert L.gcoo_device_bytes(4, 4, 0, binding.GCOO_MAX_P + 1) == 0
+    assert L.gcoo_device_bytes(4, 4, 2 ** 31, 2) == 0
+
+
+def test_strerror_and_free_null(L):
+    assert L.gcoo_strerror(0) == b"ok"
+    for s in (-1, -2, -3, -4, -99):
+        assert len(L.gcoo_strerror(s)) > 0
+    assert L.gcoo_free(None) == 0
+    assert L.gcoo_last_hip_error() is not None
+
+
+def test_from_csr_rejects_bad_arguments_before_touching_the_device(L):
+    out = C.c_void_p()
+    rp = np.array([0, 1, 2], np.int32)
+    ci = np.array([0, 1], np.int32)
+    va = np.ones(2, np.float32)
+    fake = C.c_void_p(256 * 1024)          # aligned, never dereferenced on these paths
+    call = lambda **kw: L.gcoo_from_csr(kw.get("m", 2), kw.get("k", 2), kw.get("rp", rp).ctypes.data,
+                                        kw.get("ci", ci).ctypes.data, va.ctypes.data, 0, kw.get("p", 2),
+                                        kw.get("buf", fake), kw.get("bytes", 1 << 20), None, C.byref(out))
+    assert call(p=0) == binding.GCOO_EINVAL
+    assert call(p=257) == binding.GCOO_EINVAL
+    assert call(m=-1) == binding.GCOO_EINVAL
+    assert call(buf=C.c_void_p(0)) == binding.GCOO_EINVAL
+    assert call(buf=C.c_void_p(256 * 1024 + 4)) == binding.GCOO_EINVAL          # misaligned
+    assert call(rp=np.array([0, 2, 1], np.int32)) == binding.GCOO_EBOUNDS       # decreasing
+    assert call(rp=np.array([1, 1, 2], np.int32)) == binding.GCOO_EBOUNDS       # does not start at 0
+    assert call(ci=np.array([0, 2], np.int32)) == binding.GCOO_EBOUNDS          # column == k
+    assert call(ci=np.array([-1, 0], np.int32)) == binding.GCOO_EBOUNDS
+    assert call(bytes=16) == binding.GCOO_ENOMEM
+    assert out.value is None
+    assert L.gcoo_from_csr(2, 2, None, None, None, 0, 2, fake, 1 << 20, None, C.byref(out)) == binding.GCOO_EINVAL
+    assert L.gcoo_from_csr(2, 2, rp.ctypes.data, ci.ctypes.data, va.ctypes.data, 0, 2, fake, 1 << 20, None, None) \
+        == binding.GCOO_EINVAL
+
+
+def test_spdm_and_info_reject_null_handle(L):
+    assert L.gcoo_spdm(None, None, 4, 4, None, 4, None) == binding.GCOO_EINVAL
+    assert L.gcoo_spdm_variant(None, None, 4, 4, None, 4, None, 0) == binding.GCOO_EINVAL
+    assert L.gcoo_info(None, None, None, None, None, None) == binding.GCOO_EINVAL
+    assert L.gcoo_export(None, None, None, None, None, None, None) == binding.GCOO_EINVAL
+    n = C.c_int64()
+    assert L.gcoo_dense_nnz(-1, 2, None, 2, None, C.byref(n)) == binding.GCOO_EINVAL
+    assert L.gcoo_dense_nnz(2, 4, None, 2, None, C.byref(n)) == binding.GCOO_EINVAL     # lda < k
+    out = C.c_void_p()
+    assert L.gcoo_from_dense(2, 2, None, 2, 2, C.c_void_p(4096), 1 << 20, None, C.byref(out)) == binding.GCOO_EINVAL

@@ -1,0 +1,284 @@
+"""GPU parity: the HIP path (through the C ABI) against the CPU oracle, element by element.
+
+Integer work (the GCOO arrays) must be bit-identical.  The product must satisfy
+max |C_gpu - C64| / (|A|.|B|) <= 1e-5 elementwise, and be exactly zero where |A|.|B| is zero.
+"""
+import numpy as np
+import pytest
+import scipy.sparse as sp
+
+torch = pytest.importorskip("torch")
+
+from oracle import gcoo_oracle as orc
+from paper_2005_14469_amd import binding, workloads
+
+pytestmark = pytest.mark.gpu
+
+TOL = 1e-5
+DEV = "cuda:0"
+
+
+def _say(msg):
+    print(msg, flush=True)
+
+
+def _assert_arrays_equal(exp, G):
+    assert np.array_equal(exp["rows"], G.rows)
+    assert np.array_equal(exp["cols"], G.cols)
+    assert np.array_equal(exp["values"].view(np.uint32), G.values.view(np.uint32))     # bit patterns
+    assert np.array_equal(exp["gIdxes"], G.gIdxes.astype(np.int64))
+    assert np.array_equal(exp["nnzPerGroup"], G.nnzPerGroup)
+
+
+def _check_product(w, p, variant, Bt=None, r0=0, r1=None, A=None):
+    """Run the GPU path on workload w and compare rows [r0, r1) with the oracle."""
+    A = A or binding.gcoo_from_csr(w.m, w.k, w.row_ptr, w.col_idx, w.vals, p, device=DEV)
+    Bt = Bt if Bt is not None else torch.from_numpy(w.B).to(DEV)
+    Cg = torch.full((w.m, Bt.shape[1]), float("nan"), dtype=torch.float32, device=DEV)   # must be fully overwritten
+    binding.gcoo_spdm(A, Bt, Cg, variant=variant)
+    torch.cuda.synchronize()
+    Ch = Cg.cpu().numpy()
+    r1 = w.m if r1 is None else r1
+    C64, D64 = orc.spdm_csr(w.k, Bt.shape[1], w.row_ptr, w.col_idx, w.vals, Bt.cpu().numpy(), r0, r1)
+    err, bad = orc.max_scaled_error(Ch[r0:r1], C64, D64)
+    assert bad == 0, f"{bad} elements are NaN or nonzero where the scale is zero"
+    assert err <= TOL, f"scaled error {err:.3e} > {TOL}"
+    return err, A, Ch
+
+
+def _variants_for(p, N):
+    v = [binding.VARIANT_LDS]
+    if p <= 128:
+        v += [binding.VARIANT_REG, binding.VARIANT_REG_NORUN]
+    return v
+
+
+# ------------------------------------------------------------------ conversion (bit-exact)
+
+@pytest.mark.parametrize("p", [1, 2, 3, 8, 32, 64, 100, 256])
+@pytest.mark.parametrize("shape", [(1, 1), (50, 40), (129, 300), (256, 256), (1000, 70000)])
+def test_gcoo_from_csr_bit_exact(p, shape):
+    m, k = shape
+    if k > 60000 and p not in (8, 100):
+        pytest.skip("the three-pass radix case is run for two group heights only")
+    _say(f"gcoo_from_csr m={m} k={k} p={p}")
+    w = workloads.uniform_random(m, k, 1, 0.9 if m * k > 100 else 0.3, seed=7 * m + p)
+    G = orc.gcoo_from_csr(w.m, w.k, w.row_ptr, w.col_idx, w.vals, p)
+    for on_device in (False, True):
+        if on_device:
+            args = [torch.from_numpy(x).to(DEV) for x in (w.row_ptr, w.col_idx, w.vals)]
+        else:
+            args = [w.row_ptr, w.col_idx, w.vals]
+        A = binding.gcoo_from_csr(w.m, w.k, *args, p, device=DEV)
+        assert A.info() == dict(m=m, k=k, nnz=w.nnz, p=p, g=G.g)
+        _assert_arrays_equal(A.export(), G)
+        A.free()
+
+
+def test_gcoo_from_csr_unsorted_repeated_and_explicit_zero_entries():
+    _say("gcoo_from_csr unsorted/duplicate input")
+    rng = np.random.default_rng(5)
+    m, k, p = 70, 33, 16
+    w = workloads.uniform_random(m, k, 1, 0.6, seed=3)
+    rp, ci, va = w.row_ptr.copy(), w.col_idx.copy(), w.vals.copy()
+    for i in range(m):
+        s, e = rp[i], rp[i + 1]
+        if e - s > 2:
+            perm = rng.permutation(e - s)
+            ci[s:e] = ci[s:e][perm]
+            va[s:e] = va[s:e][perm]
+            ci[s + 1] = ci[s]                       # repeated coordinate, order of input must survive
+    va[::9] = 0.0
+    va[4::9] = -0.0
+    va[5::31] = np.nan
+    G = orc.gcoo_from_csr(m, k, rp, ci, va, p)
+    A = binding.gcoo_from_csr(m, k, rp, ci, va, p, device=DEV)
+    _assert_arrays_equal(A.export(), G)
+
+
+def test_gcoo_empty_shapes():
+    _say("gcoo_from_csr empty shapes")
+    for m, k in [(0, 5), (5, 3), (5, 0)]:
+        rp = np.zeros(m + 1, np.int32)
+        A = binding.gcoo_from_csr(m, k, rp, np.zeros(0, np.int32), np.zeros(0, np.float32), 2, device=DEV)
+        G = orc.gcoo_from_csr(m, k, rp, np.zeros(0, np.int32), np.zeros(0, np.float32), 2)
+        _assert_arrays_equal(A.export(), G)
+        if k > 0:
+            B = torch.randn(k, 8, device=DEV)
+            C = binding.gcoo_spdm(A, B)
+            torch.cuda.synchronize()
+            assert C.shape == (m, 8) and not C.any()
+
+
+@pytest.mark.parametrize("p", [1, 4, 32, 50, 128])
+@pytest.mark.parametrize("shape", [(1, 1), (37, 29), (256, 256), (300, 1111)])
+def test_gcoo_from_dense_bit_exact(p, shape):
+    m, k = shape
+    _say(f"gcoo_from_dense m={m} k={k} p={p}")
+    rng = np.random.default_rng(m + k + p)
+    Ah = ((rng.random((m, k)) < 0.2) * rng.standard_normal((m, k))).astype(np.float32)
+    Ah[0, 0] = -0.0                                   # dropped
+    if m > 1:
+        Ah[1, k - 1] = np.nan                         # kept
+    G = orc.gcoo_from_dense(Ah, p)
+    Ad = torch.from_numpy(Ah).to(DEV)
+    assert binding.gcoo_dense_nnz(Ad) == G.nnz
+    A = binding.gcoo_from_dense(Ad, p)
+    assert A.info()["nnz"] == G.nnz
+    _assert_arrays_equal(A.export(), G)
+    # a view with a leading dimension larger than k
+    big = torch.zeros((m, k + 5), dtype=torch.float32, device=DEV)
+    big[:, :k] = Ad
+    A2 = binding.gcoo_from_dense(big[:, :k], p)
+    _assert_arrays_equal(A2.export(), G)
+
+
+# ------------------------------------------------------------------ product
+
+@pytest.mark.parametrize("p", [1, 2, 8, 16, 32, 64, 128, 256])
+def test_config0_all_variants(p):
+    w = workloads.config(0)
+    for variant in _variants_for(p, w.N):
+        _say(f"config0 p={p} variant={variant}")
+        err, _, _ = _check_product(w, p, variant)
+        assert err < 2e-6          # rounding alone sits near 1e-7; more means a lost or misplaced entry
+
+
+@pytest.mark.parametrize("m,k,N,p", [
+    (1, 1, 1, 1), (5, 7, 3, 2), (33, 65, 64, 32), (100, 90, 260, 32), (129, 257, 516, 64),
+    (300, 200, 1028, 16), (77, 500, 250, 128), (64, 64, 4, 8), (130, 40, 1000, 20), (513, 100, 768, 32),
+])
+def test_ragged_shapes_all_variants(m, k, N, p):
+    w = workloads.uniform_random(m, k, N, 0.8, seed=m * 1000 + N)
+    for variant in _variants_for(p, N):
+        _say(f"ragged m={m} k={k} N={N} p={p} variant={variant}")
+        _check_product(w, p, variant)
+
+
+def test_auto_variant_and_strided_operands():
+    _say("strided B and C")
+    w = workloads.uniform_random(200, 150, 96, 0.9, seed=21)
+    A = binding.gcoo_from_csr(w.m, w.k, w.row_ptr, w.col_idx, w.vals, 32, device=DEV)
+    Bbig = torch.zeros((w.k, 200), device=DEV)
+    Bbig[:, 4:100] = torch.from_numpy(w.B).to(DEV)
+    Cbig = torch.full((w.m, 160), 7.0, device=DEV)
+    for off in (4, 5):                                # 16-byte aligned and unaligned column offsets
+        Bv = Bbig[:, off:off + 96]
+        if off != 4:
+            Bv.copy_(torch.from_numpy(w.B).to(DEV))
+        Cv = Cbig[:, 8:104]
+        binding.gcoo_spdm(A, Bv, Cv)
+        torch.cuda.synchronize()
+        C64, D64 = orc.spdm_csr(w.k, 96, w.row_ptr, w.col_idx, w.vals, w.B)
+        err, bad = orc.max_scaled_error(Cv.cpu().numpy(), C64, D64)
+        assert bad == 0 and err <= TOL
+        assert torch.all(Cbig[:, :8] == 7.0) and torch.all(Cbig[:, 104:] == 7.0)       # nothing outside C touched
+
+
+def test_special_cases_bit_exact():
+    """Products that are exact in fp32: the GPU result must equal them bit for bit."""
+    _say("special cases")
+    rng = np.random.default_rng(3)
+    n, N = 150, 132
+    B = rng.standard_normal((n, N)).astype(np.float32)
+    Bt = torch.from_numpy(B).to(DEV)
+    perm = rng.permutation(n)
+    d = rng.standard_normal(n).astype(np.float32)
+    cases = {
+        "identity": (sp.identity(n, dtype=np.float32, format="csr"), B),
+        "permutation": (sp.csr_matrix((np.ones(n, np.float32), (np.arange(n), perm)), shape=(n, n)), B[perm]),
+        "zero": (sp.csr_matrix((n, n), dtype=np.float32), np.zeros_like(B)),
+        "diagonal": (sp.diags(d, format="csr", dtype=np.float32), d[:, None] * B),
+        "single": (sp.csr_matrix((np.array([2.5], np.float32), ([4], [9])), shape=(n, n)), None),
+    }
+    single = np.zeros_like(B)
+    single[4] = np.float32(2.5) * B[9]
+    cases["single"] = (cases["single"][0], single)
+    for name, (S, expect) in cases.items():
+        S = sp.csr_matrix(S)
+        for p in (8, 32, 64):
+            A = binding.gcoo_from_csr(n, n, S.indptr.astype(np.int32), S.indices.astype(np.int32),
+                                      S.data.astype(np.float32), p, device=DEV)
+            for variant in _variants_for(p, N):
+                C = binding.gcoo_spdm(A, Bt, variant=variant)
+                torch.cuda.synchronize()
+                assert np.array_equal(C.cpu().numpy(), expect), (name, p, variant)
+
+
+def test_unstored_entries_are_skipped_not_multiplied():
+    _say("non-finite B rows that A never touches")
+    w = workloads.uniform_random(64, 64, 128, 0.98, seed=9)
+    untouched = np.setdiff1d(np.arange(w.k), w.col_idx)
+    assert untouched.size > 0
+    B = w.B.copy()
+    B[untouched] = np.inf
+    B[untouched[0]] = np.nan
+    w.B = B
+    for variant in _variants_for(32, w.N):
+        _check_product(w, 32, variant)
+
+
+def test_independent_of_p_and_deterministic():
+    _say("p independence / determinism")
+    w = workloads.uniform_random(256, 256, 256, 0.9, seed=13)
+    Bt = torch.from_numpy(w.B).to(DEV)
+    outs = []
+    for p in (8, 32, 64, 128):
+        A = binding.gcoo_from_csr(w.m, w.k, w.row_ptr, w.col_idx, w.vals, p, device=DEV)
+        c1 = binding.gcoo_spdm(A, Bt, variant=binding.VARIANT_REG).cpu().numpy()
+        c2 = binding.gcoo_spdm(A, Bt, variant=binding.VARIANT_REG).cpu().numpy()
+        assert np.array_equal(c1, c2)
+        outs.append(c1)
+    # every row sums its terms by ascending column whatever p is: identical bits
+    for o in outs[1:]:
+        assert np.array_equal(o, outs[0])
+
+
+def test_linearity_in_B_power_of_two_scale():
+    _say("linearity")
+    w = workloads.uniform_random(128, 128, 128, 0.9, seed=17)
+    A = binding.gcoo_from_csr(w.m, w.k, w.row_ptr, w.col_idx, w.vals, 32, device=DEV)
+    Bt = torch.from_numpy(w.B).to(DEV)
+    c1 = binding.gcoo_spdm(A, Bt).cpu().numpy()
+    c4 = binding.gcoo_spdm(A, Bt * 4.0).cpu().numpy()
+    assert np.array_equal(c4, c1 * np.float32(4.0))
+
+
+@pytest.mark.parametrize("index,p", [(1, 32), (4, 32), (4, 64)])
+def test_mid_size_configs_full_check(index, p):
+    """4000^2 s=0.95 and the skewed 16384^2 x 512 workload, every element against the oracle."""
+    w = workloads.config(index)
+    _say(f"config{index} p={p} nnz={w.nnz}")
+    _check_product(w, p, binding.VARIANT_AUTO)
+
+
+@pytest.mark.parametrize("index", [2, 3])
+def test_full_size_configs_sampled_rows(index):
+    """8000^2 at s=0.9 and s=0.995 in the launch configuration the benchmark times (p=32, automatic
+    variant); the oracle recomputes a sample of row bands: the first, the last (ragged tile
+    columns are in every row) and random ones."""
+    w = workloads.config(index)
+    _say(f"config{index} nnz={w.nnz}")
+    A = binding.gcoo_from_csr(w.m, w.k, w.row_ptr, w.col_idx, w.vals, 32, device=DEV)
+    G = A.export()
+    assert int(G["gIdxes"][-1]) == w.nnz and int(G["nnzPerGroup"].sum()) == w.nnz
+    # conversion at full size: group q is the CSR range of its rows, sorted by (col,row)
+    rng = np.random.default_rng(index)
+    for q in [0, A.info()["g"] - 1] + rng.integers(0, A.info()["g"], 6).tolist():
+        r0, r1 = q * 32, min(q * 32 + 32, w.m)
+        sub = orc.gcoo_from_csr(r1 - r0, w.k, w.row_ptr[r0:r1 + 1] - w.row_ptr[r0],
+                                w.col_idx[w.row_ptr[r0]:w.row_ptr[r1]], w.vals[w.row_ptr[r0]:w.row_ptr[r1]], 32)
+        s, e = int(G["gIdxes"][q]), int(G["gIdxes"][q + 1])
+        assert np.array_equal(G["cols"][s:e], sub.cols) and np.array_equal(G["rows"][s:e], sub.rows + r0)
+        assert np.array_equal(G["values"][s:e].view(np.uint32), sub.values.view(np.uint32))
+    Bt = torch.from_numpy(w.B).to(DEV)
+    Cg = torch.full((w.m, w.N), float("nan"), dtype=torch.float32, device=DEV)
+    binding.gcoo_spdm(A, Bt, Cg)
+    torch.cuda.synchronize()
+    assert not torch.isnan(Cg).any()
+    bands = [0, (w.m - 1) // 32] + rng.integers(0, (w.m + 31) // 32, 6).tolist()
+    for q in bands:
+        r0, r1 = q * 32, min(q * 32 + 32, w.m)
+        C64, D64 = orc.spdm_csr(w.k, w.N, w.row_ptr, w.col_idx, w.vals, w.B, r0, r1)
+        err, bad = orc.max_scaled_error(Cg[r0:r1].cpu().numpy(), C64, D64)
+        assert bad == 0 and err <= TOL, (q, err, bad)
