@@ -1,0 +1,230 @@
+#!/usr/bin/env python3
+"""Benchmark of the GCOO SpDM hot path on one MI355X.
+
+A step is one pass of the whole path over one synthetic input that is already resident in
+HBM: CSR (device) -> GCOO conversion kernels -> SpDM kernel -> C.  Prints ONE JSON line.
+
+  metric / value   effective GFLOP/s of the step, 2*nnz*N / t_step (Equation 2 of the paper
+                   generalised to m x k times k x N), conversion included
+  spdm             the SpDM kernel alone (the paper's "kernel calculation" part of its
+                   breakdown, Section 4.3): time from HIP events around each launch on the
+                   launch stream, effective GFLOP/s, and the same for the conversion
+  roofline         for the dominant kernel (SpDM): algorithmic bytes 12*nnz + 4*k*N + 4*m*N per
+                   launch over its measured duration, against 8 TB/s
+  cpu_baseline     the CPU oracle, timed as it stands on the host cores on a bounded sample
+  dense            rocBLAS/hipBLASLt SGEMM (torch.mm, fp32) on the densified A, for the crossover
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0          # MI355X HBM3E, published
+FP32_VECTOR_PEAK_TF = 157.3    # published (packed fp32); plain v_fma_f32 reaches half of it
+
+
+def parse():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=50)
+    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--workload", default="config3",
+                    help="config0..config4 (the five named workloads); config3 = 8000^2, sparsity 0.995")
+    ap.add_argument("--p", type=int, default=0, help="group height; 0 = library default for the workload")
+    ap.add_argument("--variant", type=int, default=0, help="0 auto, 1 LDS, 2 register+runs, 3 register per-entry")
+    ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle timing")
+    ap.add_argument("--no-dense", action="store_true", help="skip the dense SGEMM timing")
+    ap.add_argument("--secondary", default="config2", help="second workload reported in the same line ('' = none)")
+    return ap.parse_args()
+
+
+def time_path(torch, binding, w, dev, p, variant, steps, warmup):
+    """Times `steps` passes of convert + multiply; returns per-step and per-kernel times in ms."""
+    rp = torch.from_numpy(w.row_ptr).to(dev)
+    ci = torch.from_numpy(w.col_idx).to(dev)
+    va = torch.from_numpy(w.vals).to(dev)
+    B = torch.from_numpy(w.B).to(dev)
+    C = torch.empty((w.m, w.N), dtype=torch.float32, device=dev)
+    need = binding.gcoo_device_bytes(w.m, w.k, w.nnz, p)
+    buf = torch.empty(need, dtype=torch.uint8, device=dev)
+    import ctypes as Cc
+    L = binding.lib()
+    stream = torch.cuda.current_stream()
+    sp = Cc.c_void_p(stream.cuda_stream)
+
+    def convert():
+        out = Cc.c_void_p()
+        rc = L.gcoo_from_csr(w.m, w.k, rp.data_ptr(), ci.data_ptr(), va.data_ptr(), 1, p, buf.data_ptr(), need, sp,
+                             Cc.byref(out))
+        if rc != 0:
+            raise binding.GcooError(rc, "gcoo_from_csr")
+        return out
+
+    def multiply(h):
+        rc = L.gcoo_spdm_variant(h, B.data_ptr(), B.stride(0), w.N, C.data_ptr(), C.stride(0), sp, variant)
+        if rc != 0:
+            raise binding.GcooError(rc, "gcoo_spdm")
+
+    for _ in range(warmup):
+        h = convert()
+        multiply(h)
+        L.gcoo_free(h)
+    torch.cuda.synchronize()
+    ev = [[torch.cuda.Event(enable_timing=True) for _ in range(3)] for _ in range(steps)]
+    t0 = time.perf_counter()
+    for i in range(steps):
+        ev[i][0].record(stream)
+        h = convert()
+        ev[i][1].record(stream)
+        multiply(h)
+        ev[i][2].record(stream)
+        L.gcoo_free(h)
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    conv = [ev[i][0].elapsed_time(ev[i][1]) for i in range(steps)]
+    mult = [ev[i][1].elapsed_time(ev[i][2]) for i in range(steps)]
+    h = convert()
+    picked = L.gcoo_spdm_pick(h, B.data_ptr(), B.stride(0), w.N, C.data_ptr(), C.stride(0)) if variant == 0 else variant
+    L.gcoo_free(h)
+    torch.cuda.synchronize()
+    return dict(ms_per_step=(t1 - t0) * 1e3 / steps, convert_ms=sum(conv) / steps, spdm_ms=sum(mult) / steps,
+                spdm_ms_min=min(mult), variant=int(picked), B=B, C=C)
+
+
+def dense_ms(torch, w, dev, reps=5):
+    """fp32 SGEMM on the densified A (library GEMM; context for the crossover, not part of the path)."""
+    import numpy as np
+    A = np.zeros((w.m, w.k), np.float32)
+    rows = np.repeat(np.arange(w.m), np.diff(w.row_ptr))
+    A[rows, w.col_idx] = w.vals
+    Ad = torch.from_numpy(A).to(dev)
+    B = torch.from_numpy(w.B).to(dev)
+    torch.backends.cuda.matmul.allow_tf32 = False
+    for _ in range(2):
+        torch.mm(Ad, B)
+    torch.cuda.synchronize()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record()
+    for _ in range(reps):
+        torch.mm(Ad, B)
+    e1.record()
+    torch.cuda.synchronize()
+    return e0.elapsed_time(e1) / reps
+
+
+def cpu_baseline(w, p, budget_flops=1.2e11):
+    """The oracle as it stands (conversion + product, fp64 sums) on a row slice of the workload."""
+    from oracle import gcoo_oracle as orc
+    flops_full = 2.0 * w.nnz * w.N
+    rows = w.m if flops_full <= budget_flops else max(p, int(w.m * budget_flops / flops_full) // p * p)
+    rp = (w.row_ptr[:rows + 1] - w.row_ptr[0]).astype("int32")
+    nnz = int(rp[-1])
+    ci, va = w.col_idx[:nnz], w.vals[:nnz]
+    t0 = time.perf_counter()
+    orc.gcoo_from_csr(rows, w.k, rp, ci, va, p)
+    t1 = time.perf_counter()
+    orc.spdm_csr(w.k, w.N, rp, ci, va, w.B, 0, rows, want_scale=False)
+    t2 = time.perf_counter()
+    return dict(value=2.0 * nnz * w.N / (t2 - t0) / 1e9, unit="GFLOP/s", cores=orc.num_threads(), kind="oracle",
+                sample=f"rows 0..{rows - 1} of {w.m} ({nnz} nonzeros): conversion {1e3 * (t1 - t0):.0f} ms + "
+                       f"product {1e3 * (t2 - t1):.0f} ms, fp64 sums, OpenMP over rows")
+
+
+def read_traffic(kernel: str, workload: str):
+    """HBM bytes per launch from the committed rocprofv3 --pmc summary, if there is one."""
+    path = os.path.join(ROOT, "profiles", f"{kernel}_{workload}_pmc.txt")
+    if not os.path.exists(path):
+        return None
+    vals = {}
+    for line in open(path):
+        if "=" in line and not line.startswith("#"):
+            k, v = line.split("=", 1)
+            try:
+                vals[k.strip()] = float(v.split()[0])
+            except ValueError:
+                pass
+    if "FETCH_BYTES_PER_LAUNCH" in vals and "WRITE_BYTES_PER_LAUNCH" in vals:
+        return vals["FETCH_BYTES_PER_LAUNCH"] + vals["WRITE_BYTES_PER_LAUNCH"]
+    return None
+
+
+def default_p(name: str) -> int:
+    return 32
+
+
+def run_one(torch, binding, workloads, name, args, dev, steps, warmup):
+    idx = int(name.replace("config", ""))
+    w = workloads.config(idx)
+    p = args.p or default_p(name)
+    r = time_path(torch, binding, w, dev, p, args.variant, steps, warmup)
+    flops = 2.0 * w.nnz * w.N
+    alg_bytes = 12.0 * w.nnz + 4.0 * w.k * w.N + 4.0 * w.m * w.N
+    out = dict(
+        workload=name, m=w.m, k=w.k, N=w.N, nnz=w.nnz, p=p, variant=r["variant"],
+        ms_per_step=r["ms_per_step"], gflops=flops / r["ms_per_step"] / 1e6,
+        convert_ms=r["convert_ms"], spdm_ms=r["spdm_ms"], spdm_ms_min=r["spdm_ms_min"],
+        spdm_gflops=flops / r["spdm_ms"] / 1e6,
+        hbm_gbs=alg_bytes / r["spdm_ms"] / 1e6, hbm_frac=alg_bytes / r["spdm_ms"] / 1e6 / HBM_PEAK_GBS,
+        valu_frac_of_published=flops / r["spdm_ms"] / 1e9 / FP32_VECTOR_PEAK_TF,
+        alg_bytes=alg_bytes,
+    )
+    return w, out
+
+
+def main():
+    args = parse()
+    if args.gpus != 1:
+        print("bench.py: this build runs on one GPU only (the path needs no second one); use --gpus 1", file=sys.stderr)
+        sys.exit(2)
+    import torch
+    from paper_2005_14469_amd import binding, build, workloads
+
+    if not os.path.exists(binding.LIB_PATH):
+        build.build()
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible; the HIP path has no CPU fallback", file=sys.stderr)
+        sys.exit(3)
+    dev = torch.device("cuda:0")
+    torch.cuda.set_device(dev)
+
+    w, head = run_one(torch, binding, workloads, args.workload, args, dev, args.steps, args.warmup)
+    line = {
+        "metric": "fp32 SpDM effective GFLOP/s (2*nnz*N/t, whole path: CSR->GCOO conversion + SpDM kernel)",
+        "value": head["gflops"], "unit": "GFLOP/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": head["ms_per_step"], "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "f32", "data": "synthetic",
+        "config": {"workload": f"{args.workload}: A {w.m}x{w.k} uniform random, nnz={w.nnz}, B {w.k}x{w.N}, fp32",
+                   "p": head["p"], "variant": head["variant"]},
+        "spdm": {"ms": head["spdm_ms"], "ms_min": head["spdm_ms_min"], "gflops": head["spdm_gflops"],
+                 "convert_ms": head["convert_ms"], "frac_of_fp32_vector_peak": head["valu_frac_of_published"]},
+        "roofline": {"bound": "hbm", "achieved": head["hbm_gbs"], "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                     "frac": head["hbm_frac"], "traffic": read_traffic("spdm_reg", args.workload),
+                     "kernel": "gcoo::spdm_reg", "algorithmic_bytes_per_launch": head["alg_bytes"]},
+    }
+    if not args.no_dense:
+        d = dense_ms(torch, w, dev)
+        line["dense"] = {"sgemm_ms": d, "spdm_speedup_over_dense": d / head["spdm_ms"]}
+    if args.secondary and args.secondary != args.workload:
+        w2, sec = run_one(torch, binding, workloads, args.secondary, args, dev, max(5, args.steps // 5), 2)
+        line["secondary"] = {k: sec[k] for k in ("workload", "nnz", "p", "variant", "ms_per_step", "gflops", "convert_ms",
+                                                 "spdm_ms", "spdm_gflops", "hbm_frac", "valu_frac_of_published")}
+        line["secondary"]["roofline"] = {"bound": "alu", "achieved": sec["spdm_gflops"] / 1e3, "peak": FP32_VECTOR_PEAK_TF,
+                                         "unit": "TFLOP/s", "frac": sec["valu_frac_of_published"]}
+        if not args.no_dense:
+            d2 = dense_ms(torch, w2, dev)
+            line["secondary"]["dense_sgemm_ms"] = d2
+        del w2
+    if not args.no_cpu:
+        line["cpu_baseline"] = cpu_baseline(w, head["p"])
+    print(json.dumps(line))
+
+
+if __name__ == "__main__":
+    main()

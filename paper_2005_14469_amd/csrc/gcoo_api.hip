@@ -294,6 +294,7 @@ namespace {
 
 struct Shape {
     bool al4, al2;
+    bool wide_pitch;   // row pitch of B in bytes does not fit 32 bits: LDS variant only
 };
 
 Shape shape_of(const float* B, int64_t ldb, int64_t N, const float* C, int64_t ldc)
@@ -301,6 +302,7 @@ Shape shape_of(const float* B, int64_t ldb, int64_t N, const float* C, int64_t l
     const uintptr_t pb = reinterpret_cast<uintptr_t>(B), pc = reinterpret_cast<uintptr_t>(C);
     Shape s;
     s.al4 = (N % 4 == 0) && (ldb % 4 == 0) && (ldc % 4 == 0) && (pb % 16 == 0) && (pc % 16 == 0);
+    s.wide_pitch = ldb > 0x3fffffffLL;
     s.al2 = (N % 2 == 0) && (ldb % 2 == 0) && (ldc % 2 == 0) && (pb % 8 == 0) && (pc % 8 == 0);
     return s;
 }
@@ -320,6 +322,7 @@ double expected_run_length(const gcoo_matrix* A)
 void reg_config(int32_t p, const Shape& sh, int* P, int* V)
 {
     *P = 0; *V = 0;
+    if (sh.wide_pitch) return;
     if (p <= 32 && sh.al4) { *P = p <= 8 ? 8 : (p <= 16 ? 16 : 32); *V = 4; }
     else if (p <= 64 && sh.al2) { *P = 64; *V = 2; }
     else if (p <= 128) { *P = 128; *V = 1; }

@@ -157,9 +157,9 @@ __device__ __forceinline__ float acc_get(const AccFile& acc, int slot)
     return t == 0 ? acc.t0[i] : (t == 1 ? acc.t1[i] : (t == 2 ? acc.t2[i] : acc.t3[i]));
 }
 
-// One lane's V adjacent values of row `col` of B.  `off` = byte-free element offset of the lane's
-// first column.  Lanes of a tile that lie beyond N were pointed at column 0 by the caller, so
-// every address is inside B.
+// One lane's V adjacent values of row `col` of B, loaded by the compiler (waits inserted by
+// the compiler).  Used outside the pipelined loop.  Lanes of a tile that lie beyond N were
+// pointed at column 0 by the caller, so every address is inside B.
 template <int V>
 __device__ __forceinline__ void load_b(const float* __restrict__ Bl, int64_t ldb, int32_t col, float (&b)[V])
 {
@@ -173,6 +173,89 @@ __device__ __forceinline__ void load_b(const float* __restrict__ Bl, int64_t ldb
     } else {
         b[0] = *ptr;
     }
+}
+
+// The same load issued from an asm statement: the compiler does not know that the result is
+// still in flight, so it puts no s_waitcnt in front of the uses and the pipelined loop places
+// its own (wait_vm below).  The destination may be touched only by asm statements that come
+// after such a wait; the build checks the generated code for that.
+// Address = 64-bit scalar row base + 32-bit per-lane byte offset.
+template <int V>
+__device__ __forceinline__ void load_b_async(const float* row_base, uint32_t lane_off, float (&b)[V])
+{
+    if constexpr (V == 4) {
+        f32x4 t;
+        asm volatile("global_load_dwordx4 %0, %1, %2" : "=v"(t) : "v"(lane_off), "s"(row_base));
+        b[0] = t.x; b[1] = t.y; b[2] = t.z; b[3] = t.w;
+    } else if constexpr (V == 2) {
+        f32x2 t;
+        asm volatile("global_load_dwordx2 %0, %1, %2" : "=v"(t) : "v"(lane_off), "s"(row_base));
+        b[0] = t.x; b[1] = t.y;
+    } else {
+        asm volatile("global_load_dword %0, %1, %2" : "=v"(b[0]) : "v"(lane_off), "s"(row_base));
+    }
+}
+
+// Wait until at most `younger` vector-memory loads are still in flight (they complete in order,
+// so everything issued before the youngest `younger` ones has arrived).
+template <int N>
+__device__ __forceinline__ void wait_vm_imm()
+{
+    asm volatile("s_waitcnt vmcnt(%0)" ::"n"(N));
+}
+// The same with a run-time count 0..8: s_waitcnt takes an immediate only, so a three-level
+// compare tree picks one of nine.  Kept in one asm statement so that no compiler code lands
+// between the branches.
+template <int J>
+__device__ __forceinline__ void wait_vm(uint32_t younger)
+{
+    static_assert(J == 8, "one case per possible number of loads of a chunk");
+    asm volatile(
+        "s_cmp_gt_u32 %0, 3\n\t"
+        "s_cbranch_scc1 14f\n\t"
+        "s_cmp_gt_u32 %0, 1\n\t"
+        "s_cbranch_scc1 12f\n\t"
+        "s_cmp_eq_u32 %0, 0\n\t"
+        "s_cbranch_scc1 10f\n\t"
+        "s_waitcnt vmcnt(1)\n\t"
+        "s_branch 19f\n\t"
+        "10:\n\t"
+        "s_waitcnt vmcnt(0)\n\t"
+        "s_branch 19f\n\t"
+        "12:\n\t"
+        "s_cmp_eq_u32 %0, 2\n\t"
+        "s_cbranch_scc1 13f\n\t"
+        "s_waitcnt vmcnt(3)\n\t"
+        "s_branch 19f\n\t"
+        "13:\n\t"
+        "s_waitcnt vmcnt(2)\n\t"
+        "s_branch 19f\n\t"
+        "14:\n\t"
+        "s_cmp_gt_u32 %0, 5\n\t"
+        "s_cbranch_scc1 16f\n\t"
+        "s_cmp_eq_u32 %0, 4\n\t"
+        "s_cbranch_scc1 15f\n\t"
+        "s_waitcnt vmcnt(5)\n\t"
+        "s_branch 19f\n\t"
+        "15:\n\t"
+        "s_waitcnt vmcnt(4)\n\t"
+        "s_branch 19f\n\t"
+        "16:\n\t"
+        "s_cmp_gt_u32 %0, 7\n\t"
+        "s_cbranch_scc1 18f\n\t"
+        "s_cmp_eq_u32 %0, 6\n\t"
+        "s_cbranch_scc1 17f\n\t"
+        "s_waitcnt vmcnt(7)\n\t"
+        "s_branch 19f\n\t"
+        "17:\n\t"
+        "s_waitcnt vmcnt(6)\n\t"
+        "s_branch 19f\n\t"
+        "18:\n\t"
+        "s_waitcnt vmcnt(8)\n\t"
+        "19:"
+        :
+        : "s"(younger)
+        : "scc");
 }
 
 // J entries of a group held in SGPRs.
@@ -196,18 +279,21 @@ __device__ __forceinline__ void load_chunk(Chunk<J>& c, const uint32_t* __restri
 }
 
 // P: rows of partial sums kept (>= p of the matrix); V: columns per lane; J: entries per
-// pipeline step; REUSE: follow runs of equal columns (one B load per run) or load per entry.
+// pipeline step (= kChunk, the chunk length the ctl words were built for); REUSE: follow runs
+// of equal columns (one B load per run) or load per entry.
 //
 // Pipeline, per step n over chunks of J entries:
-//   scalar-load chunk n+2  |  issue the B loads of chunk n+1  |  multiply-add chunk n
+//   issue the B loads of chunk n+1  |  scalar-load chunk n+2  |  wait for chunk n  |  multiply-add chunk n
 // Chunk buffers rotate with period 3, B buffers with period 2; the loop body is unrolled six
-// steps so that every buffer index is a compile-time constant.
+// steps so that every buffer index is a compile-time constant.  The wait lets the loads of
+// chunk n+1 stay in flight: their number is the head count stored in the chunk's first ctl word.
 template <int P, int V, int J, bool REUSE>
 __global__ __launch_bounds__(64) void spdm_reg(const float* __restrict__ values, const int32_t* __restrict__ cols,
                                                const uint32_t* __restrict__ ctl, const int32_t* __restrict__ gIdxes,
                                                int64_t m, int32_t p, int64_t g, const float* __restrict__ B, int64_t ldb,
                                                int64_t N, float* __restrict__ C, int64_t ldc, int64_t total)
 {
+    static_assert(J == kChunk, "ctl words carry per-chunk head counts for chunks of kChunk entries");
     // XCD-aware order: workgroup ids go round-robin over the 8 XCDs, so XCD x is given the
     // contiguous slice [x*per, (x+1)*per) of the (tile-major) work list: it walks through all
     // groups of one column tile of B before moving to the next tile, which keeps that tile of
@@ -221,7 +307,13 @@ __global__ __launch_bounds__(64) void spdm_reg(const float* __restrict__ values,
     const int lane = threadIdx.x;
     const int64_t j0 = tile * (64 * V) + (int64_t)lane * V;
     const bool in = j0 < N;                                // N % V == 0: a lane is all in or all out
-    const float* __restrict__ Bl = B + (in ? j0 : 0);
+    // Row bases are wave-uniform (SGPRs); the lane's place inside the tile is a 32-bit byte
+    // offset.  Lanes beyond N read the first columns of the tile instead (always inside B).
+    const float* __restrict__ Bt = B + tile * (64 * V);
+    const char* Bbytes = reinterpret_cast<const char*>(Bt);
+    const uint32_t ldb4 = (uint32_t)ldb * 4u;              // the launcher checks that ldb*4 fits 32 bits
+    const uint32_t lane_off = in ? (uint32_t)(lane * V * 4) : 0u;
+    const float* __restrict__ Bl = Bt + (in ? lane * V : 0);
     const int32_t beg = gIdxes[q], end = gIdxes[q + 1];
     const int32_t nch = (end - beg) / J;
 
@@ -233,12 +325,23 @@ __global__ __launch_bounds__(64) void spdm_reg(const float* __restrict__ values,
     float bcur[V];
 #pragma unroll
     for (int v = 0; v < V; ++v) bcur[v] = 0.0f;
+    // every load buffer starts defined: a slot that gets no load (not a run head) is still named
+    // as an operand of the multiply-add statement, which then ignores it
+#pragma unroll
+    for (int i = 0; i < 2; ++i)
+#pragma unroll
+        for (int j = 0; j < J; ++j)
+#pragma unroll
+            for (int v = 0; v < V; ++v) bq[i][j][v] = 0.0f;
 
     auto issue = [&](const Chunk<J>& c, float (&dst)[J][V]) {
 #pragma unroll
         for (int j = 0; j < J; ++j)
-            if (!REUSE || (c.ctl[j] & kHeadBit)) load_b<V>(Bl, ldb, c.col[j], dst[j]);
+            if (!REUSE || (c.ctl[j] & kHeadBit))
+                load_b_async<V>(reinterpret_cast<const float*>(Bbytes + (uint64_t)(uint32_t)c.col[j] * ldb4), lane_off, dst[j]);
     };
+    // Number of loads `issue` starts for a chunk.
+    auto loads_of = [&](const Chunk<J>& c) -> uint32_t { return REUSE ? ((c.ctl[0] >> kCountShift) & 15u) : (uint32_t)J; };
     // The first entry of a run multiplies straight out of its load buffer.  Only when a run goes
     // on to a second entry is the segment copied to `bcur` (once per run of length >= 2), and a
     // run that is still open at the end of a chunk is copied too, because its buffer is about
@@ -255,18 +358,41 @@ __global__ __launch_bounds__(64) void spdm_reg(const float* __restrict__ values,
         if constexpr (REUSE) keep_if_head<V>(c.ctl[J - 1], src[J - 1], bcur);
     };
 
-    if (nch > 0) { load_chunk<J>(ck[0], ctl, cols, values, beg); }
-    if (nch > 1) { load_chunk<J>(ck[1], ctl, cols, values, beg + J); }
-    if (nch > 0) { issue(ck[0], bq[0]); }
-    for (int32_t n0 = 0; n0 < nch; n0 += 6) {
+    // Loads issued by asm are invisible to the compiler, so they may be in flight only where the
+    // compiler has no reason to move their destination registers: inside the body of the
+    // steady-state loop.  The loop is entered and left with nothing in flight (vmcnt(0) before
+    // the first step and at the end of the last one).
+    int32_t n = 0;
+    if (nch >= 8) {
+        load_chunk<J>(ck[0], ctl, cols, values, beg);
+        load_chunk<J>(ck[1], ctl, cols, values, beg + J);
+        issue(ck[0], bq[0]);
+        wait_vm_imm<0>();
+        // steady state: every step has a next and a next-but-one chunk, so nothing is conditional
+        do {
 #pragma unroll
-        for (int s = 0; s < 6; ++s) {
-            const int32_t n = n0 + s;
-            if (n >= nch) break;
-            if (n + 1 < nch) issue(ck[(s + 1) % 3], bq[(s + 1) % 2]);
-            if (n + 2 < nch) load_chunk<J>(ck[(s + 2) % 3], ctl, cols, values, beg + (n + 2) * J);
-            compute(ck[s % 3], bq[s % 2]);
-        }
+            for (int s = 0; s < 6; ++s) {
+                issue(ck[(s + 1) % 3], bq[(s + 1) % 2]);
+                load_chunk<J>(ck[(s + 2) % 3], ctl, cols, values, beg + (n + s + 2) * J);
+                if constexpr (REUSE) wait_vm<J>(loads_of(ck[(s + 1) % 3])); else wait_vm_imm<J>();
+                compute(ck[s % 3], bq[s % 2]);
+            }
+            n += 6;
+            if (n + 8 > nch) wait_vm_imm<0>();           // last round: drain before leaving
+        } while (n + 8 <= nch);
+        // chunk n has arrived in load buffer 0; chunks n, n+1 are in the scalar buffers 0 and 1
+        compute(ck[0], bq[0]);
+        issue(ck[1], bq[1]);
+        wait_vm_imm<0>();
+        compute(ck[1], bq[1]);
+        n += 2;
+    }
+    // the last (up to seven) chunks, one at a time
+    for (; n < nch; ++n) {
+        load_chunk<J>(ck[0], ctl, cols, values, beg + n * J);
+        issue(ck[0], bq[0]);
+        wait_vm_imm<0>();
+        compute(ck[0], bq[0]);
     }
     // entries left over after the last full chunk: one at a time, the segment always in bcur
     for (int32_t e = beg + nch * J; e < end; ++e) {
@@ -308,6 +434,7 @@ hipError_t launch_spdm_reg_instance(const SpdmArgs& a, hipStream_t s)
     const int64_t total = a.g * tiles;
     const int64_t grid = (total + 7) / 8 * 8;          // whole rounds over the 8 XCDs
     if (grid <= 0 || grid > 0x7fffffffLL) return hipErrorInvalidConfiguration;
+    if (a.ldb > 0x3fffffffLL) return hipErrorInvalidValue;   // row pitch in bytes is kept in 32 bits
     spdm_reg<P, V, J, REUSE><<<dim3((unsigned)grid), dim3(64), 0, s>>>(a.values, a.cols, a.ctl, a.gIdxes, a.m, a.p, a.g, a.B,
                                                                      a.ldb, a.N, a.C, a.ldc, total);
     return hipGetLastError();

@@ -6,9 +6,14 @@
 
 namespace gcoo {
 
-// Bit 31 of a ctl word marks the first entry of a run of equal columns inside a group;
-// bits 0..7 hold the row inside the group (row - q*p).
+// One control word per stored entry, built after the sort:
+//   bit 31      first entry of a run of equal columns inside its group
+//   bits 0..7   row inside the group (row - q*p)
+//   bits 8..11  only in the first entry of every chunk of kChunk entries of a group (counted
+//               from the group's start): number of run heads in that chunk
 constexpr uint32_t kHeadBit = 0x80000000u;
+constexpr int kChunk = 8;
+constexpr int kCountShift = 8;
 
 struct SpdmArgs {
     const float* values;

@@ -9,7 +9,7 @@
 namespace gcoo {
 
 
-// ctl[e] for every entry: built once per matrix, after the sort.
+// ctl[e] for every entry: built once per matrix, after the sort.  One workgroup per group.
 __global__ void mark_runs(const int32_t* __restrict__ gIdxes, const int32_t* __restrict__ rows,
                           const int32_t* __restrict__ cols, int32_t p, int64_t g, uint32_t* __restrict__ ctl)
 {
@@ -19,7 +19,13 @@ __global__ void mark_runs(const int32_t* __restrict__ gIdxes, const int32_t* __r
     const int32_t row0 = (int32_t)(q * p);
     for (int32_t e = beg + (int32_t)threadIdx.x; e < end; e += (int32_t)blockDim.x) {
         const bool head = (e == beg) || (cols[e] != cols[e - 1]);
-        ctl[e] = (uint32_t)(rows[e] - row0) | (head ? kHeadBit : 0u);
+        uint32_t w = (uint32_t)(rows[e] - row0) | (head ? kHeadBit : 0u);
+        if ((e - beg) % kChunk == 0) {
+            uint32_t heads = head ? 1u : 0u;
+            for (int32_t f = e + 1; f < e + kChunk && f < end; ++f) heads += (cols[f] != cols[f - 1]) ? 1u : 0u;
+            w |= heads << kCountShift;
+        }
+        ctl[e] = w;
     }
 }
 
