@@ -38,7 +38,7 @@ def parse():
     ap.add_argument("--workload", default="config3",
                     help="config0..config4 (the five named workloads); config3 = 8000^2, sparsity 0.995")
     ap.add_argument("--p", type=int, default=0, help="group height; 0 = library default for the workload")
-    ap.add_argument("--variant", type=int, default=0, help="0 auto, 1 LDS, 2 register+runs, 3 register per-entry")
+    ap.add_argument("--variant", type=int, default=0, help="0 auto, 1 partial sums in LDS, 2 partial sums in registers")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle timing")
     ap.add_argument("--no-dense", action="store_true", help="skip the dense SGEMM timing")
     ap.add_argument("--secondary", default="config2", help="second workload reported in the same line ('' = none)")
@@ -205,8 +205,8 @@ def main():
         "spdm": {"ms": head["spdm_ms"], "ms_min": head["spdm_ms_min"], "gflops": head["spdm_gflops"],
                  "convert_ms": head["convert_ms"], "frac_of_fp32_vector_peak": head["valu_frac_of_published"]},
         "roofline": {"bound": "hbm", "achieved": head["hbm_gbs"], "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                     "frac": head["hbm_frac"], "traffic": read_traffic("spdm_reg", args.workload),
-                     "kernel": "gcoo::spdm_reg", "algorithmic_bytes_per_launch": head["alg_bytes"]},
+                     "frac": head["hbm_frac"], "traffic": read_traffic("spdm_sched", args.workload),
+                     "kernel": "gcoo::spdm_sched", "algorithmic_bytes_per_launch": head["alg_bytes"]},
     }
     if not args.no_dense:
         d = dense_ms(torch, w, dev)

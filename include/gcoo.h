@@ -57,7 +57,8 @@ typedef struct gcoo_matrix gcoo_matrix;
 /*
  * Device bytes a gcoo_from_csr() / gcoo_from_dense() call needs in dev_buf for an m x k matrix
  * with nnz stored entries and group height p: the five arrays of Section 3.1 (Table 1:
- * 3*nnz + 2*g elements, plus one sentinel) and the scratch space the conversion kernels use.
+ * 3*nnz + 2*g elements, plus one sentinel), the run schedule derived from them for the register
+ * kernel (at most 3*nnz + 264*g words) and the scratch space the conversion kernels use.
  * Returns 0 for invalid arguments.  Pure host arithmetic.
  */
 size_t gcoo_device_bytes(int64_t m, int64_t k, int64_t nnz, int32_t p);
@@ -119,10 +120,9 @@ int gcoo_spdm(const gcoo_matrix* A, const float* B_dev, int64_t ldb, int64_t N,
  *   variant  GCOO_VARIANT_AUTO, or one of the GCOO_VARIANT_* below.  A variant that does not
  *            support this matrix/shape returns GCOO_EINVAL.
  */
-#define GCOO_VARIANT_AUTO      0
-#define GCOO_VARIANT_LDS       1  /* accumulators in LDS; any p, any alignment */
-#define GCOO_VARIANT_REG       2  /* accumulators in VGPRs, B value reused along a run of equal columns */
-#define GCOO_VARIANT_REG_NORUN 3  /* accumulators in VGPRs, one B load per entry (for run length ~ 1) */
+#define GCOO_VARIANT_AUTO 0
+#define GCOO_VARIANT_LDS  1  /* partial sums in LDS, reads the five arrays directly; any p, any alignment */
+#define GCOO_VARIANT_REG  2  /* partial sums in VGPRs, reads the run schedule built at conversion; p <= 128 */
 int gcoo_spdm_variant(const gcoo_matrix* A, const float* B_dev, int64_t ldb, int64_t N,
                       float* C_dev, int64_t ldc, void* stream, int variant);
 

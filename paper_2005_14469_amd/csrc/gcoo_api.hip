@@ -4,13 +4,14 @@
 
 #include <hip/hip_runtime.h>
 
-#include <cmath>
 #include <cstdio>
 #include <cstring>
 #include <new>
 #include <string>
 
 #include "gcoo_build_kernels.hpp"
+#include "gcoo_sched.hpp"
+#include "gcoo_sched_build.hpp"
 #include "gcoo_spdm_launch.hpp"
 #include "gcoo_spdm_lds_kernel.hpp"
 
@@ -39,7 +40,8 @@ __device__ unsigned long long g_dense_total;
 
 // Carve-up of the caller's device buffer.  Offsets depend on (m, nnz, g) only.
 struct Layout {
-    size_t values, rows, cols, gIdxes, nnzPerGroup, ctl;   // kept for the life of the handle
+    size_t values, rows, cols, gIdxes, nnzPerGroup;        // the five arrays of the format
+    size_t sched_hdr, sched;                               // run schedule of the register kernel
     size_t tmp_cols, tmp_rows, tmp_vals;                   // conversion scratch (second sort buffer)
     size_t in_row_ptr, in_cols, in_vals;                   // staging of a host CSR input
     size_t counter;                                        // 8-byte device counter
@@ -60,7 +62,8 @@ Layout make_layout(int64_t m, int64_t nnz, int64_t g)
     L.values = take(n4);
     L.rows = take(n4);
     L.cols = take(n4);
-    L.ctl = take(n4);
+    L.sched_hdr = take((size_t)g * gcoo::kMaxRun * sizeof(gcoo::SchedClass));
+    L.sched = take(((size_t)nnz * 3 + (size_t)g * gcoo::kSchedPad) * 4);
     L.tmp_cols = take(n4);
     L.tmp_rows = take(n4);
     L.tmp_vals = take(n4);
@@ -98,7 +101,8 @@ struct gcoo_matrix {
     int32_t* cols() const { return reinterpret_cast<int32_t*>(base + L.cols); }
     int32_t* gIdxes() const { return reinterpret_cast<int32_t*>(base + L.gIdxes); }
     int32_t* nnzPerGroup() const { return reinterpret_cast<int32_t*>(base + L.nnzPerGroup); }
-    uint32_t* ctl() const { return reinterpret_cast<uint32_t*>(base + L.ctl); }
+    gcoo::SchedClass* sched_hdr() const { return reinterpret_cast<gcoo::SchedClass*>(base + L.sched_hdr); }
+    uint32_t* sched() const { return reinterpret_cast<uint32_t*>(base + L.sched); }
 };
 
 namespace {
@@ -116,10 +120,12 @@ int new_handle(int64_t m, int64_t k, int64_t nnz, int32_t p, void* dev_buf, gcoo
     return GCOO_OK;
 }
 
-int launch_mark_runs(const gcoo_matrix* h, hipStream_t s)
+// Builds the run schedule of the register kernel from the finished GCOO arrays.
+int launch_build_schedule(const gcoo_matrix* h, hipStream_t s)
 {
-    if (h->g > 0 && h->nnz > 0) {
-        gcoo::mark_runs<<<dim3((unsigned)h->g), dim3(256), 0, s>>>(h->gIdxes(), h->rows(), h->cols(), h->p, h->g, h->ctl());
+    if (h->g > 0) {
+        gcoo::build_schedule<<<dim3((unsigned)h->g), dim3(256), 0, s>>>(h->gIdxes(), h->rows(), h->cols(), h->values(), h->p,
+                                                                        h->g, h->sched_hdr(), h->sched());
         HIP_TRY(hipGetLastError());
     }
     return GCOO_OK;
@@ -216,7 +222,7 @@ int gcoo_from_csr(int64_t m, int64_t k, const int32_t* row_ptr, const int32_t* c
             src_c = dc; src_r = dr; src_v = dv;
         }
     }
-    rc = launch_mark_runs(h, s);
+    rc = launch_build_schedule(h, s);
     if (rc != GCOO_OK) { delete h; return rc; }
     *out = h;
     return GCOO_OK;
@@ -282,7 +288,7 @@ int gcoo_from_dense(int64_t m, int64_t k, const float* A_dev, int64_t lda, int32
         hipError_t e = hipGetLastError();
         if (e != hipSuccess) { delete h; return hip_fail(e, "fill_from_dense"); }
     }
-    rc = launch_mark_runs(h, s);
+    rc = launch_build_schedule(h, s);
     if (rc != GCOO_OK) { delete h; return rc; }
     *out = h;
     return GCOO_OK;
@@ -307,37 +313,24 @@ Shape shape_of(const float* B, int64_t ldb, int64_t N, const float* C, int64_t l
     return s;
 }
 
-// Expected run length under uniform sparsity: a column of a p-row band holds Binomial(p, d)
-// entries, so runs average p*d / (1 - (1-d)^p) entries (Section 3.3 cut down to one band).
-double expected_run_length(const gcoo_matrix* A)
+// Columns per lane of the register kernel that serves this p and alignment; 0 if none does.
+int sched_width(int32_t p, const Shape& sh)
 {
-    if (A->nnz == 0 || A->m == 0 || A->k == 0) return 1.0;
-    const double d = (double)A->nnz / ((double)A->m * (double)A->k);
-    const double pe = (double)(A->p < A->m ? A->p : A->m);
-    const double none = std::pow(1.0 - d, pe);
-    return none >= 1.0 ? 1.0 : pe * d / (1.0 - none);
-}
-
-// Which (P, V) instance of spdm_reg serves this p and alignment; V = 0 if none.
-void reg_config(int32_t p, const Shape& sh, int* P, int* V)
-{
-    *P = 0; *V = 0;
-    if (sh.wide_pitch) return;
-    if (p <= 32 && sh.al4) { *P = p <= 8 ? 8 : (p <= 16 ? 16 : 32); *V = 4; }
-    else if (p <= 64 && sh.al2) { *P = 64; *V = 2; }
-    else if (p <= 128) { *P = 128; *V = 1; }
+    if (sh.wide_pitch) return 0;
+    if (p <= 32 && sh.al4) return 4;
+    if (p <= 64 && sh.al2) return 2;
+    if (p <= 128) return 1;
+    return 0;
 }
 
 }  // namespace
 
 namespace gcoo {
-hipError_t launch_spdm_reg(int P, int V, bool reuse, const SpdmArgs& a, hipStream_t s)
+hipError_t launch_spdm_sched(int V, const SpdmArgs& a, hipStream_t s)
 {
-    if (V == 4 && P == 8) return launch_spdm_reg_p8_v4(reuse, a, s);
-    if (V == 4 && P == 16) return launch_spdm_reg_p16_v4(reuse, a, s);
-    if (V == 4 && P == 32) return launch_spdm_reg_p32_v4(reuse, a, s);
-    if (V == 2 && P == 64) return launch_spdm_reg_p64_v2(reuse, a, s);
-    if (V == 1 && P == 128) return launch_spdm_reg_p128_v1(reuse, a, s);
+    if (V == 4) return launch_spdm_sched_v4(a, s);
+    if (V == 2) return launch_spdm_sched_v2(a, s);
+    if (V == 1) return launch_spdm_sched_v1(a, s);
     return hipErrorInvalidValue;
 }
 }  // namespace gcoo
@@ -360,10 +353,7 @@ int gcoo_spdm_pick(const gcoo_matrix* A, const float* B_dev, int64_t ldb, int64_
 {
     int rc = check_spdm_args(A, B_dev, ldb, N, C_dev, ldc);
     if (rc != GCOO_OK) return rc;
-    int P, V;
-    reg_config(A->p, shape_of(B_dev, ldb, N, C_dev, ldc), &P, &V);
-    if (V == 0) return GCOO_VARIANT_LDS;
-    return expected_run_length(A) >= 1.25 ? GCOO_VARIANT_REG : GCOO_VARIANT_REG_NORUN;
+    return sched_width(A->p, shape_of(B_dev, ldb, N, C_dev, ldc)) ? GCOO_VARIANT_REG : GCOO_VARIANT_LDS;
 }
 
 int gcoo_spdm_variant(const gcoo_matrix* A, const float* B_dev, int64_t ldb, int64_t N, float* C_dev, int64_t ldc,
@@ -371,7 +361,7 @@ int gcoo_spdm_variant(const gcoo_matrix* A, const float* B_dev, int64_t ldb, int
 {
     int rc = check_spdm_args(A, B_dev, ldb, N, C_dev, ldc);
     if (rc != GCOO_OK) return rc;
-    if (variant < GCOO_VARIANT_AUTO || variant > GCOO_VARIANT_REG_NORUN) return GCOO_EINVAL;
+    if (variant < GCOO_VARIANT_AUTO || variant > GCOO_VARIANT_REG) return GCOO_EINVAL;
     if (variant == GCOO_VARIANT_AUTO) variant = gcoo_spdm_pick(A, B_dev, ldb, N, C_dev, ldc);
     if (A->m == 0 || N == 0) return GCOO_OK;
     hipStream_t s = static_cast<hipStream_t>(stream);
@@ -386,12 +376,11 @@ int gcoo_spdm_variant(const gcoo_matrix* A, const float* B_dev, int64_t ldb, int
         HIP_TRY(hipGetLastError());
         return GCOO_OK;
     }
-    int P, V;
-    reg_config(A->p, shape_of(B_dev, ldb, N, C_dev, ldc), &P, &V);
+    const int V = sched_width(A->p, shape_of(B_dev, ldb, N, C_dev, ldc));
     if (V == 0) return GCOO_EINVAL;
-    gcoo::SpdmArgs a{A->values(), A->cols(), A->ctl(), A->gIdxes(), A->m, A->p, A->g, B_dev, ldb, N, C_dev, ldc};
-    hipError_t e = gcoo::launch_spdm_reg(P, V, variant == GCOO_VARIANT_REG, a, s);
-    if (e != hipSuccess) return hip_fail(e, "spdm_reg launch");
+    gcoo::SpdmArgs a{A->sched_hdr(), A->sched(), A->gIdxes(), A->m, A->p, A->g, B_dev, ldb, N, C_dev, ldc};
+    hipError_t e = gcoo::launch_spdm_sched(V, a, s);
+    if (e != hipSuccess) return hip_fail(e, "spdm_sched launch");
     return GCOO_OK;
 }
 

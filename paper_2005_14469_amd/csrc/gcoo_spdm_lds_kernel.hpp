@@ -1,33 +1,12 @@
-// The run-marking kernel (one control word per stored entry) and the LDS variant of the SpDM
-// kernel (Algorithm 2 of the paper with the partial sums in LDS; the fallback for every shape).
+// The LDS variant of the SpDM kernel: Algorithm 2 of the paper with the partial sums in LDS.
+// It reads the five GCOO arrays as they are and serves every shape.
 #pragma once
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
-#include "gcoo_spdm_launch.hpp"
 
 namespace gcoo {
 
-
-// ctl[e] for every entry: built once per matrix, after the sort.  One workgroup per group.
-__global__ void mark_runs(const int32_t* __restrict__ gIdxes, const int32_t* __restrict__ rows,
-                          const int32_t* __restrict__ cols, int32_t p, int64_t g, uint32_t* __restrict__ ctl)
-{
-    const int64_t q = blockIdx.x;
-    if (q >= g) return;
-    const int32_t beg = gIdxes[q], end = gIdxes[q + 1];
-    const int32_t row0 = (int32_t)(q * p);
-    for (int32_t e = beg + (int32_t)threadIdx.x; e < end; e += (int32_t)blockDim.x) {
-        const bool head = (e == beg) || (cols[e] != cols[e - 1]);
-        uint32_t w = (uint32_t)(rows[e] - row0) | (head ? kHeadBit : 0u);
-        if ((e - beg) % kChunk == 0) {
-            uint32_t heads = head ? 1u : 0u;
-            for (int32_t f = e + 1; f < e + kChunk && f < end; ++f) heads += (cols[f] != cols[f - 1]) ? 1u : 0u;
-            w |= heads << kCountShift;
-        }
-        ctl[e] = w;
-    }
-}
 
 // ---------------------------------------------------------------------------------------------
 // Variant LDS: the p x 64 partial sums of a wave live in LDS (one column per lane, so no bank
