@@ -5,6 +5,7 @@
 #include <hip/hip_runtime.h>
 
 #include <cstdio>
+#include <cstdlib>
 #include <cstring>
 #include <new>
 #include <string>
@@ -48,8 +49,33 @@ struct Layout {
     size_t total;
 };
 
-Layout make_layout(int64_t m, int64_t nnz, int64_t g)
+// Column windows of the run schedule: bands of kWindowCols columns (a band of B of that many
+// rows by one column tile stays in the L2 of the XCD working on the tile), at most kMaxWindows,
+// and fewer when the matrix has so many groups that the per-window headers would dominate.
+constexpr int64_t kWindowCols = 2048;
+
+void pick_windows(int64_t k, int64_t g, int32_t* nw, int32_t* window_cols)
 {
+    int64_t wc = kWindowCols;
+    if (const char* e = std::getenv("GCOO_WINDOW_COLS")) {
+        const long v = std::atol(e);
+        if (v >= 64) wc = v;
+    }
+    int64_t n = (k + wc - 1) / wc;
+    const int64_t cap_groups = g > 0 ? (int64_t(1) << 22) / g : gcoo::kMaxWindows;
+    int64_t cap = gcoo::kMaxWindows;
+    if (cap_groups < cap) cap = cap_groups;
+    if (cap < 1) cap = 1;
+    if (n > cap) n = cap;
+    if (n < 1) n = 1;
+    *nw = (int32_t)n;
+    *window_cols = (int32_t)((k + n - 1) / n > 0 ? (k + n - 1) / n : 1);
+}
+
+Layout make_layout(int64_t m, int64_t k, int64_t nnz, int64_t g)
+{
+    int32_t nw, wc;
+    pick_windows(k, g, &nw, &wc);
     Layout L{};
     size_t at = 0;
     auto take = [&](size_t bytes) { size_t o = at; at += al(bytes ? bytes : 1); return o; };
@@ -62,8 +88,8 @@ Layout make_layout(int64_t m, int64_t nnz, int64_t g)
     L.values = take(n4);
     L.rows = take(n4);
     L.cols = take(n4);
-    L.sched_hdr = take((size_t)g * gcoo::kMaxRun * sizeof(gcoo::SchedClass));
-    L.sched = take(((size_t)nnz * 3 + (size_t)g * gcoo::kSchedPad) * 4);
+    L.sched_hdr = take((size_t)g * nw * gcoo::kMaxRun * sizeof(gcoo::SchedClass));
+    L.sched = take((size_t)gcoo::sched_words(nnz, g, nw) * 4);
     L.tmp_cols = take(n4);
     L.tmp_rows = take(n4);
     L.tmp_vals = take(n4);
@@ -93,6 +119,7 @@ int radix_passes(int64_t k)
 struct gcoo_matrix {
     int64_t m, k, nnz, g;
     int32_t p;
+    int32_t nw, window_cols;
     int device;
     char* base;
     Layout L;
@@ -114,7 +141,8 @@ int new_handle(int64_t m, int64_t k, int64_t nnz, int32_t p, void* dev_buf, gcoo
     h->m = m; h->k = k; h->nnz = nnz; h->p = p;
     h->g = (m + p - 1) / p;
     h->base = static_cast<char*>(dev_buf);
-    h->L = make_layout(m, nnz, h->g);
+    h->L = make_layout(m, k, nnz, h->g);
+    pick_windows(k, h->g, &h->nw, &h->window_cols);
     if (hipGetDevice(&h->device) != hipSuccess) h->device = -1;
     *out = h;
     return GCOO_OK;
@@ -125,7 +153,7 @@ int launch_build_schedule(const gcoo_matrix* h, hipStream_t s)
 {
     if (h->g > 0) {
         gcoo::build_schedule<<<dim3((unsigned)h->g), dim3(256), 0, s>>>(h->gIdxes(), h->rows(), h->cols(), h->values(), h->p,
-                                                                        h->g, h->sched_hdr(), h->sched());
+                                                                        h->g, h->nw, h->window_cols, h->sched_hdr(), h->sched());
         HIP_TRY(hipGetLastError());
     }
     return GCOO_OK;
@@ -138,7 +166,7 @@ extern "C" {
 size_t gcoo_device_bytes(int64_t m, int64_t k, int64_t nnz, int32_t p)
 {
     if (!dims_ok(m, k, nnz, p)) return 0;
-    return make_layout(m, nnz, (m + p - 1) / p).total;
+    return make_layout(m, k, nnz, (m + p - 1) / p).total;
 }
 
 int gcoo_from_csr(int64_t m, int64_t k, const int32_t* row_ptr, const int32_t* col_idx, const float* vals,
@@ -168,7 +196,7 @@ int gcoo_from_csr(int64_t m, int64_t k, const int32_t* row_ptr, const int32_t* c
     }
     if (nnz > 0 && (!col_idx || !vals)) return GCOO_EINVAL;
     const int64_t g = (m + p - 1) / p;
-    const Layout L = make_layout(m, nnz, g);
+    const Layout L = make_layout(m, k, nnz, g);
     if (dev_buf_bytes < L.total) return GCOO_ENOMEM;
 
     gcoo_matrix* h = nullptr;
@@ -258,7 +286,7 @@ int gcoo_from_dense(int64_t m, int64_t k, const float* A_dev, int64_t lda, int32
     const int64_t g = (m + p - 1) / p;
     // gIdxes / nnzPerGroup / counter sit at the front of the buffer at offsets that do not
     // depend on nnz, so step 1 can run before the buffer size for this nnz is checked.
-    const Layout L0 = make_layout(m, 0, g);
+    const Layout L0 = make_layout(m, k, 0, g);
     if (dev_buf_bytes < L0.total) return GCOO_ENOMEM;
     char* base = static_cast<char*>(dev_buf);
     int32_t* cnt = reinterpret_cast<int32_t*>(base + L0.nnzPerGroup);
@@ -277,7 +305,7 @@ int gcoo_from_dense(int64_t m, int64_t k, const float* A_dev, int64_t lda, int32
     }
     if (total > (unsigned long long)INT32_MAX) return GCOO_EINVAL;
     const int64_t nnz = (int64_t)total;
-    const Layout L = make_layout(m, nnz, g);
+    const Layout L = make_layout(m, k, nnz, g);
     if (dev_buf_bytes < L.total) return GCOO_ENOMEM;
     gcoo_matrix* h = nullptr;
     int rc = new_handle(m, k, nnz, p, dev_buf, &h);
@@ -378,7 +406,7 @@ int gcoo_spdm_variant(const gcoo_matrix* A, const float* B_dev, int64_t ldb, int
     }
     const int V = sched_width(A->p, shape_of(B_dev, ldb, N, C_dev, ldc));
     if (V == 0) return GCOO_EINVAL;
-    gcoo::SpdmArgs a{A->sched_hdr(), A->sched(), A->gIdxes(), A->m, A->p, A->g, B_dev, ldb, N, C_dev, ldc};
+    gcoo::SpdmArgs a{A->sched_hdr(), A->sched(), A->gIdxes(), A->m, A->p, A->g, A->nw, B_dev, ldb, N, C_dev, ldc};
     hipError_t e = gcoo::launch_spdm_sched(V, a, s);
     if (e != hipSuccess) return hip_fail(e, "spdm_sched launch");
     return GCOO_OK;

@@ -7,116 +7,136 @@
 
 namespace gcoo {
 
-// One workgroup (256 threads) per group.  Pass 1 counts the pieces of each class, pass 2 gives
-// every piece its rank inside its class (entries are visited in order; ranks come from ballots
-// and running counts, so the listing is the same on every run) and writes it out.
+// One workgroup (256 threads) per group.  Per window: pass 1 counts the pieces of each class,
+// pass 2 gives every piece its rank inside its class (entries are visited in order; ranks come
+// from ballots and running counts, so the listing is the same on every run) and writes it out.
 __global__ __launch_bounds__(256) void build_schedule(const int32_t* __restrict__ gIdxes, const int32_t* __restrict__ rows,
                                                       const int32_t* __restrict__ cols, const float* __restrict__ values,
-                                                      int32_t p, int64_t g, SchedClass* __restrict__ hdr,
-                                                      uint32_t* __restrict__ stream)
+                                                      int32_t p, int64_t g, int32_t nw, int32_t window_cols,
+                                                      SchedClass* __restrict__ hdr, uint32_t* __restrict__ stream)
 {
-    __shared__ int32_t cnt[kMaxRun];          // pieces per class
-    __shared__ int32_t demote[kMaxRun];       // class listed as pieces of class 1
-    __shared__ int32_t seg[kMaxRun];          // first word of the class
-    __shared__ int32_t base[kMaxRun];         // pieces of the class already placed
-    __shared__ int32_t wcnt[4][kMaxRun];      // per wave, per class, in the current tile
+    __shared__ int32_t wstart[kMaxWindows + 1];   // first entry of each window
+    __shared__ int32_t cnt[kMaxRun];              // pieces per class in the current window
+    __shared__ int32_t demote[kMaxRun];           // class listed as pieces of class 1
+    __shared__ int32_t seg[kMaxRun];              // first word of the class
+    __shared__ int32_t base[kMaxRun];             // pieces of the class already placed
+    __shared__ int32_t wcnt[4][kMaxRun];          // per wave, per class, in the current tile
+    __shared__ int32_t at_s;                      // words used so far by this group
     const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
     const int64_t q = blockIdx.x;
     if (q >= g) return;
     const int32_t beg = gIdxes[q], end = gIdxes[q + 1];
     const int32_t row0 = (int32_t)(q * p);
-    uint32_t* __restrict__ out = stream + sched_group_base(beg, q);
+    uint32_t* __restrict__ out = stream + sched_group_base(beg, q, nw);
+    SchedClass* __restrict__ h = hdr + q * nw * kMaxRun;
 
-    if (tid < kMaxRun) { cnt[tid] = 0; base[tid] = 0; demote[tid] = 0; }
-    __syncthreads();
-
-    // Length of the natural piece (run cut every kMaxRun entries) that entry e belongs to, and
-    // e's place in it.
-    auto natural_piece = [&](int32_t e, int& pos) -> int {
-        const int32_t c = cols[e];
-        int32_t rs = e;                                   // first entry of the run
-        while (rs > beg && cols[rs - 1] == c) --rs;
-        pos = (e - rs) % kMaxRun;
-        const int32_t ps = e - pos;                       // first entry of the piece
-        int len = pos + 1;
-        while (len < kMaxRun && ps + len < end && cols[ps + len] == c) ++len;
-        return len;
-    };
-
-    for (int32_t e = beg + tid; e < end; e += 256) {
-        int pos;
-        const int L = natural_piece(e, pos);
-        if (pos == 0) atomicAdd(&cnt[L - 1], 1);          // a count: the order of the adds is irrelevant
-    }
-    __syncthreads();
-    if (tid == 0) {
-        for (int L = 2; L <= kMaxRun; ++L)
-            if (cnt[L - 1] > 0 && cnt[L - 1] * L < kMinClassEntries) {
-                demote[L - 1] = 1;
-                cnt[0] += cnt[L - 1] * L;
-                cnt[L - 1] = 0;
-            }
-        int32_t at = 0;
-        for (int L = 1; L <= kMaxRun; ++L) {
-            const int J = runs_per_chunk(L);
-            const int32_t chunks = (cnt[L - 1] + 2 * J - 1) / (2 * J) * 2;      // even
-            seg[L - 1] = at;
-            hdr[q * kMaxRun + (L - 1)] = SchedClass{at, chunks};
-            at += chunks * chunk_dwords(L);
+    // window w = entries [wstart[w], wstart[w+1]): first entry whose column is >= w*window_cols
+    if (tid <= nw) {
+        const int64_t lim = (int64_t)tid * window_cols;
+        int32_t lo = beg, hi = end;
+        while (lo < hi) {
+            const int32_t mid = lo + (hi - lo) / 2;
+            if ((int64_t)cols[mid] < lim) lo = mid + 1; else hi = mid;
         }
+        wstart[tid] = (tid == nw) ? end : lo;
     }
+    if (tid == 0) at_s = 0;
     __syncthreads();
 
     const uint64_t lt = (1ull << lane) - 1ull;
-    for (int32_t t0 = beg; t0 < end; t0 += 256) {
-        const int32_t e = t0 + tid;
-        int L = 0;                                        // class of the piece that starts at e (0: none)
-        if (e < end) {
-            int pos;
-            const int nat = natural_piece(e, pos);
-            if (demote[nat - 1]) L = 1;
-            else if (pos == 0) L = nat;
-        }
+    for (int32_t w = 0; w < nw; ++w) {
+        const int32_t wb = wstart[w], we = wstart[w + 1];
+        if (tid < kMaxRun) { cnt[tid] = 0; base[tid] = 0; demote[tid] = 0; }
         __syncthreads();
-        int32_t before = 0;
-#pragma unroll
-        for (int c = 1; c <= kMaxRun; ++c) {
-            const uint64_t mk = __ballot(L == c);
-            if (L == c) before = __popcll(mk & lt);
-            if (lane == 0) wcnt[wv][c - 1] = __popcll(mk);
-        }
-        __syncthreads();
-        if (L) {
-            int32_t rank = base[L - 1] + before;
-            for (int w = 0; w < wv; ++w) rank += wcnt[w][L - 1];
-            const int J = runs_per_chunk(L);
-            uint32_t* ck = out + seg[L - 1] + (rank / J) * chunk_dwords(L);
-            const int j = rank % J;
-            ck[j] = (uint32_t)cols[e];
-            for (int i = 0; i < L; ++i) {
-                ck[J + j * L + i] = (uint32_t)(rows[e + i] - row0);
-                ck[J + J * L + j * L + i] = __float_as_uint(values[e + i]);
-            }
-        }
-        __syncthreads();
-        if (tid < kMaxRun) base[tid] += wcnt[0][tid] + wcnt[1][tid] + wcnt[2][tid] + wcnt[3][tid];
-    }
-    __syncthreads();
 
-    // dummy pieces that fill the class up to its (even) number of chunks
-    if (tid < kMaxRun && cnt[tid] > 0) {
-        const int L = tid + 1, J = runs_per_chunk(L);
-        const int32_t padded = (cnt[tid] + 2 * J - 1) / (2 * J) * 2 * J;
-        const uint32_t any_col = (uint32_t)cols[beg];
-        for (int32_t r = cnt[tid]; r < padded; ++r) {
-            uint32_t* ck = out + seg[tid] + (r / J) * chunk_dwords(L);
-            const int j = r % J;
-            ck[j] = any_col;
-            for (int i = 0; i < L; ++i) {
-                ck[J + j * L + i] = (uint32_t)p;          // the row nobody stores
-                ck[J + J * L + j * L + i] = 0u;
+        // Length of the natural piece (run cut every kMaxRun entries) that entry e belongs to,
+        // and e's place in it.  A run has one column, so it lies inside one window.
+        auto natural_piece = [&](int32_t e, int& pos) -> int {
+            const int32_t c = cols[e];
+            int32_t rs = e;                               // first entry of the run
+            while (rs > wb && cols[rs - 1] == c) --rs;
+            pos = (e - rs) % kMaxRun;
+            const int32_t ps = e - pos;                   // first entry of the piece
+            int len = pos + 1;
+            while (len < kMaxRun && ps + len < we && cols[ps + len] == c) ++len;
+            return len;
+        };
+
+        for (int32_t e = wb + tid; e < we; e += 256) {
+            int pos;
+            const int L = natural_piece(e, pos);
+            if (pos == 0) atomicAdd(&cnt[L - 1], 1);      // a count: the order of the adds is irrelevant
+        }
+        __syncthreads();
+        if (tid == 0) {
+            for (int L = 2; L <= kMaxRun; ++L)
+                if (cnt[L - 1] > 0 && cnt[L - 1] * L < kMinClassEntries) {
+                    demote[L - 1] = 1;
+                    cnt[0] += cnt[L - 1] * L;
+                    cnt[L - 1] = 0;
+                }
+            int32_t at = at_s;
+            for (int L = 1; L <= kMaxRun; ++L) {
+                const int J = runs_per_chunk(L);
+                const int32_t chunks = (cnt[L - 1] + 2 * J - 1) / (2 * J) * 2;      // even
+                seg[L - 1] = at;
+                h[w * kMaxRun + (L - 1)] = SchedClass{at, chunks};
+                at += chunks * chunk_dwords(L);
+            }
+            at_s = at;
+        }
+        __syncthreads();
+
+        for (int32_t t0 = wb; t0 < we; t0 += 256) {
+            const int32_t e = t0 + tid;
+            int L = 0;                                    // class of the piece that starts at e (0: none)
+            if (e < we) {
+                int pos;
+                const int nat = natural_piece(e, pos);
+                if (demote[nat - 1]) L = 1;
+                else if (pos == 0) L = nat;
+            }
+            int32_t before = 0;
+#pragma unroll
+            for (int c = 1; c <= kMaxRun; ++c) {
+                const uint64_t mk = __ballot(L == c);
+                if (L == c) before = __popcll(mk & lt);
+                if (lane == 0) wcnt[wv][c - 1] = __popcll(mk);
+            }
+            __syncthreads();
+            if (L) {
+                int32_t rank = base[L - 1] + before;
+                for (int x = 0; x < wv; ++x) rank += wcnt[x][L - 1];
+                const int J = runs_per_chunk(L);
+                uint32_t* ck = out + seg[L - 1] + (rank / J) * chunk_dwords(L);
+                const int j = rank % J;
+                ck[j] = (uint32_t)cols[e];
+                for (int i = 0; i < L; ++i) {
+                    ck[J + j * L + i] = (uint32_t)(rows[e + i] - row0);
+                    ck[J + J * L + j * L + i] = __float_as_uint(values[e + i]);
+                }
+            }
+            __syncthreads();
+            if (tid < kMaxRun) base[tid] += wcnt[0][tid] + wcnt[1][tid] + wcnt[2][tid] + wcnt[3][tid];
+            __syncthreads();
+        }
+
+        // dummy pieces that fill the class up to its (even) number of chunks
+        if (tid < kMaxRun && cnt[tid] > 0) {
+            const int L = tid + 1, J = runs_per_chunk(L);
+            const int32_t padded = (cnt[tid] + 2 * J - 1) / (2 * J) * 2 * J;
+            const uint32_t any_col = (uint32_t)cols[wb];
+            for (int32_t r = cnt[tid]; r < padded; ++r) {
+                uint32_t* ck = out + seg[tid] + (r / J) * chunk_dwords(L);
+                const int j = r % J;
+                ck[j] = any_col;
+                for (int i = 0; i < L; ++i) {
+                    ck[J + j * L + i] = (uint32_t)p;      // the row nobody stores
+                    ck[J + J * L + j * L + i] = 0u;
+                }
             }
         }
+        __syncthreads();
     }
 }
 

@@ -228,7 +228,7 @@ __device__ __forceinline__ void run_class(AccFile& acc, const uint32_t* __restri
 template <int V>
 __global__ __launch_bounds__(64) void spdm_sched(const SchedClass* __restrict__ hdr, const uint32_t* __restrict__ stream,
                                                  const int32_t* __restrict__ gIdxes, int64_t m, int32_t p, int64_t g,
-                                                 const float* __restrict__ B, int64_t ldb, int64_t N, float* __restrict__ C,
+                                                 int32_t nw, const float* __restrict__ B, int64_t ldb, int64_t N, float* __restrict__ C,
                                                  int64_t ldc, int64_t total)
 {
     // XCD-aware order: workgroup ids go round-robin over the 8 XCDs, so XCD x is given the
@@ -253,16 +253,19 @@ __global__ __launch_bounds__(64) void spdm_sched(const SchedClass* __restrict__ 
     AccFile acc;
     acc.t0 = 0.0f; acc.t1 = 0.0f; acc.t2 = 0.0f; acc.t3 = 0.0f; acc.t4 = 0.0f;
 
-    const uint32_t* __restrict__ gs = stream + sched_group_base(gIdxes[q], q);
-    const SchedClass* __restrict__ h = hdr + q * kMaxRun;
-    run_class<1, V>(acc, gs + h[0].first_word, h[0].chunks, Bbytes, ldb4, lane_off);
-    run_class<2, V>(acc, gs + h[1].first_word, h[1].chunks, Bbytes, ldb4, lane_off);
-    run_class<3, V>(acc, gs + h[2].first_word, h[2].chunks, Bbytes, ldb4, lane_off);
-    run_class<4, V>(acc, gs + h[3].first_word, h[3].chunks, Bbytes, ldb4, lane_off);
-    run_class<5, V>(acc, gs + h[4].first_word, h[4].chunks, Bbytes, ldb4, lane_off);
-    run_class<6, V>(acc, gs + h[5].first_word, h[5].chunks, Bbytes, ldb4, lane_off);
-    run_class<7, V>(acc, gs + h[6].first_word, h[6].chunks, Bbytes, ldb4, lane_off);
-    run_class<8, V>(acc, gs + h[7].first_word, h[7].chunks, Bbytes, ldb4, lane_off);
+    // window by window (a band of B that stays in L2), class by class
+    const uint32_t* __restrict__ gs = stream + sched_group_base(gIdxes[q], q, nw);
+    const SchedClass* __restrict__ h = hdr + q * nw * kMaxRun;
+    for (int32_t w8 = 0; w8 < nw * kMaxRun; w8 += kMaxRun) {
+        run_class<1, V>(acc, gs + h[w8 + 0].first_word, h[w8 + 0].chunks, Bbytes, ldb4, lane_off);
+        run_class<2, V>(acc, gs + h[w8 + 1].first_word, h[w8 + 1].chunks, Bbytes, ldb4, lane_off);
+        run_class<3, V>(acc, gs + h[w8 + 2].first_word, h[w8 + 2].chunks, Bbytes, ldb4, lane_off);
+        run_class<4, V>(acc, gs + h[w8 + 3].first_word, h[w8 + 3].chunks, Bbytes, ldb4, lane_off);
+        run_class<5, V>(acc, gs + h[w8 + 4].first_word, h[w8 + 4].chunks, Bbytes, ldb4, lane_off);
+        run_class<6, V>(acc, gs + h[w8 + 5].first_word, h[w8 + 5].chunks, Bbytes, ldb4, lane_off);
+        run_class<7, V>(acc, gs + h[w8 + 6].first_word, h[w8 + 6].chunks, Bbytes, ldb4, lane_off);
+        run_class<8, V>(acc, gs + h[w8 + 7].first_word, h[w8 + 7].chunks, Bbytes, ldb4, lane_off);
+    }
 
     // epilogue: each lane stores its V adjacent columns of every row of the group (coalesced
     // along N); rows beyond m (last group), the sink row p and lanes beyond N are skipped.
@@ -298,7 +301,7 @@ hipError_t launch_spdm_sched_instance(const SpdmArgs& a, hipStream_t s)
     if (grid <= 0 || grid > 0x7fffffffLL) return hipErrorInvalidConfiguration;
     if (a.ldb > 0x3fffffffLL) return hipErrorInvalidValue;   // row pitch in bytes is kept in 32 bits
     if (a.p + 1 > acc_stride<V>()) return hipErrorInvalidValue;
-    spdm_sched<V><<<dim3((unsigned)grid), dim3(64), 0, s>>>(a.hdr, a.stream, a.gIdxes, a.m, a.p, a.g, a.B, a.ldb, a.N, a.C,
+    spdm_sched<V><<<dim3((unsigned)grid), dim3(64), 0, s>>>(a.hdr, a.stream, a.gIdxes, a.m, a.p, a.g, a.nw, a.B, a.ldb, a.N, a.C,
                                                             a.ldc, total);
     return hipGetLastError();
 }

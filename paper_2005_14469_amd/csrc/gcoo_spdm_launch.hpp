@@ -9,12 +9,13 @@ namespace gcoo {
 struct SchedClass;
 
 struct SpdmArgs {
-    const SchedClass* hdr;     // [g][kMaxRun]
+    const SchedClass* hdr;     // [g][nw][kMaxRun]
     const uint32_t* stream;    // run schedule
     const int32_t* gIdxes;     // [g+1]
     int64_t m;
     int32_t p;
     int64_t g;
+    int32_t nw;                // column windows of the schedule
     const float* B;
     int64_t ldb;
     int64_t N;
