@@ -58,7 +58,7 @@ typedef struct gcoo_matrix gcoo_matrix;
  * Device bytes a gcoo_from_csr() / gcoo_from_dense() call needs in dev_buf for an m x k matrix
  * with nnz stored entries and group height p: the five arrays of Section 3.1 (Table 1:
  * 3*nnz + 2*g elements, plus one sentinel), the run schedule derived from them for the register
- * kernel (at most 4*nnz + 1536*g words) and the scratch space the conversion kernels use.
+ * kernel (at most 3*nnz + 2048*g + 128 words) and the scratch space the conversion kernels use.
  * Returns 0 for invalid arguments.  Pure host arithmetic.
  */
 size_t gcoo_device_bytes(int64_t m, int64_t k, int64_t nnz, int32_t p);

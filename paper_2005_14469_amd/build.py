@@ -37,10 +37,39 @@ def stale() -> bool:
     return any(os.path.getmtime(f) > t for f in _deps())
 
 
+def _checked(src: str) -> bool:
+    """Sources whose generated code is verified by isa_check (kernels that issue loads from asm)."""
+    return os.path.basename(src).startswith("spdm_sched_v")
+
+
 def _compile(src: str) -> str:
     obj = os.path.join(OBJ, os.path.basename(src)[:-4] + ".o")
-    subprocess.check_call(["hipcc", *FLAGS, "-I", os.path.join(ROOT, "include"), "-I", CSRC, "-c", src, "-o", obj])
+    extra = ["-save-temps=obj"] if _checked(src) else []      # keeps the device assembly next to the object
+    subprocess.check_call(["hipcc", *FLAGS, *extra, "-I", os.path.join(ROOT, "include"), "-I", CSRC, "-c", src, "-o", obj])
     return obj
+
+
+def verify_generated_code() -> None:
+    """Refuse to link a library whose asm-issued loads are not provably safe.
+
+    The register SpDM kernel keeps loads in flight behind the compiler's back; isa_check proves
+    on the assembly that no instruction touches a register before a wait has covered its load.
+    A compiler change (or a careless edit) that breaks this would read stale registers or, worse,
+    use them as addresses, so the check is part of the build, not only of the tests.
+    """
+    from . import isa_check
+    for src in sources():
+        if not _checked(src):
+            continue
+        stem = os.path.basename(src)[:-4]
+        asm = os.path.join(OBJ, f"{stem}-hip-amdgcn-amd-amdhsa-gfx950.s")
+        text = open(asm).read()
+        v = stem.rsplit("v", 1)[1]
+        regs, bad = isa_check.check(text, f"_ZN4gcoo10spdm_schedILi{v}E")
+        if not regs:
+            raise RuntimeError(f"{stem}: no asm-issued loads found in the generated code (check is blind)")
+        if bad:
+            raise RuntimeError(f"{stem}: {len(bad)} instructions touch registers with a load in flight, e.g. {bad[:3]}")
 
 
 def build(force: bool = True, jobs: int = 8) -> str:
@@ -48,6 +77,7 @@ def build(force: bool = True, jobs: int = 8) -> str:
         os.makedirs(OBJ, exist_ok=True)
         with ThreadPoolExecutor(max_workers=jobs) as ex:
             objs = list(ex.map(_compile, sources()))
+        verify_generated_code()
         tmp = LIB + f".tmp{os.getpid()}"
         subprocess.check_call(["hipcc", "--offload-arch=gfx950", "-shared", "-fPIC", "-o", tmp, *objs])
         os.replace(tmp, LIB)

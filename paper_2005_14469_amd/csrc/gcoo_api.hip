@@ -151,7 +151,7 @@ int new_handle(int64_t m, int64_t k, int64_t nnz, int32_t p, void* dev_buf, gcoo
 // Builds the run schedule of the register kernel from the finished GCOO arrays.
 int launch_build_schedule(const gcoo_matrix* h, hipStream_t s)
 {
-    if (h->g > 0) {
+    if (h->g > 0 && h->p <= gcoo::kSchedMaxP) {              // no register kernel above that height
         gcoo::build_schedule<<<dim3((unsigned)h->g), dim3(256), 0, s>>>(h->gIdxes(), h->rows(), h->cols(), h->values(), h->p,
                                                                         h->g, h->nw, h->window_cols, h->sched_hdr(), h->sched());
         HIP_TRY(hipGetLastError());

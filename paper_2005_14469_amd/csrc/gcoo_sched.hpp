@@ -1,32 +1,43 @@
 // The run schedule: a kernel-private re-listing of a GCOO matrix that makes the reuse loop of
 // Algorithm 2 ("while the next entry has the same col, reuse the fetched B value") free of
-// run-time branches.
+// run-time branches, and that the SpDM kernel can stream through LDS (the staging of a group's
+// entries in shared memory of Algorithm 2).
 //
-// Inside a group, a run is a maximal stretch of entries with one column (they share one fetched
-// segment of B).  Runs longer than kMaxRun are cut into pieces of kMaxRun.  The columns are cut
-// into `nw` windows of `window_cols` columns; the pieces of one (group, window) are re-listed by
-// length class L = 1..kMaxRun, in column order inside a class, packed into chunks of
-// runs_per_chunk(L) pieces.  A chunk is chunk_dwords(L) 32-bit words:
-//     col[J] | row[J*L] | value bits[J*L]        (J = runs_per_chunk(L); piece j owns entries j*L .. j*L+L-1)
-// where row is the row inside the group.  The windows keep the waves that work on one column
-// tile of B inside a band of B that fits the L2 of their XCD, whatever class they are in.
+// Runs and classes.  Inside a group, a run is a maximal stretch of entries with one column (they
+// share one fetched segment of B).  Runs longer than kMaxRun are cut into pieces of kMaxRun.  The
+// columns are cut into `nw` windows of `window_cols` columns; the pieces of one (group, window)
+// are re-listed by length class L = 1..kMaxRun, in column order inside a class.  The windows keep
+// the waves that work on one column tile of B inside a band of B that fits the L2 of their XCD,
+// whatever class they are in.
 //
-// A class is filled up with dummy pieces to a whole, even number of chunks (the kernel's loop
-// takes them two at a time): a valid column and entries whose row is p, one past the rows of the
-// group; the SpDM kernel keeps a partial sum for that row too and never stores it, so a dummy
-// entry has no effect on C whatever B holds.
+// Chunks and bodies.  J = runs_per_chunk(L) pieces make a chunk; kBody = 4 chunks make a body,
+// the unit of the kernel's loop (one turn multiplies four chunks while the B loads of the next
+// three chunks are in flight).  A class segment is
+//     pre-block | block 0 | block 1 | ... | block nb-1
+// Block b (block_dwords(L) 32-bit words) holds what turn b needs:
+//     col[4*J]         columns of chunks 4b+3 .. 4b+6 (the loads that turn b starts)
+//     rowpack[4][RP]   rows inside the group, one byte each, of chunks 4b .. 4b+3 (RP = ceil(J*L/4) words per chunk)
+//     val[4][VS]       value bits of chunks 4b .. 4b+3 (VS = J*L rounded up to a multiple of 4 words)
+// and the pre-block (4*J words) holds {unused, columns of chunks 0, 1, 2}.  Piece j of a chunk
+// owns entries j*L .. j*L+L-1 of the chunk.  Column slots of chunks that do not exist hold a
+// valid column (the load happens and is ignored).
+//
+// Dummy pieces fill a class up to whole bodies: a valid column and entries whose row is p, one
+// past the rows of the group; the SpDM kernel keeps a partial sum for that row too and never
+// stores it, so a dummy entry has no effect on C whatever B holds.
 //
 // A class with little work in a (group, window) is not worth a loop of its own (starting and
 // draining the load pipeline costs a few memory latencies): when the pieces of class L > 1 hold
 // fewer than kMinClassEntries entries, they are listed as L pieces of class 1 instead (the same
 // column fetched L times in a row, which the vector cache absorbs).
 //
-// Group q owns the words [4*gIdxes[q] + kSchedPad*nw*q, ...) of the stream.  Real pieces take at
-// most 3 words per entry (column of the piece, row, value).  Dummy pieces: class 1 adds at most
-// 45 words per window; a class L > 1 exists only with kMinClassEntries entries or more and adds at
-// most 49 words, less than one word per five entries.  So 4 words per entry plus kSchedPad words
-// per window bound a group, and no prefix sum over groups is needed.
-// hdr[(q*nw + w)*kMaxRun + L-1] = {first word of the class relative to the group's base, number of chunks}.
+// Space.  Group q owns the words [3*gIdxes[q] + kSchedPad*nw*q, ...) of the stream.  A real entry
+// costs at most block_dwords(1)/16 = 2.25 words.  Dummy pieces and the pre-block add at most one
+// block plus one pre-block per class: 52 words for class 1; a class L > 1 exists only with
+// kMinClassEntries entries or more and adds at most 92 words, under 0.4 words per entry.  So
+// 3 words per entry plus kSchedPad words per (group, window) bound a group, and no prefix sum over
+// groups is needed.  The kernel reads whole 512-byte lines, so the stream ends with that much slack.
+// hdr[(q*nw + w)*kMaxRun + L-1] = {first word of the class segment relative to the group's base, nb}.
 #pragma once
 #include <hip/hip_runtime.h>
 #include <stdint.h>
@@ -34,27 +45,41 @@
 namespace gcoo {
 
 constexpr int kMaxRun = 8;
-
-__host__ __device__ constexpr int runs_per_chunk(int L) { return L == 1 ? 8 : (L <= 3 ? 4 : (L <= 6 ? 2 : 1)); }
-__host__ __device__ constexpr int chunk_dwords(int L) { return runs_per_chunk(L) * (1 + 2 * L); }
-
+constexpr int kBody = 4;                 // chunks per loop turn of the SpDM kernel
 constexpr int kMinClassEntries = 256;
-
-constexpr int kSchedPad = 48;            // words per (group, window) for the dummy pieces of class 1
+constexpr int kSchedPad = 64;            // words per (group, window) for class 1's dummy pieces and pre-block
+constexpr int kSchedSlack = 128;         // words after the last group (whole-line reads)
 constexpr int kMaxWindows = 32;
+constexpr int kSchedMaxP = 128;          // rows are stored as bytes and row p must fit too
+
+__host__ __device__ constexpr int runs_per_chunk(int L) { return L <= 3 ? 4 : (L <= 6 ? 2 : 1); }
+__host__ __device__ constexpr int rowpack_dwords(int L) { return (runs_per_chunk(L) * L + 3) / 4; }
+__host__ __device__ constexpr int pre_dwords(int L) { return kBody * runs_per_chunk(L); }
+// words of one chunk's values inside a block: J*L rounded up to whole 16-byte LDS reads
+__host__ __device__ constexpr int val_stride(int L) { return (runs_per_chunk(L) * L + 3) / 4 * 4; }
+__host__ __device__ constexpr int block_dwords(int L)
+{
+    return kBody * runs_per_chunk(L) + kBody * rowpack_dwords(L) + kBody * val_stride(L);
+}
+// word offsets inside a block
+__host__ __device__ constexpr int blk_rowpack(int L, int c) { return kBody * runs_per_chunk(L) + c * rowpack_dwords(L); }
+__host__ __device__ constexpr int blk_val(int L, int c)
+{
+    return kBody * runs_per_chunk(L) + kBody * rowpack_dwords(L) + c * val_stride(L);
+}
 
 __host__ __device__ inline int64_t sched_group_base(int64_t first_entry, int64_t q, int32_t nw)
 {
-    return 4 * first_entry + (int64_t)kSchedPad * nw * q;
+    return 3 * first_entry + (int64_t)kSchedPad * nw * q;
 }
 __host__ __device__ inline int64_t sched_words(int64_t nnz, int64_t g, int32_t nw)
 {
-    return 4 * nnz + (int64_t)kSchedPad * nw * g;
+    return 3 * nnz + (int64_t)kSchedPad * nw * g + kSchedSlack;
 }
 
 struct SchedClass {
-    int32_t first_word;   // relative to the group's base
-    int32_t chunks;
+    int32_t first_word;   // of the pre-block, relative to the group's base
+    int32_t bodies;       // nb
 };
 
 }  // namespace gcoo

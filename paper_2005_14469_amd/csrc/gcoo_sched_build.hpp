@@ -7,6 +7,33 @@
 
 namespace gcoo {
 
+// Where the pieces of class L land.  `x` = chunk index inside the class, `j` = piece inside the chunk.
+__device__ __forceinline__ int32_t sched_col_word(int L, int32_t x, int j)
+{
+    const int J = runs_per_chunk(L);
+    if (x < 3) return (x + 1) * J + j;                                        // pre-block
+    const int32_t b = (x - 3) / kBody, sl = (x - 3) % kBody;
+    return pre_dwords(L) + b * block_dwords(L) + sl * J + j;
+}
+__device__ __forceinline__ int32_t sched_block_word(int L, int32_t x) { return pre_dwords(L) + (x / kBody) * block_dwords(L); }
+
+// Writes piece (x, j) of class L: its column and its L (row, value) pairs, read from entry e on.
+// rows == nullptr writes a dummy piece (row p, value 0).
+__device__ __forceinline__ void sched_put_piece(uint32_t* __restrict__ seg, int L, int32_t x, int j, uint32_t col,
+                                                const int32_t* rows, const float* values, int32_t e, int32_t row0, int32_t p)
+{
+    const int J = runs_per_chunk(L), c = x % kBody;
+    seg[sched_col_word(L, x, j)] = col;
+    uint32_t* blk = seg + sched_block_word(L, x);
+    uint8_t* rp = reinterpret_cast<uint8_t*>(blk + blk_rowpack(L, c));
+    uint32_t* vp = blk + blk_val(L, c);
+    for (int i = 0; i < L; ++i) {
+        rp[j * L + i] = (uint8_t)(rows ? rows[e + i] - row0 : p);
+        vp[j * L + i] = rows ? __float_as_uint(values[e + i]) : 0u;
+    }
+    (void)J;
+}
+
 // One workgroup (256 threads) per group.  Per window: pass 1 counts the pieces of each class,
 // pass 2 gives every piece its rank inside its class (entries are visited in order; ranks come
 // from ballots and running counts, so the listing is the same on every run) and writes it out.
@@ -18,7 +45,7 @@ __global__ __launch_bounds__(256) void build_schedule(const int32_t* __restrict_
     __shared__ int32_t wstart[kMaxWindows + 1];   // first entry of each window
     __shared__ int32_t cnt[kMaxRun];              // pieces per class in the current window
     __shared__ int32_t demote[kMaxRun];           // class listed as pieces of class 1
-    __shared__ int32_t seg[kMaxRun];              // first word of the class
+    __shared__ int32_t seg[kMaxRun];              // first word of the class segment
     __shared__ int32_t base[kMaxRun];             // pieces of the class already placed
     __shared__ int32_t wcnt[4][kMaxRun];          // per wave, per class, in the current tile
     __shared__ int32_t at_s;                      // words used so far by this group
@@ -77,11 +104,11 @@ __global__ __launch_bounds__(256) void build_schedule(const int32_t* __restrict_
                 }
             int32_t at = at_s;
             for (int L = 1; L <= kMaxRun; ++L) {
-                const int J = runs_per_chunk(L);
-                const int32_t chunks = (cnt[L - 1] + 2 * J - 1) / (2 * J) * 2;      // even
+                const int per_body = kBody * runs_per_chunk(L);
+                const int32_t bodies = (cnt[L - 1] + per_body - 1) / per_body;
                 seg[L - 1] = at;
-                h[w * kMaxRun + (L - 1)] = SchedClass{at, chunks};
-                at += chunks * chunk_dwords(L);
+                h[w * kMaxRun + (L - 1)] = SchedClass{at, bodies};
+                if (bodies > 0) at += pre_dwords(L) + bodies * block_dwords(L);
             }
             at_s = at;
         }
@@ -108,32 +135,25 @@ __global__ __launch_bounds__(256) void build_schedule(const int32_t* __restrict_
                 int32_t rank = base[L - 1] + before;
                 for (int x = 0; x < wv; ++x) rank += wcnt[x][L - 1];
                 const int J = runs_per_chunk(L);
-                uint32_t* ck = out + seg[L - 1] + (rank / J) * chunk_dwords(L);
-                const int j = rank % J;
-                ck[j] = (uint32_t)cols[e];
-                for (int i = 0; i < L; ++i) {
-                    ck[J + j * L + i] = (uint32_t)(rows[e + i] - row0);
-                    ck[J + J * L + j * L + i] = __float_as_uint(values[e + i]);
-                }
+                sched_put_piece(out + seg[L - 1], L, rank / J, rank % J, (uint32_t)cols[e], rows, values, e, row0, p);
             }
             __syncthreads();
             if (tid < kMaxRun) base[tid] += wcnt[0][tid] + wcnt[1][tid] + wcnt[2][tid] + wcnt[3][tid];
             __syncthreads();
         }
 
-        // dummy pieces that fill the class up to its (even) number of chunks
+        // dummy pieces up to whole bodies, and a valid column in every column slot that belongs
+        // to no chunk (slot 0 of the pre-block, the three chunks after the last one)
         if (tid < kMaxRun && cnt[tid] > 0) {
-            const int L = tid + 1, J = runs_per_chunk(L);
-            const int32_t padded = (cnt[tid] + 2 * J - 1) / (2 * J) * 2 * J;
+            const int L = tid + 1, J = runs_per_chunk(L), per_body = kBody * J;
+            const int32_t padded = (cnt[tid] + per_body - 1) / per_body * per_body;
             const uint32_t any_col = (uint32_t)cols[wb];
-            for (int32_t r = cnt[tid]; r < padded; ++r) {
-                uint32_t* ck = out + seg[tid] + (r / J) * chunk_dwords(L);
-                const int j = r % J;
-                ck[j] = any_col;
-                for (int i = 0; i < L; ++i) {
-                    ck[J + j * L + i] = (uint32_t)p;      // the row nobody stores
-                    ck[J + J * L + j * L + i] = 0u;
-                }
+            uint32_t* sg = out + seg[tid];
+            for (int32_t r = cnt[tid]; r < padded; ++r) sched_put_piece(sg, L, r / J, r % J, any_col, nullptr, nullptr, 0, row0, p);
+            const int32_t nch = padded / J;
+            for (int j = 0; j < J; ++j) {
+                sg[j] = any_col;
+                for (int32_t x = nch; x < nch + 3; ++x) sg[sched_col_word(L, x, j)] = any_col;
             }
         }
         __syncthreads();

@@ -2,10 +2,11 @@
 //
 // Work unit = (group q, column tile): one wave64 computes a  p x (64*V)  tile of C.  Every lane
 // owns V adjacent columns and keeps (p+1) x V partial sums.  The entries of the group are
-// wave-uniform data: they come through scalar loads into SGPRs (the role shared memory plus
-// broadcast plays in Algorithm 2), the B row segment of a run of entries is one coalesced
-// vector load per lane, and all entries of the run multiply out of those registers
-// (Section 3.3, "high computation-to-memory ratio").  The entries are read from the run
+// wave-uniform data: the wave streams them from global memory into LDS with coalesced loads, far
+// ahead of their use, and reads them back with broadcast reads (the staging in shared memory of
+// Algorithm 2); the B row segment of a run of entries is one coalesced vector load per lane, and
+// all entries of the run multiply out of those registers (Section 3.3, "high
+// computation-to-memory ratio").  The entries are read from the run
 // schedule (gcoo_sched.hpp), in which runs are sorted by length, so the code for a run of L
 // entries is straight-line: no "is the next column the same" test at run time.
 #pragma once
@@ -57,7 +58,7 @@ __device__ __forceinline__ float acc_get(const AccFile& acc, int reg)
 }
 
 // Instruction text.  GCOO_FMA_Vn(i): the V multiply-adds of entry i of a run (operands a<i> =
-// value in an SGPR, b0..b3 = the run's B segment).  GCOO_ENT(i) = select row c<i>, then those.
+// the entry's value, the same in every lane of a VGPR; b0..b3 = the run's B segment).  GCOO_ENT(i) = select row c<i>, then those.
 #define GCOO_FMA_V1(i) "v_fma_f32 v124, %[a" #i "], %[b0], v124\n\t"
 #define GCOO_FMA_V2(i) GCOO_FMA_V1(i) "v_fma_f32 v189, %[a" #i "], %[b1], v189\n\t"
 #define GCOO_FMA_V4(i)                                  \
@@ -80,14 +81,14 @@ __device__ __forceinline__ float acc_get(const AccFile& acc, int reg)
 #define GCOO_B_V1(b) [b0] "v"((b)[0])
 #define GCOO_B_V2(b) GCOO_B_V1(b), [b1] "v"((b)[1])
 #define GCOO_B_V4(b) GCOO_B_V2(b), [b2] "v"((b)[2]), [b3] "v"((b)[3])
-#define GCOO_E1(c, a) [c0] "s"((c)[0]), [a0] "s"((a)[0])
-#define GCOO_E2(c, a) GCOO_E1(c, a), [c1] "s"((c)[1]), [a1] "s"((a)[1])
-#define GCOO_E3(c, a) GCOO_E2(c, a), [c2] "s"((c)[2]), [a2] "s"((a)[2])
-#define GCOO_E4(c, a) GCOO_E3(c, a), [c3] "s"((c)[3]), [a3] "s"((a)[3])
-#define GCOO_E5(c, a) GCOO_E4(c, a), [c4] "s"((c)[4]), [a4] "s"((a)[4])
-#define GCOO_E6(c, a) GCOO_E5(c, a), [c5] "s"((c)[5]), [a5] "s"((a)[5])
-#define GCOO_E7(c, a) GCOO_E6(c, a), [c6] "s"((c)[6]), [a6] "s"((a)[6])
-#define GCOO_E8(c, a) GCOO_E7(c, a), [c7] "s"((c)[7]), [a7] "s"((a)[7])
+#define GCOO_E1(c, a) [c0] "s"((c)[0]), [a0] "v"((a)[0])
+#define GCOO_E2(c, a) GCOO_E1(c, a), [c1] "s"((c)[1]), [a1] "v"((a)[1])
+#define GCOO_E3(c, a) GCOO_E2(c, a), [c2] "s"((c)[2]), [a2] "v"((a)[2])
+#define GCOO_E4(c, a) GCOO_E3(c, a), [c3] "s"((c)[3]), [a3] "v"((a)[3])
+#define GCOO_E5(c, a) GCOO_E4(c, a), [c4] "s"((c)[4]), [a4] "v"((a)[4])
+#define GCOO_E6(c, a) GCOO_E5(c, a), [c5] "s"((c)[5]), [a5] "v"((a)[5])
+#define GCOO_E7(c, a) GCOO_E6(c, a), [c6] "s"((c)[6]), [a6] "v"((a)[6])
+#define GCOO_E8(c, a) GCOO_E7(c, a), [c7] "s"((c)[7]), [a7] "v"((a)[7])
 
 #define GCOO_RUN_ASM(L, VN) \
     asm volatile(GCOO_RUN##L(GCOO_FMA_V##VN) GCOO_OFF : GCOO_ACC_OPERANDS(acc) : GCOO_E##L(c, a), GCOO_B_V##VN(b))
@@ -114,7 +115,7 @@ __device__ __forceinline__ void run_fma(AccFile& acc, const uint32_t* c, const f
 // A lane's V adjacent values of a row of B, issued from an asm statement: the compiler does not
 // know that the result is still in flight, so it puts no s_waitcnt in front of the uses and the
 // pipelined loop places its own.  The destination may be read only by asm statements that come
-// after such a wait (tests/test_isa.py checks the generated code for that).
+// after such a wait (the build verifies the generated code for that: isa_check.py).
 // Address = 64-bit scalar row base + 32-bit per-lane byte offset.
 template <int V>
 __device__ __forceinline__ void load_b_async(const char* row_base, uint32_t lane_off, float (&b)[V])
@@ -140,89 +141,124 @@ __device__ __forceinline__ void wait_vm()
     asm volatile("s_waitcnt vmcnt(%0)" ::"n"(N));
 }
 
-// The scalar part of one chunk of the schedule: the J columns, and the J*L (row, value) pairs.
-template <int J>
-struct SCols {
-    uint32_t col[J];
-};
-template <int L, int J>
-struct SEntries {
-    uint32_t row[J * L];
-    float val[J * L];
-};
+typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
 
-template <int L, int J>
-__device__ __forceinline__ void load_cols(SCols<J>& c, const uint32_t* __restrict__ chunk)
+// One 512-byte line of the schedule stream, 8 bytes per lane, issued from asm like the B loads.
+__device__ __forceinline__ u32x2 load_line_async(const uint32_t* line, uint32_t lane8)
 {
-#pragma unroll
-    for (int j = 0; j < J; ++j) c.col[j] = chunk[j];
-}
-template <int L, int J>
-__device__ __forceinline__ void load_entries(SEntries<L, J>& c, const uint32_t* __restrict__ chunk)
-{
-#pragma unroll
-    for (int i = 0; i < J * L; ++i) c.row[i] = chunk[J + i];
-#pragma unroll
-    for (int i = 0; i < J * L; ++i) c.val[i] = __uint_as_float(chunk[J + J * L + i]);
+    u32x2 t;
+    asm volatile("global_load_dwordx2 %0, %1, %2" : "=v"(t) : "v"(lane8), "s"(line));
+    return t;
 }
 
-// All chunks of one length class of one group; nch is even (the schedule pads it).
-//
-// Pipeline, per step n:
-//   issue the J loads of chunk n+1 | scalar-load the columns of chunk n+2 and the entries of
-//   chunk n+1 | wait until only those J loads are in flight | multiply-add chunk n.
-// All buffers are double: the body is two steps, so every buffer index is a compile-time
-// constant.  Asm-issued loads are in flight only inside straight-line code: the loop is entered
-// and left with vmcnt(0), because at those joins the compiler may move registers around.
-template <int L, int V>
-__device__ __forceinline__ void run_class(AccFile& acc, const uint32_t* __restrict__ s, int32_t nch, const char* Bbytes,
-                                          uint32_t ldb4, uint32_t lane_off)
+// The line goes to LDS at lds_addr (this lane's 8 bytes).  Issued from asm because its source is
+// an asm-loaded register.  The compiler does not see this store, so the ring is only ever read
+// through volatile pointers (read_ring4): those reads are neither removed nor moved across asm
+// statements, and LDS executes a wave's operations in order.
+__device__ __forceinline__ void store_line_lds(uint32_t lds_addr, u32x2 v)
 {
-    constexpr int J = runs_per_chunk(L);
-    constexpr int CD = chunk_dwords(L);
-    if (nch <= 0) return;
-    SCols<J> cb[2];
-    SEntries<L, J> eb[2];
-    float bq[2][J][V];
+    asm volatile("ds_write_b64 %0, %1" : : "v"(lds_addr), "v"(v));
+}
 
-    auto issue = [&](const SCols<J>& c, float (&dst)[J][V]) {
-#pragma unroll
-        for (int j = 0; j < J; ++j) load_b_async<V>(Bbytes + (uint64_t)c.col[j] * ldb4, lane_off, dst[j]);
-    };
-    auto compute = [&](const SEntries<L, J>& c, const float (&src)[J][V]) {
-#pragma unroll
-        for (int j = 0; j < J; ++j) run_fma<L, V>(acc, &c.row[j * L], &c.val[j * L], src[j]);
-    };
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 
-    load_cols<L, J>(cb[0], s);
-    load_entries<L, J>(eb[0], s);
-    load_cols<L, J>(cb[1], s + CD);
-    issue(cb[0], bq[0]);
-    wait_vm<0>();
-    int32_t n = 0;
-    while (n + 4 <= nch) {
-        // step n: chunks n+1 .. n+3 exist
-        issue(cb[1], bq[1]);
-        load_cols<L, J>(cb[0], s + (int64_t)(n + 2) * CD);
-        load_entries<L, J>(eb[1], s + (int64_t)(n + 1) * CD);
-        wait_vm<J>();
-        compute(eb[0], bq[0]);
-        // step n+1
-        issue(cb[0], bq[0]);
-        load_cols<L, J>(cb[1], s + (int64_t)(n + 3) * CD);
-        load_entries<L, J>(eb[0], s + (int64_t)(n + 2) * CD);
-        wait_vm<J>();
-        compute(eb[1], bq[1]);
-        n += 2;
-        if (n + 4 > nch) wait_vm<0>();                   // last round: drain before leaving
+typedef __attribute__((address_space(3))) uint32_t lds_u32;
+typedef __attribute__((address_space(3))) u32x4 lds_u32x4;
+
+// N words (a multiple of 4) of the ring, one 16-byte broadcast read each.
+template <int N>
+__device__ __forceinline__ void read_ring4(const lds_u32* p, uint32_t (&out)[N])
+{
+    static_assert(N % 4 == 0, "");
+#pragma unroll
+    for (int i = 0; i < N / 4; ++i) {
+        const u32x4 t = *(const volatile lds_u32x4*)(p + 4 * i);
+        out[4 * i] = t.x; out[4 * i + 1] = t.y; out[4 * i + 2] = t.z; out[4 * i + 3] = t.w;
     }
-    // two chunks are left: n (arrived in load buffer 0, entries in eb[0]) and n+1 (columns in cb[1])
-    issue(cb[1], bq[1]);
-    load_entries<L, J>(eb[1], s + (int64_t)(n + 1) * CD);
-    wait_vm<J>();
-    compute(eb[0], bq[0]);
-    wait_vm<0>();
-    compute(eb[1], bq[1]);
+}
+
+// LDS ring of the stream: kRing lines of 128 words per wave.
+constexpr int kRing = 3;
+constexpr int kLineWords = 128;
+
+// All bodies of one length class of one (group, window).
+//
+// Turn b of the loop multiplies chunks 4b .. 4b+3 (kBody = 4) and starts the B loads of chunks
+// 4b+3 .. 4b+6, so three chunks of loads are always in flight behind the one being used.  Line b
+// of the stream = the 128 words from word b*BD of the segment: the pre-block-sized lead (for
+// b = 0 the pre-block itself), then block b.  It was loaded two turns earlier and sits in LDS:
+// its columns and row bytes are read back and moved to SGPRs (v_readfirstlane), its values are
+// read back into VGPRs, where every lane holds the same number.  Per turn the vector-memory
+// order is
+//     line(b+2), B(4b+3) | B(4b+4) | B(4b+5) | B(4b+6)
+// so the wait before chunk 4b+st leaves 3J+1 loads in flight for st = 0..2 and 3J for st = 3; after
+// that last wait line(b+2) has arrived and is written to LDS.  Loads are in flight across the
+// back-edge of the loop and from the start-up into the loop; the class ends with vmcnt(0).
+template <int L, int V>
+__device__ __forceinline__ void run_class(AccFile& acc, const uint32_t* seg, int32_t nb, const char* Bbytes, uint32_t ldb4,
+                                          uint32_t lane_off, const lds_u32* ring, uint32_t ring_lds, int lane)
+{
+    constexpr int J = runs_per_chunk(L), RP = rowpack_dwords(L), VS = val_stride(L), BD = block_dwords(L), PRE = pre_dwords(L);
+    static_assert(kBody == 4 && PRE + BD <= kLineWords, "a line holds the lead and one block; four load buffers rotate");
+    if (nb <= 0) return;
+    float bq[kBody][J][V];
+    const uint32_t lane8 = (uint32_t)lane * 8u;
+
+    auto issue = [&](const uint32_t* col, float (&dst)[J][V]) {
+#pragma unroll
+        for (int j = 0; j < J; ++j) load_b_async<V>(Bbytes + (uint64_t)col[j] * ldb4, lane_off, dst[j]);
+    };
+
+    // start: lines 0 and 1 to LDS, then chunks 0..2 in flight (their columns are the pre-block)
+    {
+        u32x2 l0 = load_line_async(seg, lane8);
+        u32x2 l1 = load_line_async(seg + (int64_t)(nb > 1 ? 1 : 0) * BD, lane8);
+        wait_vm<0>();
+        store_line_lds(ring_lds + lane8, l0);
+        store_line_lds(ring_lds + kLineWords * 4 + lane8, l1);
+        uint32_t c0[PRE];
+        read_ring4<PRE>(ring, c0);
+#pragma unroll
+        for (int i = J; i < PRE; ++i) c0[i] = __builtin_amdgcn_readfirstlane(c0[i]);
+        issue(&c0[J], bq[0]);
+        issue(&c0[2 * J], bq[1]);
+        issue(&c0[3 * J], bq[2]);
+    }
+
+    int32_t slot = 0;                                                      // b % kRing
+    for (int32_t b = 0; b < nb; ++b) {
+        const lds_u32* blk = ring + slot * kLineWords + PRE;
+        const int32_t nxt = b + 2 < nb ? b + 2 : nb - 1;
+        u32x2 ln = load_line_async(seg + (int64_t)nxt * BD, lane8);
+        uint32_t col[kBody * J], rpk[kBody * RP];
+        read_ring4<kBody * J>(blk, col);
+        read_ring4<kBody * RP>(blk + kBody * J, rpk);
+#pragma unroll
+        for (int i = 0; i < kBody * J; ++i) col[i] = __builtin_amdgcn_readfirstlane(col[i]);
+#pragma unroll
+        for (int i = 0; i < kBody * RP; ++i) rpk[i] = __builtin_amdgcn_readfirstlane(rpk[i]);
+#pragma unroll
+        for (int st = 0; st < kBody; ++st) {
+            issue(&col[st * J], bq[(st + 3) % kBody]);
+            uint32_t vw[VS];
+            read_ring4<VS>(blk + blk_val(L, st), vw);
+            float va[VS];
+#pragma unroll
+            for (int i = 0; i < VS; ++i) va[i] = __uint_as_float(vw[i]);
+            if (st < 3) wait_vm<3 * J + 1>(); else wait_vm<3 * J>();
+#pragma unroll
+            for (int j = 0; j < J; ++j) {
+                uint32_t r[L];
+#pragma unroll
+                for (int i = 0; i < L; ++i) r[i] = rpk[st * RP + (j * L + i) / 4] >> (8 * ((j * L + i) % 4));
+                run_fma<L, V>(acc, r, &va[j * L], bq[st][j]);
+            }
+        }
+        const int32_t wslot = slot == 0 ? 2 : slot - 1;                    // (b + 2) % kRing
+        store_line_lds(ring_lds + (uint32_t)wslot * (kLineWords * 4) + lane8, ln);
+        slot = slot == kRing - 1 ? 0 : slot + 1;
+    }
+    wait_vm<0>();                                                          // the loads of chunks past the end
 }
 
 template <int V>
@@ -253,18 +289,30 @@ __global__ __launch_bounds__(64) void spdm_sched(const SchedClass* __restrict__ 
     AccFile acc;
     acc.t0 = 0.0f; acc.t1 = 0.0f; acc.t2 = 0.0f; acc.t3 = 0.0f; acc.t4 = 0.0f;
 
-    // window by window (a band of B that stays in L2), class by class
-    const uint32_t* __restrict__ gs = stream + sched_group_base(gIdxes[q], q, nw);
-    const SchedClass* __restrict__ h = hdr + q * nw * kMaxRun;
+    // the wave's ring of stream lines (one wave per workgroup)
+    __shared__ __attribute__((aligned(16))) uint32_t ring_mem[kRing * kLineWords];
+    const lds_u32* ring = (const lds_u32*)ring_mem;
+    const uint32_t ring_lds = (uint32_t)(uintptr_t)ring;
+
+    // window by window (a band of B that stays in L2), class by class.  The header words are
+    // made scalar by hand: after the volatile LDS reads the compiler no longer does it itself.
+    const uint32_t* gs = stream + sched_group_base(__builtin_amdgcn_readfirstlane(gIdxes[q]), q, nw);
+    const SchedClass* h = hdr + q * nw * kMaxRun;
     for (int32_t w8 = 0; w8 < nw * kMaxRun; w8 += kMaxRun) {
-        run_class<1, V>(acc, gs + h[w8 + 0].first_word, h[w8 + 0].chunks, Bbytes, ldb4, lane_off);
-        run_class<2, V>(acc, gs + h[w8 + 1].first_word, h[w8 + 1].chunks, Bbytes, ldb4, lane_off);
-        run_class<3, V>(acc, gs + h[w8 + 2].first_word, h[w8 + 2].chunks, Bbytes, ldb4, lane_off);
-        run_class<4, V>(acc, gs + h[w8 + 3].first_word, h[w8 + 3].chunks, Bbytes, ldb4, lane_off);
-        run_class<5, V>(acc, gs + h[w8 + 4].first_word, h[w8 + 4].chunks, Bbytes, ldb4, lane_off);
-        run_class<6, V>(acc, gs + h[w8 + 5].first_word, h[w8 + 5].chunks, Bbytes, ldb4, lane_off);
-        run_class<7, V>(acc, gs + h[w8 + 6].first_word, h[w8 + 6].chunks, Bbytes, ldb4, lane_off);
-        run_class<8, V>(acc, gs + h[w8 + 7].first_word, h[w8 + 7].chunks, Bbytes, ldb4, lane_off);
+        int32_t fw[kMaxRun], nb[kMaxRun];
+#pragma unroll
+        for (int i = 0; i < kMaxRun; ++i) {
+            fw[i] = __builtin_amdgcn_readfirstlane(h[w8 + i].first_word);
+            nb[i] = __builtin_amdgcn_readfirstlane(h[w8 + i].bodies);
+        }
+        run_class<1, V>(acc, gs + fw[0], nb[0], Bbytes, ldb4, lane_off, ring, ring_lds, lane);
+        run_class<2, V>(acc, gs + fw[1], nb[1], Bbytes, ldb4, lane_off, ring, ring_lds, lane);
+        run_class<3, V>(acc, gs + fw[2], nb[2], Bbytes, ldb4, lane_off, ring, ring_lds, lane);
+        run_class<4, V>(acc, gs + fw[3], nb[3], Bbytes, ldb4, lane_off, ring, ring_lds, lane);
+        run_class<5, V>(acc, gs + fw[4], nb[4], Bbytes, ldb4, lane_off, ring, ring_lds, lane);
+        run_class<6, V>(acc, gs + fw[5], nb[5], Bbytes, ldb4, lane_off, ring, ring_lds, lane);
+        run_class<7, V>(acc, gs + fw[6], nb[6], Bbytes, ldb4, lane_off, ring, ring_lds, lane);
+        run_class<8, V>(acc, gs + fw[7], nb[7], Bbytes, ldb4, lane_off, ring, ring_lds, lane);
     }
 
     // epilogue: each lane stores its V adjacent columns of every row of the group (coalesced
