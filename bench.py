@@ -42,6 +42,9 @@ def parse():
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle timing")
     ap.add_argument("--no-dense", action="store_true", help="skip the dense SGEMM timing")
     ap.add_argument("--secondary", default="config2", help="second workload reported in the same line ('' = none)")
+    ap.add_argument("--copy-calibration", action="store_true",
+                    help="only run a plain 256 MiB device copy a few times: the reference launch against which the "
+                         "FETCH_SIZE / WRITE_SIZE counters of rocprofv3 --pmc are scaled")
     return ap.parse_args()
 
 
@@ -193,6 +196,14 @@ def main():
         sys.exit(3)
     dev = torch.device("cuda:0")
     torch.cuda.set_device(dev)
+    if args.copy_calibration:
+        src = torch.ones(64 * 1024 * 1024, dtype=torch.float32, device=dev)
+        dst = torch.empty_like(src)
+        for _ in range(5):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        print(json.dumps({"copy_calibration": {"bytes_read": src.numel() * 4, "bytes_written": dst.numel() * 4, "launches": 5}}))
+        return
 
     w, head = run_one(torch, binding, workloads, args.workload, args, dev, args.steps, args.warmup)
     line = {
