@@ -152,7 +152,7 @@ int new_handle(int64_t m, int64_t k, int64_t nnz, int32_t p, void* dev_buf, gcoo
 int launch_build_schedule(const gcoo_matrix* h, hipStream_t s)
 {
     if (h->g > 0 && h->p <= gcoo::kSchedMaxP) {              // no register kernel above that height
-        gcoo::build_schedule<<<dim3((unsigned)h->g), dim3(256), 0, s>>>(h->gIdxes(), h->rows(), h->cols(), h->values(), h->p,
+        gcoo::build_schedule<<<dim3((unsigned)h->g), dim3(gcoo::kBuildThreads), 0, s>>>(h->gIdxes(), h->rows(), h->cols(), h->values(), h->p,
                                                                         h->g, h->nw, h->window_cols, h->sched_hdr(), h->sched());
         HIP_TRY(hipGetLastError());
     }
@@ -240,10 +240,10 @@ int gcoo_from_csr(int64_t m, int64_t k, const int32_t* row_ptr, const int32_t* c
             int32_t* dr = to_final ? fin_r : tmp_r;
             float* dv = to_final ? fin_v : tmp_v;
             if (pass == 0)
-                gcoo::sort_groups_by_col_digit<true><<<dim3((unsigned)g), dim3(64), 0, s>>>(
+                gcoo::sort_groups_by_col_digit<true><<<dim3((unsigned)g), dim3(gcoo::kSortWaves * gcoo::kWave), 0, s>>>(
                     h->gIdxes(), d_row_ptr, m, p, src_c, src_r, src_v, dc, dr, dv, 8 * pass);
             else
-                gcoo::sort_groups_by_col_digit<false><<<dim3((unsigned)g), dim3(64), 0, s>>>(
+                gcoo::sort_groups_by_col_digit<false><<<dim3((unsigned)g), dim3(gcoo::kSortWaves * gcoo::kWave), 0, s>>>(
                     h->gIdxes(), d_row_ptr, m, p, src_c, src_r, src_v, dc, dr, dv, 8 * pass);
             hipError_t e = hipGetLastError();
             if (e != hipSuccess) { delete h; return hip_fail(e, "sort_groups_by_col_digit"); }

@@ -53,58 +53,85 @@ __device__ __forceinline__ uint64_t match_digit(uint32_t d, bool is_active)
 
 // ---------------------------------------------------------------------------------------------
 // Algorithm 1, step 2 for a CSR input: one pass of a stable least-significant-digit radix sort
-// of every group's entries on an 8-bit digit of the column index.  One wave per group.
+// of every group's entries on an 8-bit digit of the column index.  One workgroup of kSortWaves
+// waves per group.
 //
 // The CSR order of a group's entries is (row, input position); sorting that stably by column
-// gives (column, row, input position).  Each pass is a counting sort: histogram of the digit
-// (LDS), exclusive scan, then the entries are taken 64 at a time in order and every entry gets
-// slot = digit base + number of earlier entries with the same digit.  "Earlier in the same
-// 64" comes from ballots, so the placement does not depend on timing.
+// gives (column, row, input position).  Each pass is a counting sort.  The group's entries are
+// cut into kSortWaves contiguous parts, one per wave.  Every wave counts the digits of its part
+// (LDS, a histogram of its own); from those counts each (wave, digit) gets the slot where the
+// wave's first entry with that digit goes: digit base + what earlier waves hold of the digit.
+// Then every wave walks its part 64 entries at a time, in order, and gives each entry
+// slot = that running base + number of earlier entries of the 64 with the same digit (ballots).
+// Nothing depends on timing: counts are sums, ranks come from ballots.
 //
 // FIRST: the source is the CSR input itself (row of an entry = search in row_ptr); otherwise the
 // source is the (cols, rows, values) triple written by the previous pass.
 // ---------------------------------------------------------------------------------------------
+constexpr int kSortWaves = 16;
+
 template <bool FIRST>
-__global__ __launch_bounds__(kWave) void sort_groups_by_col_digit(
+__global__ __launch_bounds__(kSortWaves * kWave) void sort_groups_by_col_digit(
     const int32_t* __restrict__ gIdxes, const int32_t* __restrict__ row_ptr, int64_t m, int32_t p,
     const int32_t* __restrict__ src_cols, const int32_t* __restrict__ src_rows, const float* __restrict__ src_vals,
     int32_t* __restrict__ dst_cols, int32_t* __restrict__ dst_rows, float* __restrict__ dst_vals, int shift)
 {
-    __shared__ int32_t base[256];
-    const int lane = threadIdx.x;
+    __shared__ int32_t slot_of[kSortWaves][256];      // counts, then running slots, per wave and digit
+    __shared__ int32_t total[256];
+    const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
     const int64_t q = blockIdx.x;
     const int32_t beg = gIdxes[q], end = gIdxes[q + 1];
     if (beg >= end) return;
+    // part of wave wv: whole 64-entry tiles
+    const int32_t tiles = (end - beg + kWave - 1) / kWave;
+    const int32_t tiles_per = (tiles + kSortWaves - 1) / kSortWaves;
+    const int32_t pb = beg + wv * tiles_per * kWave;
+    const int32_t pe = (pb + tiles_per * kWave < end) ? pb + tiles_per * kWave : end;
 
-    for (int i = lane; i < 256; i += kWave) base[i] = 0;
+    for (int i = tid; i < kSortWaves * 256; i += kSortWaves * kWave) (&slot_of[0][0])[i] = 0;
     __syncthreads();
-    for (int32_t e = beg + lane; e < end; e += kWave)
-        atomicAdd(&base[((uint32_t)src_cols[e] >> shift) & 255u], 1);   // counts only: order-free
+    for (int32_t e = pb + lane; e < pe; e += kWave)
+        atomicAdd(&slot_of[wv][((uint32_t)src_cols[e] >> shift) & 255u], 1);   // counts only: order-free
     __syncthreads();
-
-    // exclusive scan of the 256 counts: lane owns bins 4*lane .. 4*lane+3
-    int32_t c0 = base[4 * lane], c1 = base[4 * lane + 1], c2 = base[4 * lane + 2], c3 = base[4 * lane + 3];
-    int32_t sum = c0 + c1 + c2 + c3, incl = sum;
-#pragma unroll
-    for (int d = 1; d < kWave; d <<= 1) {
-        int32_t t = __shfl_up(incl, d, kWave);
-        if (lane >= d) incl += t;
+    if (tid < 256) {
+        int32_t run = 0;
+        for (int w = 0; w < kSortWaves; ++w) {
+            const int32_t c = slot_of[w][tid];
+            slot_of[w][tid] = run;
+            run += c;
+        }
+        total[tid] = run;
     }
-    int32_t ex = incl - sum;
     __syncthreads();
-    base[4 * lane] = ex;
-    base[4 * lane + 1] = ex + c0;
-    base[4 * lane + 2] = ex + c0 + c1;
-    base[4 * lane + 3] = ex + c0 + c1 + c2;
+    if (wv == 0) {
+        // exclusive scan of the 256 digit totals: lane owns digits 4*lane .. 4*lane+3
+        const int32_t c0 = total[4 * lane], c1 = total[4 * lane + 1], c2 = total[4 * lane + 2], c3 = total[4 * lane + 3];
+        const int32_t sum = c0 + c1 + c2 + c3;
+        int32_t incl = sum;
+#pragma unroll
+        for (int d = 1; d < kWave; d <<= 1) {
+            const int32_t t = __shfl_up(incl, d, kWave);
+            if (lane >= d) incl += t;
+        }
+        const int32_t ex = incl - sum;
+        total[4 * lane] = ex;
+        total[4 * lane + 1] = ex + c0;
+        total[4 * lane + 2] = ex + c0 + c1;
+        total[4 * lane + 3] = ex + c0 + c1 + c2;
+    }
+    __syncthreads();
+    for (int i = tid; i < kSortWaves * 256; i += kSortWaves * kWave) (&slot_of[0][0])[i] += total[i & 255];
     __syncthreads();
 
+    // From here on the waves do not meet again: a wave's LDS operations execute in order, and the
+    // volatile accesses keep the compiler from reordering the read of a slot and its update.
+    volatile int32_t* my_slot = slot_of[wv];
     const int64_t r_lo = q * p;
     const int64_t r_hi = (r_lo + p < m) ? r_lo + p : m;
     const uint64_t lt = lanemask_lt();
-
-    for (int32_t t0 = beg; t0 < end; t0 += kWave) {
+    for (int32_t t0 = pb; t0 < pe; t0 += kWave) {
         const int32_t e = t0 + lane;
-        const bool act = e < end;
+        const bool act = e < pe;
         int32_t col = 0, row = 0;
         float val = 0.0f;
         if (act) {
@@ -114,7 +141,7 @@ __global__ __launch_bounds__(kWave) void sort_groups_by_col_digit(
                 // row r with row_ptr[r] <= e < row_ptr[r+1]; empty rows are skipped by the upper bound
                 int64_t lo = r_lo, hi = r_hi;          // answer in [lo, hi)
                 while (hi - lo > 1) {
-                    int64_t mid = (lo + hi) >> 1;
+                    const int64_t mid = (lo + hi) >> 1;
                     if (row_ptr[mid] <= e) lo = mid; else hi = mid;
                 }
                 row = (int32_t)lo;
@@ -126,10 +153,10 @@ __global__ __launch_bounds__(kWave) void sort_groups_by_col_digit(
         const uint64_t same = match_digit(d, act);
         const int32_t before = __popcll(same & lt);
         int32_t slot = 0;
-        if (act) slot = base[d];
-        __syncthreads();                                   // all lanes have read base[] before it moves
-        if (act && before == 0) base[d] = slot + __popcll(same);   // first lane of each digit advances it
-        __syncthreads();
+        if (act) slot = my_slot[d];
+        __builtin_amdgcn_wave_barrier();
+        if (act && before == 0) my_slot[d] = slot + __popcll(same);   // first lane of each digit advances it
+        __builtin_amdgcn_wave_barrier();
         if (act) {
             const int32_t at = beg + slot + before;
             dst_cols[at] = col;

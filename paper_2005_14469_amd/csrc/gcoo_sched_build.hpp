@@ -34,10 +34,13 @@ __device__ __forceinline__ void sched_put_piece(uint32_t* __restrict__ seg, int 
     (void)J;
 }
 
-// One workgroup (256 threads) per group.  Per window: pass 1 counts the pieces of each class,
+// One workgroup (kBuildThreads threads) per group.  Per window: pass 1 counts the pieces of each class,
 // pass 2 gives every piece its rank inside its class (entries are visited in order; ranks come
 // from ballots and running counts, so the listing is the same on every run) and writes it out.
-__global__ __launch_bounds__(256) void build_schedule(const int32_t* __restrict__ gIdxes, const int32_t* __restrict__ rows,
+constexpr int kBuildThreads = 1024;
+constexpr int kBuildWaves = kBuildThreads / 64;
+
+__global__ __launch_bounds__(kBuildThreads) void build_schedule(const int32_t* __restrict__ gIdxes, const int32_t* __restrict__ rows,
                                                       const int32_t* __restrict__ cols, const float* __restrict__ values,
                                                       int32_t p, int64_t g, int32_t nw, int32_t window_cols,
                                                       SchedClass* __restrict__ hdr, uint32_t* __restrict__ stream)
@@ -47,7 +50,7 @@ __global__ __launch_bounds__(256) void build_schedule(const int32_t* __restrict_
     __shared__ int32_t demote[kMaxRun];           // class listed as pieces of class 1
     __shared__ int32_t seg[kMaxRun];              // first word of the class segment
     __shared__ int32_t base[kMaxRun];             // pieces of the class already placed
-    __shared__ int32_t wcnt[4][kMaxRun];          // per wave, per class, in the current tile
+    __shared__ int32_t wcnt[kBuildWaves][kMaxRun];          // per wave, per class, in the current tile
     __shared__ int32_t at_s;                      // words used so far by this group
     const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
     const int64_t q = blockIdx.x;
@@ -89,7 +92,7 @@ __global__ __launch_bounds__(256) void build_schedule(const int32_t* __restrict_
             return len;
         };
 
-        for (int32_t e = wb + tid; e < we; e += 256) {
+        for (int32_t e = wb + tid; e < we; e += kBuildThreads) {
             int pos;
             const int L = natural_piece(e, pos);
             if (pos == 0) atomicAdd(&cnt[L - 1], 1);      // a count: the order of the adds is irrelevant
@@ -114,7 +117,7 @@ __global__ __launch_bounds__(256) void build_schedule(const int32_t* __restrict_
         }
         __syncthreads();
 
-        for (int32_t t0 = wb; t0 < we; t0 += 256) {
+        for (int32_t t0 = wb; t0 < we; t0 += kBuildThreads) {
             const int32_t e = t0 + tid;
             int L = 0;                                    // class of the piece that starts at e (0: none)
             if (e < we) {
@@ -138,7 +141,11 @@ __global__ __launch_bounds__(256) void build_schedule(const int32_t* __restrict_
                 sched_put_piece(out + seg[L - 1], L, rank / J, rank % J, (uint32_t)cols[e], rows, values, e, row0, p);
             }
             __syncthreads();
-            if (tid < kMaxRun) base[tid] += wcnt[0][tid] + wcnt[1][tid] + wcnt[2][tid] + wcnt[3][tid];
+            if (tid < kMaxRun) {
+                int32_t add = 0;
+                for (int x = 0; x < kBuildWaves; ++x) add += wcnt[x][tid];
+                base[tid] += add;
+            }
             __syncthreads();
         }
 

@@ -345,12 +345,12 @@ hipError_t launch_spdm_sched_instance(const SpdmArgs& a, hipStream_t s)
 {
     const int64_t tiles = (a.N + 64 * V - 1) / (64 * V);
     const int64_t total = a.g * tiles;
-    const int64_t grid = (total + 7) / 8 * 8;          // whole rounds over the 8 XCDs
+    const int64_t grid = (total + 7) / 8 * 8;              // whole rounds over the 8 XCDs
     if (grid <= 0 || grid > 0x7fffffffLL) return hipErrorInvalidConfiguration;
     if (a.ldb > 0x3fffffffLL) return hipErrorInvalidValue;   // row pitch in bytes is kept in 32 bits
     if (a.p + 1 > acc_stride<V>()) return hipErrorInvalidValue;
-    spdm_sched<V><<<dim3((unsigned)grid), dim3(64), 0, s>>>(a.hdr, a.stream, a.gIdxes, a.m, a.p, a.g, a.nw, a.B, a.ldb, a.N, a.C,
-                                                            a.ldc, total);
+    spdm_sched<V><<<dim3((unsigned)grid), dim3(64), 0, s>>>(a.hdr, a.stream, a.gIdxes, a.m, a.p, a.g, a.nw, a.B, a.ldb, a.N,
+                                                            a.C, a.ldc, total);
     return hipGetLastError();
 }
 
