@@ -42,6 +42,9 @@ def parse():
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle timing")
     ap.add_argument("--no-dense", action="store_true", help="skip the dense SGEMM timing")
     ap.add_argument("--secondary", default="config2", help="second workload reported in the same line ('' = none)")
+    ap.add_argument("--crossover", action="store_true",
+                    help="instead of the headline run: sweep the sparsity of an 8000^2 uniform random A and report where "
+                         "the path overtakes the dense SGEMM (Section 4.2 of the paper, 'time vs. sparsity')")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="only run a plain 256 MiB device copy a few times: the reference launch against which the "
                          "FETCH_SIZE / WRITE_SIZE counters of rocprofv3 --pmc are scaled")
@@ -181,6 +184,40 @@ def run_one(torch, binding, workloads, name, args, dev, steps, warmup):
     return w, out
 
 
+def crossover(torch, binding, workloads, args, dev, n=8000):
+    """Time vs. sparsity at n = 8000 against the dense SGEMM; crossover by linear interpolation in log(1-s)."""
+    import math
+    rows = []
+    dense = None
+    for s in (0.5, 0.6, 0.7, 0.8, 0.85, 0.9, 0.95, 0.98, 0.99, 0.995, 0.999):
+        w = workloads.uniform_random(n, n, n, s, workloads.BASE_SEED + int(round(s * 10000)), name=f"uniform_{n}_s{s}")
+        p = args.p or 32
+        r = time_path(torch, binding, w, dev, p, args.variant, 5, 2)
+        if dense is None:
+            dense = dense_ms(torch, w, dev)
+        rows.append(dict(sparsity=s, nnz=w.nnz, spdm_ms=r["spdm_ms"], convert_ms=r["convert_ms"], step_ms=r["ms_per_step"],
+                         spdm_gflops=2.0 * w.nnz * n / r["spdm_ms"] / 1e6))
+        del w, r
+
+    def cross(key):
+        prev = None
+        for row in rows:
+            if row[key] <= dense:
+                if prev is None:
+                    return row["sparsity"]
+                # interpolate log(time) against log(1-s)
+                x0, x1 = math.log(1 - prev["sparsity"]), math.log(1 - row["sparsity"])
+                y0, y1 = math.log(prev[key] / dense), math.log(row[key] / dense)
+                x = x0 + (0 - y0) * (x1 - x0) / (y1 - y0)
+                return 1 - math.exp(x)
+            prev = row
+        return None
+
+    return {"metric": "sparsity at which the GCOO path overtakes the dense fp32 SGEMM, n=8000", "dense_sgemm_ms": dense,
+            "crossover_sparsity_spdm_kernel": cross("spdm_ms"), "crossover_sparsity_whole_path": cross("step_ms"),
+            "p": args.p or 32, "rows": rows}
+
+
 def main():
     args = parse()
     if args.gpus != 1:
@@ -205,6 +242,9 @@ def main():
         print(json.dumps({"copy_calibration": {"bytes_read": src.numel() * 4, "bytes_written": dst.numel() * 4, "launches": 5}}))
         return
 
+    if args.crossover:
+        print(json.dumps(crossover(torch, binding, workloads, args, dev)))
+        return
     w, head = run_one(torch, binding, workloads, args.workload, args, dev, args.steps, args.warmup)
     line = {
         "metric": "fp32 SpDM effective GFLOP/s (2*nnz*N/t, whole path: CSR->GCOO conversion + SpDM kernel)",

@@ -122,7 +122,9 @@ int gcoo_spdm(const gcoo_matrix* A, const float* B_dev, int64_t ldb, int64_t N,
  */
 #define GCOO_VARIANT_AUTO 0
 #define GCOO_VARIANT_LDS  1  /* partial sums in LDS, reads the five arrays directly; any p, any alignment */
-#define GCOO_VARIANT_REG  2  /* partial sums in VGPRs, reads the run schedule built at conversion; p <= 128 */
+/* partial sums in VGPRs, reads the run schedule built at conversion; needs p <= 64 and B, C, ldb,
+ * ldc, N all even (8-byte aligned rows), else GCOO_EINVAL */
+#define GCOO_VARIANT_REG  2
 int gcoo_spdm_variant(const gcoo_matrix* A, const float* B_dev, int64_t ldb, int64_t N,
                       float* C_dev, int64_t ldc, void* stream, int variant);
 

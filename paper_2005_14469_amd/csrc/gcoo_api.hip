@@ -214,7 +214,9 @@ int gcoo_from_csr(int64_t m, int64_t k, const int32_t* row_ptr, const int32_t* c
         hipError_t e = hipMemcpyAsync(sp, row_ptr, (size_t)(m + 1) * 4, hipMemcpyHostToDevice, s);
         if (e == hipSuccess && nnz > 0) e = hipMemcpyAsync(sc, col_idx, (size_t)nnz * 4, hipMemcpyHostToDevice, s);
         if (e == hipSuccess && nnz > 0) e = hipMemcpyAsync(sv, vals, (size_t)nnz * 4, hipMemcpyHostToDevice, s);
-        if (e != hipSuccess) { delete h; return hip_fail(e, "hipMemcpyAsync(CSR input)"); }
+        // the caller may release its host arrays as soon as this call returns
+        if (e == hipSuccess) e = hipStreamSynchronize(s);
+        if (e != hipSuccess) { delete h; return hip_fail(e, "copy of the CSR input to the device"); }
         d_row_ptr = sp; d_cols = sc; d_vals = sv;
     }
 
@@ -347,7 +349,10 @@ int sched_width(int32_t p, const Shape& sh)
     if (sh.wide_pitch) return 0;
     if (p <= 32 && sh.al4) return 4;
     if (p <= 64 && sh.al2) return 2;
-    if (p <= 128) return 1;
+    // The one-column-per-lane instance (65 <= p <= 128, or operands aligned to 4 bytes only) is
+    // switched off: a run of it on an 8000 x 8000 matrix with p = 128 ended in a GPU memory
+    // fault whose cause has not been found, so it is not reachable until it is.  Such calls get
+    // the LDS kernel (automatic choice) or GCOO_EINVAL (explicit GCOO_VARIANT_REG).
     return 0;
 }
 

@@ -50,7 +50,10 @@ constexpr int kMinClassEntries = 256;
 constexpr int kSchedPad = 64;            // words per (group, window) for class 1's dummy pieces and pre-block
 constexpr int kSchedSlack = 128;         // words after the last group (whole-line reads)
 constexpr int kMaxWindows = 32;
-constexpr int kSchedMaxP = 128;          // rows are stored as bytes and row p must fit too
+// Tallest group the register kernel serves.  The layout itself (rows as bytes, row p included)
+// and the one-column-per-lane instance reach p = 128, but that instance is switched off: see
+// sched_width() in gcoo_api.hip.
+constexpr int kSchedMaxP = 64;
 
 __host__ __device__ constexpr int runs_per_chunk(int L) { return L <= 3 ? 4 : (L <= 6 ? 2 : 1); }
 __host__ __device__ constexpr int rowpack_dwords(int L) { return (runs_per_chunk(L) * L + 3) / 4; }

@@ -46,9 +46,13 @@ def _check_product(w, p, variant, Bt=None, r0=0, r1=None, A=None):
     return err, A, Ch
 
 
+REG_MAX_P = 64
+
+
 def _variants_for(p, N):
+    """The kernels that serve group height p and N columns (torch tensors are 16-byte aligned)."""
     v = [binding.VARIANT_LDS]
-    if p <= 128:
+    if p <= REG_MAX_P and N % 2 == 0:
         v += [binding.VARIANT_REG]
     return v
 
@@ -155,6 +159,27 @@ def test_ragged_shapes_all_variants(m, k, N, p):
         _check_product(w, p, variant)
 
 
+def test_register_kernel_refuses_what_it_does_not_serve():
+    _say("REG variant: p > 64 and odd N are refused, AUTO falls back to the LDS kernel")
+    w = workloads.uniform_random(256, 256, 64, 0.9, seed=5)
+    Bt = torch.from_numpy(w.B).to(DEV)
+    for p, N in [(128, 64), (65, 64), (32, 63)]:
+        A = binding.gcoo_from_csr(w.m, w.k, w.row_ptr, w.col_idx, w.vals, p, device=DEV)
+        Bv = Bt[:, :N].contiguous()
+        Cv = torch.empty((w.m, N), device=DEV)
+        assert binding.gcoo_spdm_pick(A, Bv, Cv) == binding.VARIANT_LDS
+        with pytest.raises(binding.GcooError):
+            binding.gcoo_spdm(A, Bv, Cv, variant=binding.VARIANT_REG)
+        torch.cuda.synchronize()
+
+
+@pytest.mark.skip(reason="the one-column-per-lane register kernel (65 <= p <= 128) is switched off in the library: "
+                         "one run of it at 8000 x 8000, p = 128 ended in a GPU memory fault of unknown cause")
+def test_register_kernel_one_column_per_lane():
+    w = workloads.config(3)
+    _check_product(w, 128, binding.VARIANT_REG, r0=0, r1=128)
+
+
 def test_auto_variant_and_strided_operands():
     _say("strided B and C")
     w = workloads.uniform_random(200, 150, 96, 0.9, seed=21)
@@ -225,7 +250,7 @@ def test_independent_of_p_and_deterministic():
     C64, D64 = orc.spdm_csr(w.k, w.N, w.row_ptr, w.col_idx, w.vals, w.B)
     for p in (8, 32, 64, 128):
         A = binding.gcoo_from_csr(w.m, w.k, w.row_ptr, w.col_idx, w.vals, p, device=DEV)
-        for variant in (binding.VARIANT_REG, binding.VARIANT_LDS):
+        for variant in _variants_for(p, w.N):
             c1 = binding.gcoo_spdm(A, Bt, variant=variant).cpu().numpy()
             c2 = binding.gcoo_spdm(A, Bt, variant=variant).cpu().numpy()
             assert np.array_equal(c1, c2)                    # no atomics anywhere: same bits on every run
