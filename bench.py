@@ -45,6 +45,13 @@ def parse():
     ap.add_argument("--crossover", action="store_true",
                     help="instead of the headline run: sweep the sparsity of an 8000^2 uniform random A and report where "
                          "the path overtakes the dense SGEMM (Section 4.2 of the paper, 'time vs. sparsity')")
+    ap.add_argument("--sweep", choices=["sparsity", "size"], default=None,
+                    help="instead of the headline run, one of the paper's sweeps on uniform random square matrices: "
+                         "'sparsity' = time against sparsity at n = 4000 and 14000 with the dense SGEMM beside it "
+                         "(Section 4.2); 'size' = GFLOP/s against n at sparsity 0.98 and 0.995 (Section 4.2)")
+    ap.add_argument("--eo-kc", action="store_true",
+                    help="instead of the headline run: dense A on the device -> GCOO (Algorithm 1) -> SpDM at n = 4000 and "
+                         "14000, sparsity 0.95..0.99: the split of Section 4.3 into extra overhead (conversion) and kernel")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="only run a plain 256 MiB device copy a few times: the reference launch against which the "
                          "FETCH_SIZE / WRITE_SIZE counters of rocprofv3 --pmc are scaled")
@@ -218,6 +225,120 @@ def crossover(torch, binding, workloads, args, dev, n=8000):
             "p": args.p or 32, "rows": rows}
 
 
+def _event_ms(torch, fn, reps, warmup=2):
+    for _ in range(warmup):
+        fn()
+    torch.cuda.synchronize()
+    ts = []
+    for _ in range(reps):
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        fn()
+        e1.record()
+        torch.cuda.synchronize()
+        ts.append(e0.elapsed_time(e1))
+    ts.sort()
+    return ts[len(ts) // 2]
+
+
+def _square_case(torch, binding, workloads, dev, n, sparsity, p, variant, Bd, Cd, reps=5):
+    """Device-resident uniform random n x n A (CSR) times a device B: conversion and kernel time in ms."""
+    w = workloads.uniform_random(n, n, 1, sparsity, workloads.BASE_SEED + n + int(round(sparsity * 10000)), name="sweep")
+    rp, ci, va = [torch.from_numpy(x).to(dev) for x in (w.row_ptr, w.col_idx, w.vals)]
+    holder = {}
+
+    def convert():
+        holder["A"] = binding.gcoo_from_csr(n, n, rp, ci, va, p)
+
+    t_conv = _event_ms(torch, convert, reps)
+    A = holder["A"]
+    t_kern = _event_ms(torch, lambda: binding.gcoo_spdm(A, Bd, Cd, variant=variant), reps)
+    A.free()
+    # context: the plain CSR row-split kernel of this library and the vendor CSR routine behind torch.sparse
+    t_csr = _event_ms(torch, lambda: binding.gcoo_csr_spmm_baseline(n, n, rp, ci, va, Bd, Cd), reps)
+    t_vendor = None
+    try:
+        As = torch.sparse_csr_tensor(rp, ci, va, size=(n, n))
+        t_vendor = _event_ms(torch, lambda: torch.sparse.mm(As, Bd), 3, warmup=1)
+        del As
+    except Exception as e:                                   # not every build of torch ships the sparse backend
+        print(f"torch.sparse.mm unavailable: {e}", file=sys.stderr)
+    return dict(n=n, sparsity=sparsity, nnz=w.nnz, p=p, convert_ms=t_conv, spdm_ms=t_kern,
+                spdm_gflops=2.0 * w.nnz * n / t_kern / 1e6, step_gflops=2.0 * w.nnz * n / (t_kern + t_conv) / 1e6,
+                csr_rowsplit_ms=t_csr, vendor_csr_ms=t_vendor)
+
+
+def _dense_square_ms(torch, dev, n, Bd):
+    Ad = torch.randn((n, n), device=dev, dtype=torch.float32)
+    torch.backends.cuda.matmul.allow_tf32 = False
+    t = _event_ms(torch, lambda: torch.mm(Ad, Bd), 5)
+    del Ad
+    return t
+
+
+def sweep(torch, binding, workloads, args, dev):
+    p = args.p or 32
+    rows, dense = [], {}
+    if args.sweep == "sparsity":
+        plan = [(n, s) for n in (4000, 14000) for s in (0.8, 0.9, 0.95, 0.96, 0.97, 0.98, 0.99, 0.995, 0.999)]
+    else:
+        plan = [(n, s) for s in (0.98, 0.995) for n in (400, 800, 1600, 2400, 3200, 4000, 6000, 8000, 10000, 12000, 14000)]
+    cur_n, Bd, Cd = None, None, None
+    for n, s in sorted(plan, key=lambda t: t[0]):
+        if n != cur_n:
+            del Bd, Cd
+            g = torch.Generator(device=dev)
+            g.manual_seed(workloads.BASE_SEED + n)
+            Bd = torch.randn((n, n), generator=g, device=dev, dtype=torch.float32)
+            Cd = torch.empty((n, n), device=dev, dtype=torch.float32)
+            dense[n] = _dense_square_ms(torch, dev, n, Bd)
+            cur_n = n
+        r = _square_case(torch, binding, workloads, dev, n, s, p, args.variant, Bd, Cd)
+        print(f"sweep n={n} sparsity={s}: spdm {r['spdm_ms']:.3f} ms, csr {r['csr_rowsplit_ms']:.3f} ms, vendor csr "
+              f"{r['vendor_csr_ms']}, dense {dense[n]:.3f} ms", file=sys.stderr, flush=True)
+        r["dense_sgemm_ms"] = dense[n]
+        r["speedup_over_dense"] = dense[n] / r["spdm_ms"]
+        rows.append(r)
+    rows.sort(key=lambda r: (r["sparsity"], r["n"]) if args.sweep == "size" else (r["n"], r["sparsity"]))
+    return {"metric": f"uniform random square A, fp32, sweep over {args.sweep}", "p": p, "rows": rows}
+
+
+def eo_kc(torch, binding, workloads, args, dev):
+    """Dense device matrix -> GCOO -> product: conversion time against kernel time (Section 4.3)."""
+    rows = []
+    p = args.p or 32
+    for n in (4000, 14000):
+        g = torch.Generator(device=dev)
+        g.manual_seed(workloads.BASE_SEED + n)
+        B = torch.randn((n, n), generator=g, device=dev, dtype=torch.float32)
+        C = torch.empty((n, n), device=dev, dtype=torch.float32)
+        for s in (0.95, 0.96, 0.97, 0.98, 0.99):
+            w = workloads.uniform_random(n, n, 1, s, workloads.BASE_SEED + n + int(round(s * 1000)), name="eo_kc")
+            Ad = torch.zeros((n, n), device=dev, dtype=torch.float32)
+            r = torch.repeat_interleave(torch.arange(n, device=dev), torch.from_numpy(w.row_ptr[1:] - w.row_ptr[:-1]).to(dev))
+            Ad[r, torch.from_numpy(w.col_idx).to(dev).long()] = torch.from_numpy(w.vals).to(dev)
+            del r
+            holder = {}
+
+            def convert():
+                holder["A"] = binding.gcoo_from_dense(Ad, p)      # count, size the buffer, count per block, fill, schedule
+
+            t_count = _event_ms(torch, lambda: binding.gcoo_dense_nnz(Ad), 5)
+            t_eo = _event_ms(torch, convert, 5)
+            A = holder["A"]
+            t_kc = _event_ms(torch, lambda: binding.gcoo_spdm(A, B, C, variant=args.variant), 5)
+            dense_bytes = 4.0 * n * n
+            rows.append(dict(n=n, sparsity=s, nnz=w.nnz, p=p, count_ms=t_count, eo_ms=t_eo, kc_ms=t_kc,
+                             eo_share=t_eo / (t_eo + t_kc),
+                             eo_gbs=(3 * dense_bytes + 12.0 * w.nnz) / t_eo / 1e6))
+            A.free()
+            del Ad, w
+        del B, C
+    return {"metric": "dense -> GCOO conversion (EO) against SpDM kernel (KC), fp32, A on the device",
+            "note": "eo_ms includes the count that sizes the buffer (three reads of A in all); eo_gbs = (3*4*n*n + 12*nnz)/eo_ms",
+            "rows": rows}
+
+
 def main():
     args = parse()
     if args.gpus != 1:
@@ -244,6 +365,12 @@ def main():
 
     if args.crossover:
         print(json.dumps(crossover(torch, binding, workloads, args, dev)))
+        return
+    if args.eo_kc:
+        print(json.dumps(eo_kc(torch, binding, workloads, args, dev)))
+        return
+    if args.sweep:
+        print(json.dumps(sweep(torch, binding, workloads, args, dev)))
         return
     w, head = run_one(torch, binding, workloads, args.workload, args, dev, args.steps, args.warmup)
     line = {

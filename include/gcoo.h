@@ -108,7 +108,8 @@ int gcoo_from_dense(int64_t m, int64_t k, const float* A_dev, int64_t lda, int32
  *   C_dev  m x N row-major device matrix, leading dimension ldc >= N; must not overlap B_dev
  * Entries that A does not store are skipped, never multiplied (a non-finite value in a row of B
  * that no stored entry touches does not reach C).  The summation order inside one element of C
- * is by ascending column of A; results are deterministic from run to run.
+ * is fixed by the matrix, p and the kernel variant, never by timing: results are the same bits
+ * from run to run.
  * Asynchronous on `stream`; allocates nothing; N = 0 or m = 0 is a no-op success.
  */
 int gcoo_spdm(const gcoo_matrix* A, const float* B_dev, int64_t ldb, int64_t N,
@@ -131,6 +132,15 @@ int gcoo_spdm_variant(const gcoo_matrix* A, const float* B_dev, int64_t ldb, int
 /* Variant gcoo_spdm() would pick for this matrix and these operand shapes (one of GCOO_VARIANT_* > 0). */
 int gcoo_spdm_pick(const gcoo_matrix* A, const float* B_dev, int64_t ldb, int64_t N,
                    const float* C_dev, int64_t ldc);
+
+/*
+ * Context for benchmarks, not part of the GCOO path: a plain CSR row-split SpMM (one wave per row
+ * and 256 columns, no staging, no reuse of B across rows), the kind of routine Section 4 of the
+ * paper compares against.  All pointers are device pointers; C (m x N) is fully overwritten.
+ */
+int gcoo_csr_spmm_baseline(int64_t m, int64_t k, const int32_t* row_ptr_dev, const int32_t* col_idx_dev,
+                           const float* vals_dev, const float* B_dev, int64_t ldb, int64_t N,
+                           float* C_dev, int64_t ldc, void* stream);
 
 /* Release the host handle.  The device buffer stays the caller's.  NULL is accepted. */
 int gcoo_free(gcoo_matrix* A);

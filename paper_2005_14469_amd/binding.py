@@ -22,7 +22,7 @@ VARIANT_AUTO, VARIANT_LDS, VARIANT_REG = 0, 1, 2
 # every symbol include/gcoo.h declares
 SYMBOLS = ["gcoo_device_bytes", "gcoo_from_csr", "gcoo_dense_nnz", "gcoo_from_dense", "gcoo_spdm",
            "gcoo_spdm_variant", "gcoo_spdm_pick", "gcoo_free", "gcoo_info", "gcoo_export",
-           "gcoo_strerror", "gcoo_last_hip_error"]
+           "gcoo_strerror", "gcoo_last_hip_error", "gcoo_csr_spmm_baseline"]
 
 _lib = None
 
@@ -67,6 +67,8 @@ def lib():
         L.gcoo_info.argtypes = [vp, C.POINTER(i64), C.POINTER(i64), C.POINTER(i64), C.POINTER(i32), C.POINTER(i64)]
         L.gcoo_export.restype = C.c_int
         L.gcoo_export.argtypes = [vp, vp, vp, vp, vp, vp, vp]
+        L.gcoo_csr_spmm_baseline.restype = C.c_int
+        L.gcoo_csr_spmm_baseline.argtypes = [i64, i64, vp, vp, vp, vp, i64, i64, vp, i64, vp]
         L.gcoo_strerror.restype = C.c_char_p
         L.gcoo_strerror.argtypes = [C.c_int]
         L.gcoo_last_hip_error.restype = C.c_char_p
@@ -210,3 +212,19 @@ def gcoo_spdm(A: GcooMatrix, B: torch.Tensor, C_out: torch.Tensor | None = None,
 
 def gcoo_spdm_pick(A: GcooMatrix, B: torch.Tensor, C_out: torch.Tensor) -> int:
     return int(lib().gcoo_spdm_pick(A.handle, B.data_ptr(), B.stride(0), B.shape[1], C_out.data_ptr(), C_out.stride(0)))
+
+
+def gcoo_csr_spmm_baseline(m: int, k: int, row_ptr: torch.Tensor, col_idx: torch.Tensor, vals: torch.Tensor,
+                           B: torch.Tensor, C_out: torch.Tensor | None = None, stream=None) -> torch.Tensor:
+    """The plain CSR row-split SpMM kept for comparison (device tensors only)."""
+    assert row_ptr.is_cuda and row_ptr.dtype == torch.int32 and col_idx.dtype == torch.int32 and vals.dtype == torch.float32
+    assert B.is_cuda and B.dtype == torch.float32 and B.dim() == 2 and B.shape[0] == k and (B.stride(1) == 1 or B.shape[1] <= 1)
+    N = B.shape[1]
+    if C_out is None:
+        C_out = torch.empty((m, N), dtype=torch.float32, device=B.device)
+    ldb = B.stride(0) if B.shape[0] > 1 else max(N, 1)
+    ldc = C_out.stride(0) if C_out.shape[0] > 1 else max(N, 1)
+    with torch.cuda.device(B.device):
+        _check(lib().gcoo_csr_spmm_baseline(m, k, row_ptr.data_ptr(), col_idx.data_ptr(), vals.data_ptr(), B.data_ptr(), ldb, N,
+                                            C_out.data_ptr(), ldc, _stream_ptr(stream)), "gcoo_csr_spmm_baseline")
+    return C_out

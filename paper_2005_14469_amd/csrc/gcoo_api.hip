@@ -46,6 +46,7 @@ struct Layout {
     size_t tmp_cols, tmp_rows, tmp_vals;                   // conversion scratch (second sort buffer)
     size_t in_row_ptr, in_cols, in_vals;                   // staging of a host CSR input
     size_t counter;                                        // 8-byte device counter
+    size_t blk;                                            // dense input: entries per (group, column block)
     size_t total;
 };
 
@@ -72,6 +73,16 @@ void pick_windows(int64_t k, int64_t g, int32_t* nw, int32_t* window_cols)
     *window_cols = (int32_t)((k + n - 1) / n > 0 ? (k + n - 1) / n : 1);
 }
 
+// Column blocks of the dense-input kernels: kDenseThreads*vw columns each.  The block table in the
+// layout is sized for vw = 1 (the most blocks).
+int64_t dense_blocks(int64_t k, int vw = 1) { return (k + gcoo::kDenseThreads * vw - 1) / (gcoo::kDenseThreads * vw); }
+
+// 4 when rows of A can be read with 16-byte loads, else 1.
+int dense_vec_width(const float* A, int64_t lda, int64_t k)
+{
+    return (k % 4 == 0 && lda % 4 == 0 && reinterpret_cast<uintptr_t>(A) % 16 == 0) ? 4 : 1;
+}
+
 Layout make_layout(int64_t m, int64_t k, int64_t nnz, int64_t g)
 {
     int32_t nw, wc;
@@ -85,6 +96,7 @@ Layout make_layout(int64_t m, int64_t k, int64_t nnz, int64_t g)
     L.gIdxes = take((size_t)(g + 1) * 4);
     L.nnzPerGroup = take((size_t)g * 4);
     L.counter = take(8);
+    L.blk = take((size_t)g * (size_t)dense_blocks(k) * 4);
     L.values = take(n4);
     L.rows = take(n4);
     L.cols = take(n4);
@@ -269,7 +281,10 @@ int gcoo_dense_nnz(int64_t m, int64_t k, const float* A_dev, int64_t lda, void* 
     unsigned long long got = 0;
     HIP_TRY(hipMemsetAsync(dptr, 0, 8, s));
     const unsigned blocks = (unsigned)(m < 2048 ? m : 2048);
-    gcoo::count_dense_total<<<dim3(blocks), dim3(256), 0, s>>>(A_dev, lda, m, k, dptr);
+    if (dense_vec_width(A_dev, lda, k) == 4)
+        gcoo::count_dense_total<4><<<dim3(blocks), dim3(256), 0, s>>>(A_dev, lda, m, k, dptr);
+    else
+        gcoo::count_dense_total<1><<<dim3(blocks), dim3(256), 0, s>>>(A_dev, lda, m, k, dptr);
     HIP_TRY(hipGetLastError());
     HIP_TRY(hipMemcpyAsync(&got, dptr, 8, hipMemcpyDeviceToHost, s));
     HIP_TRY(hipStreamSynchronize(s));
@@ -293,10 +308,23 @@ int gcoo_from_dense(int64_t m, int64_t k, const float* A_dev, int64_t lda, int32
     char* base = static_cast<char*>(dev_buf);
     int32_t* cnt = reinterpret_cast<int32_t*>(base + L0.nnzPerGroup);
     int32_t* idx = reinterpret_cast<int32_t*>(base + L0.gIdxes);
+    int32_t* blk = reinterpret_cast<int32_t*>(base + L0.blk);
     unsigned long long* tot = reinterpret_cast<unsigned long long*>(base + L0.counter);
     unsigned long long total = 0;
+    const int vw = dense_vec_width(A_dev, lda, k);
+    const int64_t nblk = dense_blocks(k, vw);
+    // one workgroup per (group, column block); a band holds fewer than 2^31 elements so that
+    // 32-bit counts cannot wrap before the total is checked
+    if (nblk > 0 && g > 0x7fffffffLL / nblk) return GCOO_EINVAL;
+    if ((int64_t)p * k > INT32_MAX) return GCOO_EINVAL;
     if (g > 0) {
-        gcoo::count_dense_per_group<<<dim3((unsigned)g), dim3(256), 0, s>>>(A_dev, lda, m, k, p, cnt);
+        if (nblk > 0) {
+            const dim3 grid((unsigned)(nblk * g)), block(gcoo::kDenseThreads);
+            if (vw == 4) gcoo::count_dense_blocks<4><<<grid, block, 0, s>>>(A_dev, lda, m, k, p, nblk, blk);
+            else gcoo::count_dense_blocks<1><<<grid, block, 0, s>>>(A_dev, lda, m, k, p, nblk, blk);
+            HIP_TRY(hipGetLastError());
+        }
+        gcoo::scan_dense_blocks<<<dim3((unsigned)g), dim3(256), 0, s>>>(blk, nblk, cnt);
         HIP_TRY(hipGetLastError());
         gcoo::scan_group_counts<<<dim3(1), dim3(256), 0, s>>>(cnt, g, idx, tot);
         HIP_TRY(hipGetLastError());
@@ -313,10 +341,13 @@ int gcoo_from_dense(int64_t m, int64_t k, const float* A_dev, int64_t lda, int32
     int rc = new_handle(m, k, nnz, p, dev_buf, &h);
     if (rc != GCOO_OK) return rc;
     if (g > 0 && nnz > 0) {
-        gcoo::fill_from_dense<<<dim3((unsigned)g), dim3(64), 0, s>>>(A_dev, lda, m, k, p, h->gIdxes(), h->values(),
-                                                                     h->rows(), h->cols());
+        const dim3 grid((unsigned)(nblk * g)), block(gcoo::kDenseThreads);
+        if (vw == 4)
+            gcoo::fill_dense_blocks<4><<<grid, block, 0, s>>>(A_dev, lda, m, k, p, nblk, h->gIdxes(), blk, h->values(), h->rows(), h->cols());
+        else
+            gcoo::fill_dense_blocks<1><<<grid, block, 0, s>>>(A_dev, lda, m, k, p, nblk, h->gIdxes(), blk, h->values(), h->rows(), h->cols());
         hipError_t e = hipGetLastError();
-        if (e != hipSuccess) { delete h; return hip_fail(e, "fill_from_dense"); }
+        if (e != hipSuccess) { delete h; return hip_fail(e, "fill_dense_blocks"); }
     }
     rc = launch_build_schedule(h, s);
     if (rc != GCOO_OK) { delete h; return rc; }

@@ -167,25 +167,92 @@ __global__ __launch_bounds__(kSortWaves * kWave) void sort_groups_by_col_digit(
 }
 
 // ---------------------------------------------------------------------------------------------
-// Algorithm 1, step 1 for a dense input: entries != 0 per group.  One workgroup per group;
-// threads stride over the band row by row (coalesced), block-reduce, one write.
+// Algorithm 1 for a dense input.  The band of group q (pb rows x k columns) is cut into blocks of
+// kDenseThreads*VW columns; workgroup (block, q) gives every thread VW adjacent columns, and the
+// threads of a wave read 64*VW adjacent floats of a row at a time (coalesced), row after row.
+//
+// Step 1 (count_dense_blocks): entries != 0 per block.  scan_dense_blocks then turns the counts
+// of a group into offsets (exclusive prefix sum over its blocks) and their sum into
+// nnzPerGroup[q]; scan_group_counts makes gIdxes from that.
 // ---------------------------------------------------------------------------------------------
-__global__ __launch_bounds__(256) void count_dense_per_group(const float* __restrict__ A, int64_t lda, int64_t m, int64_t k,
-                                                              int32_t p, int32_t* __restrict__ nnzPerGroup)
+constexpr int kDenseThreads = 256;
+
+// VW adjacent floats of a row: one 16-byte load when VW = 4 (the launcher checks alignment).
+template <int VW>
+struct DenseVec { float x[VW]; };
+
+template <int VW>
+__device__ __forceinline__ DenseVec<VW> load_dense(const float* a)
 {
-    __shared__ int32_t part[4];
-    const int64_t q = blockIdx.x;
-    const int64_t r0 = q * p, r1 = (r0 + p < m) ? r0 + p : m;
-    int32_t n = 0;
-    for (int64_t r = r0; r < r1; ++r) {
-        const float* a = A + r * lda;
-        for (int64_t j = threadIdx.x; j < k; j += 256) n += (a[j] != 0.0f) ? 1 : 0;
+    DenseVec<VW> v;
+    if constexpr (VW == 4) {
+        const float4 t = *reinterpret_cast<const float4*>(a);
+        v.x[0] = t.x; v.x[1] = t.y; v.x[2] = t.z; v.x[3] = t.w;
+    } else {
+        v.x[0] = *a;
     }
+    return v;
+}
+
+__device__ __forceinline__ int32_t block_sum_256(int32_t n, int32_t* part)
+{
 #pragma unroll
     for (int d = 32; d >= 1; d >>= 1) n += __shfl_down(n, d, kWave);
     if ((threadIdx.x & 63) == 0) part[threadIdx.x >> 6] = n;
     __syncthreads();
-    if (threadIdx.x == 0) nnzPerGroup[q] = part[0] + part[1] + part[2] + part[3];
+    return part[0] + part[1] + part[2] + part[3];
+}
+
+// Thread t of block b owns columns (b*kDenseThreads + t)*VW .. +VW-1 of the band (k % VW == 0 when VW > 1).
+template <int VW>
+__global__ __launch_bounds__(kDenseThreads) void count_dense_blocks(const float* __restrict__ A, int64_t lda, int64_t m, int64_t k,
+                                                                     int32_t p, int64_t nblk, int32_t* __restrict__ blk_cnt)
+{
+    __shared__ int32_t part[4];
+    const int64_t q = blockIdx.x / nblk, b = blockIdx.x - q * nblk;      // blockIdx.x = q*nblk + b
+    const int64_t c = (b * kDenseThreads + threadIdx.x) * VW;
+    const int64_t r0 = q * p, r1 = (r0 + p < m) ? r0 + p : m;
+    int32_t n = 0;
+    if (c < k) {
+        const float* a = A + r0 * lda + c;
+        for (int64_t r = r0; r < r1; ++r, a += lda) {
+            const DenseVec<VW> v = load_dense<VW>(a);
+#pragma unroll
+            for (int u = 0; u < VW; ++u) n += (v.x[u] != 0.0f) ? 1 : 0;
+        }
+    }
+    const int32_t tot = block_sum_256(n, part);
+    if (threadIdx.x == 0) blk_cnt[blockIdx.x] = tot;
+}
+
+// One workgroup per group: blk[q][0..nblk) counts -> exclusive offsets in place, sum -> nnzPerGroup[q].
+__global__ __launch_bounds__(256) void scan_dense_blocks(int32_t* __restrict__ blk, int64_t nblk, int32_t* __restrict__ nnzPerGroup)
+{
+    __shared__ int32_t wsum[4];
+    __shared__ int32_t carry_s;
+    if (threadIdx.x == 0) carry_s = 0;
+    __syncthreads();
+    const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
+    int32_t* b = blk + (int64_t)blockIdx.x * nblk;
+    for (int64_t t0 = 0; t0 < nblk; t0 += 256) {
+        const int64_t i = t0 + threadIdx.x;
+        const int32_t v = (i < nblk) ? b[i] : 0;
+        int32_t incl = v;
+#pragma unroll
+        for (int d = 1; d < kWave; d <<= 1) {
+            const int32_t t = __shfl_up(incl, d, kWave);
+            if (lane >= d) incl += t;
+        }
+        if (lane == 63) wsum[w] = incl;
+        __syncthreads();
+        int32_t off = carry_s;
+        for (int j = 0; j < w; ++j) off += wsum[j];
+        if (i < nblk) b[i] = off + incl - v;
+        __syncthreads();
+        if (threadIdx.x == 255) carry_s = off + incl;
+        __syncthreads();
+    }
+    if (threadIdx.x == 0) nnzPerGroup[blockIdx.x] = carry_s;
 }
 
 // Exclusive prefix sum of nnzPerGroup[g] into gIdxes[g+1] (sentinel = total).  One workgroup;
@@ -224,54 +291,83 @@ __global__ __launch_bounds__(256) void scan_group_counts(const int32_t* __restri
 }
 
 // ---------------------------------------------------------------------------------------------
-// Algorithm 1, step 2 for a dense input.  One wave per group.  The band (pb rows x k columns)
-// is walked in column-major order, 64 elements at a time: element index t -> column t / pb,
-// band row t % pb.  A ballot of "!= 0" gives each nonzero its rank among the 64, a running
-// count carries over, and the entry is written straight to its final slot: the output is in
-// (column, row) order with no sort.  Reads of one 64-chunk touch pb rows x (64/pb) columns;
-// consecutive chunks reuse the same cache lines.
+// Algorithm 1, step 2 for a dense input (fill_dense_blocks), same blocks as step 1.  Inside a
+// group the entries are ordered by (column, row), so the entries of block b come right after
+// those of blocks 0..b-1, column by column, and inside a column by row.  Thread c counts the
+// entries of its column, a workgroup-wide exclusive prefix sum of those counts gives the first
+// slot of every column, and the thread walks its column a second time (now from cache) and
+// writes each entry to its final slot.  No sort, no atomics: the slot of an entry is a
+// function of the matrix alone.
 // ---------------------------------------------------------------------------------------------
-__global__ __launch_bounds__(kWave) void fill_from_dense(const float* __restrict__ A, int64_t lda, int64_t m, int64_t k,
-                                                         int32_t p, const int32_t* __restrict__ gIdxes,
-                                                         float* __restrict__ values, int32_t* __restrict__ rows,
-                                                         int32_t* __restrict__ cols)
+template <int VW>
+__global__ __launch_bounds__(kDenseThreads) void fill_dense_blocks(const float* __restrict__ A, int64_t lda, int64_t m, int64_t k,
+                                                                    int32_t p, int64_t nblk, const int32_t* __restrict__ gIdxes,
+                                                                    const int32_t* __restrict__ blk_off, float* __restrict__ values,
+                                                                    int32_t* __restrict__ rows, int32_t* __restrict__ cols)
 {
-    const int lane = threadIdx.x;
-    const int64_t q = blockIdx.x;
-    const int64_t r0 = q * p;
-    const int64_t pb = (r0 + p < m) ? p : (m - r0);       // rows in this band
-    const int64_t total = pb * k;
-    int64_t at = gIdxes[q];
-    const uint64_t lt = lanemask_lt();
-    for (int64_t t0 = 0; t0 < total; t0 += kWave) {
-        const int64_t t = t0 + lane;
-        float a = 0.0f;
-        int64_t c = 0, r = 0;
-        if (t < total) {
-            c = t / pb;
-            r = r0 + (t - c * pb);
-            a = A[r * lda + c];
+    __shared__ int32_t wsum[4];
+    const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
+    const int64_t q = blockIdx.x / nblk, b = blockIdx.x - q * nblk;      // blockIdx.x = q*nblk + b
+    const int64_t c = (b * kDenseThreads + threadIdx.x) * VW;
+    const int64_t r0 = q * p, r1 = (r0 + p < m) ? r0 + p : m;
+    const float* col0 = A + r0 * lda + c;
+    int32_t n[VW];
+#pragma unroll
+    for (int u = 0; u < VW; ++u) n[u] = 0;
+    if (c < k) {
+        const float* a = col0;
+        for (int64_t r = r0; r < r1; ++r, a += lda) {
+            const DenseVec<VW> v = load_dense<VW>(a);
+#pragma unroll
+            for (int u = 0; u < VW; ++u) n[u] += (v.x[u] != 0.0f) ? 1 : 0;
         }
-        const bool nz = (t < total) && (a != 0.0f);
-        const uint64_t bal = __ballot(nz);
-        if (nz) {
-            const int64_t slot = at + __popcll(bal & lt);
-            values[slot] = a;
-            rows[slot] = (int32_t)r;
-            cols[slot] = (int32_t)c;
+    }
+    int32_t mine = 0;
+#pragma unroll
+    for (int u = 0; u < VW; ++u) mine += n[u];
+    int32_t incl = mine;
+#pragma unroll
+    for (int d = 1; d < kWave; d <<= 1) {
+        const int32_t t = __shfl_up(incl, d, kWave);
+        if (lane >= d) incl += t;
+    }
+    if (lane == 63) wsum[w] = incl;
+    __syncthreads();
+    int32_t first = gIdxes[q] + blk_off[blockIdx.x] + incl - mine;       // slot of the first entry of this thread's columns
+    for (int j = 0; j < w; ++j) first += wsum[j];
+    if (c < k && mine > 0) {
+        int32_t at[VW];
+#pragma unroll
+        for (int u = 0; u < VW; ++u) { at[u] = first; first += n[u]; }
+        const float* a = col0;
+        for (int64_t r = r0; r < r1; ++r, a += lda) {
+            const DenseVec<VW> v = load_dense<VW>(a);
+#pragma unroll
+            for (int u = 0; u < VW; ++u) {
+                if (v.x[u] != 0.0f) {
+                    values[at[u]] = v.x[u];
+                    rows[at[u]] = (int32_t)r;
+                    cols[at[u]] = (int32_t)(c + u);
+                    ++at[u];
+                }
+            }
         }
-        at += __popcll(bal);
     }
 }
 
 // Total count of entries != 0 of a dense matrix (Algorithm 1, step 1, without the grouping).
+template <int VW>
 __global__ __launch_bounds__(256) void count_dense_total(const float* __restrict__ A, int64_t lda, int64_t m, int64_t k,
                                                           unsigned long long* __restrict__ total)
 {
     unsigned long long n = 0;
     for (int64_t r = blockIdx.x; r < m; r += gridDim.x) {
         const float* a = A + r * lda;
-        for (int64_t j = threadIdx.x; j < k; j += 256) n += (a[j] != 0.0f) ? 1u : 0u;
+        for (int64_t j = (int64_t)threadIdx.x * VW; j < k; j += 256 * VW) {
+            const DenseVec<VW> v = load_dense<VW>(a + j);
+#pragma unroll
+            for (int u = 0; u < VW; ++u) n += (v.x[u] != 0.0f) ? 1u : 0u;
+        }
     }
 #pragma unroll
     for (int d = 32; d >= 1; d >>= 1) n += __shfl_down(n, d, kWave);

@@ -114,8 +114,8 @@ def test_gcoo_empty_shapes():
             assert C.shape == (m, 8) and not C.any()
 
 
-@pytest.mark.parametrize("p", [1, 4, 32, 50, 128])
-@pytest.mark.parametrize("shape", [(1, 1), (37, 29), (256, 256), (300, 1111)])
+@pytest.mark.parametrize("p", [1, 4, 32, 50, 128, 256])
+@pytest.mark.parametrize("shape", [(1, 1), (37, 29), (256, 256), (300, 1111), (2000, 3001)])
 def test_gcoo_from_dense_bit_exact(p, shape):
     m, k = shape
     _say(f"gcoo_from_dense m={m} k={k} p={p}")
@@ -306,3 +306,19 @@ def test_full_size_configs_sampled_rows(index):
         C64, D64 = orc.spdm_csr(w.k, w.N, w.row_ptr, w.col_idx, w.vals, w.B, r0, r1)
         err, bad = orc.max_scaled_error(Cg[r0:r1].cpu().numpy(), C64, D64)
         assert bad == 0 and err <= TOL, (q, err, bad)
+
+
+@pytest.mark.parametrize("shape", [(300, 200, 1028), (77, 500, 250), (1, 1, 1)])
+def test_csr_baseline_kernel(shape):
+    """The comparison kernel of the benchmark is held to the same bound as the path itself."""
+    m, k, N = shape
+    _say(f"csr baseline m={m} k={k} N={N}")
+    w = workloads.uniform_random(m, k, N, 0.8, seed=m + N)
+    args = [torch.from_numpy(x).to(DEV) for x in (w.row_ptr, w.col_idx, w.vals)]
+    Bt = torch.from_numpy(w.B).to(DEV)
+    Cg = torch.full((m, N), float("nan"), dtype=torch.float32, device=DEV)
+    binding.gcoo_csr_spmm_baseline(m, k, *args, Bt, Cg)
+    torch.cuda.synchronize()
+    C64, D64 = orc.spdm_csr(w.k, N, w.row_ptr, w.col_idx, w.vals, w.B)
+    err, bad = orc.max_scaled_error(Cg.cpu().numpy(), C64, D64)
+    assert bad == 0 and err <= TOL
