@@ -55,6 +55,16 @@ typedef enum gcoo_status {
 typedef struct gcoo_matrix gcoo_matrix;
 
 /*
+ * Group height to use when the caller has no better idea (the paper leaves p to a tuner, Section 5).
+ * 32 is the tallest group the widest instance of the register kernel holds (32 rows x 4 columns
+ * per lane); on MI355X it was the fastest of {4, 8, 16, 32, 64} for uniform random matrices of
+ * density 0.001 .. 0.5, for a power-law row-length matrix and for a diagonal one.  A caller that
+ * multiplies the same matrix many times can do better by timing a few values (the Python binding
+ * has gcoo_tune_p for that).  Pure host arithmetic; 0 for invalid arguments.
+ */
+int32_t gcoo_default_p(int64_t m, int64_t k, int64_t nnz, int64_t N);
+
+/*
  * Device bytes a gcoo_from_csr() / gcoo_from_dense() call needs in dev_buf for an m x k matrix
  * with nnz stored entries and group height p: the five arrays of Section 3.1 (Table 1:
  * 3*nnz + 2*g elements, plus one sentinel), the run schedule derived from them for the register

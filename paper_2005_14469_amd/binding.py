@@ -20,7 +20,7 @@ GCOO_MAX_P = 256
 VARIANT_AUTO, VARIANT_LDS, VARIANT_REG = 0, 1, 2
 
 # every symbol include/gcoo.h declares
-SYMBOLS = ["gcoo_device_bytes", "gcoo_from_csr", "gcoo_dense_nnz", "gcoo_from_dense", "gcoo_spdm",
+SYMBOLS = ["gcoo_default_p", "gcoo_device_bytes", "gcoo_from_csr", "gcoo_dense_nnz", "gcoo_from_dense", "gcoo_spdm",
            "gcoo_spdm_variant", "gcoo_spdm_pick", "gcoo_free", "gcoo_info", "gcoo_export",
            "gcoo_strerror", "gcoo_last_hip_error", "gcoo_csr_spmm_baseline"]
 
@@ -67,6 +67,8 @@ def lib():
         L.gcoo_info.argtypes = [vp, C.POINTER(i64), C.POINTER(i64), C.POINTER(i64), C.POINTER(i32), C.POINTER(i64)]
         L.gcoo_export.restype = C.c_int
         L.gcoo_export.argtypes = [vp, vp, vp, vp, vp, vp, vp]
+        L.gcoo_default_p.restype = C.c_int32
+        L.gcoo_default_p.argtypes = [i64, i64, i64, i64]
         L.gcoo_csr_spmm_baseline.restype = C.c_int
         L.gcoo_csr_spmm_baseline.argtypes = [i64, i64, vp, vp, vp, vp, i64, i64, vp, i64, vp]
         L.gcoo_strerror.restype = C.c_char_p
@@ -228,3 +230,42 @@ def gcoo_csr_spmm_baseline(m: int, k: int, row_ptr: torch.Tensor, col_idx: torch
         _check(lib().gcoo_csr_spmm_baseline(m, k, row_ptr.data_ptr(), col_idx.data_ptr(), vals.data_ptr(), B.data_ptr(), ldb, N,
                                             C_out.data_ptr(), ldc, _stream_ptr(stream)), "gcoo_csr_spmm_baseline")
     return C_out
+
+
+def gcoo_default_p(m: int, k: int, nnz: int, N: int) -> int:
+    return int(lib().gcoo_default_p(m, k, nnz, N))
+
+
+def gcoo_tune_p(m: int, k: int, row_ptr, col_idx, vals, B: torch.Tensor, candidates=(8, 16, 32, 64), reps: int = 5,
+                include_conversion: bool = False):
+    """Times conversion + product for each group height and returns (best p, {p: ms}).
+
+    The tuner the paper leaves as future work (Section 5), in its simplest form: the matrix and a
+    B of the real width are needed, nothing is modelled.  With include_conversion the time of
+    the conversion counts too (a matrix that is multiplied once)."""
+    C_out = torch.empty((m, B.shape[1]), dtype=torch.float32, device=B.device)
+    times = {}
+    for p in candidates:
+        A = gcoo_from_csr(m, k, row_ptr, col_idx, vals, p, device=B.device)
+        holder = [A]
+
+        def step():
+            if include_conversion:
+                holder[0].free()
+                holder[0] = gcoo_from_csr(m, k, row_ptr, col_idx, vals, p, device=B.device)
+            gcoo_spdm(holder[0], B, C_out)
+
+        step()
+        torch.cuda.synchronize()
+        ts = []
+        for _ in range(reps):
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record()
+            step()
+            e1.record()
+            torch.cuda.synchronize()
+            ts.append(e0.elapsed_time(e1))
+        ts.sort()
+        times[p] = ts[len(ts) // 2]
+        holder[0].free()
+    return min(times, key=times.get), times

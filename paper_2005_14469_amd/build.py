@@ -65,11 +65,12 @@ def verify_generated_code() -> None:
         asm = os.path.join(OBJ, f"{stem}-hip-amdgcn-amd-amdhsa-gfx950.s")
         text = open(asm).read()
         v = stem.rsplit("v", 1)[1]
-        regs, bad = isa_check.check(text, f"_ZN4gcoo10spdm_schedILi{v}E")
-        if not regs:
-            raise RuntimeError(f"{stem}: no asm-issued loads found in the generated code (check is blind)")
-        if bad:
-            raise RuntimeError(f"{stem}: {len(bad)} instructions touch registers with a load in flight, e.g. {bad[:3]}")
+        for kernel in (f"_ZN4gcoo10spdm_schedILi{v}E", f"_ZN4gcoo15spdm_sched_coopILi{v}E"):
+            regs, bad = isa_check.check(text, kernel)
+            if not regs:
+                raise RuntimeError(f"{stem}: no asm-issued loads found in {kernel} (check is blind)")
+            if bad:
+                raise RuntimeError(f"{stem} {kernel}: {len(bad)} instructions touch registers with a load in flight, e.g. {bad[:3]}")
 
 
 def build(force: bool = True, jobs: int = 8) -> str:

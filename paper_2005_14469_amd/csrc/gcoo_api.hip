@@ -175,6 +175,12 @@ int launch_build_schedule(const gcoo_matrix* h, hipStream_t s)
 
 extern "C" {
 
+int32_t gcoo_default_p(int64_t m, int64_t k, int64_t nnz, int64_t N)
+{
+    if (m < 0 || k < 0 || nnz < 0 || N < 0) return 0;
+    return 32;
+}
+
 size_t gcoo_device_bytes(int64_t m, int64_t k, int64_t nnz, int32_t p)
 {
     if (!dims_ok(m, k, nnz, p)) return 0;
@@ -389,6 +395,27 @@ int sched_width(int32_t p, const Shape& sh)
 
 }  // namespace
 
+namespace {
+
+// When the launch has too few (group, tile) items to fill the machine, the longest group sets
+// the run time: groups well above the mean load of a wave slot are then shared by the eight
+// waves of a workgroup (spdm_sched_coop).  Returns the entry count from which a group is
+// treated that way, INT32_MAX for "none".  The groups' sizes are not known on the host, so the
+// threshold comes from totals only.
+int32_t heavy_group_min(const gcoo_matrix* A, int64_t tiles)
+{
+    constexpr int64_t kWaveSlots = 2048;                   // 256 compute units x 8 resident waves of the register kernel
+    constexpr int64_t kMinHeavy = 1024;
+    const int64_t items = A->g * tiles;
+    if (items <= 0 || items > 2 * kWaveSlots || A->nnz <= 0) return INT32_MAX;
+    const int64_t mean_per_slot = A->nnz * tiles / kWaveSlots;
+    int64_t t = mean_per_slot + mean_per_slot / 2;
+    if (t < kMinHeavy) t = kMinHeavy;
+    return t >= INT32_MAX ? INT32_MAX : (int32_t)t;
+}
+
+}  // namespace
+
 namespace gcoo {
 hipError_t launch_spdm_sched(int V, const SpdmArgs& a, hipStream_t s)
 {
@@ -442,7 +469,8 @@ int gcoo_spdm_variant(const gcoo_matrix* A, const float* B_dev, int64_t ldb, int
     }
     const int V = sched_width(A->p, shape_of(B_dev, ldb, N, C_dev, ldc));
     if (V == 0) return GCOO_EINVAL;
-    gcoo::SpdmArgs a{A->sched_hdr(), A->sched(), A->gIdxes(), A->m, A->p, A->g, A->nw, B_dev, ldb, N, C_dev, ldc};
+    gcoo::SpdmArgs a{A->sched_hdr(), A->sched(), A->gIdxes(), A->m, A->p, A->g, A->nw, B_dev, ldb, N, C_dev, ldc,
+                     heavy_group_min(A, (N + 64 * V - 1) / (64 * V))};
     hipError_t e = gcoo::launch_spdm_sched(V, a, s);
     if (e != hipSuccess) return hip_fail(e, "spdm_sched launch");
     return GCOO_OK;

@@ -57,6 +57,14 @@ __device__ __forceinline__ float acc_get(const AccFile& acc, int reg)
     return t == 0 ? acc.t1[i] : (t == 1 ? acc.t2[i] : (t == 2 ? acc.t3[i] : acc.t4[i]));
 }
 
+__device__ __forceinline__ void acc_add(AccFile& acc, int reg, float x)
+{
+    const int s = reg - kAccFirst;
+    if (s < 4) { acc.t0[s] += x; return; }
+    const int t = (s - 4) >> 5, i = (s - 4) & 31;
+    if (t == 0) acc.t1[i] += x; else if (t == 1) acc.t2[i] += x; else if (t == 2) acc.t3[i] += x; else acc.t4[i] += x;
+}
+
 // Instruction text.  GCOO_FMA_Vn(i): the V multiply-adds of entry i of a run (operands a<i> =
 // the entry's value, the same in every lane of a VGPR; b0..b3 = the run's B segment).  GCOO_ENT(i) = select row c<i>, then those.
 #define GCOO_FMA_V1(i) "v_fma_f32 v124, %[a" #i "], %[b0], v124\n\t"
@@ -194,13 +202,19 @@ constexpr int kLineWords = 128;
 // so the wait before chunk 4b+st leaves 3J+1 loads in flight for st = 0..2 and 3J for st = 3; after
 // that last wait line(b+2) has arrived and is written to LDS.  Loads are in flight across the
 // back-edge of the loop and from the start-up into the loop; the class ends with vmcnt(0).
-template <int L, int V>
-__device__ __forceinline__ void run_class(AccFile& acc, const uint32_t* seg, int32_t nb, const char* Bbytes, uint32_t ldb4,
-                                          uint32_t lane_off, const lds_u32* ring, uint32_t ring_lds, int lane)
+//
+// SUB: the caller works on bodies [b0, b1) of the segment only (a group shared by the waves of
+// a workgroup).  The columns of the first three chunks of body b0 > 0 are not in a pre-block of
+// their own: they are the last three column slots of block b0-1, so that block's line is
+// fetched once at start-up.  The loads that the last turn starts for chunks past b1 fetch rows
+// that belong to the next part of the segment (or the padding columns): valid rows, ignored.
+template <int L, int V, bool SUB = false>
+__device__ __forceinline__ void run_class(AccFile& acc, const uint32_t* seg, int32_t b0, int32_t b1, const char* Bbytes,
+                                          uint32_t ldb4, uint32_t lane_off, const lds_u32* ring, uint32_t ring_lds, int lane)
 {
     constexpr int J = runs_per_chunk(L), RP = rowpack_dwords(L), VS = val_stride(L), BD = block_dwords(L), PRE = pre_dwords(L);
     static_assert(kBody == 4 && PRE + BD <= kLineWords, "a line holds the lead and one block; four load buffers rotate");
-    if (nb <= 0) return;
+    if (b1 <= b0) return;
     float bq[kBody][J][V];
     const uint32_t lane8 = (uint32_t)lane * 8u;
 
@@ -209,15 +223,25 @@ __device__ __forceinline__ void run_class(AccFile& acc, const uint32_t* seg, int
         for (int j = 0; j < J; ++j) load_b_async<V>(Bbytes + (uint64_t)col[j] * ldb4, lane_off, dst[j]);
     };
 
-    // start: lines 0 and 1 to LDS, then chunks 0..2 in flight (their columns are the pre-block)
+    // start: lines b0 and b0+1 to LDS, then chunks 0..2 of body b0 in flight
     {
-        u32x2 l0 = load_line_async(seg, lane8);
-        u32x2 l1 = load_line_async(seg + (int64_t)(nb > 1 ? 1 : 0) * BD, lane8);
-        wait_vm<0>();
+        u32x2 l0 = load_line_async(seg + (int64_t)b0 * BD, lane8);
+        u32x2 l1 = load_line_async(seg + (int64_t)(b0 + 1 < b1 ? b0 + 1 : b0) * BD, lane8);
+        const lds_u32* pre = ring;                                         // the three chunks' columns sit at pre[J .. 4J)
+        if constexpr (SUB) {
+            // (b0 > 0 is wave-uniform; both sides issue the same number of loads so that the
+            // waits below hold on either path)
+            u32x2 lp = load_line_async(seg + (int64_t)(b0 > 0 ? b0 - 1 : 0) * BD, lane8);
+            wait_vm<0>();
+            store_line_lds(ring_lds + 2 * kLineWords * 4 + lane8, lp);
+            if (b0 > 0) pre = ring + 2 * kLineWords + PRE;
+        } else {
+            wait_vm<0>();
+        }
         store_line_lds(ring_lds + lane8, l0);
         store_line_lds(ring_lds + kLineWords * 4 + lane8, l1);
         uint32_t c0[PRE];
-        read_ring4<PRE>(ring, c0);
+        read_ring4<PRE>(pre, c0);
 #pragma unroll
         for (int i = J; i < PRE; ++i) c0[i] = __builtin_amdgcn_readfirstlane(c0[i]);
         issue(&c0[J], bq[0]);
@@ -225,10 +249,10 @@ __device__ __forceinline__ void run_class(AccFile& acc, const uint32_t* seg, int
         issue(&c0[3 * J], bq[2]);
     }
 
-    int32_t slot = 0;                                                      // b % kRing
-    for (int32_t b = 0; b < nb; ++b) {
+    int32_t slot = 0;                                                      // (b - b0) % kRing
+    for (int32_t b = b0; b < b1; ++b) {
         const lds_u32* blk = ring + slot * kLineWords + PRE;
-        const int32_t nxt = b + 2 < nb ? b + 2 : nb - 1;
+        const int32_t nxt = b + 2 < b1 ? b + 2 : b1 - 1;
         u32x2 ln = load_line_async(seg + (int64_t)nxt * BD, lane8);
         uint32_t col[kBody * J], rpk[kBody * RP];
         read_ring4<kBody * J>(blk, col);
@@ -254,7 +278,7 @@ __device__ __forceinline__ void run_class(AccFile& acc, const uint32_t* seg, int
                 run_fma<L, V>(acc, r, &va[j * L], bq[st][j]);
             }
         }
-        const int32_t wslot = slot == 0 ? 2 : slot - 1;                    // (b + 2) % kRing
+        const int32_t wslot = slot == 0 ? 2 : slot - 1;                    // (b - b0 + 2) % kRing
         store_line_lds(ring_lds + (uint32_t)wslot * (kLineWords * 4) + lane8, ln);
         slot = slot == kRing - 1 ? 0 : slot + 1;
     }
@@ -265,7 +289,7 @@ template <int V>
 __global__ __launch_bounds__(64) void spdm_sched(const SchedClass* __restrict__ hdr, const uint32_t* __restrict__ stream,
                                                  const int32_t* __restrict__ gIdxes, int64_t m, int32_t p, int64_t g,
                                                  int32_t nw, const float* __restrict__ B, int64_t ldb, int64_t N, float* __restrict__ C,
-                                                 int64_t ldc, int64_t total)
+                                                 int64_t ldc, int64_t total, int32_t heavy_min)
 {
     // XCD-aware order: workgroup ids go round-robin over the 8 XCDs, so XCD x is given the
     // contiguous slice [x*per, (x+1)*per) of the (tile-major) work list: it walks through all
@@ -276,6 +300,9 @@ __global__ __launch_bounds__(64) void spdm_sched(const SchedClass* __restrict__ 
     const int64_t w = (int64_t)(bid & 7u) * per + (bid >> 3);
     if (w >= total) return;
     const int64_t tile = w / g, q = w - tile * g;
+    // groups with heavy_min entries or more are left to spdm_sched_coop (launched beside this kernel)
+    const int32_t first_entry = __builtin_amdgcn_readfirstlane(gIdxes[q]);
+    if (__builtin_amdgcn_readfirstlane(gIdxes[q + 1]) - first_entry >= heavy_min) return;
 
     const int lane = threadIdx.x;
     const int64_t j0 = tile * (64 * V) + (int64_t)lane * V;
@@ -296,7 +323,7 @@ __global__ __launch_bounds__(64) void spdm_sched(const SchedClass* __restrict__ 
 
     // window by window (a band of B that stays in L2), class by class.  The header words are
     // made scalar by hand: after the volatile LDS reads the compiler no longer does it itself.
-    const uint32_t* gs = stream + sched_group_base(__builtin_amdgcn_readfirstlane(gIdxes[q]), q, nw);
+    const uint32_t* gs = stream + sched_group_base(first_entry, q, nw);
     const SchedClass* h = hdr + q * nw * kMaxRun;
     for (int32_t w8 = 0; w8 < nw * kMaxRun; w8 += kMaxRun) {
         int32_t fw[kMaxRun], nb[kMaxRun];
@@ -305,14 +332,14 @@ __global__ __launch_bounds__(64) void spdm_sched(const SchedClass* __restrict__ 
             fw[i] = __builtin_amdgcn_readfirstlane(h[w8 + i].first_word);
             nb[i] = __builtin_amdgcn_readfirstlane(h[w8 + i].bodies);
         }
-        run_class<1, V>(acc, gs + fw[0], nb[0], Bbytes, ldb4, lane_off, ring, ring_lds, lane);
-        run_class<2, V>(acc, gs + fw[1], nb[1], Bbytes, ldb4, lane_off, ring, ring_lds, lane);
-        run_class<3, V>(acc, gs + fw[2], nb[2], Bbytes, ldb4, lane_off, ring, ring_lds, lane);
-        run_class<4, V>(acc, gs + fw[3], nb[3], Bbytes, ldb4, lane_off, ring, ring_lds, lane);
-        run_class<5, V>(acc, gs + fw[4], nb[4], Bbytes, ldb4, lane_off, ring, ring_lds, lane);
-        run_class<6, V>(acc, gs + fw[5], nb[5], Bbytes, ldb4, lane_off, ring, ring_lds, lane);
-        run_class<7, V>(acc, gs + fw[6], nb[6], Bbytes, ldb4, lane_off, ring, ring_lds, lane);
-        run_class<8, V>(acc, gs + fw[7], nb[7], Bbytes, ldb4, lane_off, ring, ring_lds, lane);
+        run_class<1, V>(acc, gs + fw[0], 0, nb[0], Bbytes, ldb4, lane_off, ring, ring_lds, lane);
+        run_class<2, V>(acc, gs + fw[1], 0, nb[1], Bbytes, ldb4, lane_off, ring, ring_lds, lane);
+        run_class<3, V>(acc, gs + fw[2], 0, nb[2], Bbytes, ldb4, lane_off, ring, ring_lds, lane);
+        run_class<4, V>(acc, gs + fw[3], 0, nb[3], Bbytes, ldb4, lane_off, ring, ring_lds, lane);
+        run_class<5, V>(acc, gs + fw[4], 0, nb[4], Bbytes, ldb4, lane_off, ring, ring_lds, lane);
+        run_class<6, V>(acc, gs + fw[5], 0, nb[5], Bbytes, ldb4, lane_off, ring, ring_lds, lane);
+        run_class<7, V>(acc, gs + fw[6], 0, nb[6], Bbytes, ldb4, lane_off, ring, ring_lds, lane);
+        run_class<8, V>(acc, gs + fw[7], 0, nb[7], Bbytes, ldb4, lane_off, ring, ring_lds, lane);
     }
 
     // epilogue: each lane stores its V adjacent columns of every row of the group (coalesced
@@ -343,6 +370,109 @@ __global__ __launch_bounds__(64) void spdm_sched(const SchedClass* __restrict__ 
     }
 }
 
+// ---------------------------------------------------------------------------------------------
+// A group with many entries, shared by the kCoopWaves waves of one workgroup (the nnz-balanced
+// splitting that the paper leaves as future work, Section 5).  All waves work on the same
+// (group, column tile): wave w takes the w-th part of the bodies of every class segment, keeps
+// partial sums of its own, and the partial sums are added up through LDS in wave order
+// (((w0 + w1) + w2) + ...), so the result does not depend on timing.  Wave 0 stores C.
+// One workgroup per (tile, group); workgroups of groups below heavy_min return at once (those
+// groups are computed by spdm_sched).
+// ---------------------------------------------------------------------------------------------
+constexpr int kCoopWaves = 8;
+
+template <int V>
+__global__ __launch_bounds__(64 * kCoopWaves) void spdm_sched_coop(const SchedClass* __restrict__ hdr, const uint32_t* __restrict__ stream,
+                                                                   const int32_t* __restrict__ gIdxes, int64_t m, int32_t p, int64_t g,
+                                                                   int32_t nw, const float* __restrict__ B, int64_t ldb, int64_t N,
+                                                                   float* __restrict__ C, int64_t ldc, int64_t total, int32_t heavy_min)
+{
+    constexpr int S = acc_stride<V>(), P = S - 1;          // rows an instance can hold
+    __shared__ __attribute__((aligned(16))) uint32_t ring_mem[kCoopWaves][kRing * kLineWords];
+    __shared__ __attribute__((aligned(16))) float part[P * 64 * V];        // one wave's partial sums: [row][lane][V]
+
+    const int64_t w = blockIdx.x;                          // tile-major like spdm_sched
+    if (w >= total) return;
+    const int64_t tile = w / g, q = w - tile * g;
+    const int32_t first_entry = __builtin_amdgcn_readfirstlane(gIdxes[q]);
+    if (__builtin_amdgcn_readfirstlane(gIdxes[q + 1]) - first_entry < heavy_min) return;   // the whole workgroup
+
+    const int lane = threadIdx.x & 63;
+    const int wv = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const int64_t j0 = tile * (64 * V) + (int64_t)lane * V;
+    const bool in = j0 < N;
+    const char* Bbytes = reinterpret_cast<const char*>(B + tile * (64 * V));
+    const uint32_t lane_off = in ? (uint32_t)(lane * V * 4) : 0u;
+    const uint32_t ldb4 = (uint32_t)ldb * 4u;
+
+    AccFile acc;
+    acc.t0 = 0.0f; acc.t1 = 0.0f; acc.t2 = 0.0f; acc.t3 = 0.0f; acc.t4 = 0.0f;
+
+    const lds_u32* ring = (const lds_u32*)ring_mem[wv];
+    const uint32_t ring_lds = (uint32_t)(uintptr_t)ring;
+
+    const uint32_t* gs = stream + sched_group_base(first_entry, q, nw);
+    const SchedClass* h = hdr + q * nw * kMaxRun;
+    for (int32_t w8 = 0; w8 < nw * kMaxRun; w8 += kMaxRun) {
+        int32_t fw[kMaxRun], b0[kMaxRun], b1[kMaxRun];
+#pragma unroll
+        for (int i = 0; i < kMaxRun; ++i) {
+            fw[i] = __builtin_amdgcn_readfirstlane(h[w8 + i].first_word);
+            const int32_t nb = __builtin_amdgcn_readfirstlane(h[w8 + i].bodies);
+            b0[i] = (int32_t)((int64_t)nb * wv / kCoopWaves);
+            b1[i] = (int32_t)((int64_t)nb * (wv + 1) / kCoopWaves);
+        }
+        run_class<1, V, true>(acc, gs + fw[0], b0[0], b1[0], Bbytes, ldb4, lane_off, ring, ring_lds, lane);
+        run_class<2, V, true>(acc, gs + fw[1], b0[1], b1[1], Bbytes, ldb4, lane_off, ring, ring_lds, lane);
+        run_class<3, V, true>(acc, gs + fw[2], b0[2], b1[2], Bbytes, ldb4, lane_off, ring, ring_lds, lane);
+        run_class<4, V, true>(acc, gs + fw[3], b0[3], b1[3], Bbytes, ldb4, lane_off, ring, ring_lds, lane);
+        run_class<5, V, true>(acc, gs + fw[4], b0[4], b1[4], Bbytes, ldb4, lane_off, ring, ring_lds, lane);
+        run_class<6, V, true>(acc, gs + fw[5], b0[5], b1[5], Bbytes, ldb4, lane_off, ring, ring_lds, lane);
+        run_class<7, V, true>(acc, gs + fw[6], b0[6], b1[6], Bbytes, ldb4, lane_off, ring, ring_lds, lane);
+        run_class<8, V, true>(acc, gs + fw[7], b0[7], b1[7], Bbytes, ldb4, lane_off, ring, ring_lds, lane);
+    }
+
+    // partial sums of waves 1 .. kCoopWaves-1 into wave 0, one wave at a time (every wave of the
+    // workgroup reaches every barrier: nothing above or below leaves the kernel early)
+    for (int src = 1; src < kCoopWaves; ++src) {
+        if (wv == src) {
+#pragma unroll
+            for (int r = 0; r < P; ++r)
+#pragma unroll
+                for (int v = 0; v < V; ++v) part[(r * 64 + lane) * V + v] = acc_get(acc, kAccFirst + v * S + r);
+        }
+        __syncthreads();
+        if (wv == 0) {
+#pragma unroll
+            for (int r = 0; r < P; ++r)
+#pragma unroll
+                for (int v = 0; v < V; ++v) acc_add(acc, kAccFirst + v * S + r, part[(r * 64 + lane) * V + v]);
+        }
+        __syncthreads();
+    }
+
+    if (wv == 0 && in) {
+        const int64_t row0 = q * p;
+        float* __restrict__ Cl = C + j0;
+#pragma unroll
+        for (int r = 0; r < P; ++r) {
+            if (r < p && row0 + r < m) {
+                float* dst = Cl + (row0 + r) * ldc;
+                if constexpr (V == 4) {
+                    f32x4 o = {acc_get(acc, kAccFirst + r), acc_get(acc, kAccFirst + S + r), acc_get(acc, kAccFirst + 2 * S + r),
+                               acc_get(acc, kAccFirst + 3 * S + r)};
+                    __builtin_nontemporal_store(o, reinterpret_cast<f32x4*>(dst));
+                } else if constexpr (V == 2) {
+                    f32x2 o = {acc_get(acc, kAccFirst + r), acc_get(acc, kAccFirst + S + r)};
+                    __builtin_nontemporal_store(o, reinterpret_cast<f32x2*>(dst));
+                } else {
+                    __builtin_nontemporal_store(acc_get(acc, kAccFirst + r), dst);
+                }
+            }
+        }
+    }
+}
+
 template <int V>
 hipError_t launch_spdm_sched_instance(const SpdmArgs& a, hipStream_t s)
 {
@@ -353,7 +483,11 @@ hipError_t launch_spdm_sched_instance(const SpdmArgs& a, hipStream_t s)
     if (a.ldb > 0x3fffffffLL) return hipErrorInvalidValue;   // row pitch in bytes is kept in 32 bits
     if (a.p + 1 > acc_stride<V>()) return hipErrorInvalidValue;
     spdm_sched<V><<<dim3((unsigned)grid), dim3(64), 0, s>>>(a.hdr, a.stream, a.gIdxes, a.m, a.p, a.g, a.nw, a.B, a.ldb, a.N,
-                                                            a.C, a.ldc, total);
+                                                            a.C, a.ldc, total, a.heavy_min);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess || a.heavy_min == INT32_MAX) return e;
+    spdm_sched_coop<V><<<dim3((unsigned)total), dim3(64 * kCoopWaves), 0, s>>>(a.hdr, a.stream, a.gIdxes, a.m, a.p, a.g, a.nw, a.B,
+                                                                              a.ldb, a.N, a.C, a.ldc, total, a.heavy_min);
     return hipGetLastError();
 }
 

@@ -3,6 +3,7 @@
 #pragma once
 #include <hip/hip_runtime.h>
 #include <stdint.h>
+#include <limits.h>
 
 namespace gcoo {
 
@@ -21,6 +22,7 @@ struct SpdmArgs {
     int64_t N;
     float* C;
     int64_t ldc;
+    int32_t heavy_min;         // groups with this many entries or more go to the workgroup-shared kernel (INT32_MAX: none)
 };
 
 // V = 4 needs p <= 32, V = 2 needs p <= 64, V = 1 needs p <= 128; N, ldb, ldc and both base

@@ -180,6 +180,21 @@ def test_register_kernel_one_column_per_lane():
     _check_product(w, 128, binding.VARIANT_REG, r0=0, r1=128)
 
 
+@pytest.mark.parametrize("m,k,N,p,sparsity", [
+    (64, 6000, 256, 32, 0.5), (40, 3000, 520, 16, 0.7), (128, 5000, 128, 64, 0.8), (33, 9000, 64, 32, 0.97),
+    (256, 2500, 1024, 32, 0.9),
+])
+def test_heavy_groups_shared_by_a_workgroup(m, k, N, p, sparsity):
+    """Few (group, tile) items with thousands of entries each: the register kernel hands such groups
+    to eight waves that split the entries and add their partial sums in a fixed order."""
+    w = workloads.uniform_random(m, k, N, sparsity, seed=m + k + N)
+    _say(f"heavy groups m={m} k={k} N={N} p={p} nnz={w.nnz}")
+    err, A, c1 = _check_product(w, p, binding.VARIANT_REG)
+    assert err < 2e-6
+    _, _, c2 = _check_product(w, p, binding.VARIANT_REG, A=A)
+    assert np.array_equal(c1, c2)                        # same bits on every run
+
+
 def test_auto_variant_and_strided_operands():
     _say("strided B and C")
     w = workloads.uniform_random(200, 150, 96, 0.9, seed=21)
@@ -322,3 +337,12 @@ def test_csr_baseline_kernel(shape):
     C64, D64 = orc.spdm_csr(w.k, N, w.row_ptr, w.col_idx, w.vals, w.B)
     err, bad = orc.max_scaled_error(Cg.cpu().numpy(), C64, D64)
     assert bad == 0 and err <= TOL
+
+
+def test_tune_p_returns_a_measured_candidate():
+    _say("gcoo_tune_p")
+    w = workloads.uniform_random(512, 512, 256, 0.9, seed=4)
+    args = [torch.from_numpy(x).to(DEV) for x in (w.row_ptr, w.col_idx, w.vals)]
+    best, times = binding.gcoo_tune_p(w.m, w.k, *args, torch.from_numpy(w.B).to(DEV), candidates=(8, 32, 128), reps=2)
+    assert set(times) == {8, 32, 128} and best in times and all(t > 0 for t in times.values())
+    assert binding.gcoo_default_p(w.m, w.k, w.nnz, w.N) == 32
