@@ -167,6 +167,17 @@ int gcoo_export(const gcoo_matrix* A, float* values, int32_t* rows, int32_t* col
                 int64_t* gIdxes, int32_t* nnzPerGroup, void* stream);
 
 /* Static text for a status code. */
+/*
+ * Introspection for tests: the band schedule, the kernel-private re-listing that the
+ * workgroup-shared SpDM kernel reads (built at conversion for p <= 32 and matrices below 6 %
+ * density).  gcoo_band_words() = its size in 32-bit words, 0 if this matrix has none.
+ * gcoo_export_band() copies it to HOST buffers: `words` (gcoo_band_words entries), `ucount`
+ * (distinct columns per super-group of 8 groups, ceil(g/8) entries) and `ucols` (nnz entries; the
+ * columns of super-group Q start at index gIdxes[8Q]); any of them may be NULL.  Synchronises `stream`.
+ */
+int64_t gcoo_band_words(const gcoo_matrix* A);
+int gcoo_export_band(const gcoo_matrix* A, uint32_t* words, int32_t* ucount, int32_t* ucols, void* stream);
+
 const char* gcoo_strerror(int status);
 
 /* Text of the last HIP error seen by the calling thread inside this library ("" if none). */

@@ -22,7 +22,8 @@ VARIANT_AUTO, VARIANT_LDS, VARIANT_REG = 0, 1, 2
 # every symbol include/gcoo.h declares
 SYMBOLS = ["gcoo_default_p", "gcoo_device_bytes", "gcoo_from_csr", "gcoo_dense_nnz", "gcoo_from_dense", "gcoo_spdm",
            "gcoo_spdm_variant", "gcoo_spdm_pick", "gcoo_free", "gcoo_info", "gcoo_export",
-           "gcoo_strerror", "gcoo_last_hip_error", "gcoo_csr_spmm_baseline"]
+           "gcoo_strerror", "gcoo_last_hip_error", "gcoo_csr_spmm_baseline",
+           "gcoo_band_words", "gcoo_export_band"]
 
 _lib = None
 
@@ -67,6 +68,10 @@ def lib():
         L.gcoo_info.argtypes = [vp, C.POINTER(i64), C.POINTER(i64), C.POINTER(i64), C.POINTER(i32), C.POINTER(i64)]
         L.gcoo_export.restype = C.c_int
         L.gcoo_export.argtypes = [vp, vp, vp, vp, vp, vp, vp]
+        L.gcoo_band_words.restype = C.c_int64
+        L.gcoo_band_words.argtypes = [vp]
+        L.gcoo_export_band.restype = C.c_int
+        L.gcoo_export_band.argtypes = [vp, vp, vp, vp, vp]
         L.gcoo_default_p.restype = C.c_int32
         L.gcoo_default_p.argtypes = [i64, i64, i64, i64]
         L.gcoo_csr_spmm_baseline.restype = C.c_int
@@ -123,6 +128,19 @@ class GcooMatrix:
         _check(lib().gcoo_export(self.handle, v.ctypes.data, r.ctypes.data, c.ctypes.data, gi.ctypes.data,
                                  npg.ctypes.data, _stream_ptr(stream)), "gcoo_export")
         return dict(values=v, rows=r, cols=c, gIdxes=gi, nnzPerGroup=npg)
+
+    def export_band(self, stream=None):
+        """The band schedule as numpy arrays on the host, or None if this matrix has none."""
+        n = int(lib().gcoo_band_words(self.handle))
+        if n == 0:
+            return None
+        i = self.info()
+        words = np.empty(n, np.uint32)
+        ucount = np.empty((i["g"] + 7) // 8, np.int32)
+        ucols = np.empty(i["nnz"], np.int32)
+        _check(lib().gcoo_export_band(self.handle, words.ctypes.data, ucount.ctypes.data, ucols.ctypes.data,
+                                      _stream_ptr(stream)), "gcoo_export_band")
+        return dict(words=words, ucount=ucount, ucols=ucols)
 
     def free(self):
         if self._h is not None:

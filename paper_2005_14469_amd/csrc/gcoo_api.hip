@@ -10,6 +10,8 @@
 #include <new>
 #include <string>
 
+#include "gcoo_band.hpp"
+#include "gcoo_band_build.hpp"
 #include "gcoo_build_kernels.hpp"
 #include "gcoo_sched.hpp"
 #include "gcoo_sched_build.hpp"
@@ -43,6 +45,7 @@ __device__ unsigned long long g_dense_total;
 struct Layout {
     size_t values, rows, cols, gIdxes, nnzPerGroup;        // the five arrays of the format
     size_t sched_hdr, sched;                               // run schedule of the register kernel
+    size_t band_ucols, band_ucount, band_stream;           // band schedule of the workgroup-shared kernel (may be empty)
     size_t tmp_cols, tmp_rows, tmp_vals;                   // conversion scratch (second sort buffer)
     size_t in_row_ptr, in_cols, in_vals;                   // staging of a host CSR input
     size_t counter;                                        // 8-byte device counter
@@ -83,7 +86,17 @@ int dense_vec_width(const float* A, int64_t lda, int64_t k)
     return (k % 4 == 0 && lda % 4 == 0 && reinterpret_cast<uintptr_t>(A) % 16 == 0) ? 4 : 1;
 }
 
-Layout make_layout(int64_t m, int64_t k, int64_t nnz, int64_t g)
+// The band schedule is built when the band kernel can use it (p, k within its limits) and the
+// matrix is sparse enough for that kernel to pay: below about 6 % density most column runs
+// inside a group are one or two entries long, and the register kernel is then bound by the B
+// segments it fetches per run rather than by its multiply-adds.
+bool band_schedule_wanted(int64_t m, int64_t k, int64_t nnz, int32_t p)
+{
+    if (p > gcoo::kBandMaxP || k > gcoo::kBandMaxK || nnz <= 0 || m <= 0 || k <= 0) return false;
+    return (double)nnz <= 0.06 * (double)m * (double)k;
+}
+
+Layout make_layout(int64_t m, int64_t k, int64_t nnz, int64_t g, int32_t p)
 {
     int32_t nw, wc;
     pick_windows(k, g, &nw, &wc);
@@ -102,6 +115,10 @@ Layout make_layout(int64_t m, int64_t k, int64_t nnz, int64_t g)
     L.cols = take(n4);
     L.sched_hdr = take((size_t)g * nw * gcoo::kMaxRun * sizeof(gcoo::SchedClass));
     L.sched = take((size_t)gcoo::sched_words(nnz, g, nw) * 4);
+    const bool band = band_schedule_wanted(m, k, nnz, p);
+    L.band_ucols = take(band ? n4 : 0);
+    L.band_ucount = take(band ? (size_t)((g + gcoo::kBandWaves - 1) / gcoo::kBandWaves) * 4 : 0);
+    L.band_stream = take(band ? (size_t)gcoo::band_stream_words(nnz, g, k) * 4 : 0);
     L.tmp_cols = take(n4);
     L.tmp_rows = take(n4);
     L.tmp_vals = take(n4);
@@ -132,6 +149,7 @@ struct gcoo_matrix {
     int64_t m, k, nnz, g;
     int32_t p;
     int32_t nw, window_cols;
+    bool has_band;
     int device;
     char* base;
     Layout L;
@@ -142,6 +160,10 @@ struct gcoo_matrix {
     int32_t* nnzPerGroup() const { return reinterpret_cast<int32_t*>(base + L.nnzPerGroup); }
     gcoo::SchedClass* sched_hdr() const { return reinterpret_cast<gcoo::SchedClass*>(base + L.sched_hdr); }
     uint32_t* sched() const { return reinterpret_cast<uint32_t*>(base + L.sched); }
+    int32_t* band_ucols() const { return reinterpret_cast<int32_t*>(base + L.band_ucols); }
+    int32_t* band_ucount() const { return reinterpret_cast<int32_t*>(base + L.band_ucount); }
+    uint32_t* band_stream() const { return reinterpret_cast<uint32_t*>(base + L.band_stream); }
+    int64_t super_groups() const { return (g + gcoo::kBandWaves - 1) / gcoo::kBandWaves; }
 };
 
 namespace {
@@ -153,7 +175,8 @@ int new_handle(int64_t m, int64_t k, int64_t nnz, int32_t p, void* dev_buf, gcoo
     h->m = m; h->k = k; h->nnz = nnz; h->p = p;
     h->g = (m + p - 1) / p;
     h->base = static_cast<char*>(dev_buf);
-    h->L = make_layout(m, k, nnz, h->g);
+    h->L = make_layout(m, k, nnz, h->g, p);
+    h->has_band = band_schedule_wanted(m, k, nnz, p);
     pick_windows(k, h->g, &h->nw, &h->window_cols);
     if (hipGetDevice(&h->device) != hipSuccess) h->device = -1;
     *out = h;
@@ -166,6 +189,16 @@ int launch_build_schedule(const gcoo_matrix* h, hipStream_t s)
     if (h->g > 0 && h->p <= gcoo::kSchedMaxP) {              // no register kernel above that height
         gcoo::build_schedule<<<dim3((unsigned)h->g), dim3(gcoo::kBuildThreads), 0, s>>>(h->gIdxes(), h->rows(), h->cols(), h->values(), h->p,
                                                                         h->g, h->nw, h->window_cols, h->sched_hdr(), h->sched());
+        HIP_TRY(hipGetLastError());
+    }
+    if (h->g > 0 && h->has_band) {
+        const size_t bitmap_bytes = (size_t)((h->k + 31) / 32) * 4;
+        gcoo::band_union<<<dim3((unsigned)h->super_groups()), dim3(gcoo::kBandBuildThreads), bitmap_bytes, s>>>(
+            h->gIdxes(), h->cols(), h->g, h->k, h->band_ucols(), h->band_ucount());
+        HIP_TRY(hipGetLastError());
+        const size_t table_bytes = 2 * (size_t)((h->k + 63) / 64 + 1) * 4;
+        gcoo::band_fill<<<dim3((unsigned)(h->super_groups() * gcoo::kBandWaves)), dim3(gcoo::kBandBuildThreads), table_bytes, s>>>(
+            h->gIdxes(), h->rows(), h->cols(), h->values(), h->p, h->g, h->k, h->band_ucols(), h->band_ucount(), h->band_stream());
         HIP_TRY(hipGetLastError());
     }
     return GCOO_OK;
@@ -184,7 +217,7 @@ int32_t gcoo_default_p(int64_t m, int64_t k, int64_t nnz, int64_t N)
 size_t gcoo_device_bytes(int64_t m, int64_t k, int64_t nnz, int32_t p)
 {
     if (!dims_ok(m, k, nnz, p)) return 0;
-    return make_layout(m, k, nnz, (m + p - 1) / p).total;
+    return make_layout(m, k, nnz, (m + p - 1) / p, p).total;
 }
 
 int gcoo_from_csr(int64_t m, int64_t k, const int32_t* row_ptr, const int32_t* col_idx, const float* vals,
@@ -214,7 +247,7 @@ int gcoo_from_csr(int64_t m, int64_t k, const int32_t* row_ptr, const int32_t* c
     }
     if (nnz > 0 && (!col_idx || !vals)) return GCOO_EINVAL;
     const int64_t g = (m + p - 1) / p;
-    const Layout L = make_layout(m, k, nnz, g);
+    const Layout L = make_layout(m, k, nnz, g, p);
     if (dev_buf_bytes < L.total) return GCOO_ENOMEM;
 
     gcoo_matrix* h = nullptr;
@@ -309,7 +342,7 @@ int gcoo_from_dense(int64_t m, int64_t k, const float* A_dev, int64_t lda, int32
     const int64_t g = (m + p - 1) / p;
     // gIdxes / nnzPerGroup / counter sit at the front of the buffer at offsets that do not
     // depend on nnz, so step 1 can run before the buffer size for this nnz is checked.
-    const Layout L0 = make_layout(m, k, 0, g);
+    const Layout L0 = make_layout(m, k, 0, g, p);
     if (dev_buf_bytes < L0.total) return GCOO_ENOMEM;
     char* base = static_cast<char*>(dev_buf);
     int32_t* cnt = reinterpret_cast<int32_t*>(base + L0.nnzPerGroup);
@@ -341,7 +374,7 @@ int gcoo_from_dense(int64_t m, int64_t k, const float* A_dev, int64_t lda, int32
     }
     if (total > (unsigned long long)INT32_MAX) return GCOO_EINVAL;
     const int64_t nnz = (int64_t)total;
-    const Layout L = make_layout(m, k, nnz, g);
+    const Layout L = make_layout(m, k, nnz, g, p);
     if (dev_buf_bytes < L.total) return GCOO_ENOMEM;
     gcoo_matrix* h = nullptr;
     int rc = new_handle(m, k, nnz, p, dev_buf, &h);
@@ -520,6 +553,23 @@ int gcoo_export(const gcoo_matrix* A, float* values, int32_t* rows, int32_t* col
         for (int64_t i = 0; i <= A->g; ++i) gIdxes[i] = narrow[i];
     delete[] narrow;
     if (e != hipSuccess) return hip_fail(e, "hipStreamSynchronize");
+    return GCOO_OK;
+}
+
+int64_t gcoo_band_words(const gcoo_matrix* A)
+{
+    if (!A || !A->has_band) return 0;
+    return gcoo::band_stream_words(A->nnz, A->g, A->k);
+}
+
+int gcoo_export_band(const gcoo_matrix* A, uint32_t* words, int32_t* ucount, int32_t* ucols, void* stream)
+{
+    if (!A || !A->has_band) return GCOO_EINVAL;
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    if (words) HIP_TRY(hipMemcpyAsync(words, A->band_stream(), (size_t)gcoo_band_words(A) * 4, hipMemcpyDeviceToHost, s));
+    if (ucount) HIP_TRY(hipMemcpyAsync(ucount, A->band_ucount(), (size_t)A->super_groups() * 4, hipMemcpyDeviceToHost, s));
+    if (ucols && A->nnz) HIP_TRY(hipMemcpyAsync(ucols, A->band_ucols(), (size_t)A->nnz * 4, hipMemcpyDeviceToHost, s));
+    HIP_TRY(hipStreamSynchronize(s));
     return GCOO_OK;
 }
 

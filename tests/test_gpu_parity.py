@@ -137,6 +137,54 @@ def test_gcoo_from_dense_bit_exact(p, shape):
     _assert_arrays_equal(A2.export(), G)
 
 
+def _band_base(first_entry, q, k):
+    return (3 * first_entry + 3) // 4 * 4 + (56 * ((k + 63) // 64 + 2) + 4) * q
+
+
+@pytest.mark.parametrize("m,k,p,s", [
+    (100, 300, 32, 0.95), (257, 1000, 32, 0.99), (70, 200, 16, 0.94), (33, 50, 8, 0.95), (300, 70, 32, 0.96),
+    (1, 1, 1, 0.0), (520, 5000, 32, 0.97), (64, 4000, 32, 0.999), (2000, 2000, 32, 0.98), (256, 64, 32, 0.95),
+])
+def test_band_schedule_bit_exact(m, k, p, s):
+    """The band schedule written by the HIP builder equals the Python model word for word."""
+    from tests import band_model
+    _say(f"band schedule m={m} k={k} p={p} sparsity={s}")
+    w = workloads.uniform_random(m, k, 1, s, seed=3 * m + k)
+    A = binding.gcoo_from_csr(w.m, w.k, w.row_ptr, w.col_idx, w.vals, p, device=DEV)
+    got = A.export_band()
+    if w.nnz == 0 or w.nnz > 0.06 * m * k:
+        assert got is None
+        return
+    assert got is not None
+    G = orc.gcoo_from_csr(w.m, w.k, w.row_ptr, w.col_idx, w.vals, p)
+    streams, info = band_model.build(m, k, p, G.gIdxes, G.rows, G.cols, G.values)
+    for Q, (ucols, NB) in enumerate(info):
+        assert got["ucount"][Q] == len(ucols)
+        e0 = int(G.gIdxes[8 * Q])
+        assert np.array_equal(got["ucols"][e0:e0 + len(ucols)], ucols)
+    for q, st in enumerate(streams):
+        base = _band_base(int(G.gIdxes[min(q, G.g)]), q, k)
+        assert np.array_equal(got["words"][base:base + len(st)], st), f"stream {q}"
+
+
+def test_band_schedule_bit_exact_with_repeated_coordinates():
+    from tests import band_model
+    from tests.test_band_model import repeated_coordinates_workload
+    m, k, N, row_ptr, col_idx, vals, B = repeated_coordinates_workload()
+    # density of this input is above the limit for the band schedule at its real size: embed it in a wider matrix
+    k2 = 4000
+    for p in (8, 32):
+        _say(f"band schedule with repeated coordinates p={p}")
+        A = binding.gcoo_from_csr(m, k2, row_ptr, col_idx, vals, p, device=DEV)
+        got = A.export_band()
+        assert got is not None
+        G = orc.gcoo_from_csr(m, k2, row_ptr, col_idx, vals, p)
+        streams, info = band_model.build(m, k2, p, G.gIdxes, G.rows, G.cols, G.values)
+        for q, st in enumerate(streams):
+            base = _band_base(int(G.gIdxes[min(q, G.g)]), q, k2)
+            assert np.array_equal(got["words"][base:base + len(st)], st), f"stream {q}"
+
+
 # ------------------------------------------------------------------ product
 
 @pytest.mark.parametrize("p", [1, 2, 8, 16, 32, 64, 128, 256])
