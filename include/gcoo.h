@@ -136,6 +136,10 @@ int gcoo_spdm(const gcoo_matrix* A, const float* B_dev, int64_t ldb, int64_t N,
 /* partial sums in VGPRs, reads the run schedule built at conversion; needs p <= 64 and B, C, ldb,
  * ldc, N all even (8-byte aligned rows), else GCOO_EINVAL */
 #define GCOO_VARIANT_REG  2
+/* eight groups per workgroup share the rows of B through LDS, reads the band schedule built at
+ * conversion (gcoo_band_words() > 0: p <= 32, density below 6 %); needs B, C, ldb, ldc, N multiples
+ * of 4 elements (16-byte aligned rows), else GCOO_EINVAL */
+#define GCOO_VARIANT_BAND 3
 int gcoo_spdm_variant(const gcoo_matrix* A, const float* B_dev, int64_t ldb, int64_t N,
                       float* C_dev, int64_t ldc, void* stream, int variant);
 

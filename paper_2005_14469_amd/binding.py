@@ -17,7 +17,7 @@ LIB_PATH = os.path.join(_HERE, "libgcoo.so")
 
 GCOO_OK, GCOO_EINVAL, GCOO_EBOUNDS, GCOO_ENOMEM, GCOO_EHIP = 0, -1, -2, -3, -4
 GCOO_MAX_P = 256
-VARIANT_AUTO, VARIANT_LDS, VARIANT_REG = 0, 1, 2
+VARIANT_AUTO, VARIANT_LDS, VARIANT_REG, VARIANT_BAND = 0, 1, 2, 3
 
 # every symbol include/gcoo.h declares
 SYMBOLS = ["gcoo_default_p", "gcoo_device_bytes", "gcoo_from_csr", "gcoo_dense_nnz", "gcoo_from_dense", "gcoo_spdm",

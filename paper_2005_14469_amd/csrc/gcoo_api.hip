@@ -485,7 +485,7 @@ int gcoo_spdm_variant(const gcoo_matrix* A, const float* B_dev, int64_t ldb, int
 {
     int rc = check_spdm_args(A, B_dev, ldb, N, C_dev, ldc);
     if (rc != GCOO_OK) return rc;
-    if (variant < GCOO_VARIANT_AUTO || variant > GCOO_VARIANT_REG) return GCOO_EINVAL;
+    if (variant < GCOO_VARIANT_AUTO || variant > GCOO_VARIANT_BAND) return GCOO_EINVAL;
     if (variant == GCOO_VARIANT_AUTO) variant = gcoo_spdm_pick(A, B_dev, ldb, N, C_dev, ldc);
     if (A->m == 0 || N == 0) return GCOO_OK;
     hipStream_t s = static_cast<hipStream_t>(stream);
@@ -498,6 +498,14 @@ int gcoo_spdm_variant(const gcoo_matrix* A, const float* B_dev, int64_t ldb, int
         gcoo::spdm_lds<<<dim3((unsigned)total), dim3(64), smem, s>>>(A->values(), A->rows(), A->cols(), A->gIdxes(), A->m,
                                                                      A->p, B_dev, ldb, N, C_dev, ldc, A->g);
         HIP_TRY(hipGetLastError());
+        return GCOO_OK;
+    }
+    if (variant == GCOO_VARIANT_BAND) {
+        if (!A->has_band || !shape_of(B_dev, ldb, N, C_dev, ldc).al4) return GCOO_EINVAL;
+        gcoo::BandArgs a{A->band_stream(), A->gIdxes(), A->band_ucount(), A->m, A->p, A->g, A->k, A->super_groups(),
+                         B_dev, ldb, N, C_dev, ldc};
+        hipError_t e = gcoo::launch_spdm_band(a, s);
+        if (e != hipSuccess) return hip_fail(e, "spdm_band launch");
         return GCOO_OK;
     }
     const int V = sched_width(A->p, shape_of(B_dev, ldb, N, C_dev, ldc));

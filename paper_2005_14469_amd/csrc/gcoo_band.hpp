@@ -67,7 +67,7 @@ __host__ __device__ inline int64_t band_stream_base(int64_t first_entry, int64_t
 __host__ __device__ inline int64_t band_stream_words(int64_t nnz, int64_t g, int64_t k)
 {
     const int64_t nq = (g + kBandWaves - 1) / kBandWaves;
-    return band_stream_base(nnz, nq * kBandWaves, k);
+    return band_stream_base(nnz, nq * kBandWaves, k) + kBandBlockMax;   // the kernel reads whole blocks: slack behind the last one
 }
 
 }  // namespace gcoo

@@ -33,4 +33,22 @@ hipError_t launch_spdm_sched_v4(const SpdmArgs& a, hipStream_t s);
 hipError_t launch_spdm_sched_v2(const SpdmArgs& a, hipStream_t s);
 hipError_t launch_spdm_sched_v1(const SpdmArgs& a, hipStream_t s);
 
+// The workgroup-shared kernel (band schedule): p <= 32; N, ldb, ldc multiples of 4; B and C 16-byte aligned.
+struct BandArgs {
+    const uint32_t* stream;    // band schedule
+    const int32_t* gIdxes;     // [g+1]
+    const int32_t* ucount;     // [nq] distinct columns per super-group
+    int64_t m;
+    int32_t p;
+    int64_t g;
+    int64_t k;
+    int64_t nq;                // super-groups
+    const float* B;
+    int64_t ldb;
+    int64_t N;
+    float* C;
+    int64_t ldc;
+};
+hipError_t launch_spdm_band(const BandArgs& a, hipStream_t s);
+
 }  // namespace gcoo

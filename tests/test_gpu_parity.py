@@ -243,6 +243,44 @@ def test_heavy_groups_shared_by_a_workgroup(m, k, N, p, sparsity):
     assert np.array_equal(c1, c2)                        # same bits on every run
 
 
+@pytest.mark.parametrize("m,k,N,p,sparsity", [
+    (100, 300, 8, 32, 0.95), (257, 1000, 260, 32, 0.99), (70, 200, 4, 16, 0.94), (33, 50, 12, 8, 0.95), (300, 70, 64, 32, 0.96),
+    (1, 1, 4, 1, 0.0), (520, 5000, 512, 32, 0.97), (64, 4000, 256, 32, 0.999), (2000, 2000, 300, 32, 0.98), (256, 64, 1028, 32, 0.95),
+    (1000, 3000, 256, 32, 0.94),
+])
+def test_band_variant(m, k, N, p, sparsity):
+    """The kernel whose eight waves share the rows of B through LDS, on matrices sparse enough to have a band schedule."""
+    w = workloads.uniform_random(m, k, N, sparsity, seed=5 * m + k + N)
+    _say(f"band variant m={m} k={k} N={N} p={p} nnz={w.nnz}")
+    if w.nnz == 0 or w.nnz > 0.06 * m * k:
+        pytest.skip("no band schedule for this matrix")
+    err, A, c1 = _check_product(w, p, binding.VARIANT_BAND)
+    assert err < 2e-6
+    _, _, c2 = _check_product(w, p, binding.VARIANT_BAND, A=A)
+    assert np.array_equal(c1, c2)
+
+
+def test_band_variant_repeated_coordinates_and_strides():
+    from tests.test_band_model import repeated_coordinates_workload
+    m, k, N, row_ptr, col_idx, vals, B = repeated_coordinates_workload()
+    _say("band variant: repeated coordinates, strided operands")
+    k2, N2 = 4000, 12
+    rng = np.random.default_rng(2)
+    Bh = rng.standard_normal((k2, N2)).astype(np.float32)
+    A = binding.gcoo_from_csr(m, k2, row_ptr, col_idx, vals, 32, device=DEV)
+    Bbig = torch.zeros((k2, 40), device=DEV)
+    Bbig[:, 8:8 + N2] = torch.from_numpy(Bh).to(DEV)
+    Cbig = torch.full((m, 32), 7.0, device=DEV)
+    binding.gcoo_spdm(A, Bbig[:, 8:8 + N2], Cbig[:, 4:4 + N2], variant=binding.VARIANT_BAND)
+    torch.cuda.synchronize()
+    C64, D64 = orc.spdm_csr(k2, N2, row_ptr, col_idx, vals, Bh)
+    err, bad = orc.max_scaled_error(Cbig[:, 4:4 + N2].cpu().numpy(), C64, D64)
+    assert bad == 0 and err <= TOL
+    assert torch.all(Cbig[:, :4] == 7.0) and torch.all(Cbig[:, 4 + N2:] == 7.0)
+    with pytest.raises(binding.GcooError):                  # rows not 16-byte aligned
+        binding.gcoo_spdm(A, Bbig[:, 9:9 + N2], Cbig[:, 4:4 + N2], variant=binding.VARIANT_BAND)
+
+
 def test_auto_variant_and_strided_operands():
     _say("strided B and C")
     w = workloads.uniform_random(200, 150, 96, 0.9, seed=21)
