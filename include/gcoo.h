@@ -137,7 +137,7 @@ int gcoo_spdm(const gcoo_matrix* A, const float* B_dev, int64_t ldb, int64_t N,
  * ldc, N all even (8-byte aligned rows), else GCOO_EINVAL */
 #define GCOO_VARIANT_REG  2
 /* eight groups per workgroup share the rows of B through LDS, reads the band schedule built at
- * conversion (gcoo_band_words() > 0: p <= 32, density below 6 %); needs B, C, ldb, ldc, N multiples
+ * conversion (gcoo_band_words() > 0, see gcoo_set_band_policy()); needs B, C, ldb, ldc, N multiples
  * of 4 elements (16-byte aligned rows), else GCOO_EINVAL */
 #define GCOO_VARIANT_BAND 3
 int gcoo_spdm_variant(const gcoo_matrix* A, const float* B_dev, int64_t ldb, int64_t N,
@@ -172,9 +172,21 @@ int gcoo_export(const gcoo_matrix* A, float* values, int32_t* rows, int32_t* col
 
 /* Static text for a status code. */
 /*
+ * When conversions build the band schedule (process-wide setting, not thread-safe; takes effect
+ * for matrices converted afterwards).  GCOO_BAND_AUTO: only for matrices on which gcoo_spdm()
+ * then picks GCOO_VARIANT_BAND (at least 10000 columns, density 1.5 % .. 6 %, p <= 32).
+ * GCOO_BAND_ALWAYS: whenever the band kernel could run (p <= 32, density <= 6 %, at most 262144
+ * columns); gcoo_spdm() keeps its usual choice and GCOO_VARIANT_BAND must be asked for.
+ * GCOO_BAND_NEVER: never.
+ */
+#define GCOO_BAND_AUTO   0
+#define GCOO_BAND_ALWAYS 1
+#define GCOO_BAND_NEVER  2
+int gcoo_set_band_policy(int policy);
+
+/*
  * Introspection for tests: the band schedule, the kernel-private re-listing that the
- * workgroup-shared SpDM kernel reads (built at conversion for p <= 32 and matrices below 6 %
- * density).  gcoo_band_words() = its size in 32-bit words, 0 if this matrix has none.
+ * workgroup-shared SpDM kernel reads (built at conversion as gcoo_set_band_policy() says).  gcoo_band_words() = its size in 32-bit words, 0 if this matrix has none.
  * gcoo_export_band() copies it to HOST buffers: `words` (gcoo_band_words entries), `ucount`
  * (distinct columns per super-group of 8 groups, ceil(g/8) entries) and `ucols` (nnz entries; the
  * columns of super-group Q start at index gIdxes[8Q]); any of them may be NULL.  Synchronises `stream`.

@@ -18,12 +18,13 @@ LIB_PATH = os.path.join(_HERE, "libgcoo.so")
 GCOO_OK, GCOO_EINVAL, GCOO_EBOUNDS, GCOO_ENOMEM, GCOO_EHIP = 0, -1, -2, -3, -4
 GCOO_MAX_P = 256
 VARIANT_AUTO, VARIANT_LDS, VARIANT_REG, VARIANT_BAND = 0, 1, 2, 3
+BAND_AUTO, BAND_ALWAYS, BAND_NEVER = 0, 1, 2
 
 # every symbol include/gcoo.h declares
 SYMBOLS = ["gcoo_default_p", "gcoo_device_bytes", "gcoo_from_csr", "gcoo_dense_nnz", "gcoo_from_dense", "gcoo_spdm",
            "gcoo_spdm_variant", "gcoo_spdm_pick", "gcoo_free", "gcoo_info", "gcoo_export",
            "gcoo_strerror", "gcoo_last_hip_error", "gcoo_csr_spmm_baseline",
-           "gcoo_band_words", "gcoo_export_band"]
+           "gcoo_band_words", "gcoo_export_band", "gcoo_set_band_policy"]
 
 _lib = None
 
@@ -68,6 +69,8 @@ def lib():
         L.gcoo_info.argtypes = [vp, C.POINTER(i64), C.POINTER(i64), C.POINTER(i64), C.POINTER(i32), C.POINTER(i64)]
         L.gcoo_export.restype = C.c_int
         L.gcoo_export.argtypes = [vp, vp, vp, vp, vp, vp, vp]
+        L.gcoo_set_band_policy.restype = C.c_int
+        L.gcoo_set_band_policy.argtypes = [C.c_int]
         L.gcoo_band_words.restype = C.c_int64
         L.gcoo_band_words.argtypes = [vp]
         L.gcoo_export_band.restype = C.c_int
@@ -287,3 +290,7 @@ def gcoo_tune_p(m: int, k: int, row_ptr, col_idx, vals, B: torch.Tensor, candida
         times[p] = ts[len(ts) // 2]
         holder[0].free()
     return min(times, key=times.get), times
+
+
+def gcoo_set_band_policy(policy: int) -> None:
+    _check(lib().gcoo_set_band_policy(policy), "gcoo_set_band_policy")

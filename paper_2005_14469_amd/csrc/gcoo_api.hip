@@ -86,14 +86,33 @@ int dense_vec_width(const float* A, int64_t lda, int64_t k)
     return (k % 4 == 0 && lda % 4 == 0 && reinterpret_cast<uintptr_t>(A) % 16 == 0) ? 4 : 1;
 }
 
-// The band schedule is built when the band kernel can use it (p, k within its limits) and the
-// matrix is sparse enough for that kernel to pay: below about 6 % density most column runs
-// inside a group are one or two entries long, and the register kernel is then bound by the B
-// segments it fetches per run rather than by its multiply-adds.
-bool band_schedule_wanted(int64_t m, int64_t k, int64_t nnz, int32_t p)
+// The band schedule costs conversion time and memory, so it is built only where the band
+// kernel is the one gcoo_spdm() will pick.  Measured on MI355X with uniform random matrices
+// (n = 2000 .. 14000, density 0.1 % .. 5 %): the band kernel is faster than the register kernel
+// from about 10000 columns on and between 1.5 % and 6 % density (1.1x .. 1.7x); the B tile of a
+// column tile then no longer stays in L2 between the groups that need it, and eight groups sharing
+// each fetched row matters more than the extra step-by-step overhead of the band kernel.
+// Below 6 % most column runs inside a group are one or two entries long; above it the register
+// kernel is bound by its multiply-adds, not by the rows it fetches.
+// gcoo_set_band_policy() overrides the choice.
+int g_band_policy = GCOO_BAND_AUTO;
+
+bool band_schedule_possible(int64_t m, int64_t k, int64_t nnz, int32_t p)
 {
     if (p > gcoo::kBandMaxP || k > gcoo::kBandMaxK || nnz <= 0 || m <= 0 || k <= 0) return false;
     return (double)nnz <= 0.06 * (double)m * (double)k;
+}
+
+// Where the band kernel is the faster one.
+bool band_kernel_preferred(int64_t m, int64_t k, int64_t nnz, int32_t p)
+{
+    return band_schedule_possible(m, k, nnz, p) && k >= 10000 && (double)nnz >= 0.015 * (double)m * (double)k;
+}
+
+bool band_schedule_wanted(int64_t m, int64_t k, int64_t nnz, int32_t p)
+{
+    if (g_band_policy == GCOO_BAND_NEVER || !band_schedule_possible(m, k, nnz, p)) return false;
+    return g_band_policy == GCOO_BAND_ALWAYS || band_kernel_preferred(m, k, nnz, p);
 }
 
 Layout make_layout(int64_t m, int64_t k, int64_t nnz, int64_t g, int32_t p)
@@ -149,7 +168,8 @@ struct gcoo_matrix {
     int64_t m, k, nnz, g;
     int32_t p;
     int32_t nw, window_cols;
-    bool has_band;
+    bool has_band;             // the band schedule was built
+    bool band_preferred;       // and the band kernel is the automatic choice
     int device;
     char* base;
     Layout L;
@@ -177,6 +197,7 @@ int new_handle(int64_t m, int64_t k, int64_t nnz, int32_t p, void* dev_buf, gcoo
     h->base = static_cast<char*>(dev_buf);
     h->L = make_layout(m, k, nnz, h->g, p);
     h->has_band = band_schedule_wanted(m, k, nnz, p);
+    h->band_preferred = h->has_band && band_kernel_preferred(m, k, nnz, p);
     pick_windows(k, h->g, &h->nw, &h->window_cols);
     if (hipGetDevice(&h->device) != hipSuccess) h->device = -1;
     *out = h;
@@ -207,6 +228,13 @@ int launch_build_schedule(const gcoo_matrix* h, hipStream_t s)
 }  // namespace
 
 extern "C" {
+
+int gcoo_set_band_policy(int policy)
+{
+    if (policy < GCOO_BAND_AUTO || policy > GCOO_BAND_NEVER) return GCOO_EINVAL;
+    g_band_policy = policy;
+    return GCOO_OK;
+}
 
 int32_t gcoo_default_p(int64_t m, int64_t k, int64_t nnz, int64_t N)
 {
@@ -477,7 +505,9 @@ int gcoo_spdm_pick(const gcoo_matrix* A, const float* B_dev, int64_t ldb, int64_
 {
     int rc = check_spdm_args(A, B_dev, ldb, N, C_dev, ldc);
     if (rc != GCOO_OK) return rc;
-    return sched_width(A->p, shape_of(B_dev, ldb, N, C_dev, ldc)) ? GCOO_VARIANT_REG : GCOO_VARIANT_LDS;
+    const Shape sh = shape_of(B_dev, ldb, N, C_dev, ldc);
+    if (A->band_preferred && sh.al4 && !sh.wide_pitch) return GCOO_VARIANT_BAND;
+    return sched_width(A->p, sh) ? GCOO_VARIANT_REG : GCOO_VARIANT_LDS;
 }
 
 int gcoo_spdm_variant(const gcoo_matrix* A, const float* B_dev, int64_t ldb, int64_t N, float* C_dev, int64_t ldc,

@@ -29,6 +29,9 @@
 //     type 2: 4 pieces of 2        12 words:  2 offset words, 2 row words, 8 values
 //     type 4: 2 pieces of 4        12 words:  1 offset word, 2 row words, 1 unused, 8 values
 //     type 8: 1 piece  of 8        12 words:  1 offset word, 2 row words, 1 unused, 8 values
+// Pieces of 4 and of 2 that would leave a chunk partly filled are halved and join the end of
+// the list of the next smaller type, so that only the last chunk of type 1 can hold unused piece
+// slots (at most three entries that multiply by zero).
 // offset = slot * 1024 as 16-bit halves (the byte offset of the B row inside the LDS band),
 // rows = row inside the group, one byte each, values = fp32 bits.  Unused piece slots of the last
 // chunk of a type hold offset 0, row p (the sink row of the accumulators) and value 0.

@@ -145,11 +145,19 @@ __device__ __forceinline__ int32_t band_blocks_of(const int32_t* __restrict__ ro
 #pragma unroll
             for (int ti = 0; ti < 4; ++ti) heads[t][ti] = __ballot(type[t] == (1 << ti) && in_piece[t] == 0);
         }
-        int32_t cnt[4], nch[4], off[4];
+        // Pieces per type as cut from the runs (nat), then after the pieces of 4 and of 2 that
+        // would leave a chunk partly filled have been halved into the next smaller type (cnt).
+        int32_t nat[4], cnt[4], nch[4], off[4];
+#pragma unroll
+        for (int ti = 0; ti < 4; ++ti) nat[ti] = __popcll(heads[0][ti]) + __popcll(heads[1][ti]);
+        cnt[3] = nat[3];
+        cnt[2] = nat[2] & ~1;                                  // whole chunks of two 4s
+        const int32_t twos = nat[1] + 2 * (nat[2] - cnt[2]);
+        cnt[1] = twos & ~3;                                    // whole chunks of four 2s
+        cnt[0] = nat[0] + 2 * (twos - cnt[1]);
         int32_t size = kBandHdr;
 #pragma unroll
         for (int ti = 0; ti < 4; ++ti) {
-            cnt[ti] = __popcll(heads[0][ti]) + __popcll(heads[1][ti]);
             const int J = band_pieces_per_chunk(1 << ti);
             nch[ti] = (cnt[ti] + J - 1) / J;
             off[ti] = size;
@@ -174,13 +182,25 @@ __device__ __forceinline__ int32_t band_blocks_of(const int32_t* __restrict__ ro
             for (int t = 0; t < 2; ++t) {
                 const int32_t i = cur + t * 64 + lane;
                 if (i < seg_end) {
-                    const int T = type[t], ti = band_type_index(T), J = band_pieces_per_chunk(T);
+                    int T = type[t], u = in_piece[t];
+                    const int nti = band_type_index(T);
                     const int32_t h = head[t];
-                    int32_t rank;
-                    if (h < 64) rank = __popcll(heads[0][ti] & ((1ull << h) - 1ull));
-                    else rank = __popcll(heads[0][ti]) + __popcll(heads[1][ti] & ((1ull << (h - 64)) - 1ull));
+                    int32_t rank;                                 // of the piece among the pieces of its type, in entry order
+                    if (h < 64) rank = __popcll(heads[0][nti] & ((1ull << h) - 1ull));
+                    else rank = __popcll(heads[0][nti]) + __popcll(heads[1][nti] & ((1ull << (h - 64)) - 1ull));
+                    if (T == 4 && rank >= cnt[2]) {               // halved: two 2s behind the 2s cut from the runs
+                        rank = nat[1] + 2 * (rank - cnt[2]) + (u >> 1);
+                        u &= 1;
+                        T = 2;
+                    }
+                    if (T == 2 && rank >= cnt[1]) {               // halved: two 1s behind the 1s cut from the runs
+                        rank = nat[0] + 2 * (rank - cnt[1]) + u;
+                        u = 0;
+                        T = 1;
+                    }
+                    const int ti = band_type_index(T), J = band_pieces_per_chunk(T);
                     uint32_t* ch = blk + off[ti] + (rank / J) * band_chunk_words(T);
-                    const int j = rank % J, u = in_piece[t];
+                    const int j = rank % J;
                     reinterpret_cast<uint8_t*>(ch + band_chunk_rows_at(T))[j * T + u] = (uint8_t)(rows[i] - row0);
                     ch[band_chunk_vals_at(T) + j * T + u] = __float_as_uint(values[i]);
                     if (u == 0) {

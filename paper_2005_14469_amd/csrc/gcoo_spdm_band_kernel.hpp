@@ -40,66 +40,98 @@ __device__ __forceinline__ void band_b(const char __attribute__((address_space(3
     b[0] = t.x; b[1] = t.y; b[2] = t.z; b[3] = t.w;
 }
 
+// The words of one chunk of type T, as read from the ring.
+template <int T>
+struct BandChunk {
+    static constexpr int kReads = band_chunk_words(T) / 4;
+    u32x4 w[kReads];
+};
+
+template <int T>
+__device__ __forceinline__ BandChunk<T> band_chunk_read(const lds_u32* cp)
+{
+    BandChunk<T> c;
+#pragma unroll
+    for (int i = 0; i < BandChunk<T>::kReads; ++i) c.w[i] = ring_read4(cp + 4 * i);
+    return c;
+}
+
+// Byte offset inside the band of the B row of piece j.
+template <int T>
+__device__ __forceinline__ uint32_t band_chunk_offset(const BandChunk<T>& c, int j)
+{
+    const uint32_t word = (j < 2) ? c.w[0].x : c.w[0].y;
+    return (j & 1) ? word >> 16 : word & 0xffffu;
+}
+
+// Piece j of the chunk times its B segment: rows to SGPRs, values stay in VGPRs.
+template <int T>
+__device__ __forceinline__ void band_chunk_fma(AccFile& acc, const BandChunk<T>& c, int j, const uint32_t (&rowword)[2],
+                                               const float (&b)[4])
+{
+    // row bytes of piece j start at byte j*T of the row words; values at word 4 + j*T
+    uint32_t r[T];
+    float a[T];
+#pragma unroll
+    for (int u = 0; u < T; ++u) {
+        const int byte = j * T + u;
+        r[u] = rowword[byte / 4] >> (8 * (byte % 4));
+        const int vw = 4 + j * T + u;
+        const u32x4 q = c.w[vw / 4];
+        const uint32_t bits = (vw % 4 == 0) ? q.x : (vw % 4 == 1) ? q.y : (vw % 4 == 2) ? q.z : q.w;
+        a[u] = __uint_as_float(bits);
+    }
+    run_fma<T, 4>(acc, r, a, b);
+}
+
+// All n chunks of type T that start at cp.  Software pipeline: the ring words of a chunk are read
+// two chunks ahead; the B segment of piece j of the next chunk is read from the band as soon as
+// piece j of this chunk has been multiplied (into the registers that piece just freed), so those
+// reads are in flight behind the multiply-adds of the other pieces.
+template <int T>
+__device__ __forceinline__ const lds_u32* band_chunks(AccFile& acc, const lds_u32* cp, int32_t n,
+                                                       const char __attribute__((address_space(3)))* band_lane)
+{
+    constexpr int J = band_pieces_per_chunk(T), W = band_chunk_words(T);
+    if (n <= 0) return cp;
+    // three register sets take turns (this chunk, the next, the one being read), so that no
+    // words are copied from set to set: the loop body is written out three times
+    BandChunk<T> s0 = band_chunk_read<T>(cp);
+    BandChunk<T> s1 = band_chunk_read<T>(cp + (n > 1 ? W : 0));
+    BandChunk<T> s2 = s1;
+    float b[J][4];
+#pragma unroll
+    for (int j = 0; j < J; ++j) band_b(band_lane, band_chunk_offset<T>(s0, j), b[j]);
+    auto turn = [&](const BandChunk<T>& c0, const BandChunk<T>& c1, BandChunk<T>& c2, int32_t c) {
+        const int32_t ahead = c + 2 < n ? 2 : n - 1 - c;          // the last chunks are read again instead of reading past the end
+        c2 = band_chunk_read<T>(cp + ahead * W);
+        // the row words sit behind the offset words: T = 1, 2: words 2, 3; T = 4, 8: words 1, 2
+        const uint32_t rowword[2] = {uni(T <= 2 ? c0.w[0].z : c0.w[0].y), uni(T <= 2 ? c0.w[0].w : c0.w[0].z)};
+#pragma unroll
+        for (int j = 0; j < J; ++j) {
+            band_chunk_fma<T>(acc, c0, j, rowword, b[j]);
+            band_b(band_lane, band_chunk_offset<T>(c1, j), b[j]);  // piece j of the next chunk (of this one again after the last)
+        }
+        cp += W;
+    };
+    for (int32_t c = 0; c < n; c += 3) {
+        turn(s0, s1, s2, c);
+        if (c + 1 < n) turn(s1, s2, s0, c + 1);
+        if (c + 2 < n) turn(s2, s0, s1, c + 2);
+    }
+    return cp;
+}
+
 // All chunks of one block (in the ring at `blk`) against the band whose LDS address, plus this
 // lane's place in a row, is band_lane.
 __device__ __forceinline__ void band_block(AccFile& acc, const lds_u32* blk, const char __attribute__((address_space(3)))* band_lane,
                                            uint32_t counts)
 {
-    const int32_t n1 = counts & 255u, n2 = (counts >> 8) & 255u, n4 = (counts >> 16) & 255u, n8 = counts >> 24;
     const lds_u32* cp = blk + kBandHdr;
-    for (int32_t c = 0; c < n1; ++c, cp += 8) {
-        const u32x4 h = ring_read4(cp), v = ring_read4(cp + 4);
-        float b0[4], b1[4], b2[4], b3[4];
-        band_b(band_lane, h.x & 0xffffu, b0);
-        band_b(band_lane, h.x >> 16, b1);
-        band_b(band_lane, h.y & 0xffffu, b2);
-        band_b(band_lane, h.y >> 16, b3);
-        const uint32_t rw = uni(h.z);
-        const uint32_t r0 = rw, r1 = rw >> 8, r2 = rw >> 16, r3 = rw >> 24;
-        const float a0 = __uint_as_float(v.x), a1 = __uint_as_float(v.y), a2 = __uint_as_float(v.z), a3 = __uint_as_float(v.w);
-        run_fma<1, 4>(acc, &r0, &a0, b0);
-        run_fma<1, 4>(acc, &r1, &a1, b1);
-        run_fma<1, 4>(acc, &r2, &a2, b2);
-        run_fma<1, 4>(acc, &r3, &a3, b3);
-    }
-    for (int32_t c = 0; c < n2; ++c, cp += 12) {
-        const u32x4 h = ring_read4(cp), v0 = ring_read4(cp + 4), v1 = ring_read4(cp + 8);
-        float b0[4], b1[4], b2[4], b3[4];
-        band_b(band_lane, h.x & 0xffffu, b0);
-        band_b(band_lane, h.x >> 16, b1);
-        band_b(band_lane, h.y & 0xffffu, b2);
-        band_b(band_lane, h.y >> 16, b3);
-        const uint32_t ra = uni(h.z), rb = uni(h.w);
-        const uint32_t r0[2] = {ra, ra >> 8}, r1[2] = {ra >> 16, ra >> 24}, r2[2] = {rb, rb >> 8}, r3[2] = {rb >> 16, rb >> 24};
-        const float a0[2] = {__uint_as_float(v0.x), __uint_as_float(v0.y)}, a1[2] = {__uint_as_float(v0.z), __uint_as_float(v0.w)};
-        const float a2[2] = {__uint_as_float(v1.x), __uint_as_float(v1.y)}, a3[2] = {__uint_as_float(v1.z), __uint_as_float(v1.w)};
-        run_fma<2, 4>(acc, r0, a0, b0);
-        run_fma<2, 4>(acc, r1, a1, b1);
-        run_fma<2, 4>(acc, r2, a2, b2);
-        run_fma<2, 4>(acc, r3, a3, b3);
-    }
-    for (int32_t c = 0; c < n4; ++c, cp += 12) {
-        const u32x4 h = ring_read4(cp), v0 = ring_read4(cp + 4), v1 = ring_read4(cp + 8);
-        float b0[4], b1[4];
-        band_b(band_lane, h.x & 0xffffu, b0);
-        band_b(band_lane, h.x >> 16, b1);
-        const uint32_t ra = uni(h.y), rb = uni(h.z);
-        const uint32_t r0[4] = {ra, ra >> 8, ra >> 16, ra >> 24}, r1[4] = {rb, rb >> 8, rb >> 16, rb >> 24};
-        const float a0[4] = {__uint_as_float(v0.x), __uint_as_float(v0.y), __uint_as_float(v0.z), __uint_as_float(v0.w)};
-        const float a1[4] = {__uint_as_float(v1.x), __uint_as_float(v1.y), __uint_as_float(v1.z), __uint_as_float(v1.w)};
-        run_fma<4, 4>(acc, r0, a0, b0);
-        run_fma<4, 4>(acc, r1, a1, b1);
-    }
-    for (int32_t c = 0; c < n8; ++c, cp += 12) {
-        const u32x4 h = ring_read4(cp), v0 = ring_read4(cp + 4), v1 = ring_read4(cp + 8);
-        float b0[4];
-        band_b(band_lane, h.x & 0xffffu, b0);
-        const uint32_t ra = uni(h.y), rb = uni(h.z);
-        const uint32_t r0[8] = {ra, ra >> 8, ra >> 16, ra >> 24, rb, rb >> 8, rb >> 16, rb >> 24};
-        const float a0[8] = {__uint_as_float(v0.x), __uint_as_float(v0.y), __uint_as_float(v0.z), __uint_as_float(v0.w),
-                             __uint_as_float(v1.x), __uint_as_float(v1.y), __uint_as_float(v1.z), __uint_as_float(v1.w)};
-        run_fma<8, 4>(acc, r0, a0, b0);
-    }
+    cp = band_chunks<1>(acc, cp, (int32_t)(counts & 255u), band_lane);
+    cp = band_chunks<2>(acc, cp, (int32_t)((counts >> 8) & 255u), band_lane);
+    cp = band_chunks<4>(acc, cp, (int32_t)((counts >> 16) & 255u), band_lane);
+    band_chunks<8>(acc, cp, (int32_t)(counts >> 24), band_lane);
 }
 
 __global__ __launch_bounds__(64 * kBandWaves) void spdm_band(const uint32_t* __restrict__ stream, const int32_t* __restrict__ gIdxes,
@@ -121,7 +153,11 @@ __global__ __launch_bounds__(64 * kBandWaves) void spdm_band(const uint32_t* __r
     const int64_t q = Q * kBandWaves + wv;
     const int64_t j0 = tile * 256 + (int64_t)lane * 4;
     const bool in = j0 < N;
-    const float* Bl = B + tile * 256 + (in ? lane * 4 : 0);      // lanes beyond N re-read the first columns of the tile
+    // Row bases are wave-uniform (SGPRs); the lane's place inside the tile is a 32-bit byte
+    // offset.  Lanes beyond N read the first columns of the tile instead (always inside B).
+    const char* Bbytes = reinterpret_cast<const char*>(B + tile * 256);
+    const uint32_t lane_off = in ? (uint32_t)lane * 16u : 0u;
+    const uint32_t ldb4 = (uint32_t)ldb * 4u;                     // the launcher checks that ldb*4 fits 32 bits
     const int32_t nb = (int32_t)((uni((uint32_t)ucount[Q]) + kBandRows - 1) / kBandRows);
     const uint32_t* st = stream + band_stream_base((int32_t)uni((uint32_t)gIdxes[q < g ? q : g]), q, k);
 
@@ -137,14 +173,21 @@ __global__ __launch_bounds__(64 * kBandWaves) void spdm_band(const uint32_t* __r
     auto fetch_block = [&](int64_t pos) -> u32x4 {                // 256 words from `pos`: a block and what follows it
         return *reinterpret_cast<const u32x4*>(st + pos + lane * 4);
     };
+    // The header of a band's first block is also read one step ahead with scalar loads (the
+    // address is the same for the whole wave), so that the step can start its fetches from
+    // SGPRs at once instead of reading the ring and moving eleven words to SGPRs.
+    struct Head { u32x4 a, b, c; };                               // words 0..3, 4..7, 8..11 of a block
+    auto head_at = [&](int64_t pos) -> Head {
+        const u32x4* hp = reinterpret_cast<const u32x4*>(st + pos);
+        return Head{hp[0], hp[1], hp[2]};
+    };
     // A wave always fetches and stores its eight rows of a band: where the band has fewer than 64
     // rows the header names row 0 of B and the slot is never read.
     f32x4 pr[8];
-    auto fetch_rows = [&](const lds_u32* hdr) {                   // this wave's rows of the band that the header announces
-        const u32x4 ia = ring_read4(hdr + 4), ib = ring_read4(hdr + 8);
-        const uint32_t id[8] = {uni(ia.x), uni(ia.y), uni(ia.z), uni(ia.w), uni(ib.x), uni(ib.y), uni(ib.z), uni(ib.w)};
+    auto fetch_rows = [&](const Head& h) {                        // this wave's rows of the band that the header announces
+        const uint32_t id[8] = {h.b.x, h.b.y, h.b.z, h.b.w, h.c.x, h.c.y, h.c.z, h.c.w};
 #pragma unroll
-        for (int t = 0; t < 8; ++t) pr[t] = *reinterpret_cast<const f32x4*>(Bl + (int64_t)id[t] * ldb);
+        for (int t = 0; t < 8; ++t) pr[t] = *reinterpret_cast<const f32x4*>(Bbytes + (uint64_t)id[t] * ldb4 + lane_off);
     };
     auto store_rows = [&](int buf) {
 #pragma unroll
@@ -152,40 +195,46 @@ __global__ __launch_bounds__(64 * kBandWaves) void spdm_band(const uint32_t* __r
     };
 
     // start: the pre-block says what to fetch for band 0
-    int64_t pos = 0;
+    int64_t pos;
+    Head hd;
     {
-        ring_w[0 * 64 + lane] = fetch_block(0);
-        const u32x4 h = ring_read4(ring);
-        pos = (int64_t)uni(h.z);
-        fetch_rows(ring);
+        const Head pre = head_at(0);
+        pos = (int64_t)pre.a.z;
+        fetch_rows(pre);
         const u32x4 first = fetch_block(pos);
+        hd = head_at(pos);
         store_rows(0);
         ring_w[1 * 64 + lane] = first;
     }
     __syncthreads();
 
     for (int32_t b = 0; b < nb; ++b) {
-        const lds_u32* blk = ring + ((b + 1) & 1) * kBandBlockMax;   // this band's first block
-        const int64_t next_pos = pos + (int64_t)uni(ring_read4(blk).z);
-        // band b+1: rows and first block on their way while band b is multiplied (after the last
-        // band the header names row 0 eight times and the block read stays inside the stream's slack)
-        fetch_rows(blk);
+        // band b+1: rows, first block and its header on their way while band b is multiplied (after
+        // the last band the header names row 0 eight times and the reads stay inside the stream's slack)
+        const int64_t next_pos = pos + (int64_t)hd.a.z;
+        const Head hn = head_at(next_pos);
+        fetch_rows(hd);
         const u32x4 next_block = fetch_block(next_pos);
 
         const char __attribute__((address_space(3)))* band_lane = band0 + (b & 1) * kBandBufBytes + lane * 16;
-        int64_t bpos = pos;
-        for (;;) {                                                // the blocks of this band: one, unless the group has many entries in it
-            const u32x4 h = ring_read4(blk);
-            band_block(acc, blk, band_lane, uni(h.x));
-            if (uni(h.y) & 1u) break;
-            bpos += (int64_t)uni(h.w);
-            ring_w[2 * 64 + lane] = fetch_block(bpos);
-            blk = ring + 2 * kBandBlockMax;
+        const lds_u32* blk = ring + ((b + 1) & 1) * kBandBlockMax;   // this band's first block
+        band_block(acc, blk, band_lane, hd.a.x);
+        if (!(hd.a.y & 1u)) {                                     // further blocks of this band: a group with many entries in it
+            int64_t bpos = pos + (int64_t)hd.a.w;
+            for (;;) {
+                ring_w[2 * 64 + lane] = fetch_block(bpos);
+                blk = ring + 2 * kBandBlockMax;
+                const u32x4 h = ring_read4(blk);
+                band_block(acc, blk, band_lane, uni(h.x));
+                if (uni(h.y) & 1u) break;
+                bpos += (int64_t)uni(h.w);
+            }
         }
 
         store_rows((b + 1) & 1);
         ring_w[(b & 1) * 64 + lane] = next_block;
         pos = next_pos;
+        hd = hn;
         __syncthreads();
     }
 

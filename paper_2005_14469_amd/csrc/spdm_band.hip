@@ -10,6 +10,7 @@ hipError_t launch_spdm_band(const BandArgs& a, hipStream_t s)
     const int64_t grid = (total + 7) / 8 * 8;              // whole rounds over the 8 XCDs
     if (grid <= 0 || grid > 0x7fffffffLL) return hipErrorInvalidConfiguration;
     if (a.p > kBandMaxP || a.N % 4 != 0 || a.ldb % 4 != 0 || a.ldc % 4 != 0) return hipErrorInvalidValue;
+    if (a.ldb > 0x3fffffffLL) return hipErrorInvalidValue;   // row pitch in bytes is kept in 32 bits
     // more LDS than the default limit of a workgroup: ask for it once per device
     static thread_local int asked_on = -1;
     int dev = -1;

@@ -78,6 +78,13 @@ def build(m, k, p, gIdxes, rows, cols, vals):
                         slot = int(rank[i]) - R * b
                         for (x, t) in pieces_of_run(j - i):
                             lists[t].append((slot, i + x))
+                    # pieces that would leave a chunk of 4s or 2s partly filled are halved and join the
+                    # end of the next smaller type's list (the two halves in order)
+                    for t in (4, 2):
+                        J = JT[t]; keep = len(lists[t]) // J * J
+                        for (sl, st) in lists[t][keep:]:
+                            lists[t // 2] += [(sl, st), (sl, st + t // 2)]
+                        del lists[t][keep:]
                     body = []
                     counts = {}
                     for t in TYPES:

@@ -22,6 +22,14 @@ def _say(msg):
     print(msg, flush=True)
 
 
+@pytest.fixture
+def band_always():
+    """Conversions inside the test build the band schedule whenever the band kernel could run."""
+    binding.gcoo_set_band_policy(binding.BAND_ALWAYS)
+    yield
+    binding.gcoo_set_band_policy(binding.BAND_AUTO)
+
+
 def _assert_arrays_equal(exp, G):
     assert np.array_equal(exp["rows"], G.rows)
     assert np.array_equal(exp["cols"], G.cols)
@@ -145,7 +153,7 @@ def _band_base(first_entry, q, k):
     (100, 300, 32, 0.95), (257, 1000, 32, 0.99), (70, 200, 16, 0.94), (33, 50, 8, 0.95), (300, 70, 32, 0.96),
     (1, 1, 1, 0.0), (520, 5000, 32, 0.97), (64, 4000, 32, 0.999), (2000, 2000, 32, 0.98), (256, 64, 32, 0.95),
 ])
-def test_band_schedule_bit_exact(m, k, p, s):
+def test_band_schedule_bit_exact(band_always, m, k, p, s):
     """The band schedule written by the HIP builder equals the Python model word for word."""
     from tests import band_model
     _say(f"band schedule m={m} k={k} p={p} sparsity={s}")
@@ -167,7 +175,7 @@ def test_band_schedule_bit_exact(m, k, p, s):
         assert np.array_equal(got["words"][base:base + len(st)], st), f"stream {q}"
 
 
-def test_band_schedule_bit_exact_with_repeated_coordinates():
+def test_band_schedule_bit_exact_with_repeated_coordinates(band_always):
     from tests import band_model
     from tests.test_band_model import repeated_coordinates_workload
     m, k, N, row_ptr, col_idx, vals, B = repeated_coordinates_workload()
@@ -248,7 +256,7 @@ def test_heavy_groups_shared_by_a_workgroup(m, k, N, p, sparsity):
     (1, 1, 4, 1, 0.0), (520, 5000, 512, 32, 0.97), (64, 4000, 256, 32, 0.999), (2000, 2000, 300, 32, 0.98), (256, 64, 1028, 32, 0.95),
     (1000, 3000, 256, 32, 0.94),
 ])
-def test_band_variant(m, k, N, p, sparsity):
+def test_band_variant(band_always, m, k, N, p, sparsity):
     """The kernel whose eight waves share the rows of B through LDS, on matrices sparse enough to have a band schedule."""
     w = workloads.uniform_random(m, k, N, sparsity, seed=5 * m + k + N)
     _say(f"band variant m={m} k={k} N={N} p={p} nnz={w.nnz}")
@@ -260,7 +268,7 @@ def test_band_variant(m, k, N, p, sparsity):
     assert np.array_equal(c1, c2)
 
 
-def test_band_variant_repeated_coordinates_and_strides():
+def test_band_variant_repeated_coordinates_and_strides(band_always):
     from tests.test_band_model import repeated_coordinates_workload
     m, k, N, row_ptr, col_idx, vals, B = repeated_coordinates_workload()
     _say("band variant: repeated coordinates, strided operands")
@@ -432,3 +440,24 @@ def test_tune_p_returns_a_measured_candidate():
     best, times = binding.gcoo_tune_p(w.m, w.k, *args, torch.from_numpy(w.B).to(DEV), candidates=(8, 32, 128), reps=2)
     assert set(times) == {8, 32, 128} and best in times and all(t > 0 for t in times.values())
     assert binding.gcoo_default_p(w.m, w.k, w.nnz, w.N) == 32
+
+
+def test_band_policy_and_automatic_choice():
+    """By default a matrix gets a band schedule only where the band kernel is the automatic choice."""
+    _say("band policy")
+    w = workloads.uniform_random(64, 12000, 256, 0.97, seed=8)         # 12000 columns, 3 % dense
+    Bt = torch.from_numpy(w.B).to(DEV)
+    Cg = torch.empty((w.m, w.N), device=DEV)
+    A = binding.gcoo_from_csr(w.m, w.k, w.row_ptr, w.col_idx, w.vals, 32, device=DEV)
+    assert A.export_band() is not None and binding.gcoo_spdm_pick(A, Bt, Cg) == binding.VARIANT_BAND
+    _check_product(w, 32, binding.VARIANT_AUTO, A=A)
+    w2 = workloads.uniform_random(64, 3000, 256, 0.97, seed=8)         # too few columns for the band kernel to pay
+    A2 = binding.gcoo_from_csr(w2.m, w2.k, w2.row_ptr, w2.col_idx, w2.vals, 32, device=DEV)
+    assert A2.export_band() is None
+    assert binding.gcoo_spdm_pick(A2, torch.from_numpy(w2.B).to(DEV), Cg) == binding.VARIANT_REG
+    binding.gcoo_set_band_policy(binding.BAND_NEVER)
+    try:
+        A3 = binding.gcoo_from_csr(w.m, w.k, w.row_ptr, w.col_idx, w.vals, 32, device=DEV)
+        assert A3.export_band() is None and binding.gcoo_spdm_pick(A3, Bt, Cg) == binding.VARIANT_REG
+    finally:
+        binding.gcoo_set_band_policy(binding.BAND_AUTO)
