@@ -26,6 +26,8 @@ ROOT = os.path.dirname(os.path.abspath(__file__))
 if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
+KERNEL_NAMES = {1: "gcoo::spdm_lds", 2: "gcoo::spdm_sched", 3: "gcoo::spdm_band"}
+KERNEL_FILES = {1: "spdm_lds", 2: "spdm_sched", 3: "spdm_band"}
 HBM_PEAK_GBS = 8000.0          # MI355X HBM3E, published
 FP32_VECTOR_PEAK_TF = 157.3    # published (packed fp32); plain v_fma_f32 reaches half of it
 
@@ -36,7 +38,8 @@ def parse():
     ap.add_argument("--steps", type=int, default=50)
     ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--workload", default="config3",
-                    help="config0..config4 (the five named workloads); config3 = 8000^2, sparsity 0.995")
+                    help="config0..config4 (the five named workloads; config3 = 8000^2, sparsity 0.995), or "
+                         "uniform_<n>_<sparsity> for a square uniform random A with N = n")
     ap.add_argument("--p", type=int, default=0, help="group height; 0 = library default for the workload")
     ap.add_argument("--variant", type=int, default=0, help="0 auto, 1 partial sums in LDS, 2 partial sums in registers")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle timing")
@@ -173,8 +176,11 @@ def default_p(name: str) -> int:
 
 
 def run_one(torch, binding, workloads, name, args, dev, steps, warmup):
-    idx = int(name.replace("config", ""))
-    w = workloads.config(idx)
+    if name.startswith("uniform_"):                       # uniform_<n>_<sparsity>: square uniform random A, N = n
+        _, n_, s_ = name.split("_")
+        w = workloads.uniform_random(int(n_), int(n_), int(n_), float(s_), workloads.BASE_SEED + int(n_), name=name)
+    else:
+        w = workloads.config(int(name.replace("config", "")))
     p = args.p or default_p(name)
     r = time_path(torch, binding, w, dev, p, args.variant, steps, warmup)
     flops = 2.0 * w.nnz * w.N
@@ -383,8 +389,8 @@ def main():
         "spdm": {"ms": head["spdm_ms"], "ms_min": head["spdm_ms_min"], "gflops": head["spdm_gflops"],
                  "convert_ms": head["convert_ms"], "frac_of_fp32_vector_peak": head["valu_frac_of_published"]},
         "roofline": {"bound": "hbm", "achieved": head["hbm_gbs"], "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                     "frac": head["hbm_frac"], "traffic": read_traffic("spdm_sched", args.workload),
-                     "kernel": "gcoo::spdm_sched", "algorithmic_bytes_per_launch": head["alg_bytes"]},
+                     "frac": head["hbm_frac"], "traffic": read_traffic(KERNEL_FILES.get(head["variant"], "spdm_sched"), args.workload),
+                     "kernel": KERNEL_NAMES.get(head["variant"], "?"), "algorithmic_bytes_per_launch": head["alg_bytes"]},
     }
     if not args.no_dense:
         d = dense_ms(torch, w, dev)

@@ -48,7 +48,7 @@ struct Layout {
     size_t band_ucols, band_ucount, band_stream;           // band schedule of the workgroup-shared kernel (may be empty)
     size_t tmp_cols, tmp_rows, tmp_vals;                   // conversion scratch (second sort buffer)
     size_t in_row_ptr, in_cols, in_vals;                   // staging of a host CSR input
-    size_t counter;                                        // 8-byte device counter
+    size_t counter;                                        // two 8-byte device counters (nnz, largest group)
     size_t blk;                                            // dense input: entries per (group, column block)
     size_t total;
 };
@@ -127,7 +127,7 @@ Layout make_layout(int64_t m, int64_t k, int64_t nnz, int64_t g, int32_t p)
     // counted into them before nnz is known
     L.gIdxes = take((size_t)(g + 1) * 4);
     L.nnzPerGroup = take((size_t)g * 4);
-    L.counter = take(8);
+    L.counter = take(16);
     L.blk = take((size_t)g * (size_t)dense_blocks(k) * 4);
     L.values = take(n4);
     L.rows = take(n4);
@@ -166,6 +166,7 @@ int radix_passes(int64_t k)
 
 struct gcoo_matrix {
     int64_t m, k, nnz, g;
+    int64_t max_group_nnz;     // entries of the largest group
     int32_t p;
     int32_t nw, window_cols;
     bool has_band;             // the band schedule was built
@@ -188,11 +189,12 @@ struct gcoo_matrix {
 
 namespace {
 
-int new_handle(int64_t m, int64_t k, int64_t nnz, int32_t p, void* dev_buf, gcoo_matrix** out)
+int new_handle(int64_t m, int64_t k, int64_t nnz, int64_t max_group_nnz, int32_t p, void* dev_buf, gcoo_matrix** out)
 {
     gcoo_matrix* h = new (std::nothrow) gcoo_matrix;
     if (!h) return GCOO_ENOMEM;
     h->m = m; h->k = k; h->nnz = nnz; h->p = p;
+    h->max_group_nnz = max_group_nnz;
     h->g = (m + p - 1) / p;
     h->base = static_cast<char*>(dev_buf);
     h->L = make_layout(m, k, nnz, h->g, p);
@@ -257,13 +259,22 @@ int gcoo_from_csr(int64_t m, int64_t k, const int32_t* row_ptr, const int32_t* c
     if (reinterpret_cast<uintptr_t>(dev_buf) % kAlign) return GCOO_EINVAL;
     hipStream_t s = static_cast<hipStream_t>(stream);
 
-    int64_t nnz;
+    const int64_t g = (m + p - 1) / p;
+    int64_t nnz, max_group_nnz = 0;
     if (src_on_device) {
-        int32_t last = 0;
-        HIP_TRY(hipMemcpyAsync(&last, row_ptr + m, sizeof(int32_t), hipMemcpyDeviceToHost, s));
+        // nnz and the size of the largest group come back in one small copy (the counters sit at
+        // an offset of the buffer that does not depend on nnz)
+        const Layout L0 = make_layout(m, k, 0, g, p);
+        if (dev_buf_bytes < L0.total) return GCOO_ENOMEM;
+        unsigned long long* stats = reinterpret_cast<unsigned long long*>(static_cast<char*>(dev_buf) + L0.counter);
+        unsigned long long got[2] = {0, 0};
+        gcoo::group_stats_from_row_ptr<<<dim3(1), dim3(256), 0, s>>>(row_ptr, m, p, g, stats);
+        HIP_TRY(hipGetLastError());
+        HIP_TRY(hipMemcpyAsync(got, stats, sizeof(got), hipMemcpyDeviceToHost, s));
         HIP_TRY(hipStreamSynchronize(s));
-        nnz = last;
-        if (nnz < 0) return GCOO_EBOUNDS;
+        if (got[0] > (unsigned long long)INT32_MAX) return GCOO_EBOUNDS;
+        nnz = (int64_t)got[0];
+        max_group_nnz = (int64_t)got[1];
     } else {
         if (row_ptr[0] != 0) return GCOO_EBOUNDS;
         for (int64_t i = 0; i < m; ++i)
@@ -272,14 +283,18 @@ int gcoo_from_csr(int64_t m, int64_t k, const int32_t* row_ptr, const int32_t* c
         if (nnz > 0 && (!col_idx || !vals)) return GCOO_EINVAL;
         for (int64_t e = 0; e < nnz; ++e)
             if (col_idx[e] < 0 || col_idx[e] >= k) return GCOO_EBOUNDS;
+        for (int64_t q = 0; q < g; ++q) {
+            const int64_t r0 = q * p, r1 = (r0 + p < m) ? r0 + p : m;
+            const int64_t n = (int64_t)row_ptr[r1] - row_ptr[r0];
+            if (n > max_group_nnz) max_group_nnz = n;
+        }
     }
     if (nnz > 0 && (!col_idx || !vals)) return GCOO_EINVAL;
-    const int64_t g = (m + p - 1) / p;
     const Layout L = make_layout(m, k, nnz, g, p);
     if (dev_buf_bytes < L.total) return GCOO_ENOMEM;
 
     gcoo_matrix* h = nullptr;
-    int rc = new_handle(m, k, nnz, p, dev_buf, &h);
+    int rc = new_handle(m, k, nnz, max_group_nnz, p, dev_buf, &h);
     if (rc != GCOO_OK) return rc;
     char* base = h->base;
 
@@ -377,7 +392,7 @@ int gcoo_from_dense(int64_t m, int64_t k, const float* A_dev, int64_t lda, int32
     int32_t* idx = reinterpret_cast<int32_t*>(base + L0.gIdxes);
     int32_t* blk = reinterpret_cast<int32_t*>(base + L0.blk);
     unsigned long long* tot = reinterpret_cast<unsigned long long*>(base + L0.counter);
-    unsigned long long total = 0;
+    unsigned long long total = 0, largest = 0;
     const int vw = dense_vec_width(A_dev, lda, k);
     const int64_t nblk = dense_blocks(k, vw);
     // one workgroup per (group, column block); a band holds fewer than 2^31 elements so that
@@ -395,8 +410,11 @@ int gcoo_from_dense(int64_t m, int64_t k, const float* A_dev, int64_t lda, int32
         HIP_TRY(hipGetLastError());
         gcoo::scan_group_counts<<<dim3(1), dim3(256), 0, s>>>(cnt, g, idx, tot);
         HIP_TRY(hipGetLastError());
-        HIP_TRY(hipMemcpyAsync(&total, tot, 8, hipMemcpyDeviceToHost, s));
+        unsigned long long got[2] = {0, 0};
+        HIP_TRY(hipMemcpyAsync(got, tot, sizeof(got), hipMemcpyDeviceToHost, s));
         HIP_TRY(hipStreamSynchronize(s));
+        total = got[0];
+        largest = got[1];
     } else {
         HIP_TRY(hipMemsetAsync(idx, 0, 4, s));          // only the sentinel exists
     }
@@ -405,7 +423,7 @@ int gcoo_from_dense(int64_t m, int64_t k, const float* A_dev, int64_t lda, int32
     const Layout L = make_layout(m, k, nnz, g, p);
     if (dev_buf_bytes < L.total) return GCOO_ENOMEM;
     gcoo_matrix* h = nullptr;
-    int rc = new_handle(m, k, nnz, p, dev_buf, &h);
+    int rc = new_handle(m, k, nnz, (int64_t)largest, p, dev_buf, &h);
     if (rc != GCOO_OK) return rc;
     if (g > 0 && nnz > 0) {
         const dim3 grid((unsigned)(nblk * g)), block(gcoo::kDenseThreads);
@@ -460,15 +478,18 @@ namespace {
 
 // When the launch has too few (group, tile) items to fill the machine, the longest group sets
 // the run time: groups well above the mean load of a wave slot are then shared by the eight
-// waves of a workgroup (spdm_sched_coop).  Returns the entry count from which a group is
-// treated that way, INT32_MAX for "none".  The groups' sizes are not known on the host, so the
-// threshold comes from totals only.
+// waves of a workgroup (spdm_sched_coop).  Sharing costs every wave a start-up per class and
+// window, so it is only used when the largest group stands out (four times the mean group, a
+// skewed matrix) or when plain waves would leave seven eighths of the machine idle.  Returns
+// the entry count from which a group is treated that way, INT32_MAX for "none".
 int32_t heavy_group_min(const gcoo_matrix* A, int64_t tiles)
 {
     constexpr int64_t kWaveSlots = 2048;                   // 256 compute units x 8 resident waves of the register kernel
     constexpr int64_t kMinHeavy = 1024;
     const int64_t items = A->g * tiles;
     if (items <= 0 || items > 2 * kWaveSlots || A->nnz <= 0) return INT32_MAX;
+    const int64_t mean_group = A->nnz / A->g;
+    if (A->max_group_nnz < 4 * mean_group && items * 8 > kWaveSlots) return INT32_MAX;
     const int64_t mean_per_slot = A->nnz * tiles / kWaveSlots;
     int64_t t = mean_per_slot + mean_per_slot / 2;
     if (t < kMinHeavy) t = kMinHeavy;

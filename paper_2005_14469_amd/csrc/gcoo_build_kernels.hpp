@@ -33,6 +33,33 @@ __global__ void group_index_from_row_ptr(const int32_t* __restrict__ row_ptr, in
     }
 }
 
+// What the host wants to know about a CSR input before it sizes anything: out[0] = nnz = row_ptr[m],
+// out[1] = entries of the largest group.  One workgroup.
+__global__ __launch_bounds__(256) void group_stats_from_row_ptr(const int32_t* __restrict__ row_ptr, int64_t m, int32_t p, int64_t g,
+                                                                 unsigned long long* __restrict__ out)
+{
+    __shared__ int32_t part[4];
+    int32_t mx = 0;
+    for (int64_t q = threadIdx.x; q < g; q += 256) {
+        const int64_t r0 = q * p, r1 = (r0 + p < m) ? r0 + p : m;
+        const int32_t n = row_ptr[r1] - row_ptr[r0];
+        mx = n > mx ? n : mx;
+    }
+#pragma unroll
+    for (int d = 32; d >= 1; d >>= 1) {
+        const int32_t o = __shfl_down(mx, d, kWave);
+        mx = o > mx ? o : mx;
+    }
+    if ((threadIdx.x & 63) == 0) part[threadIdx.x >> 6] = mx;
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        for (int i = 1; i < 4; ++i) mx = part[i] > mx ? part[i] : mx;
+        const int32_t last = row_ptr[m];
+        out[0] = last < 0 ? ~0ull : (unsigned long long)last;
+        out[1] = (unsigned long long)mx;
+    }
+}
+
 __device__ __forceinline__ uint64_t lanemask_lt()
 {
     return (1ull << (threadIdx.x & 63)) - 1ull;   // one wave per workgroup in the kernels below
@@ -256,18 +283,22 @@ __global__ __launch_bounds__(256) void scan_dense_blocks(int32_t* __restrict__ b
 }
 
 // Exclusive prefix sum of nnzPerGroup[g] into gIdxes[g+1] (sentinel = total).  One workgroup;
-// g is small (m / p), so a serial carry over 256-wide tiles is enough.
+// g is small (m / p), so a serial carry over 256-wide tiles is enough.  total[0] = nnz,
+// total[1] = entries of the largest group.
 __global__ __launch_bounds__(256) void scan_group_counts(const int32_t* __restrict__ nnzPerGroup, int64_t g,
                                                           int32_t* __restrict__ gIdxes, unsigned long long* __restrict__ total)
 {
     __shared__ int64_t wsum[4];
     __shared__ int64_t carry_s;
+    __shared__ int32_t wmax[4];
     if (threadIdx.x == 0) carry_s = 0;
     __syncthreads();
     const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
+    int32_t mx = 0;
     for (int64_t t0 = 0; t0 < g; t0 += 256) {
         const int64_t i = t0 + threadIdx.x;
         const int64_t v = (i < g) ? nnzPerGroup[i] : 0;
+        mx = (int32_t)v > mx ? (int32_t)v : mx;
         int64_t incl = v;
 #pragma unroll
         for (int d = 1; d < kWave; d <<= 1) {
@@ -283,10 +314,19 @@ __global__ __launch_bounds__(256) void scan_group_counts(const int32_t* __restri
         if (threadIdx.x == 255) carry_s = off + incl;
         __syncthreads();
     }
+#pragma unroll
+    for (int d = 32; d >= 1; d >>= 1) {
+        const int32_t o = __shfl_down(mx, d, kWave);
+        mx = o > mx ? o : mx;
+    }
+    if (lane == 0) wmax[w] = mx;
+    __syncthreads();
     if (threadIdx.x == 0) {
-        // totals above INT32_MAX are reported through *total and rejected by the host
+        // totals above INT32_MAX are reported through total[0] and rejected by the host
         gIdxes[g] = (int32_t)(carry_s > 0x7fffffffLL ? 0x7fffffffLL : carry_s);
-        *total = (unsigned long long)carry_s;
+        total[0] = (unsigned long long)carry_s;
+        for (int i = 1; i < 4; ++i) mx = wmax[i] > mx ? wmax[i] : mx;
+        total[1] = (unsigned long long)mx;
     }
 }
 
