@@ -77,10 +77,11 @@ def time_path(torch, binding, w, dev, p, variant, steps, warmup):
 
     def convert():
         out = Cc.c_void_p()
-        rc = L.gcoo_from_csr(w.m, w.k, rp.data_ptr(), ci.data_ptr(), va.data_ptr(), 1, p, buf.data_ptr(), need, sp,
-                             Cc.byref(out))
+        # the CSR arrays are on the device and nnz is known: the conversion reads nothing back
+        rc = L.gcoo_from_csr_device(w.m, w.k, w.nnz, rp.data_ptr(), ci.data_ptr(), va.data_ptr(), p, buf.data_ptr(), need, sp,
+                                    Cc.byref(out))
         if rc != 0:
-            raise binding.GcooError(rc, "gcoo_from_csr")
+            raise binding.GcooError(rc, "gcoo_from_csr_device")
         return out
 
     def multiply(h):

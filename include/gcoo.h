@@ -95,6 +95,19 @@ int gcoo_from_csr(int64_t m, int64_t k,
                   gcoo_matrix** out);
 
 /*
+ * gcoo_from_csr() for a CSR matrix that is already on the device, by a caller who knows nnz (the
+ * one who sized dev_buf with it).  Nothing is read back: the call only launches kernels on `stream`
+ * and returns.  row_ptr_dev[m] must equal nnz; if it does not, the result is unspecified but every
+ * kernel stays inside the arrays (offsets are clamped to nnz).  A later gcoo_spdm() of few work
+ * items (at most 4096 group x column-tile pairs) synchronises `stream` once, to learn the size
+ * of the largest group.
+ */
+int gcoo_from_csr_device(int64_t m, int64_t k, int64_t nnz,
+                         const int32_t* row_ptr_dev, const int32_t* col_idx_dev, const float* vals_dev,
+                         int32_t p, void* dev_buf, size_t dev_buf_bytes, void* stream,
+                         gcoo_matrix** out);
+
+/*
  * Algorithm 1, step 1: count the entries of a dense device matrix A_dev (m x k, row-major,
  * leading dimension lda >= k) that are not equal to zero.  Writes the count to *nnz (host).
  * Synchronises `stream`.  Used to size dev_buf before gcoo_from_dense().

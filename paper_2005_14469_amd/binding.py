@@ -21,7 +21,7 @@ VARIANT_AUTO, VARIANT_LDS, VARIANT_REG, VARIANT_BAND = 0, 1, 2, 3
 BAND_AUTO, BAND_ALWAYS, BAND_NEVER = 0, 1, 2
 
 # every symbol include/gcoo.h declares
-SYMBOLS = ["gcoo_default_p", "gcoo_device_bytes", "gcoo_from_csr", "gcoo_dense_nnz", "gcoo_from_dense", "gcoo_spdm",
+SYMBOLS = ["gcoo_default_p", "gcoo_device_bytes", "gcoo_from_csr", "gcoo_from_csr_device", "gcoo_dense_nnz", "gcoo_from_dense", "gcoo_spdm",
            "gcoo_spdm_variant", "gcoo_spdm_pick", "gcoo_free", "gcoo_info", "gcoo_export",
            "gcoo_strerror", "gcoo_last_hip_error", "gcoo_csr_spmm_baseline",
            "gcoo_band_words", "gcoo_export_band", "gcoo_set_band_policy"]
@@ -69,6 +69,8 @@ def lib():
         L.gcoo_info.argtypes = [vp, C.POINTER(i64), C.POINTER(i64), C.POINTER(i64), C.POINTER(i32), C.POINTER(i64)]
         L.gcoo_export.restype = C.c_int
         L.gcoo_export.argtypes = [vp, vp, vp, vp, vp, vp, vp]
+        L.gcoo_from_csr_device.restype = C.c_int
+        L.gcoo_from_csr_device.argtypes = [i64, i64, i64, vp, vp, vp, i32, vp, C.c_size_t, vp, C.POINTER(vp)]
         L.gcoo_set_band_policy.restype = C.c_int
         L.gcoo_set_band_policy.argtypes = [C.c_int]
         L.gcoo_band_words.restype = C.c_int64
@@ -164,8 +166,12 @@ def _alloc(nbytes: int, device) -> torch.Tensor:
     return buf
 
 
-def gcoo_from_csr(m: int, k: int, row_ptr, col_idx, vals, p: int, device="cuda:0", stream=None) -> GcooMatrix:
-    """row_ptr/col_idx/vals: numpy arrays (host input) or torch device tensors (device input)."""
+def gcoo_from_csr(m: int, k: int, row_ptr, col_idx, vals, p: int, device="cuda:0", stream=None,
+                  known_nnz: bool = False) -> GcooMatrix:
+    """row_ptr/col_idx/vals: numpy arrays (host input) or torch device tensors (device input).
+
+    known_nnz (device input only): the caller vouches that row_ptr[m] == len(col_idx); the
+    conversion then reads nothing back and never waits for the device (gcoo_from_csr_device)."""
     on_dev = isinstance(row_ptr, torch.Tensor)
     if on_dev:
         assert row_ptr.is_cuda and row_ptr.dtype == torch.int32 and row_ptr.is_contiguous()
@@ -185,8 +191,12 @@ def gcoo_from_csr(m: int, k: int, row_ptr, col_idx, vals, p: int, device="cuda:0
     with torch.cuda.device(device):
         buf = _alloc(need, device)
         out = C.c_void_p()
-        _check(lib().gcoo_from_csr(m, k, ptrs[0], ptrs[1], ptrs[2], 1 if on_dev else 0, p, buf.data_ptr(),
-                                   buf.numel(), _stream_ptr(stream), C.byref(out)), "gcoo_from_csr")
+        if on_dev and known_nnz:
+            _check(lib().gcoo_from_csr_device(m, k, nnz, ptrs[0], ptrs[1], ptrs[2], p, buf.data_ptr(), buf.numel(),
+                                              _stream_ptr(stream), C.byref(out)), "gcoo_from_csr_device")
+        else:
+            _check(lib().gcoo_from_csr(m, k, ptrs[0], ptrs[1], ptrs[2], 1 if on_dev else 0, p, buf.data_ptr(),
+                                       buf.numel(), _stream_ptr(stream), C.byref(out)), "gcoo_from_csr")
     return GcooMatrix(out.value, buf)
 
 

@@ -166,7 +166,7 @@ int radix_passes(int64_t k)
 
 struct gcoo_matrix {
     int64_t m, k, nnz, g;
-    int64_t max_group_nnz;     // entries of the largest group
+    mutable int64_t max_group_nnz;   // entries of the largest group; -1: still on the device (L.counter + 8), fetched on first need
     int32_t p;
     int32_t nw, window_cols;
     bool has_band;             // the band schedule was built
@@ -250,8 +250,13 @@ size_t gcoo_device_bytes(int64_t m, int64_t k, int64_t nnz, int32_t p)
     return make_layout(m, k, nnz, (m + p - 1) / p, p).total;
 }
 
-int gcoo_from_csr(int64_t m, int64_t k, const int32_t* row_ptr, const int32_t* col_idx, const float* vals,
-                  int src_on_device, int32_t p, void* dev_buf, size_t dev_buf_bytes, void* stream, gcoo_matrix** out)
+}  // extern "C"
+
+namespace {
+
+// gcoo_from_csr() and gcoo_from_csr_device().  nnz_known < 0: learn nnz from the input.
+int from_csr(int64_t m, int64_t k, const int32_t* row_ptr, const int32_t* col_idx, const float* vals, int src_on_device,
+             int64_t nnz_known, int32_t p, void* dev_buf, size_t dev_buf_bytes, void* stream, gcoo_matrix** out)
 {
     if (!out) return GCOO_EINVAL;
     *out = nullptr;
@@ -262,19 +267,26 @@ int gcoo_from_csr(int64_t m, int64_t k, const int32_t* row_ptr, const int32_t* c
     const int64_t g = (m + p - 1) / p;
     int64_t nnz, max_group_nnz = 0;
     if (src_on_device) {
-        // nnz and the size of the largest group come back in one small copy (the counters sit at
-        // an offset of the buffer that does not depend on nnz)
+        // nnz and the size of the largest group are computed on the device (the counters sit at
+        // an offset of the buffer that does not depend on nnz).  They come back in one small
+        // copy, unless the caller has given nnz: then nothing is read back here and the size of
+        // the largest group is fetched the first time a launch needs it.
         const Layout L0 = make_layout(m, k, 0, g, p);
         if (dev_buf_bytes < L0.total) return GCOO_ENOMEM;
         unsigned long long* stats = reinterpret_cast<unsigned long long*>(static_cast<char*>(dev_buf) + L0.counter);
-        unsigned long long got[2] = {0, 0};
         gcoo::group_stats_from_row_ptr<<<dim3(1), dim3(256), 0, s>>>(row_ptr, m, p, g, stats);
         HIP_TRY(hipGetLastError());
-        HIP_TRY(hipMemcpyAsync(got, stats, sizeof(got), hipMemcpyDeviceToHost, s));
-        HIP_TRY(hipStreamSynchronize(s));
-        if (got[0] > (unsigned long long)INT32_MAX) return GCOO_EBOUNDS;
-        nnz = (int64_t)got[0];
-        max_group_nnz = (int64_t)got[1];
+        if (nnz_known >= 0) {
+            nnz = nnz_known;
+            max_group_nnz = -1;
+        } else {
+            unsigned long long got[2] = {0, 0};
+            HIP_TRY(hipMemcpyAsync(got, stats, sizeof(got), hipMemcpyDeviceToHost, s));
+            HIP_TRY(hipStreamSynchronize(s));
+            if (got[0] > (unsigned long long)INT32_MAX) return GCOO_EBOUNDS;
+            nnz = (int64_t)got[0];
+            max_group_nnz = (int64_t)got[1];
+        }
     } else {
         if (row_ptr[0] != 0) return GCOO_EBOUNDS;
         for (int64_t i = 0; i < m; ++i)
@@ -317,7 +329,7 @@ int gcoo_from_csr(int64_t m, int64_t k, const int32_t* row_ptr, const int32_t* c
     // Algorithm 1, step 1: group index and counts straight from row_ptr (also writes the sentinel).
     {
         const unsigned blocks = (unsigned)((g + 1 + 255) / 256);
-        gcoo::group_index_from_row_ptr<<<dim3(blocks), dim3(256), 0, s>>>(d_row_ptr, m, p, g, h->gIdxes(), h->nnzPerGroup());
+        gcoo::group_index_from_row_ptr<<<dim3(blocks), dim3(256), 0, s>>>(d_row_ptr, m, p, g, (int32_t)nnz, h->gIdxes(), h->nnzPerGroup());
         hipError_t e = hipGetLastError();
         if (e != hipSuccess) { delete h; return hip_fail(e, "group_index_from_row_ptr"); }
     }
@@ -350,6 +362,23 @@ int gcoo_from_csr(int64_t m, int64_t k, const int32_t* row_ptr, const int32_t* c
     if (rc != GCOO_OK) { delete h; return rc; }
     *out = h;
     return GCOO_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+int gcoo_from_csr(int64_t m, int64_t k, const int32_t* row_ptr, const int32_t* col_idx, const float* vals,
+                  int src_on_device, int32_t p, void* dev_buf, size_t dev_buf_bytes, void* stream, gcoo_matrix** out)
+{
+    return from_csr(m, k, row_ptr, col_idx, vals, src_on_device, -1, p, dev_buf, dev_buf_bytes, stream, out);
+}
+
+int gcoo_from_csr_device(int64_t m, int64_t k, int64_t nnz, const int32_t* row_ptr_dev, const int32_t* col_idx_dev,
+                         const float* vals_dev, int32_t p, void* dev_buf, size_t dev_buf_bytes, void* stream, gcoo_matrix** out)
+{
+    if (nnz < 0 || nnz > INT32_MAX) { if (out) *out = nullptr; return GCOO_EINVAL; }
+    return from_csr(m, k, row_ptr_dev, col_idx_dev, vals_dev, 1, nnz, p, dev_buf, dev_buf_bytes, stream, out);
 }
 
 int gcoo_dense_nnz(int64_t m, int64_t k, const float* A_dev, int64_t lda, void* stream, int64_t* nnz)
@@ -482,12 +511,20 @@ namespace {
 // window, so it is only used when the largest group stands out (four times the mean group, a
 // skewed matrix) or when plain waves would leave seven eighths of the machine idle.  Returns
 // the entry count from which a group is treated that way, INT32_MAX for "none".
-int32_t heavy_group_min(const gcoo_matrix* A, int64_t tiles)
+int32_t heavy_group_min(const gcoo_matrix* A, int64_t tiles, hipStream_t s)
 {
     constexpr int64_t kWaveSlots = 2048;                   // 256 compute units x 8 resident waves of the register kernel
     constexpr int64_t kMinHeavy = 1024;
     const int64_t items = A->g * tiles;
     if (items <= 0 || items > 2 * kWaveSlots || A->nnz <= 0) return INT32_MAX;
+    if (A->max_group_nnz < 0) {
+        // a matrix converted without any read-back: fetch the size of its largest group now (once)
+        unsigned long long got = 0;
+        if (hipMemcpyAsync(&got, A->base + A->L.counter + 8, 8, hipMemcpyDeviceToHost, s) != hipSuccess ||
+            hipStreamSynchronize(s) != hipSuccess)
+            return INT32_MAX;
+        A->max_group_nnz = (int64_t)got;
+    }
     const int64_t mean_group = A->nnz / A->g;
     if (A->max_group_nnz < 4 * mean_group && items * 8 > kWaveSlots) return INT32_MAX;
     const int64_t mean_per_slot = A->nnz * tiles / kWaveSlots;
@@ -562,7 +599,7 @@ int gcoo_spdm_variant(const gcoo_matrix* A, const float* B_dev, int64_t ldb, int
     const int V = sched_width(A->p, shape_of(B_dev, ldb, N, C_dev, ldc));
     if (V == 0) return GCOO_EINVAL;
     gcoo::SpdmArgs a{A->sched_hdr(), A->sched(), A->gIdxes(), A->m, A->p, A->g, A->nw, B_dev, ldb, N, C_dev, ldc,
-                     heavy_group_min(A, (N + 64 * V - 1) / (64 * V))};
+                     heavy_group_min(A, (N + 64 * V - 1) / (64 * V), s)};
     hipError_t e = gcoo::launch_spdm_sched(V, a, s);
     if (e != hipSuccess) return hip_fail(e, "spdm_sched launch");
     return GCOO_OK;

@@ -17,19 +17,23 @@ constexpr int kWave = 64;
 // contiguous CSR range [row_ptr[q*p], row_ptr[min((q+1)*p, m)]): the count and the prefix sum
 // are two reads of row_ptr.  One thread per group; thread g also writes the sentinel.
 // ---------------------------------------------------------------------------------------------
-__global__ void group_index_from_row_ptr(const int32_t* __restrict__ row_ptr, int64_t m, int32_t p, int64_t g,
+__global__ void group_index_from_row_ptr(const int32_t* __restrict__ row_ptr, int64_t m, int32_t p, int64_t g, int32_t nnz,
                                          int32_t* __restrict__ gIdxes, int32_t* __restrict__ nnzPerGroup)
 {
     int64_t q = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
     if (q > g) return;
+    // Offsets are clamped to [0, nnz]: with a device input whose row_ptr does not match the nnz
+    // the buffer was laid out for, every later kernel still stays inside the arrays.
+    auto at = [&](int64_t r) { const int32_t v = row_ptr[r]; return v < 0 ? 0 : (v > nnz ? nnz : v); };
     int64_t r0 = q * p;
     if (r0 > m) r0 = m;
-    int32_t b = row_ptr[r0];
+    const int32_t b = at(r0);
     gIdxes[q] = b;
     if (q < g) {
         int64_t r1 = r0 + p;
         if (r1 > m) r1 = m;
-        nnzPerGroup[q] = row_ptr[r1] - b;
+        const int32_t n = at(r1) - b;
+        nnzPerGroup[q] = n < 0 ? 0 : n;
     }
 }
 

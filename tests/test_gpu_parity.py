@@ -76,12 +76,12 @@ def test_gcoo_from_csr_bit_exact(p, shape):
     _say(f"gcoo_from_csr m={m} k={k} p={p}")
     w = workloads.uniform_random(m, k, 1, 0.9 if m * k > 100 else 0.3, seed=7 * m + p)
     G = orc.gcoo_from_csr(w.m, w.k, w.row_ptr, w.col_idx, w.vals, p)
-    for on_device in (False, True):
+    for on_device, known_nnz in ((False, False), (True, False), (True, True)):
         if on_device:
             args = [torch.from_numpy(x).to(DEV) for x in (w.row_ptr, w.col_idx, w.vals)]
         else:
             args = [w.row_ptr, w.col_idx, w.vals]
-        A = binding.gcoo_from_csr(w.m, w.k, *args, p, device=DEV)
+        A = binding.gcoo_from_csr(w.m, w.k, *args, p, device=DEV, known_nnz=known_nnz)
         assert A.info() == dict(m=m, k=k, nnz=w.nnz, p=p, g=G.g)
         _assert_arrays_equal(A.export(), G)
         A.free()
