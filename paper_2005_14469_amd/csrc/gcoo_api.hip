@@ -210,7 +210,7 @@ int new_handle(int64_t m, int64_t k, int64_t nnz, int64_t max_group_nnz, int32_t
 int launch_build_schedule(const gcoo_matrix* h, hipStream_t s)
 {
     if (h->g > 0 && h->p <= gcoo::kSchedMaxP) {              // no register kernel above that height
-        gcoo::build_schedule<<<dim3((unsigned)h->g), dim3(gcoo::kBuildThreads), 0, s>>>(h->gIdxes(), h->rows(), h->cols(), h->values(), h->p,
+        gcoo::build_schedule<<<dim3((unsigned)(h->g * h->nw)), dim3(gcoo::kBuildThreads), 0, s>>>(h->gIdxes(), h->rows(), h->cols(), h->values(), h->p,
                                                                         h->g, h->nw, h->window_cols, h->sched_hdr(), h->sched());
         HIP_TRY(hipGetLastError());
     }

@@ -34,9 +34,13 @@ __device__ __forceinline__ void sched_put_piece(uint32_t* __restrict__ seg, int 
     (void)J;
 }
 
-// One workgroup (kBuildThreads threads) per group.  Per window: pass 1 counts the pieces of each class,
-// pass 2 gives every piece its rank inside its class (entries are visited in order; ranks come
-// from ballots and running counts, so the listing is the same on every run) and writes it out.
+// One workgroup (kBuildThreads threads) per (group, window): blockIdx.x = q*nw + w.  Pass 1 counts
+// the pieces of each class, pass 2 gives every piece its rank inside its class (entries are
+// visited in order; ranks come from ballots and running counts, so the listing is the same on
+// every run) and writes it out.  The windows of a group do not wait for each other: window w
+// (entries [wb, we) of the group) owns the words from 3*(wb - beg) + kSchedPad*w of the group's
+// part of the stream, which the space bound of gcoo_sched.hpp (3 words per entry and kSchedPad
+// per window) makes disjoint.
 constexpr int kBuildThreads = 1024;
 constexpr int kBuildWaves = kBuildThreads / 64;
 
@@ -45,39 +49,37 @@ __global__ __launch_bounds__(kBuildThreads) void build_schedule(const int32_t* _
                                                       int32_t p, int64_t g, int32_t nw, int32_t window_cols,
                                                       SchedClass* __restrict__ hdr, uint32_t* __restrict__ stream)
 {
-    __shared__ int32_t wstart[kMaxWindows + 1];   // first entry of each window
-    __shared__ int32_t cnt[kMaxRun];              // pieces per class in the current window
+    __shared__ int32_t wstart[2];                 // first entry of this window and of the next
+    __shared__ int32_t cnt[kMaxRun];              // pieces per class
     __shared__ int32_t demote[kMaxRun];           // class listed as pieces of class 1
     __shared__ int32_t seg[kMaxRun];              // first word of the class segment
     __shared__ int32_t base[kMaxRun];             // pieces of the class already placed
     __shared__ int32_t wcnt[kBuildWaves][kMaxRun];          // per wave, per class, in the current tile
-    __shared__ int32_t at_s;                      // words used so far by this group
     const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
-    const int64_t q = blockIdx.x;
+    const int64_t q = blockIdx.x / nw;
+    const int32_t w = (int32_t)(blockIdx.x - q * nw);
     if (q >= g) return;
     const int32_t beg = gIdxes[q], end = gIdxes[q + 1];
     const int32_t row0 = (int32_t)(q * p);
     uint32_t* __restrict__ out = stream + sched_group_base(beg, q, nw);
     SchedClass* __restrict__ h = hdr + q * nw * kMaxRun;
 
-    // window w = entries [wstart[w], wstart[w+1]): first entry whose column is >= w*window_cols
-    if (tid <= nw) {
-        const int64_t lim = (int64_t)tid * window_cols;
+    // window w = the entries whose column is in [w*window_cols, (w+1)*window_cols); the last window takes the rest
+    if (tid < 2) {
+        const int64_t lim = (int64_t)(w + tid) * window_cols;
         int32_t lo = beg, hi = end;
         while (lo < hi) {
             const int32_t mid = lo + (hi - lo) / 2;
             if ((int64_t)cols[mid] < lim) lo = mid + 1; else hi = mid;
         }
-        wstart[tid] = (tid == nw) ? end : lo;
+        wstart[tid] = (w + tid == nw) ? end : lo;
     }
-    if (tid == 0) at_s = 0;
+    if (tid < kMaxRun) { cnt[tid] = 0; base[tid] = 0; demote[tid] = 0; }
     __syncthreads();
 
     const uint64_t lt = (1ull << lane) - 1ull;
-    for (int32_t w = 0; w < nw; ++w) {
-        const int32_t wb = wstart[w], we = wstart[w + 1];
-        if (tid < kMaxRun) { cnt[tid] = 0; base[tid] = 0; demote[tid] = 0; }
-        __syncthreads();
+    {
+        const int32_t wb = wstart[0], we = wstart[1];
 
         // Length of the natural piece (run cut every kMaxRun entries) that entry e belongs to,
         // and e's place in it.  A run has one column, so it lies inside one window.
@@ -105,7 +107,7 @@ __global__ __launch_bounds__(kBuildThreads) void build_schedule(const int32_t* _
                     cnt[0] += cnt[L - 1] * L;
                     cnt[L - 1] = 0;
                 }
-            int32_t at = at_s;
+            int32_t at = 3 * (wb - beg) + kSchedPad * w;
             for (int L = 1; L <= kMaxRun; ++L) {
                 const int per_body = kBody * runs_per_chunk(L);
                 const int32_t bodies = (cnt[L - 1] + per_body - 1) / per_body;
@@ -113,7 +115,6 @@ __global__ __launch_bounds__(kBuildThreads) void build_schedule(const int32_t* _
                 h[w * kMaxRun + (L - 1)] = SchedClass{at, bodies};
                 if (bodies > 0) at += pre_dwords(L) + bodies * block_dwords(L);
             }
-            at_s = at;
         }
         __syncthreads();
 
@@ -163,7 +164,6 @@ __global__ __launch_bounds__(kBuildThreads) void build_schedule(const int32_t* _
                 for (int32_t x = nch; x < nch + 3; ++x) sg[sched_col_word(L, x, j)] = any_col;
             }
         }
-        __syncthreads();
     }
 }
 
