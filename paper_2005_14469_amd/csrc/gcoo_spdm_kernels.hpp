@@ -261,14 +261,17 @@ __device__ __forceinline__ void run_class(AccFile& acc, const uint32_t* seg, int
         for (int i = 0; i < kBody * J; ++i) col[i] = __builtin_amdgcn_readfirstlane(col[i]);
 #pragma unroll
         for (int i = 0; i < kBody * RP; ++i) rpk[i] = __builtin_amdgcn_readfirstlane(rpk[i]);
+        // the values of a chunk are read back one chunk ahead, so that the read is in flight
+        // behind the multiply-adds of the chunk before
+        uint32_t vnext[VS];
+        read_ring4<VS>(blk + blk_val(L, 0), vnext);
 #pragma unroll
         for (int st = 0; st < kBody; ++st) {
             issue(&col[st * J], bq[(st + 3) % kBody]);
-            uint32_t vw[VS];
-            read_ring4<VS>(blk + blk_val(L, st), vw);
             float va[VS];
 #pragma unroll
-            for (int i = 0; i < VS; ++i) va[i] = __uint_as_float(vw[i]);
+            for (int i = 0; i < VS; ++i) va[i] = __uint_as_float(vnext[i]);
+            if (st + 1 < kBody) read_ring4<VS>(blk + blk_val(L, st + 1), vnext);
             if (st < 3) wait_vm<3 * J + 1>(); else wait_vm<3 * J>();
 #pragma unroll
             for (int j = 0; j < J; ++j) {
