@@ -232,6 +232,14 @@ def crossover(torch, binding, workloads, args, dev, n=8000):
             "p": args.p or 32, "rows": rows}
 
 
+def copy_bandwidth_gbs(torch, dev):
+    """What a plain device copy of 1 GiB sustains on this machine (bytes read + bytes written per second)."""
+    src = torch.empty(256 * 1024 * 1024, dtype=torch.float32, device=dev).fill_(1.0)
+    dst = torch.empty_like(src)
+    t = _event_ms(torch, lambda: dst.copy_(src), 5)
+    return 2.0 * src.numel() * 4 / t / 1e6
+
+
 def _event_ms(torch, fn, reps, warmup=2):
     for _ in range(warmup):
         fn()
@@ -394,6 +402,9 @@ def main():
                      "kernel": KERNEL_NAMES.get(head["variant"], "?"), "algorithmic_bytes_per_launch": head["alg_bytes"]},
     }
     if not args.no_dense:
+        bw = copy_bandwidth_gbs(torch, dev)
+        line["roofline"]["measured_copy_gbs"] = bw             # the same algorithmic bytes against what a copy sustains here
+        line["roofline"]["frac_of_measured_copy"] = head["hbm_gbs"] / bw
         d = dense_ms(torch, w, dev)
         line["dense"] = {"sgemm_ms": d, "spdm_speedup_over_dense": d / head["spdm_ms"]}
     if args.secondary and args.secondary != args.workload:

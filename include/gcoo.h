@@ -187,7 +187,8 @@ int gcoo_export(const gcoo_matrix* A, float* values, int32_t* rows, int32_t* col
 /*
  * When conversions build the band schedule (process-wide setting, not thread-safe; takes effect
  * for matrices converted afterwards).  GCOO_BAND_AUTO: only for matrices on which gcoo_spdm()
- * then picks GCOO_VARIANT_BAND (at least 10000 columns, density 1.5 % .. 6 %, p <= 32).
+ * then picks GCOO_VARIANT_BAND (p <= 32, density at most 6 %, and at least 2 % with 10000 columns or
+ * more, at least 0.5 % with 13000 columns or more).
  * GCOO_BAND_ALWAYS: whenever the band kernel could run (p <= 32, density <= 6 %, at most 262144
  * columns); gcoo_spdm() keeps its usual choice and GCOO_VARIANT_BAND must be asked for.
  * GCOO_BAND_NEVER: never.

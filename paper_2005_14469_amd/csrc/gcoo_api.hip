@@ -89,7 +89,7 @@ int dense_vec_width(const float* A, int64_t lda, int64_t k)
 // The band schedule costs conversion time and memory, so it is built only where the band
 // kernel is the one gcoo_spdm() will pick.  Measured on MI355X with uniform random matrices
 // (n = 2000 .. 14000, density 0.1 % .. 5 %): the band kernel is faster than the register kernel
-// from about 10000 columns on and between 1.5 % and 6 % density (1.1x .. 1.7x); the B tile of a
+// from about 10000 columns on and between 2 % and 6 % density (1.1x .. 1.7x); the B tile of a
 // column tile then no longer stays in L2 between the groups that need it, and eight groups sharing
 // each fetched row matters more than the extra step-by-step overhead of the band kernel.
 // Below 6 % most column runs inside a group are one or two entries long; above it the register
@@ -103,10 +103,14 @@ bool band_schedule_possible(int64_t m, int64_t k, int64_t nnz, int32_t p)
     return (double)nnz <= 0.06 * (double)m * (double)k;
 }
 
-// Where the band kernel is the faster one.
+// Where the band kernel is the faster one (measured grid of uniform random square matrices,
+// n = 2000 .. 14000, density 0.1 % .. 5 %): from 10000 columns on at 2 % density or more, from
+// 13000 columns on already at 0.5 %.
 bool band_kernel_preferred(int64_t m, int64_t k, int64_t nnz, int32_t p)
 {
-    return band_schedule_possible(m, k, nnz, p) && k >= 10000 && (double)nnz >= 0.015 * (double)m * (double)k;
+    if (!band_schedule_possible(m, k, nnz, p)) return false;
+    const double density = (double)nnz / ((double)m * (double)k);
+    return (k >= 13000 && density >= 0.005) || (k >= 10000 && density >= 0.02);
 }
 
 bool band_schedule_wanted(int64_t m, int64_t k, int64_t nnz, int32_t p)
@@ -210,8 +214,13 @@ int new_handle(int64_t m, int64_t k, int64_t nnz, int64_t max_group_nnz, int32_t
 int launch_build_schedule(const gcoo_matrix* h, hipStream_t s)
 {
     if (h->g > 0 && h->p <= gcoo::kSchedMaxP) {              // no register kernel above that height
-        gcoo::build_schedule<<<dim3((unsigned)(h->g * h->nw)), dim3(gcoo::kBuildThreads), 0, s>>>(h->gIdxes(), h->rows(), h->cols(), h->values(), h->p,
-                                                                        h->g, h->nw, h->window_cols, h->sched_hdr(), h->sched());
+        const dim3 grid((unsigned)(h->g * h->nw));
+        if (h->nnz / (h->g * h->nw) <= 1024)
+            gcoo::build_schedule<256><<<grid, dim3(256), 0, s>>>(h->gIdxes(), h->rows(), h->cols(), h->values(), h->p, h->g, h->nw,
+                                                                 h->window_cols, h->sched_hdr(), h->sched());
+        else
+            gcoo::build_schedule<1024><<<grid, dim3(1024), 0, s>>>(h->gIdxes(), h->rows(), h->cols(), h->values(), h->p, h->g, h->nw,
+                                                                   h->window_cols, h->sched_hdr(), h->sched());
         HIP_TRY(hipGetLastError());
     }
     if (h->g > 0 && h->has_band) {

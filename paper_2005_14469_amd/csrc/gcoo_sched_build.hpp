@@ -41,9 +41,9 @@ __device__ __forceinline__ void sched_put_piece(uint32_t* __restrict__ seg, int 
 // (entries [wb, we) of the group) owns the words from 3*(wb - beg) + kSchedPad*w of the group's
 // part of the stream, which the space bound of gcoo_sched.hpp (3 words per entry and kSchedPad
 // per window) makes disjoint.
-constexpr int kBuildThreads = 1024;
-constexpr int kBuildWaves = kBuildThreads / 64;
-
+// kBuildThreads = 256 or 1024: the launcher takes the small workgroup when a window holds few
+// entries, so that eight of them share a compute unit instead of two.
+template <int kBuildThreads>
 __global__ __launch_bounds__(kBuildThreads) void build_schedule(const int32_t* __restrict__ gIdxes, const int32_t* __restrict__ rows,
                                                       const int32_t* __restrict__ cols, const float* __restrict__ values,
                                                       int32_t p, int64_t g, int32_t nw, int32_t window_cols,
@@ -54,6 +54,7 @@ __global__ __launch_bounds__(kBuildThreads) void build_schedule(const int32_t* _
     __shared__ int32_t demote[kMaxRun];           // class listed as pieces of class 1
     __shared__ int32_t seg[kMaxRun];              // first word of the class segment
     __shared__ int32_t base[kMaxRun];             // pieces of the class already placed
+    constexpr int kBuildWaves = kBuildThreads / 64;
     __shared__ int32_t wcnt[kBuildWaves][kMaxRun];          // per wave, per class, in the current tile
     const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
     const int64_t q = blockIdx.x / nw;
