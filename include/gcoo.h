@@ -183,7 +183,6 @@ int gcoo_info(const gcoo_matrix* A, int64_t* m, int64_t* k, int64_t* nnz, int32_
 int gcoo_export(const gcoo_matrix* A, float* values, int32_t* rows, int32_t* cols,
                 int64_t* gIdxes, int32_t* nnzPerGroup, void* stream);
 
-/* Static text for a status code. */
 /*
  * When conversions build the band schedule (process-wide setting, not thread-safe; takes effect
  * for matrices converted afterwards).  GCOO_BAND_AUTO: only for matrices on which gcoo_spdm()
@@ -200,14 +199,17 @@ int gcoo_set_band_policy(int policy);
 
 /*
  * Introspection for tests: the band schedule, the kernel-private re-listing that the
- * workgroup-shared SpDM kernel reads (built at conversion as gcoo_set_band_policy() says).  gcoo_band_words() = its size in 32-bit words, 0 if this matrix has none.
+ * workgroup-shared SpDM kernel reads (built at conversion as gcoo_set_band_policy() says).
+ * gcoo_band_words() = its size in 32-bit words, 0 if this matrix has none (or A is NULL).
  * gcoo_export_band() copies it to HOST buffers: `words` (gcoo_band_words entries), `ucount`
  * (distinct columns per super-group of 8 groups, ceil(g/8) entries) and `ucols` (nnz entries; the
- * columns of super-group Q start at index gIdxes[8Q]); any of them may be NULL.  Synchronises `stream`.
+ * columns of super-group Q start at index gIdxes[8Q]); any of them may be NULL.  Synchronises
+ * `stream`.  GCOO_EINVAL if A is NULL or has no band schedule.
  */
 int64_t gcoo_band_words(const gcoo_matrix* A);
 int gcoo_export_band(const gcoo_matrix* A, uint32_t* words, int32_t* ucount, int32_t* ucols, void* stream);
 
+/* Static text for a status code. */
 const char* gcoo_strerror(int status);
 
 /* Text of the last HIP error seen by the calling thread inside this library ("" if none). */

@@ -275,6 +275,10 @@ int from_csr(int64_t m, int64_t k, const int32_t* row_ptr, const int32_t* col_id
 
     const int64_t g = (m + p - 1) / p;
     int64_t nnz, max_group_nnz = 0;
+    if (src_on_device && nnz_known >= 0) {          // everything the host can check, before the first launch
+        if (nnz_known > 0 && (!col_idx || !vals)) return GCOO_EINVAL;
+        if (dev_buf_bytes < make_layout(m, k, nnz_known, g, p).total) return GCOO_ENOMEM;
+    }
     if (src_on_device) {
         // nnz and the size of the largest group are computed on the device (the counters sit at
         // an offset of the buffer that does not depend on nnz).  They come back in one small

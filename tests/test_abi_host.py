@@ -82,3 +82,40 @@ def test_spdm_and_info_reject_null_handle(L):
     assert L.gcoo_dense_nnz(2, 4, None, 2, None, C.byref(n)) == binding.GCOO_EINVAL     # lda < k
     out = C.c_void_p()
     assert L.gcoo_from_dense(2, 2, None, 2, 2, C.c_void_p(4096), 1 << 20, None, C.byref(out)) == binding.GCOO_EINVAL
+
+
+def test_newer_entry_points_reject_bad_arguments_on_the_host(L):
+    out = C.c_void_p()
+    fake = C.c_void_p(256 * 1024)
+    # device-CSR conversion with nnz supplied: the count must fit the 32-bit index arrays
+    assert L.gcoo_from_csr_device(2, 2, -1, fake, fake, fake, 2, fake, 1 << 20, None, C.byref(out)) == binding.GCOO_EINVAL
+    assert L.gcoo_from_csr_device(2, 2, 2 ** 31, fake, fake, fake, 2, fake, 1 << 40, None, C.byref(out)) \
+        == binding.GCOO_EINVAL
+    assert L.gcoo_from_csr_device(2, 2, 1, fake, fake, fake, 0, fake, 1 << 20, None, C.byref(out)) == binding.GCOO_EINVAL
+    assert L.gcoo_from_csr_device(2, 2, 1, fake, fake, fake, 2, fake, 16, None, C.byref(out)) == binding.GCOO_ENOMEM
+    assert L.gcoo_from_csr_device(2, 2, 1, fake, None, None, 2, fake, 1 << 20, None, C.byref(out)) == binding.GCOO_EINVAL
+    assert out.value is None
+    # band schedule policy and introspection
+    assert L.gcoo_set_band_policy(-1) == binding.GCOO_EINVAL
+    assert L.gcoo_set_band_policy(3) == binding.GCOO_EINVAL
+    assert L.gcoo_set_band_policy(binding.BAND_AUTO) == 0
+    assert L.gcoo_band_words(None) == 0
+    assert L.gcoo_export_band(None, None, None, None, None) == binding.GCOO_EINVAL
+    assert L.gcoo_spdm_pick(None, None, 4, 4, None, 4) == binding.GCOO_EINVAL
+    for variant in (-1, 4):
+        assert L.gcoo_spdm_variant(None, None, 4, 4, None, 4, None, variant) == binding.GCOO_EINVAL
+    # CSR baseline kernel: shapes are checked before anything is launched
+    assert L.gcoo_csr_spmm_baseline(-1, 2, fake, fake, fake, fake, 4, 4, fake, 4, None) == binding.GCOO_EINVAL
+    assert L.gcoo_csr_spmm_baseline(2, 2, None, fake, fake, fake, 4, 4, fake, 4, None) == binding.GCOO_EINVAL
+    assert L.gcoo_csr_spmm_baseline(2, 2, fake, fake, fake, fake, 3, 4, fake, 4, None) == binding.GCOO_EINVAL   # ldb < N
+    assert L.gcoo_csr_spmm_baseline(2, 2, fake, fake, fake, fake, 4, 4, None, 4, None) == binding.GCOO_EINVAL
+    assert L.gcoo_csr_spmm_baseline(0, 2, fake, fake, fake, fake, 4, 4, None, 4, None) == 0                     # nothing to do
+
+
+def test_default_p_is_a_size_every_kernel_serves(L):
+    # the group height that Section 4 of the paper tunes by hand; the default is one the register
+    # and the band kernel both serve, whatever the shape
+    for m, k, nnz, n in [(8000, 8000, 320000, 8000), (4000, 4000, 3200000, 4000), (0, 0, 0, 0), (1, 1, 1, 1)]:
+        assert L.gcoo_default_p(m, k, nnz, n) == 32
+    assert L.gcoo_default_p(-1, 1, 1, 1) == 0
+    assert L.gcoo_default_p(1, 1, -1, 1) == 0
