@@ -172,17 +172,13 @@ def read_traffic(kernel: str, workload: str):
     return None
 
 
-def default_p(name: str) -> int:
-    return 32
-
-
 def run_one(torch, binding, workloads, name, args, dev, steps, warmup):
     if name.startswith("uniform_"):                       # uniform_<n>_<sparsity>: square uniform random A, N = n
         _, n_, s_ = name.split("_")
         w = workloads.uniform_random(int(n_), int(n_), int(n_), float(s_), workloads.BASE_SEED + int(n_), name=name)
     else:
         w = workloads.config(int(name.replace("config", "")))
-    p = args.p or default_p(name)
+    p = args.p or binding.gcoo_default_p(w.m, w.k, w.nnz, w.N)
     r = time_path(torch, binding, w, dev, p, args.variant, steps, warmup)
     flops = 2.0 * w.nnz * w.N
     alg_bytes = 12.0 * w.nnz + 4.0 * w.k * w.N + 4.0 * w.m * w.N
@@ -205,11 +201,12 @@ def crossover(torch, binding, workloads, args, dev, n=8000):
     dense = None
     for s in (0.5, 0.6, 0.7, 0.8, 0.85, 0.9, 0.95, 0.98, 0.99, 0.995, 0.999):
         w = workloads.uniform_random(n, n, n, s, workloads.BASE_SEED + int(round(s * 10000)), name=f"uniform_{n}_s{s}")
-        p = args.p or 32
+        p = args.p or binding.gcoo_default_p(n, n, w.nnz, n)
         r = time_path(torch, binding, w, dev, p, args.variant, 5, 2)
         if dense is None:
             dense = dense_ms(torch, w, dev)
-        rows.append(dict(sparsity=s, nnz=w.nnz, spdm_ms=r["spdm_ms"], convert_ms=r["convert_ms"], step_ms=r["ms_per_step"],
+        rows.append(dict(sparsity=s, nnz=w.nnz, p=p, variant=r["variant"], spdm_ms=r["spdm_ms"], convert_ms=r["convert_ms"],
+                         step_ms=r["ms_per_step"],
                          spdm_gflops=2.0 * w.nnz * n / r["spdm_ms"] / 1e6))
         del w, r
 
@@ -229,7 +226,7 @@ def crossover(torch, binding, workloads, args, dev, n=8000):
 
     return {"metric": "sparsity at which the GCOO path overtakes the dense fp32 SGEMM, n=8000", "dense_sgemm_ms": dense,
             "crossover_sparsity_spdm_kernel": cross("spdm_ms"), "crossover_sparsity_whole_path": cross("step_ms"),
-            "p": args.p or 32, "rows": rows}
+            "p": args.p or "library default per row", "rows": rows}
 
 
 def copy_bandwidth_gbs(torch, dev):
@@ -292,7 +289,6 @@ def _dense_square_ms(torch, dev, n, Bd):
 
 
 def sweep(torch, binding, workloads, args, dev):
-    p = args.p or 32
     rows, dense = [], {}
     if args.sweep == "sparsity":
         plan = [(n, s) for n in (4000, 14000) for s in (0.8, 0.9, 0.95, 0.96, 0.97, 0.98, 0.99, 0.995, 0.999)]
@@ -308,6 +304,7 @@ def sweep(torch, binding, workloads, args, dev):
             Cd = torch.empty((n, n), device=dev, dtype=torch.float32)
             dense[n] = _dense_square_ms(torch, dev, n, Bd)
             cur_n = n
+        p = args.p or binding.gcoo_default_p(n, n, int(round(n * n * (1.0 - s))), n)
         r = _square_case(torch, binding, workloads, dev, n, s, p, args.variant, Bd, Cd)
         print(f"sweep n={n} sparsity={s}: spdm {r['spdm_ms']:.3f} ms, csr {r['csr_rowsplit_ms']:.3f} ms, vendor csr "
               f"{r['vendor_csr_ms']}, dense {dense[n]:.3f} ms", file=sys.stderr, flush=True)
@@ -315,13 +312,13 @@ def sweep(torch, binding, workloads, args, dev):
         r["speedup_over_dense"] = dense[n] / r["spdm_ms"]
         rows.append(r)
     rows.sort(key=lambda r: (r["sparsity"], r["n"]) if args.sweep == "size" else (r["n"], r["sparsity"]))
-    return {"metric": f"uniform random square A, fp32, sweep over {args.sweep}", "p": p, "rows": rows}
+    return {"metric": f"uniform random square A, fp32, sweep over {args.sweep}", "p": args.p or "library default per row",
+            "rows": rows}
 
 
 def eo_kc(torch, binding, workloads, args, dev):
     """Dense device matrix -> GCOO -> product: conversion time against kernel time (Section 4.3)."""
     rows = []
-    p = args.p or 32
     for n in (4000, 14000):
         g = torch.Generator(device=dev)
         g.manual_seed(workloads.BASE_SEED + n)
@@ -334,6 +331,7 @@ def eo_kc(torch, binding, workloads, args, dev):
             Ad[r, torch.from_numpy(w.col_idx).to(dev).long()] = torch.from_numpy(w.vals).to(dev)
             del r
             holder = {}
+            p = args.p or binding.gcoo_default_p(n, n, w.nnz, n)
 
             def convert():
                 holder["A"] = binding.gcoo_from_dense(Ad, p)      # count, size the buffer, count per block, fill, schedule

@@ -57,10 +57,15 @@ typedef struct gcoo_matrix gcoo_matrix;
 /*
  * Group height to use when the caller has no better idea (the paper leaves p to a tuner, Section 5).
  * 32 is the tallest group the widest instance of the register kernel holds (32 rows x 4 columns
- * per lane); on MI355X it was the fastest of {4, 8, 16, 32, 64} for uniform random matrices of
- * density 0.001 .. 0.5, for a power-law row-length matrix and for a diagonal one.  A caller that
- * multiplies the same matrix many times can do better by timing a few values (the Python binding
- * has gcoo_tune_p for that).  Pure host arithmetic; 0 for invalid arguments.
+ * per lane); on MI355X it was the fastest of {4, 8, 16, 32, 64} for that kernel for uniform random
+ * matrices of density 0.001 .. 0.5, for a power-law row-length matrix and for a diagonal one.
+ * 16 is returned where the workgroup-shared kernel with sixteen waves (GCOO_VARIANT_BAND, groups
+ * of at most 16 rows) was measured faster than that: N a multiple of 4, density at most 6 %, at
+ * least 192 blocks of 256 rows x 256 columns of C that fill their rounds over the 256 compute
+ * units to 80 % or more, and 9000 columns or more - or 7000 at 0.8 % density or more, or 3500
+ * between 1.5 % and 4.5 % (rounds then filled to 90 % and 95 %).  A caller that multiplies the
+ * same matrix many times can do better by timing a few values (the Python binding has
+ * gcoo_tune_p for that).  Pure host arithmetic; 0 for invalid arguments.
  */
 int32_t gcoo_default_p(int64_t m, int64_t k, int64_t nnz, int64_t N);
 
@@ -149,9 +154,12 @@ int gcoo_spdm(const gcoo_matrix* A, const float* B_dev, int64_t ldb, int64_t N,
 /* partial sums in VGPRs, reads the run schedule built at conversion; needs p <= 64 and B, C, ldb,
  * ldc, N all even (8-byte aligned rows), else GCOO_EINVAL */
 #define GCOO_VARIANT_REG  2
-/* eight groups per workgroup share the rows of B through LDS, reads the band schedule built at
- * conversion (gcoo_band_words() > 0, see gcoo_set_band_policy()); needs B, C, ldb, ldc, N multiples
- * of 4 elements (16-byte aligned rows), else GCOO_EINVAL */
+/* the groups of a workgroup (sixteen of at most 16 rows, or eight of 17..32 rows) share the rows of
+ * B through LDS; reads the band schedule built at conversion (gcoo_band_words() > 0, see
+ * gcoo_set_band_policy()); needs B, C, ldb, ldc, N multiples of 4 elements (16-byte aligned rows),
+ * else GCOO_EINVAL.  gcoo_spdm() picks it where the matrix has that schedule by the automatic
+ * rule, the operands are so aligned and C has at least 192 blocks of (256 rows of such groups) x
+ * 256 columns */
 #define GCOO_VARIANT_BAND 3
 int gcoo_spdm_variant(const gcoo_matrix* A, const float* B_dev, int64_t ldb, int64_t N,
                       float* C_dev, int64_t ldc, void* stream, int variant);
@@ -186,8 +194,9 @@ int gcoo_export(const gcoo_matrix* A, float* values, int32_t* rows, int32_t* col
 /*
  * When conversions build the band schedule (process-wide setting, not thread-safe; takes effect
  * for matrices converted afterwards).  GCOO_BAND_AUTO: only for matrices on which gcoo_spdm()
- * then picks GCOO_VARIANT_BAND (p <= 32, density at most 6 %, and at least 2 % with 10000 columns or
- * more, at least 0.5 % with 13000 columns or more).
+ * then picks GCOO_VARIANT_BAND when B is wide enough: density at most 6 % and
+ *   p <= 16:       7000 columns or more, or 3500 at 0.8 % density or more;
+ *   17 <= p <= 32: 13000 columns or more at 0.5 % or more, or 10000 at 2 % or more.
  * GCOO_BAND_ALWAYS: whenever the band kernel could run (p <= 32, density <= 6 %, at most 262144
  * columns); gcoo_spdm() keeps its usual choice and GCOO_VARIANT_BAND must be asked for.
  * GCOO_BAND_NEVER: never.
@@ -202,8 +211,9 @@ int gcoo_set_band_policy(int policy);
  * workgroup-shared SpDM kernel reads (built at conversion as gcoo_set_band_policy() says).
  * gcoo_band_words() = its size in 32-bit words, 0 if this matrix has none (or A is NULL).
  * gcoo_export_band() copies it to HOST buffers: `words` (gcoo_band_words entries), `ucount`
- * (distinct columns per super-group of 8 groups, ceil(g/8) entries) and `ucols` (nnz entries; the
- * columns of super-group Q start at index gIdxes[8Q]); any of them may be NULL.  Synchronises
+ * (distinct columns per super-group of W groups, ceil(g/W) entries; W = 16 for p <= 16, else 8) and
+ * `ucols` (nnz entries; the columns of super-group Q start at index gIdxes[W*Q]); any of them may
+ * be NULL.  Synchronises
  * `stream`.  GCOO_EINVAL if A is NULL or has no band schedule.
  */
 int64_t gcoo_band_words(const gcoo_matrix* A);

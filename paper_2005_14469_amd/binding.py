@@ -141,7 +141,8 @@ class GcooMatrix:
             return None
         i = self.info()
         words = np.empty(n, np.uint32)
-        ucount = np.empty((i["g"] + 7) // 8, np.int32)
+        W = 16 if i["p"] <= 16 else 8                      # groups per super-group
+        ucount = np.empty((i["g"] + W - 1) // W, np.int32)
         ucols = np.empty(i["nnz"], np.int32)
         _check(lib().gcoo_export_band(self.handle, words.ctypes.data, ucount.ctypes.data, ucols.ctypes.data,
                                       _stream_ptr(stream)), "gcoo_export_band")

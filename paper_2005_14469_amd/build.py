@@ -7,6 +7,7 @@ from __future__ import annotations
 
 import glob
 import os
+import re
 import subprocess
 from concurrent.futures import ThreadPoolExecutor
 
@@ -19,7 +20,8 @@ LIB = os.path.join(HERE, "libgcoo.so")
 # Packed fp32 VALU instructions are switched off for every kernel of this library.
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
-         "-Wno-unused-command-line-argument"]
+         "-Wno-unused-command-line-argument",
+         "-Wno-inline-asm"]      # the index-mode asm statements name M0 as clobbered, which clang remarks on
 
 
 def sources():
@@ -38,8 +40,10 @@ def stale() -> bool:
 
 
 def _checked(src: str) -> bool:
-    """Sources whose generated code is verified by isa_check (kernels that issue loads from asm)."""
-    return os.path.basename(src).startswith("spdm_sched_v")
+    """Sources whose generated code is verified by isa_check (kernels that issue loads from asm, or that
+    load straight to LDS next to the index mode)."""
+    name = os.path.basename(src)
+    return name.startswith("spdm_sched_v") or name == "spdm_band.hip"
 
 
 def _compile(src: str) -> str:
@@ -64,6 +68,9 @@ def verify_generated_code() -> None:
         stem = os.path.basename(src)[:-4]
         asm = os.path.join(OBJ, f"{stem}-hip-amdgcn-amd-amdhsa-gfx950.s")
         text = open(asm).read()
+        if stem == "spdm_band":
+            verify_band_code(stem, text)
+            continue
         v = stem.rsplit("v", 1)[1]
         for kernel in (f"_ZN4gcoo10spdm_schedILi{v}E", f"_ZN4gcoo15spdm_sched_coopILi{v}E"):
             regs, bad = isa_check.check(text, kernel)
@@ -71,6 +78,26 @@ def verify_generated_code() -> None:
                 raise RuntimeError(f"{stem}: no asm-issued loads found in {kernel} (check is blind)")
             if bad:
                 raise RuntimeError(f"{stem} {kernel}: {len(bad)} instructions touch registers with a load in flight, e.g. {bad[:3]}")
+
+
+def verify_band_code(stem: str, text: str) -> None:
+    """The workgroup-shared kernel: no register spills in either instance (a spilled accumulator file would
+    still be correct but pointless), and in the instance that loads straight to LDS every such load sets M0
+    itself and has arrived before the barrier that publishes it."""
+    from . import isa_check
+    for shape, direct in (("NS_10BandShape8E", False), ("NS_11BandShape16E", True)):
+        kernel = f"_ZN4gcoo9spdm_bandI{shape}"
+        body = "\n".join(isa_check.kernel_body(text, kernel))
+        if not body:
+            raise RuntimeError(f"{stem}: kernel {kernel} not found")
+        loads, problems = isa_check.check_lds_loads(text, kernel)
+        if direct and not loads:
+            raise RuntimeError(f"{stem} {kernel}: no loads to LDS found (check is blind)")
+        if problems:
+            raise RuntimeError(f"{stem} {kernel}: {problems[:3]}")
+    spills = [int(x) for x in re.findall(r"\.vgpr_spill_count:\s+(\d+)", text)]
+    if len(spills) < 2 or any(spills):
+        raise RuntimeError(f"{stem}: register spills {spills}")
 
 
 def build(force: bool = True, jobs: int = 8) -> str:

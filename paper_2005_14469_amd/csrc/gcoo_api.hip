@@ -87,11 +87,17 @@ int dense_vec_width(const float* A, int64_t lda, int64_t k)
 }
 
 // The band schedule costs conversion time and memory, so it is built only where the band
-// kernel is the one gcoo_spdm() will pick.  Measured on MI355X with uniform random matrices
-// (n = 2000 .. 14000, density 0.1 % .. 5 %): the band kernel is faster than the register kernel
-// from about 10000 columns on and between 2 % and 6 % density (1.1x .. 1.7x); the B tile of a
-// column tile then no longer stays in L2 between the groups that need it, and eight groups sharing
-// each fetched row matters more than the extra step-by-step overhead of the band kernel.
+// kernel is the one gcoo_spdm() will pick.  Measured on MI355X with uniform random square
+// matrices (n = 2000 .. 14000, density 0.1 % .. 6 %, N = n):
+//   * groups of 17..32 rows (eight waves per workgroup): the band kernel beats the register kernel
+//     from about 10000 columns on at 2 % density or more, from 13000 columns on already at 0.5 %
+//     (1.1x .. 1.7x);
+//   * groups of at most 16 rows (sixteen waves): it beats the register kernel on the same matrix from
+//     3500 columns on at 0.8 % density or more and from 7000 columns on at any density up to the limit
+//     (1.1x .. 2.7x), and it beats the register kernel with groups of 32 rows - the better height
+//     for that kernel - in the narrower region that gcoo_default_p() describes.
+// The B tile of a column tile then no longer stays in L2 between the groups that need it, and W
+// groups sharing each fetched row matters more than the step-by-step overhead of the band kernel.
 // Below 6 % most column runs inside a group are one or two entries long; above it the register
 // kernel is bound by its multiply-adds, not by the rows it fetches.
 // gcoo_set_band_policy() overrides the choice.
@@ -103,14 +109,36 @@ bool band_schedule_possible(int64_t m, int64_t k, int64_t nnz, int32_t p)
     return (double)nnz <= 0.06 * (double)m * (double)k;
 }
 
-// Where the band kernel is the faster one (measured grid of uniform random square matrices,
-// n = 2000 .. 14000, density 0.1 % .. 5 %): from 10000 columns on at 2 % density or more, from
-// 13000 columns on already at 0.5 %.
 bool band_kernel_preferred(int64_t m, int64_t k, int64_t nnz, int32_t p)
 {
     if (!band_schedule_possible(m, k, nnz, p)) return false;
     const double density = (double)nnz / ((double)m * (double)k);
+    if (gcoo::band_waves(p) == 16) return k >= 7000 || (k >= 3500 && density >= 0.008);
     return (k >= 13000 && density >= 0.005) || (k >= 10000 && density >= 0.02);
+}
+
+// A band workgroup runs for a whole (super-group, column tile): how well `items` of them fill the
+// 256 compute units, as the fraction of the rounds they need that is work.
+double band_fill_of_rounds(int64_t items)
+{
+    if (items <= 0) return 0.0;
+    const int64_t rounds = (items + 255) / 256;
+    return (double)items / (double)(rounds * 256);
+}
+
+// Group height 16 with the band kernel against 32 with the register kernel (same grid of
+// measurements): 16 wins from 9000 columns on; from 7000 on at 0.8 % density or more; from 3500 on
+// between 1.5 % and 4.5 %; the two smaller regions only where the workgroups fill their rounds.
+bool short_groups_preferred(int64_t m, int64_t k, int64_t nnz, int64_t N)
+{
+    if (N % 4 != 0 || N <= 0 || !band_kernel_preferred(m, k, nnz, 16)) return false;
+    const double density = (double)nnz / ((double)m * (double)k);
+    const int64_t items = ((m + 255) / 256) * ((N + 255) / 256);
+    const double fill = band_fill_of_rounds(items);
+    if (items < 192) return false;
+    if (k >= 9000) return fill >= 0.8;
+    if (k >= 7000 && density >= 0.008) return fill >= 0.9;
+    return k >= 3500 && density >= 0.015 && density <= 0.045 && fill >= 0.95;
 }
 
 bool band_schedule_wanted(int64_t m, int64_t k, int64_t nnz, int32_t p)
@@ -140,8 +168,9 @@ Layout make_layout(int64_t m, int64_t k, int64_t nnz, int64_t g, int32_t p)
     L.sched = take((size_t)gcoo::sched_words(nnz, g, nw) * 4);
     const bool band = band_schedule_wanted(m, k, nnz, p);
     L.band_ucols = take(band ? n4 : 0);
-    L.band_ucount = take(band ? (size_t)((g + gcoo::kBandWaves - 1) / gcoo::kBandWaves) * 4 : 0);
-    L.band_stream = take(band ? (size_t)gcoo::band_stream_words(nnz, g, k) * 4 : 0);
+    const int W = gcoo::band_waves(p);
+    L.band_ucount = take(band ? (size_t)((g + W - 1) / W) * 4 : 0);
+    L.band_stream = take(band ? (size_t)gcoo::band_stream_words(nnz, g, k, W) * 4 : 0);
     L.tmp_cols = take(n4);
     L.tmp_rows = take(n4);
     L.tmp_vals = take(n4);
@@ -188,7 +217,8 @@ struct gcoo_matrix {
     int32_t* band_ucols() const { return reinterpret_cast<int32_t*>(base + L.band_ucols); }
     int32_t* band_ucount() const { return reinterpret_cast<int32_t*>(base + L.band_ucount); }
     uint32_t* band_stream() const { return reinterpret_cast<uint32_t*>(base + L.band_stream); }
-    int64_t super_groups() const { return (g + gcoo::kBandWaves - 1) / gcoo::kBandWaves; }
+    int band_w() const { return gcoo::band_waves(p); }
+    int64_t super_groups() const { return (g + band_w() - 1) / band_w(); }
 };
 
 namespace {
@@ -226,11 +256,12 @@ int launch_build_schedule(const gcoo_matrix* h, hipStream_t s)
     if (h->g > 0 && h->has_band) {
         const size_t bitmap_bytes = (size_t)((h->k + 31) / 32) * 4;
         gcoo::band_union<<<dim3((unsigned)h->super_groups()), dim3(gcoo::kBandBuildThreads), bitmap_bytes, s>>>(
-            h->gIdxes(), h->cols(), h->g, h->k, h->band_ucols(), h->band_ucount());
+            h->gIdxes(), h->cols(), h->g, h->k, h->band_w(), h->band_ucols(), h->band_ucount());
         HIP_TRY(hipGetLastError());
         const size_t table_bytes = 2 * (size_t)((h->k + 63) / 64 + 1) * 4;
-        gcoo::band_fill<<<dim3((unsigned)(h->super_groups() * gcoo::kBandWaves)), dim3(gcoo::kBandBuildThreads), table_bytes, s>>>(
-            h->gIdxes(), h->rows(), h->cols(), h->values(), h->p, h->g, h->k, h->band_ucols(), h->band_ucount(), h->band_stream());
+        gcoo::band_fill<<<dim3((unsigned)(h->super_groups() * h->band_w())), dim3(gcoo::kBandBuildThreads), table_bytes, s>>>(
+            h->gIdxes(), h->rows(), h->cols(), h->values(), h->p, h->g, h->k, h->band_w(), h->band_ucols(), h->band_ucount(),
+            h->band_stream());
         HIP_TRY(hipGetLastError());
     }
     return GCOO_OK;
@@ -250,7 +281,7 @@ int gcoo_set_band_policy(int policy)
 int32_t gcoo_default_p(int64_t m, int64_t k, int64_t nnz, int64_t N)
 {
     if (m < 0 || k < 0 || nnz < 0 || N < 0) return 0;
-    return 32;
+    return short_groups_preferred(m, k, nnz, N) ? 16 : 32;
 }
 
 size_t gcoo_device_bytes(int64_t m, int64_t k, int64_t nnz, int32_t p)
@@ -577,7 +608,8 @@ int gcoo_spdm_pick(const gcoo_matrix* A, const float* B_dev, int64_t ldb, int64_
     int rc = check_spdm_args(A, B_dev, ldb, N, C_dev, ldc);
     if (rc != GCOO_OK) return rc;
     const Shape sh = shape_of(B_dev, ldb, N, C_dev, ldc);
-    if (A->band_preferred && sh.al4 && !sh.wide_pitch) return GCOO_VARIANT_BAND;
+    // the band kernel wants enough workgroups to occupy the chip: one per 256 rows and 256 columns
+    if (A->band_preferred && sh.al4 && !sh.wide_pitch && A->super_groups() * ((N + 255) / 256) >= 192) return GCOO_VARIANT_BAND;
     return sched_width(A->p, sh) ? GCOO_VARIANT_REG : GCOO_VARIANT_LDS;
 }
 
@@ -668,7 +700,7 @@ int gcoo_export(const gcoo_matrix* A, float* values, int32_t* rows, int32_t* col
 int64_t gcoo_band_words(const gcoo_matrix* A)
 {
     if (!A || !A->has_band) return 0;
-    return gcoo::band_stream_words(A->nnz, A->g, A->k);
+    return gcoo::band_stream_words(A->nnz, A->g, A->k, A->band_w());
 }
 
 int gcoo_export_band(const gcoo_matrix* A, uint32_t* words, int32_t* ucount, int32_t* ucols, void* stream)

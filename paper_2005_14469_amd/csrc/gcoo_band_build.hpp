@@ -38,8 +38,8 @@ __device__ __forceinline__ int32_t band_block_scan(int32_t mine, int32_t* wsum, 
 // Dynamic LDS: 2 * ceil(k/32) words.
 // ---------------------------------------------------------------------------------------------
 __global__ __launch_bounds__(kBandBuildThreads) void band_union(const int32_t* __restrict__ gIdxes, const int32_t* __restrict__ cols,
-                                                               int64_t g, int64_t k, int32_t* __restrict__ ucols,
-                                                               int32_t* __restrict__ ucount)
+                                                               int64_t g, int64_t k, int32_t W,
+                                                               int32_t* __restrict__ ucols, int32_t* __restrict__ ucount)
 {
     extern __shared__ uint32_t band_lds[];
     __shared__ int32_t wsum[kBandBuildWaves];
@@ -47,7 +47,7 @@ __global__ __launch_bounds__(kBandBuildThreads) void band_union(const int32_t* _
     const int32_t nbw = (int32_t)((k + 31) / 32);
     uint32_t* bits = band_lds;
     const int64_t Q = blockIdx.x;
-    const int64_t q0 = Q * kBandWaves, q1 = (q0 + kBandWaves < g) ? q0 + kBandWaves : g;
+    const int64_t q0 = Q * W, q1 = (q0 + W < g) ? q0 + W : g;
     const int32_t e0 = gIdxes[q0], e1 = gIdxes[q1];
     for (int32_t i = threadIdx.x; i < nbw; i += kBandBuildThreads) bits[i] = 0u;
     __syncthreads();
@@ -99,7 +99,8 @@ __device__ __forceinline__ int band_type_index(int t) { return t == 1 ? 0 : (t =
 __device__ __forceinline__ int32_t band_blocks_of(const int32_t* __restrict__ rows, const int32_t* __restrict__ cols,
                                                   const float* __restrict__ values, int32_t s, int32_t e, int32_t row0, int32_t p,
                                                   const int32_t* __restrict__ band_cols, int32_t ncols, uint32_t* __restrict__ out,
-                                                  int32_t next_cols, const int32_t* __restrict__ next_ids, int32_t total_words)
+                                                  int32_t next_cols, const int32_t* __restrict__ next_ids, int32_t total_words,
+                                                  int32_t seg)
 {
     const int lane = threadIdx.x & 63;
     int32_t words = 0;
@@ -108,8 +109,9 @@ __device__ __forceinline__ int32_t band_blocks_of(const int32_t* __restrict__ ro
     do {
         // A run here is at most kBandRunCap entries of one column (an input that repeats a
         // coordinate can hold more: they form several runs).  The segment takes the runs that
-        // start within kBandSeg entries of its first entry: at most 68 + 31 = 99 entries.
-        int32_t seg_end = cur + kBandSeg;
+        // start within seg = band_seg(W) entries of its first entry: at most seg + 31 entries, which
+        // is also what the two tiles of 64 lanes below cover.
+        int32_t seg_end = cur + seg;
         if (seg_end >= e) {
             seg_end = e;
         } else {
@@ -244,24 +246,26 @@ __device__ __forceinline__ int32_t band_blocks_of(const int32_t* __restrict__ ro
 }
 
 // ---------------------------------------------------------------------------------------------
-// One workgroup per stream (Q, w).  The entries of group q = 8Q + w are in column order, so band
+// One workgroup per stream (Q, w).  The entries of group q = W*Q + w are in column order, so band
 // b of the group is the entry range [bstart[b], bstart[b+1]).  Pass 1: every wave sizes bands
 // (wave v takes b = v, v + 16, ...); prefix sum over the bands; pass 2: the same waves write the
 // blocks.  Dynamic LDS: 2 * (NBmax + 1) words with NBmax = ceil(k / 64).
 // ---------------------------------------------------------------------------------------------
 __global__ __launch_bounds__(kBandBuildThreads) void band_fill(const int32_t* __restrict__ gIdxes, const int32_t* __restrict__ rows,
                                                               const int32_t* __restrict__ cols, const float* __restrict__ values,
-                                                              int32_t p, int64_t g, int64_t k, const int32_t* __restrict__ ucols,
-                                                              const int32_t* __restrict__ ucount, uint32_t* __restrict__ stream)
+                                                              int32_t p, int64_t g, int64_t k, int32_t W,
+                                                              const int32_t* __restrict__ ucols, const int32_t* __restrict__ ucount,
+                                                              uint32_t* __restrict__ stream)
 {
     extern __shared__ uint32_t band_lds[];
     __shared__ int32_t wsum[kBandBuildWaves];
     __shared__ int32_t total_s;
     __shared__ int32_t carry_s;
     const int lane = threadIdx.x & 63, wv = threadIdx.x >> 6;
-    const int64_t q = blockIdx.x, Q = q / kBandWaves;
-    const int w = (int)(q - Q * kBandWaves);
-    const int64_t q0 = Q * kBandWaves;
+    const int64_t q = blockIdx.x, Q = q / W;
+    const int w = (int)(q - Q * W);
+    const int64_t q0 = Q * W;
+    const int32_t R = kBandRows / W, seg = band_seg(W);
     const int32_t nU = ucount[Q];
     const int32_t NB = (nU + kBandRows - 1) / kBandRows;
     const int32_t* uc = ucols + gIdxes[q0];
@@ -288,13 +292,13 @@ __global__ __launch_bounds__(kBandBuildThreads) void band_fill(const int32_t* __
     __syncthreads();
 
     auto band_ids = [&](int32_t b, int32_t* ncols_out, int32_t* ids) {
-        // rows of B that wave w fetches for band b: slots t*8 + w
+        // rows of B that wave w fetches for band b: slots t*W + w, t < R
         int32_t n = nU - b * kBandRows;
         n = n < 0 ? 0 : (n > kBandRows ? kBandRows : n);
         *ncols_out = n;
         if (lane < 8) {
-            const int32_t slot = lane * 8 + w;
-            ids[0] = slot < n ? uc[b * kBandRows + slot] : 0;
+            const int32_t slot = lane * W + w;
+            ids[0] = (lane < R && slot < n) ? uc[b * kBandRows + slot] : 0;
         }
     };
 
@@ -302,7 +306,7 @@ __global__ __launch_bounds__(kBandBuildThreads) void band_fill(const int32_t* __
     for (int32_t b = wv; b < NB; b += kBandBuildWaves) {
         const int32_t nc = (nU - b * kBandRows < kBandRows) ? nU - b * kBandRows : kBandRows;
         const int32_t sz = band_blocks_of(rows, cols, values, bstart[b], bstart[b + 1], row0, p, uc + b * kBandRows, nc, nullptr, 0,
-                                          nullptr, 0);
+                                          nullptr, 0, seg);
         if (lane == 0) boff[b] = sz;
     }
     __syncthreads();
@@ -335,7 +339,7 @@ __global__ __launch_bounds__(kBandBuildThreads) void band_fill(const int32_t* __
         __builtin_amdgcn_wave_barrier();
         const int32_t nc = (nU - b * kBandRows < kBandRows) ? nU - b * kBandRows : kBandRows;
         band_blocks_of(rows, cols, values, bstart[b], bstart[b + 1], row0, p, uc + b * kBandRows, nc, out + boff[b], nc_next,
-                       ids_s[wv], boff[b + 1] - boff[b]);
+                       ids_s[wv], boff[b + 1] - boff[b], seg);
         __builtin_amdgcn_wave_barrier();
     }
 }

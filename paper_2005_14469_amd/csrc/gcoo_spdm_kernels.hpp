@@ -98,8 +98,10 @@ __device__ __forceinline__ void acc_add(AccFile& acc, int reg, float x)
 #define GCOO_E7(c, a) GCOO_E6(c, a), [c6] "s"((c)[6]), [a6] "v"((a)[6])
 #define GCOO_E8(c, a) GCOO_E7(c, a), [c7] "s"((c)[7]), [a7] "v"((a)[7])
 
+// The index mode keeps the row in M0, which the compiler otherwise owns (it loads M0 in front of
+// every instruction of its own that reads it): the clobber tells it that the value is gone.
 #define GCOO_RUN_ASM(L, VN) \
-    asm volatile(GCOO_RUN##L(GCOO_FMA_V##VN) GCOO_OFF : GCOO_ACC_OPERANDS(acc) : GCOO_E##L(c, a), GCOO_B_V##VN(b))
+    asm volatile(GCOO_RUN##L(GCOO_FMA_V##VN) GCOO_OFF : GCOO_ACC_OPERANDS(acc) : GCOO_E##L(c, a), GCOO_B_V##VN(b) : "m0")
 #define GCOO_RUN_CASE(L)                           \
     if constexpr (V == 4) GCOO_RUN_ASM(L, 4);      \
     else if constexpr (V == 2) GCOO_RUN_ASM(L, 2); \

@@ -184,3 +184,48 @@ def check(asm_text: str, mangled_prefix: str):
         if entry[bi] is not None:
             transfer(b, entry[bi], bad)
     return sorted(load_regs), bad
+
+
+def check_lds_loads(asm_text: str, mangled_prefix: str):
+    """Loads that write LDS directly (`global_load_lds_*`) in a kernel that also uses the VGPR index mode.
+
+    Such a load takes the LDS address of lane 0 from M0, and `s_set_gpr_idx_on/idx` overwrite M0.
+    Returns (number of such loads, list of problems).  Proved on the text, block by block:
+      * walking back from every such load, an instruction that writes M0 as a plain destination
+        (`s_mov_b32 m0`, `s_add_i32 m0`, ...) comes before any label, branch or index-mode instruction;
+      * walking back from every `s_barrier`, an `s_waitcnt` that names vmcnt(0) comes before any such load
+        (what a wave has sent to LDS has arrived before the other waves are let past the barrier).
+    """
+    body = [l.split(";")[0].strip() for l in kernel_body(asm_text, mangled_prefix)]
+    body = [l for l in body if l]
+    problems = []
+    loads = 0
+    for i, line in enumerate(body):
+        if line.startswith("global_load_lds"):
+            loads += 1
+            j = i - 1
+            while j >= 0:
+                t = body[j]
+                if re.match(r"^s_\w+\s+m0\b", t):
+                    break
+                if _LABEL.match(t) or _BRANCH.match(t) or t.startswith("s_set_gpr_idx") or t.startswith("global_load_lds"):
+                    problems.append(f"line {i}: '{line}' has no M0 write of its own (stopped at '{t}')")
+                    break
+                j -= 1
+            else:
+                problems.append(f"line {i}: '{line}' has no M0 write before it")
+        elif line.startswith("s_barrier"):
+            j = i - 1
+            while j >= 0:
+                t = body[j]
+                if t.startswith("s_waitcnt") and "vmcnt(0)" in t:
+                    break
+                if t.startswith("global_load_lds"):
+                    problems.append(f"line {i}: barrier with a load to LDS ('{t}') not awaited")
+                    break
+                if _LABEL.match(t):            # the walk stays in the block: a barrier that opens a block is judged unsafe
+                    if any(b.startswith("global_load_lds") for b in body):
+                        problems.append(f"line {i}: barrier at the start of a block, no wait seen")
+                    break
+                j -= 1
+    return loads, problems

@@ -2,18 +2,23 @@
 fills it) and an executor that multiplies with nothing but the streams, so that the format can
 be checked against the oracle on the CPU and the HIP builder against the model bit for bit.
 
+Two shapes: W = 8 waves (groups of 17..32 rows) and W = 16 (groups of at most 16 rows).
+
 Format (per group stream, 32-bit words):
-  stream(q) = pre-block, then for every band b of the super-group Q = q // 8 the blocks of (q, b)
-  block = 12 header words + chunks; at most 256 words
+  stream(q) = pre-block, then for every band b of the super-group Q = q // W the blocks of (q, b)
+  block = 12 header words + chunks; at most 256 (W = 8) or 128 (W = 16) words
     w0  n1 | n2<<8 | n4<<16 | n8<<24      chunk counts per type
     w1  bit0: last block of its band; bits 8..15: columns of the next band (first block of a band / pre-block only)
     w2  words from this block's start to the first block of the next band (first block of a band / pre-block only)
     w3  words of this block
-    w4..w11  B rows that wave w = q % 8 loads for the next band (slot t*8 + w, t = 0..7; 0 where there is none)
+    w4..w11  B rows that wave w = q % W loads for the next band (slot t*W + w, t < 64/W; 0 where there is none)
   chunk types: T1 4 runs x 1 entry (8 words), T2 4 x 2 (12), T4 2 x 4 (12), T8 1 x 8 (12)
 """
 import numpy as np
-G = 8; R = 64; SEG = 68; HDR = 12
+R = 64; HDR = 12
+def waves_of(p): return 16 if p <= 16 else 8
+def seg_of(W): return 68 if W == 8 else 24
+def block_max_of(W): return 256 if W == 8 else 128
 TYPES = (1, 2, 4, 8); JT = {1: 4, 2: 4, 4: 2, 8: 1}; SZ = {1: 8, 2: 12, 4: 12, 8: 12}
 
 def pieces_of_run(ell):
@@ -25,6 +30,7 @@ def pieces_of_run(ell):
     return out
 
 def build(m, k, p, gIdxes, rows, cols, vals):
+    G = waves_of(p); SEG = seg_of(G)
     g = (m + p - 1) // p; nQ = (g + G - 1) // G
     streams = []; info = []
     for Q in range(nQ):
@@ -37,8 +43,8 @@ def build(m, k, p, gIdxes, rows, cols, vals):
             words = []
             def loader_ids(b):   # ids for band b
                 n = max(0, min(R, nU - R * b)); ids = [0] * 8
-                for t in range(8):
-                    if t * 8 + w < n: ids[t] = int(ucols[R * b + t * 8 + w])
+                for t in range(R // G):
+                    if t * G + w < n: ids[t] = int(ucols[R * b + t * G + w])
                 return n, ids
             if q < g: s, e = int(gIdxes[q]), int(gIdxes[q + 1])
             else: s = e = 0
@@ -119,7 +125,7 @@ def build(m, k, p, gIdxes, rows, cols, vals):
                 return [w0, (1 if last else 0) | ncn << 8, delta, size] + ids
             sizes = [[HDR + len(body) for (_, body) in blocks] for blocks in band_blocks]
             for blocks in sizes:
-                for sz in blocks: assert sz <= 256, sz
+                for sz in blocks: assert sz <= block_max_of(G), sz
             n0, ids0 = loader_ids(0)
             words += hdr({1: 0, 2: 0, 4: 0, 8: 0}, True, n0, HDR, HDR, ids0)
             for b, blocks in enumerate(band_blocks):
@@ -134,6 +140,7 @@ def build(m, k, p, gIdxes, rows, cols, vals):
 
 def execute(m, k, p, N, streams, info, B):
     """C = A x B from the streams alone (fp64), following the kernel's steps."""
+    G = waves_of(p)
     g = (m + p - 1) // p; C = np.zeros((g * p + 1, N))
     nQ = len(info)
     for Q in range(nQ):
@@ -147,8 +154,9 @@ def execute(m, k, p, N, streams, info, B):
             lds = {}     # slot -> B row id, for the band being processed
             def load(hpos):
                 n = int(st[hpos + 1] >> 8) & 255; d = {}
-                for t in range(8):
-                    if t * 8 + w < n: d[t * 8 + w] = int(st[hpos + 4 + t])
+                for t in range(R // G):
+                    if t * G + w < n: d[t * G + w] = int(st[hpos + 4 + t])
+                for t in range(R // G, 8): assert st[hpos + 4 + t] == 0
                 return n, d
             nxt_n, mine = load(pos)
             # the other waves' rows: take from ucols (the model checks only its own ids)

@@ -112,10 +112,22 @@ def test_newer_entry_points_reject_bad_arguments_on_the_host(L):
     assert L.gcoo_csr_spmm_baseline(0, 2, fake, fake, fake, fake, 4, 4, None, 4, None) == 0                     # nothing to do
 
 
-def test_default_p_is_a_size_every_kernel_serves(L):
-    # the group height that Section 4 of the paper tunes by hand; the default is one the register
-    # and the band kernel both serve, whatever the shape
-    for m, k, nnz, n in [(8000, 8000, 320000, 8000), (4000, 4000, 3200000, 4000), (0, 0, 0, 0), (1, 1, 1, 1)]:
+def test_default_p_rule(L):
+    """32 (the register kernel's best height) unless the sixteen-wave band kernel was measured faster:
+    the cases below sit on both sides of every limit the header states."""
+    def dp(n, s, N=None, m=None):
+        m = n if m is None else m
+        return L.gcoo_default_p(m, n, int(m * n * (1 - s)), n if N is None else N)
+    assert dp(8000, 0.995) == 32            # the headline workload: 8000 columns at 0.5 %
+    assert dp(8000, 0.98) == 16 and dp(8000, 0.99) == 16
+    assert dp(8000, 0.9) == 32              # too dense for the band schedule
+    assert dp(4000, 0.98) == 16 and dp(4000, 0.995) == 32 and dp(4000, 0.95) == 32
+    assert dp(6000, 0.98) == 32             # 24 x 24 blocks fill 2.25 rounds of 256: 75 %
+    assert dp(12000, 0.995) == 16 and dp(14000, 0.999) == 16
+    assert dp(2000, 0.98) == 32
+    assert dp(12000, 0.98, N=256) == 32     # 47 blocks of C: too few workgroups
+    assert dp(12000, 0.98, N=12002) == 32   # rows of B not 16-byte aligned
+    for m, k, nnz, n in [(0, 0, 0, 0), (1, 1, 1, 1), (256, 256, 6000, 256)]:
         assert L.gcoo_default_p(m, k, nnz, n) == 32
     assert L.gcoo_default_p(-1, 1, 1, 1) == 0
     assert L.gcoo_default_p(1, 1, -1, 1) == 0

@@ -12,6 +12,7 @@ from tests import band_model
 @pytest.mark.parametrize("m,k,N,p,s", [
     (100, 300, 8, 32, 0.9), (257, 1000, 4, 32, 0.99), (70, 200, 4, 16, 0.3), (64, 64, 4, 32, 0.0), (33, 50, 4, 8, 0.95),
     (300, 70, 4, 32, 0.6), (1, 1, 1, 1, 0.0), (20, 130, 2, 32, 1.0),
+    (300, 500, 4, 16, 0.5), (257, 1000, 4, 16, 0.99), (120, 90, 4, 17, 0.7), (530, 200, 4, 12, 0.8),
 ])
 def test_streams_multiply_like_the_oracle(m, k, N, p, s):
     w = workloads.uniform_random(m, k, N, s, seed=m + k)
@@ -51,7 +52,7 @@ def repeated_coordinates_workload():
     return m, k, N, row_ptr, col_idx, vals, B
 
 
-@pytest.mark.parametrize("p", [1, 8, 32])
+@pytest.mark.parametrize("p", [1, 8, 16, 32])
 def test_runs_longer_than_a_group_is_tall(p):
     m, k, N, row_ptr, col_idx, vals, B = repeated_coordinates_workload()
     G = orc.gcoo_from_csr(m, k, row_ptr, col_idx, vals, p)

@@ -152,6 +152,7 @@ def _band_base(first_entry, q, k):
 @pytest.mark.parametrize("m,k,p,s", [
     (100, 300, 32, 0.95), (257, 1000, 32, 0.99), (70, 200, 16, 0.94), (33, 50, 8, 0.95), (300, 70, 32, 0.96),
     (1, 1, 1, 0.0), (520, 5000, 32, 0.97), (64, 4000, 32, 0.999), (2000, 2000, 32, 0.98), (256, 64, 32, 0.95),
+    (2000, 2000, 16, 0.98), (520, 5000, 12, 0.97), (256, 64, 16, 0.95), (700, 300, 16, 0.945), (120, 90, 17, 0.95),
 ])
 def test_band_schedule_bit_exact(band_always, m, k, p, s):
     """The band schedule written by the HIP builder equals the Python model word for word."""
@@ -168,7 +169,7 @@ def test_band_schedule_bit_exact(band_always, m, k, p, s):
     streams, info = band_model.build(m, k, p, G.gIdxes, G.rows, G.cols, G.values)
     for Q, (ucols, NB) in enumerate(info):
         assert got["ucount"][Q] == len(ucols)
-        e0 = int(G.gIdxes[8 * Q])
+        e0 = int(G.gIdxes[min(band_model.waves_of(p) * Q, G.g)])
         assert np.array_equal(got["ucols"][e0:e0 + len(ucols)], ucols)
     for q, st in enumerate(streams):
         base = _band_base(int(G.gIdxes[min(q, G.g)]), q, k)
@@ -181,7 +182,7 @@ def test_band_schedule_bit_exact_with_repeated_coordinates(band_always):
     m, k, N, row_ptr, col_idx, vals, B = repeated_coordinates_workload()
     # density of this input is above the limit for the band schedule at its real size: embed it in a wider matrix
     k2 = 4000
-    for p in (8, 32):
+    for p in (8, 16, 32):
         _say(f"band schedule with repeated coordinates p={p}")
         A = binding.gcoo_from_csr(m, k2, row_ptr, col_idx, vals, p, device=DEV)
         got = A.export_band()
@@ -255,9 +256,12 @@ def test_heavy_groups_shared_by_a_workgroup(m, k, N, p, sparsity):
     (100, 300, 8, 32, 0.95), (257, 1000, 260, 32, 0.99), (70, 200, 4, 16, 0.94), (33, 50, 12, 8, 0.95), (300, 70, 64, 32, 0.96),
     (1, 1, 4, 1, 0.0), (520, 5000, 512, 32, 0.97), (64, 4000, 256, 32, 0.999), (2000, 2000, 300, 32, 0.98), (256, 64, 1028, 32, 0.95),
     (1000, 3000, 256, 32, 0.94),
+    (2000, 2000, 300, 16, 0.98), (520, 5000, 512, 12, 0.97), (256, 64, 1028, 16, 0.95), (1000, 3000, 256, 16, 0.94),
+    (257, 1000, 260, 9, 0.99), (64, 4000, 256, 16, 0.999), (100, 300, 8, 2, 0.95), (3000, 900, 64, 16, 0.95),
 ])
 def test_band_variant(band_always, m, k, N, p, sparsity):
-    """The kernel whose eight waves share the rows of B through LDS, on matrices sparse enough to have a band schedule."""
+    """The kernel whose waves share the rows of B through LDS (both shapes: eight waves for groups of 17..32 rows,
+    sixteen for shorter groups), on matrices sparse enough to have a band schedule."""
     w = workloads.uniform_random(m, k, N, sparsity, seed=5 * m + k + N)
     _say(f"band variant m={m} k={k} N={N} p={p} nnz={w.nnz}")
     if w.nnz == 0 or w.nnz > 0.06 * m * k:
@@ -275,16 +279,17 @@ def test_band_variant_repeated_coordinates_and_strides(band_always):
     k2, N2 = 4000, 12
     rng = np.random.default_rng(2)
     Bh = rng.standard_normal((k2, N2)).astype(np.float32)
-    A = binding.gcoo_from_csr(m, k2, row_ptr, col_idx, vals, 32, device=DEV)
     Bbig = torch.zeros((k2, 40), device=DEV)
     Bbig[:, 8:8 + N2] = torch.from_numpy(Bh).to(DEV)
-    Cbig = torch.full((m, 32), 7.0, device=DEV)
-    binding.gcoo_spdm(A, Bbig[:, 8:8 + N2], Cbig[:, 4:4 + N2], variant=binding.VARIANT_BAND)
-    torch.cuda.synchronize()
     C64, D64 = orc.spdm_csr(k2, N2, row_ptr, col_idx, vals, Bh)
-    err, bad = orc.max_scaled_error(Cbig[:, 4:4 + N2].cpu().numpy(), C64, D64)
-    assert bad == 0 and err <= TOL
-    assert torch.all(Cbig[:, :4] == 7.0) and torch.all(Cbig[:, 4 + N2:] == 7.0)
+    for p in (16, 32):
+        A = binding.gcoo_from_csr(m, k2, row_ptr, col_idx, vals, p, device=DEV)
+        Cbig = torch.full((m, 32), 7.0, device=DEV)
+        binding.gcoo_spdm(A, Bbig[:, 8:8 + N2], Cbig[:, 4:4 + N2], variant=binding.VARIANT_BAND)
+        torch.cuda.synchronize()
+        err, bad = orc.max_scaled_error(Cbig[:, 4:4 + N2].cpu().numpy(), C64, D64)
+        assert bad == 0 and err <= TOL
+        assert torch.all(Cbig[:, :4] == 7.0) and torch.all(Cbig[:, 4 + N2:] == 7.0)
     with pytest.raises(binding.GcooError):                  # rows not 16-byte aligned
         binding.gcoo_spdm(A, Bbig[:, 9:9 + N2], Cbig[:, 4:4 + N2], variant=binding.VARIANT_BAND)
 
@@ -445,16 +450,24 @@ def test_tune_p_returns_a_measured_candidate():
 def test_band_policy_and_automatic_choice():
     """By default a matrix gets a band schedule only where the band kernel is the automatic choice."""
     _say("band policy")
-    w = workloads.uniform_random(64, 12000, 256, 0.97, seed=8)         # 12000 columns, 3 % dense
+    w = workloads.uniform_random(4096, 12000, 3072, 0.97, seed=8)      # 12000 columns, 3 % dense, 16 x 12 blocks of C
     Bt = torch.from_numpy(w.B).to(DEV)
     Cg = torch.empty((w.m, w.N), device=DEV)
-    A = binding.gcoo_from_csr(w.m, w.k, w.row_ptr, w.col_idx, w.vals, 32, device=DEV)
-    assert A.export_band() is not None and binding.gcoo_spdm_pick(A, Bt, Cg) == binding.VARIANT_BAND
-    _check_product(w, 32, binding.VARIANT_AUTO, A=A)
+    for p in (32, 16):
+        A = binding.gcoo_from_csr(w.m, w.k, w.row_ptr, w.col_idx, w.vals, p, device=DEV)
+        assert A.export_band() is not None and binding.gcoo_spdm_pick(A, Bt, Cg) == binding.VARIANT_BAND
+        # too few blocks of C for the workgroups of the band kernel to occupy the chip
+        assert binding.gcoo_spdm_pick(A, Bt[:, :256], Cg[:, :256]) == binding.VARIANT_REG
+        err, _, _ = _check_product(w, p, binding.VARIANT_AUTO, A=A)
+        assert err < 2e-6
     w2 = workloads.uniform_random(64, 3000, 256, 0.97, seed=8)         # too few columns for the band kernel to pay
-    A2 = binding.gcoo_from_csr(w2.m, w2.k, w2.row_ptr, w2.col_idx, w2.vals, 32, device=DEV)
-    assert A2.export_band() is None
-    assert binding.gcoo_spdm_pick(A2, torch.from_numpy(w2.B).to(DEV), Cg) == binding.VARIANT_REG
+    for p in (32, 16):
+        A2 = binding.gcoo_from_csr(w2.m, w2.k, w2.row_ptr, w2.col_idx, w2.vals, p, device=DEV)
+        assert A2.export_band() is None
+        assert binding.gcoo_spdm_pick(A2, torch.from_numpy(w2.B).to(DEV), Cg[:64, :256]) == binding.VARIANT_REG
+    w3 = workloads.uniform_random(64, 5000, 256, 0.98, seed=9)         # enough columns for groups of 16 rows, not for 32
+    assert binding.gcoo_from_csr(w3.m, w3.k, w3.row_ptr, w3.col_idx, w3.vals, 16, device=DEV).export_band() is not None
+    assert binding.gcoo_from_csr(w3.m, w3.k, w3.row_ptr, w3.col_idx, w3.vals, 32, device=DEV).export_band() is None
     binding.gcoo_set_band_policy(binding.BAND_NEVER)
     try:
         A3 = binding.gcoo_from_csr(w.m, w.k, w.row_ptr, w.col_idx, w.vals, 32, device=DEV)
