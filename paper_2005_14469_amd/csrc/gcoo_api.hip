@@ -127,8 +127,10 @@ double band_fill_of_rounds(int64_t items)
 }
 
 // Group height 16 with the band kernel against 32 with the register kernel (same grid of
-// measurements): 16 wins from 9000 columns on; from 7000 on at 0.8 % density or more; from 3500 on
-// between 1.5 % and 4.5 %; the two smaller regions only where the workgroups fill their rounds.
+// measurements, conversion included: the band schedule costs about as much again as the rest of
+// the conversion): 16 wins from 9000 columns on, and from 7000 on at 0.8 % density or more, where
+// the workgroups fill their rounds.  (From 3500 columns on the band kernel alone is up to 1.12x
+// faster between 1.5 % and 4.5 %, but not with its share of the conversion.)
 bool short_groups_preferred(int64_t m, int64_t k, int64_t nnz, int64_t N)
 {
     if (N % 4 != 0 || N <= 0 || !band_kernel_preferred(m, k, nnz, 16)) return false;
@@ -137,8 +139,7 @@ bool short_groups_preferred(int64_t m, int64_t k, int64_t nnz, int64_t N)
     const double fill = band_fill_of_rounds(items);
     if (items < 192) return false;
     if (k >= 9000) return fill >= 0.8;
-    if (k >= 7000 && density >= 0.008) return fill >= 0.9;
-    return k >= 3500 && density >= 0.015 && density <= 0.045 && fill >= 0.95;
+    return k >= 7000 && density >= 0.008 && fill >= 0.9;
 }
 
 bool band_schedule_wanted(int64_t m, int64_t k, int64_t nnz, int32_t p)
