@@ -307,6 +307,7 @@ int from_csr(int64_t m, int64_t k, const int32_t* row_ptr, const int32_t* col_id
 
     const int64_t g = (m + p - 1) / p;
     int64_t nnz, max_group_nnz = 0;
+    unsigned long long* stats_with_index = nullptr;
     if (src_on_device && nnz_known >= 0) {          // everything the host can check, before the first launch
         if (nnz_known > 0 && (!col_idx || !vals)) return GCOO_EINVAL;
         if (dev_buf_bytes < make_layout(m, k, nnz_known, g, p).total) return GCOO_ENOMEM;
@@ -319,12 +320,13 @@ int from_csr(int64_t m, int64_t k, const int32_t* row_ptr, const int32_t* col_id
         const Layout L0 = make_layout(m, k, 0, g, p);
         if (dev_buf_bytes < L0.total) return GCOO_ENOMEM;
         unsigned long long* stats = reinterpret_cast<unsigned long long*>(static_cast<char*>(dev_buf) + L0.counter);
-        gcoo::group_stats_from_row_ptr<<<dim3(1), dim3(256), 0, s>>>(row_ptr, m, p, g, stats);
-        HIP_TRY(hipGetLastError());
         if (nnz_known >= 0) {
             nnz = nnz_known;
             max_group_nnz = -1;
+            stats_with_index = stats;                             // computed by the launch that writes gIdxes
         } else {
+            gcoo::group_stats_from_row_ptr<<<dim3(1), dim3(256), 0, s>>>(row_ptr, m, p, g, stats);
+            HIP_TRY(hipGetLastError());
             unsigned long long got[2] = {0, 0};
             HIP_TRY(hipMemcpyAsync(got, stats, sizeof(got), hipMemcpyDeviceToHost, s));
             HIP_TRY(hipStreamSynchronize(s));
@@ -373,8 +375,9 @@ int from_csr(int64_t m, int64_t k, const int32_t* row_ptr, const int32_t* col_id
 
     // Algorithm 1, step 1: group index and counts straight from row_ptr (also writes the sentinel).
     {
-        const unsigned blocks = (unsigned)((g + 1 + 255) / 256);
-        gcoo::group_index_from_row_ptr<<<dim3(blocks), dim3(256), 0, s>>>(d_row_ptr, m, p, g, (int32_t)nnz, h->gIdxes(), h->nnzPerGroup());
+        const unsigned blocks = (unsigned)((g + 1 + 255) / 256) + (stats_with_index ? 1u : 0u);
+        gcoo::group_index_from_row_ptr<<<dim3(blocks), dim3(256), 0, s>>>(d_row_ptr, m, p, g, (int32_t)nnz, h->gIdxes(), h->nnzPerGroup(),
+                                                                         stats_with_index);
         hipError_t e = hipGetLastError();
         if (e != hipSuccess) { delete h; return hip_fail(e, "group_index_from_row_ptr"); }
     }

@@ -12,35 +12,10 @@ namespace gcoo {
 
 constexpr int kWave = 64;
 
-// ---------------------------------------------------------------------------------------------
-// Algorithm 1, step 1 for a CSR input.  CSR is row-major, so the entries of group q are the
-// contiguous CSR range [row_ptr[q*p], row_ptr[min((q+1)*p, m)]): the count and the prefix sum
-// are two reads of row_ptr.  One thread per group; thread g also writes the sentinel.
-// ---------------------------------------------------------------------------------------------
-__global__ void group_index_from_row_ptr(const int32_t* __restrict__ row_ptr, int64_t m, int32_t p, int64_t g, int32_t nnz,
-                                         int32_t* __restrict__ gIdxes, int32_t* __restrict__ nnzPerGroup)
-{
-    int64_t q = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
-    if (q > g) return;
-    // Offsets are clamped to [0, nnz]: with a device input whose row_ptr does not match the nnz
-    // the buffer was laid out for, every later kernel still stays inside the arrays.
-    auto at = [&](int64_t r) { const int32_t v = row_ptr[r]; return v < 0 ? 0 : (v > nnz ? nnz : v); };
-    int64_t r0 = q * p;
-    if (r0 > m) r0 = m;
-    const int32_t b = at(r0);
-    gIdxes[q] = b;
-    if (q < g) {
-        int64_t r1 = r0 + p;
-        if (r1 > m) r1 = m;
-        const int32_t n = at(r1) - b;
-        nnzPerGroup[q] = n < 0 ? 0 : n;
-    }
-}
-
 // What the host wants to know about a CSR input before it sizes anything: out[0] = nnz = row_ptr[m],
-// out[1] = entries of the largest group.  One workgroup.
-__global__ __launch_bounds__(256) void group_stats_from_row_ptr(const int32_t* __restrict__ row_ptr, int64_t m, int32_t p, int64_t g,
-                                                                 unsigned long long* __restrict__ out)
+// out[1] = entries of the largest group.  The work of one workgroup of 256 threads.
+__device__ __forceinline__ void group_stats_block(const int32_t* __restrict__ row_ptr, int64_t m, int32_t p, int64_t g,
+                                                  unsigned long long* __restrict__ out)
 {
     __shared__ int32_t part[4];
     int32_t mx = 0;
@@ -61,6 +36,44 @@ __global__ __launch_bounds__(256) void group_stats_from_row_ptr(const int32_t* _
         const int32_t last = row_ptr[m];
         out[0] = last < 0 ? ~0ull : (unsigned long long)last;
         out[1] = (unsigned long long)mx;
+    }
+}
+
+__global__ __launch_bounds__(256) void group_stats_from_row_ptr(const int32_t* __restrict__ row_ptr, int64_t m, int32_t p, int64_t g,
+                                                                 unsigned long long* __restrict__ out)
+{
+    group_stats_block(row_ptr, m, p, g, out);
+}
+
+// ---------------------------------------------------------------------------------------------
+// Algorithm 1, step 1 for a CSR input.  CSR is row-major, so the entries of group q are the
+// contiguous CSR range [row_ptr[q*p], row_ptr[min((q+1)*p, m)]): the count and the prefix sum
+// are two reads of row_ptr.  One thread per group; thread g also writes the sentinel.
+// 256 threads per workgroup, ceil((g+1)/256) workgroups; with `stats` given, one workgroup more,
+// which computes the statistics above in the same launch.
+// ---------------------------------------------------------------------------------------------
+__global__ __launch_bounds__(256) void group_index_from_row_ptr(const int32_t* __restrict__ row_ptr, int64_t m, int32_t p, int64_t g,
+                                                                 int32_t nnz, int32_t* __restrict__ gIdxes,
+                                                                 int32_t* __restrict__ nnzPerGroup, unsigned long long* __restrict__ stats)
+{
+    if (stats && blockIdx.x == gridDim.x - 1) {                   // the whole workgroup
+        group_stats_block(row_ptr, m, p, g, stats);
+        return;
+    }
+    int64_t q = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (q > g) return;
+    // Offsets are clamped to [0, nnz]: with a device input whose row_ptr does not match the nnz
+    // the buffer was laid out for, every later kernel still stays inside the arrays.
+    auto at = [&](int64_t r) { const int32_t v = row_ptr[r]; return v < 0 ? 0 : (v > nnz ? nnz : v); };
+    int64_t r0 = q * p;
+    if (r0 > m) r0 = m;
+    const int32_t b = at(r0);
+    gIdxes[q] = b;
+    if (q < g) {
+        int64_t r1 = r0 + p;
+        if (r1 > m) r1 = m;
+        const int32_t n = at(r1) - b;
+        nnzPerGroup[q] = n < 0 ? 0 : n;
     }
 }
 
