@@ -422,6 +422,44 @@ def test_full_size_configs_sampled_rows(index):
         assert bad == 0 and err <= TOL, (q, err, bad)
 
 
+def test_full_size_default_height_picks_the_band_kernel_sampled_rows():
+    """8000^2 at s=0.98, N = 8000, as the benchmark's sweeps run it: group height from gcoo_default_p (16 here),
+    automatic variant (the sixteen-wave band kernel); the oracle recomputes a sample of groups and row bands."""
+    n, s = 8000, 0.98
+    w = workloads.uniform_random(n, n, n, s, workloads.BASE_SEED + n, name="uniform_8000_0.98")
+    p = binding.gcoo_default_p(w.m, w.k, w.nnz, w.N)
+    _say(f"uniform 8000 s=0.98 nnz={w.nnz} default p={p}")
+    assert p == 16
+    A = binding.gcoo_from_csr(w.m, w.k, w.row_ptr, w.col_idx, w.vals, p, device=DEV)
+    Bt = torch.from_numpy(w.B).to(DEV)
+    Cg = torch.full((w.m, w.N), float("nan"), dtype=torch.float32, device=DEV)
+    assert binding.gcoo_spdm_pick(A, Bt, Cg) == binding.VARIANT_BAND
+    G = A.export()
+    rng = np.random.default_rng(98)
+    g = A.info()["g"]
+    for q in [0, g - 1] + rng.integers(0, g, 6).tolist():
+        r0, r1 = q * p, min(q * p + p, w.m)
+        sub = orc.gcoo_from_csr(r1 - r0, w.k, w.row_ptr[r0:r1 + 1] - w.row_ptr[r0],
+                                w.col_idx[w.row_ptr[r0]:w.row_ptr[r1]], w.vals[w.row_ptr[r0]:w.row_ptr[r1]], p)
+        b, e = int(G["gIdxes"][q]), int(G["gIdxes"][q + 1])
+        assert np.array_equal(G["cols"][b:e], sub.cols) and np.array_equal(G["rows"][b:e], sub.rows + r0)
+        assert np.array_equal(G["values"][b:e].view(np.uint32), sub.values.view(np.uint32))
+    binding.gcoo_spdm(A, Bt, Cg)
+    torch.cuda.synchronize()
+    assert not torch.isnan(Cg).any()
+    for q in [0, g - 1] + rng.integers(0, g, 8).tolist():
+        r0, r1 = q * p, min(q * p + p, w.m)
+        C64, D64 = orc.spdm_csr(w.k, w.N, w.row_ptr, w.col_idx, w.vals, w.B, r0, r1)
+        err, bad = orc.max_scaled_error(Cg[r0:r1].cpu().numpy(), C64, D64)
+        assert bad == 0 and err <= TOL, (q, err, bad)
+    # the same product through the register kernel on the same handle: every element within two roundings' worth
+    Cr = torch.empty_like(Cg)
+    binding.gcoo_spdm(A, Bt, Cr, variant=binding.VARIANT_REG)
+    torch.cuda.synchronize()
+    scale = float(torch.abs(torch.from_numpy(w.B)).max()) * float(np.abs(w.vals).max())
+    assert float((Cg - Cr).abs().max()) <= 1e-4 * scale * 8
+
+
 @pytest.mark.parametrize("shape", [(300, 200, 1028), (77, 500, 250), (1, 1, 1)])
 def test_csr_baseline_kernel(shape):
     """The comparison kernel of the benchmark is held to the same bound as the path itself."""
