@@ -25,7 +25,8 @@
 // without entries has one empty block).  A block is at most band_block_max(W) = 256 or 128 words:
 // 12 header words, then chunks:
 //     w0       n1 | n2 << 8 | n4 << 16 | n8 << 24      chunks of each type in this block
-//     w1       bit 0: last block of its band; bits 8..15: rows of the next band    (*)
+//     w1       bit 0: last block of its band; bits 1..2: piece slots in use in the last chunk of
+//              type 1 (0 = all four, or no such chunk); bits 8..15: rows of the next band    (*)
 //     w2       words from the start of this block to the first block of the next band  (*)
 //     w3       words of this block
 //     w4..w11  the B rows this wave fetches for the next band: slots t*W + w, t = 0..R-1 (0 if none

@@ -170,7 +170,7 @@ __device__ __forceinline__ int32_t band_blocks_of(const int32_t* __restrict__ ro
             // header
             if (lane == 0) {
                 blk[0] = (uint32_t)nch[0] | (uint32_t)nch[1] << 8 | (uint32_t)nch[2] << 16 | (uint32_t)nch[3] << 24;
-                blk[1] = (last_block ? 1u : 0u) | (first_block ? (uint32_t)next_cols << 8 : 0u);
+                blk[1] = (last_block ? 1u : 0u) | (uint32_t)(cnt[0] & 3) << 1 | (first_block ? (uint32_t)next_cols << 8 : 0u);
                 blk[2] = first_block ? (uint32_t)total_words : 0u;
                 blk[3] = (uint32_t)size;
             }

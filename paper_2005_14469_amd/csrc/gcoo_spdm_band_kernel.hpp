@@ -56,6 +56,23 @@ struct AccFile16 {
 #define GCOO16_RUN_ASM(L) \
     asm volatile(GCOO_RUN##L(GCOO16_FMA) GCOO_OFF : GCOO16_ACC_OPERANDS(acc) : GCOO_E##L(c, a), GCOO_B_V4(b) : "m0")
 
+// Four entries of four different columns (a chunk of type 1) in one span of the index mode.
+#define GCOO16_FMA_E(i)                                      \
+    "v_fma_f32 v60, %[a" #i "], %[b" #i "0], v60\n\t"         \
+    "v_fma_f32 v77, %[a" #i "], %[b" #i "1], v77\n\t"         \
+    "v_fma_f32 v94, %[a" #i "], %[b" #i "2], v94\n\t"         \
+    "v_fma_f32 v111, %[a" #i "], %[b" #i "3], v111\n\t"
+#define GCOO16_B_E(i, b) [b##i##0] "v"((b)[i][0]), [b##i##1] "v"((b)[i][1]), [b##i##2] "v"((b)[i][2]), [b##i##3] "v"((b)[i][3])
+// The four entries of a chunk of type 1.
+__device__ __forceinline__ void singles4_fma16(AccFile16& acc, const uint32_t (&c)[4], const float (&a)[4], const float (&b)[4][4])
+{
+    asm volatile("s_set_gpr_idx_on %[c0], gpr_idx(SRC2,DST)\n\t" GCOO16_FMA_E(0) "s_set_gpr_idx_idx %[c1]\n\t" GCOO16_FMA_E(1)
+                 "s_set_gpr_idx_idx %[c2]\n\t" GCOO16_FMA_E(2) "s_set_gpr_idx_idx %[c3]\n\t" GCOO16_FMA_E(3) GCOO_OFF
+                 : GCOO16_ACC_OPERANDS(acc)
+                 : GCOO_E4(c, a), GCOO16_B_E(0, b), GCOO16_B_E(1, b), GCOO16_B_E(2, b), GCOO16_B_E(3, b)
+                 : "m0");
+}
+
 template <int L>
 __device__ __forceinline__ void run_fma16(AccFile16& acc, const uint32_t* c, const float* a, const float (&b)[4])
 {
@@ -162,9 +179,12 @@ __device__ __forceinline__ void band_chunk_fma(typename S::Acc& acc, const BandC
 // next chunk is read from the band as soon as piece j of this chunk has been multiplied (into the
 // registers that piece just freed), so those reads are in flight behind the multiply-adds of the
 // other pieces.
+// rem (type 1 only): piece slots in use in the last chunk, 0 = all four.  The sixteen-wave
+// instance multiplies only those; the eight-wave instance multiplies the unused slots too (they
+// add zero to the sink row).
 template <int T, class S>
 __device__ __forceinline__ const lds_u32* band_chunks(typename S::Acc& acc, const lds_u32* cp, int32_t n,
-                                                       const char __attribute__((address_space(3)))* band_lane)
+                                                       const char __attribute__((address_space(3)))* band_lane, uint32_t rem = 0)
 {
     constexpr int J = band_pieces_per_chunk(T), W = band_chunk_words(T);
     if (n <= 0) return cp;
@@ -179,19 +199,40 @@ __device__ __forceinline__ const lds_u32* band_chunks(typename S::Acc& acc, cons
         }
     };
     if constexpr (S::kDirect) {
-        // two register sets take turns: the loop body is written out twice
-        BandChunk<T> s0 = band_chunk_read<T>(cp);
-        BandChunk<T> s1 = s0;
+        // No software pipeline here: with four waves per SIMD the other waves cover a chunk's two
+        // LDS round trips, and the fewest instructions win (measured: 4-5 % over the pipelined loop).
+        const int32_t full = (T == 1 && rem) ? n - 1 : n;         // chunks that are multiplied whole
+        for (int32_t c = 0; c < full; ++c) {
+            const BandChunk<T> w = band_chunk_read<T>(cp);
 #pragma unroll
-        for (int j = 0; j < J; ++j) band_b(band_lane, band_chunk_offset<T>(s0, j), b[j]);
-        auto turn = [&](const BandChunk<T>& c0, BandChunk<T>& c1, int32_t c) {
-            c1 = band_chunk_read<T>(cp + (c + 1 < n ? W : 0));    // the last chunk is read again instead of reading past the end
-            multiply(c0, c1);
+            for (int j = 0; j < J; ++j) band_b(band_lane, band_chunk_offset<T>(w, j), b[j]);
+            if constexpr (T == 1) {
+                const uint32_t rw = uni(w.w[0].z);
+                const uint32_t r[4] = {rw, rw >> 8, rw >> 16, rw >> 24};
+                const float a[4] = {__uint_as_float(w.w[1].x), __uint_as_float(w.w[1].y), __uint_as_float(w.w[1].z),
+                                    __uint_as_float(w.w[1].w)};
+                singles4_fma16(acc, r, a, b);
+            } else {
+                const uint32_t rowword[2] = {uni(T <= 2 ? w.w[0].z : w.w[0].y), uni(T <= 2 ? w.w[0].w : w.w[0].z)};
+#pragma unroll
+                for (int j = 0; j < J; ++j) band_chunk_fma<T, S>(acc, w, j, rowword, b[j]);
+            }
             cp += W;
-        };
-        for (int32_t c = 0; c < n; c += 2) {
-            turn(s0, s1, c);
-            if (c + 1 < n) turn(s1, s0, c + 1);
+        }
+        if constexpr (T == 1) {
+            if (rem) {                                            // the last chunk: only the slots in use
+                const BandChunk<T> w = band_chunk_read<T>(cp);
+#pragma unroll
+                for (int j = 0; j < 3; ++j) band_b(band_lane, band_chunk_offset<T>(w, j), b[j]);   // an unused slot names offset 0
+                const uint32_t rw = uni(w.w[0].z);
+                const uint32_t r[4] = {rw, rw >> 8, rw >> 16, rw >> 24};
+                const float a[4] = {__uint_as_float(w.w[1].x), __uint_as_float(w.w[1].y), __uint_as_float(w.w[1].z),
+                                    __uint_as_float(w.w[1].w)};
+                run_fma16<1>(acc, &r[0], &a[0], b[0]);
+                if (rem >= 2) run_fma16<1>(acc, &r[1], &a[1], b[1]);
+                if (rem >= 3) run_fma16<1>(acc, &r[2], &a[2], b[2]);
+                cp += W;
+            }
         }
     } else {
         // three register sets take turns (this chunk, the next, the one being read), so that no
@@ -220,10 +261,11 @@ __device__ __forceinline__ const lds_u32* band_chunks(typename S::Acc& acc, cons
 // lane's place in a row, is band_lane.
 template <class S>
 __device__ __forceinline__ void band_block(typename S::Acc& acc, const lds_u32* blk, const char __attribute__((address_space(3)))* band_lane,
-                                           uint32_t counts)
+                                           uint32_t counts, uint32_t flags)
 {
     const lds_u32* cp = blk + kBandHdr;
-    cp = band_chunks<1, S>(acc, cp, (int32_t)(counts & 255u), band_lane);
+    cp = band_chunks<1, S>(acc, cp, (int32_t)(counts & 255u), band_lane, (flags >> 1) & 3u);
+    if (S::kDirect && (counts >> 8) == 0) return;                 // nothing but single entries: the usual block of a very sparse matrix
     cp = band_chunks<2, S>(acc, cp, (int32_t)((counts >> 8) & 255u), band_lane);
     cp = band_chunks<4, S>(acc, cp, (int32_t)((counts >> 16) & 255u), band_lane);
     band_chunks<8, S>(acc, cp, (int32_t)(counts >> 24), band_lane);
@@ -337,7 +379,7 @@ __global__ __launch_bounds__(64 * S::W) void spdm_band(const uint32_t* __restric
 
         const char __attribute__((address_space(3)))* band_lane = band0 + (b & 1) * kBandBufBytes + lane * 16;
         const lds_u32* blk = ring + ((b + 1) & 1) * kBlock;      // this band's first block
-        band_block<S>(acc, blk, band_lane, hd.a.x);
+        band_block<S>(acc, blk, band_lane, hd.a.x, hd.a.y);
         if (!(hd.a.y & 1u)) {                                     // further blocks of this band: a group with many entries in it
             int64_t bpos = pos + (int64_t)hd.a.w;
             for (;;) {
@@ -350,7 +392,7 @@ __global__ __launch_bounds__(64 * S::W) void spdm_band(const uint32_t* __restric
                 }
                 blk = ring + 2 * kBlock;
                 const u32x4 h = ring_read4(blk);
-                band_block<S>(acc, blk, band_lane, uni(h.x));
+                band_block<S>(acc, blk, band_lane, uni(h.x), uni(h.y));
                 if (uni(h.y) & 1u) break;
                 bpos += (int64_t)uni(h.w);
             }

@@ -8,7 +8,8 @@ Format (per group stream, 32-bit words):
   stream(q) = pre-block, then for every band b of the super-group Q = q // W the blocks of (q, b)
   block = 12 header words + chunks; at most 256 (W = 8) or 128 (W = 16) words
     w0  n1 | n2<<8 | n4<<16 | n8<<24      chunk counts per type
-    w1  bit0: last block of its band; bits 8..15: columns of the next band (first block of a band / pre-block only)
+    w1  bit0: last block of its band; bits 1..2: piece slots in use in the last T1 chunk (0 = all four / none);
+        bits 8..15: columns of the next band (first block of a band / pre-block only)
     w2  words from this block's start to the first block of the next band (first block of a band / pre-block only)
     w3  words of this block
     w4..w11  B rows that wave w = q % W loads for the next band (slot t*W + w, t < 64/W; 0 where there is none)
@@ -117,12 +118,13 @@ def build(m, k, p, gIdxes, rows, cols, vals):
                             assert len(wds) == SZ[t], (t, len(wds))
                             body += wds
                     assert all(n < 256 for n in counts.values())
+                    counts["rem"] = len(lists[1]) % 4
                     blocks.append((counts, body))
                 band_blocks.append(blocks)
             # assemble with headers
             def hdr(counts, last, ncn, delta, size, ids):
                 w0 = counts[1] | counts[2] << 8 | counts[4] << 16 | counts[8] << 24
-                return [w0, (1 if last else 0) | ncn << 8, delta, size] + ids
+                return [w0, (1 if last else 0) | counts.get("rem", 0) << 1 | ncn << 8, delta, size] + ids
             sizes = [[HDR + len(body) for (_, body) in blocks] for blocks in band_blocks]
             for blocks in sizes:
                 for sz in blocks: assert sz <= block_max_of(G), sz
@@ -171,6 +173,8 @@ def execute(m, k, p, N, streams, info, B):
                     if first:
                         nxt_n, mine = load(pos); nextpos = pos + int(st[pos + 2]); first = False
                     cnt = {1: w0 & 255, 2: w0 >> 8 & 255, 4: w0 >> 16 & 255, 8: w0 >> 24 & 255}
+                    rem = fl >> 1 & 3
+                    assert rem == 0 or cnt[1] > 0
                     at = pos + HDR
                     for t in TYPES:
                         J = JT[t]
@@ -186,10 +190,12 @@ def execute(m, k, p, N, streams, info, B):
                             for j in range(J):
                                 assert offs[j] % 1024 == 0
                                 sl = int(offs[j]) // 1024
+                                unused = t == 1 and c == cnt[1] - 1 and rem and j >= rem     # a slot the kernel may skip
                                 for u in range(t):
                                     r = rb[j * t + u]; a = float(vv[j * t + u])
                                     assert r <= p
-                                    if r == p: assert a == 0.0; continue
+                                    if unused: assert r == p and a == 0.0
+                                    if r == p: assert a == 0.0 and (t > 1 or unused); continue
                                     acc[r] += a * B[band_rows[sl]].astype(np.float64)
                     assert at == pos + size
                     pos += size
