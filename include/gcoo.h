@@ -62,9 +62,9 @@ typedef struct gcoo_matrix gcoo_matrix;
  * 16 is returned where the workgroup-shared kernel with sixteen waves (GCOO_VARIANT_BAND, groups
  * of at most 16 rows) was measured faster than that: N a multiple of 4, density at most 6 %, at
  * least 192 blocks of 256 rows x 256 columns of C that fill their rounds over the 256 compute
- * units to 80 % or more, and 9000 columns or more - or 7000 at 0.8 % density or more with rounds
- * filled to 90 %.  (Conversion plus product is what was compared; a caller that converts once
- * and multiplies often gains from 16 already from 3500 columns on between 1.5 % and 4.5 %.)  Such
+ * units to 80 % or more, and 9000 columns or more at 0.4 % density or more - or 7000 at 0.8 % or
+ * more with rounds filled to 90 %.  (Conversion plus product is what was compared; a caller that
+ * converts once and multiplies often gains from 16 already from 4000 columns on between 1 % and 6 %.)  Such
  * a caller can do better still by timing a few values (the Python binding has gcoo_tune_p for
  * that).  Pure host arithmetic; 0 for invalid arguments.
  */

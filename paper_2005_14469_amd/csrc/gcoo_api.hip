@@ -128,9 +128,10 @@ double band_fill_of_rounds(int64_t items)
 
 // Group height 16 with the band kernel against 32 with the register kernel (same grid of
 // measurements, conversion included: the band schedule costs about as much again as the rest of
-// the conversion): 16 wins from 9000 columns on, and from 7000 on at 0.8 % density or more, where
-// the workgroups fill their rounds.  (From 3500 columns on the band kernel alone is up to 1.12x
-// faster between 1.5 % and 4.5 %, but not with its share of the conversion.)
+// the conversion): 16 wins from 9000 columns on at 0.4 % density or more, and from 7000 on at
+// 0.8 % or more, where the workgroups fill their rounds.  (The band kernel alone is 1.1x .. 1.2x
+// faster already from 4000 columns on between 1 % and 6 %, but not with its share of the
+// conversion; at 0.1 % the two are level even at 14000 columns.)
 bool short_groups_preferred(int64_t m, int64_t k, int64_t nnz, int64_t N)
 {
     if (N % 4 != 0 || N <= 0 || !band_kernel_preferred(m, k, nnz, 16)) return false;
@@ -138,7 +139,7 @@ bool short_groups_preferred(int64_t m, int64_t k, int64_t nnz, int64_t N)
     const int64_t items = ((m + 255) / 256) * ((N + 255) / 256);
     const double fill = band_fill_of_rounds(items);
     if (items < 192) return false;
-    if (k >= 9000) return fill >= 0.8;
+    if (k >= 9000 && density >= 0.004) return fill >= 0.8;
     return k >= 7000 && density >= 0.008 && fill >= 0.9;
 }
 
