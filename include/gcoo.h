@@ -140,6 +140,10 @@ int gcoo_from_dense(int64_t m, int64_t k, const float* A_dev, int64_t lda, int32
  * is fixed by the matrix, p and the kernel variant, never by timing: results are the same bits
  * from run to run.
  * Asynchronous on `stream`; allocates nothing; N = 0 or m = 0 is a no-op success.
+ * A matrix whose automatic kernel is the band kernel (see gcoo_set_band_policy) is converted
+ * without the register kernel's schedule; the first call that runs the register kernel on it
+ * after all builds that schedule first, on the same stream.  Calls on one handle from several
+ * host threads at once are not supported.
  */
 int gcoo_spdm(const gcoo_matrix* A, const float* B_dev, int64_t ldb, int64_t N,
               float* C_dev, int64_t ldc, void* stream);

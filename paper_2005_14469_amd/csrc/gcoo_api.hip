@@ -204,6 +204,7 @@ struct gcoo_matrix {
     mutable int64_t max_group_nnz;   // entries of the largest group; -1: still on the device (L.counter + 8), fetched on first need
     int32_t p;
     int32_t nw, window_cols;
+    mutable bool sched_built;  // the run schedule of the register kernel exists (built at conversion, or by the first launch that needs it)
     bool has_band;             // the band schedule was built
     bool band_preferred;       // and the band kernel is the automatic choice
     int device;
@@ -236,6 +237,7 @@ int new_handle(int64_t m, int64_t k, int64_t nnz, int64_t max_group_nnz, int32_t
     h->L = make_layout(m, k, nnz, h->g, p);
     h->has_band = band_schedule_wanted(m, k, nnz, p);
     h->band_preferred = h->has_band && band_kernel_preferred(m, k, nnz, p);
+    h->sched_built = false;
     pick_windows(k, h->g, &h->nw, &h->window_cols);
     if (hipGetDevice(&h->device) != hipSuccess) h->device = -1;
     *out = h;
@@ -243,7 +245,7 @@ int new_handle(int64_t m, int64_t k, int64_t nnz, int64_t max_group_nnz, int32_t
 }
 
 // Builds the run schedule of the register kernel from the finished GCOO arrays.
-int launch_build_schedule(const gcoo_matrix* h, hipStream_t s)
+int launch_build_reg_schedule(const gcoo_matrix* h, hipStream_t s)
 {
     if (h->g > 0 && h->p <= gcoo::kSchedMaxP) {              // no register kernel above that height
         const dim3 grid((unsigned)(h->g * h->nw));
@@ -254,6 +256,19 @@ int launch_build_schedule(const gcoo_matrix* h, hipStream_t s)
             gcoo::build_schedule<1024><<<grid, dim3(1024), 0, s>>>(h->gIdxes(), h->rows(), h->cols(), h->values(), h->p, h->g, h->nw,
                                                                    h->window_cols, h->sched_hdr(), h->sched());
         HIP_TRY(hipGetLastError());
+    }
+    h->sched_built = true;
+    return GCOO_OK;
+}
+
+// The kernel-private schedules that a conversion ends with.  A matrix whose automatic kernel is
+// the band kernel gets the band schedule only; should the register kernel be asked for it after
+// all (few columns of B, unaligned operands, by name), its schedule is built by that first launch.
+int launch_build_schedule(const gcoo_matrix* h, hipStream_t s)
+{
+    if (!h->band_preferred) {
+        int rc = launch_build_reg_schedule(h, s);
+        if (rc != GCOO_OK) return rc;
     }
     if (h->g > 0 && h->has_band) {
         const size_t bitmap_bytes = (size_t)((h->k + 31) / 32) * 4;
@@ -648,6 +663,10 @@ int gcoo_spdm_variant(const gcoo_matrix* A, const float* B_dev, int64_t ldb, int
     }
     const int V = sched_width(A->p, shape_of(B_dev, ldb, N, C_dev, ldc));
     if (V == 0) return GCOO_EINVAL;
+    if (!A->sched_built) {                                        // left out at conversion: the band kernel was the expected one
+        int rc = launch_build_reg_schedule(A, s);
+        if (rc != GCOO_OK) return rc;
+    }
     gcoo::SpdmArgs a{A->sched_hdr(), A->sched(), A->gIdxes(), A->m, A->p, A->g, A->nw, B_dev, ldb, N, C_dev, ldc,
                      heavy_group_min(A, (N + 64 * V - 1) / (64 * V), s)};
     hipError_t e = gcoo::launch_spdm_sched(V, a, s);

@@ -496,8 +496,15 @@ def test_band_policy_and_automatic_choice():
         assert A.export_band() is not None and binding.gcoo_spdm_pick(A, Bt, Cg) == binding.VARIANT_BAND
         # too few blocks of C for the workgroups of the band kernel to occupy the chip
         assert binding.gcoo_spdm_pick(A, Bt[:, :256], Cg[:, :256]) == binding.VARIANT_REG
-        err, _, _ = _check_product(w, p, binding.VARIANT_AUTO, A=A)
+        err, _, cfull = _check_product(w, p, binding.VARIANT_AUTO, A=A)
         assert err < 2e-6
+        # the register kernel on this handle after all: its schedule was left out at conversion and is
+        # built by this first launch
+        Cn = torch.full((w.m, 256), float("nan"), device=DEV)
+        binding.gcoo_spdm(A, Bt[:, :256], Cn)
+        torch.cuda.synchronize()
+        scale = float(np.abs(w.B).max()) * float(np.abs(w.vals).max())
+        assert float((Cn - torch.from_numpy(cfull[:, :256]).to(DEV)).abs().max()) <= 1e-4 * scale * 8
     w2 = workloads.uniform_random(64, 3000, 256, 0.97, seed=8)         # too few columns for the band kernel to pay
     for p in (32, 16):
         A2 = binding.gcoo_from_csr(w2.m, w2.k, w2.row_ptr, w2.col_idx, w2.vals, p, device=DEV)
