@@ -91,6 +91,9 @@ __device__ __forceinline__ int band_piece_of(int len, int x, int* piece_first)
 }
 
 __device__ __forceinline__ int band_type_index(int t) { return t == 1 ? 0 : (t == 2 ? 1 : (t == 4 ? 2 : 3)); }
+// a[k] for a run-time k without making `a` an array in memory
+template <class X>
+__device__ __forceinline__ X band_pick(const X (&a)[4], int k) { return k == 0 ? a[0] : (k == 1 ? a[1] : (k == 2 ? a[2] : a[3])); }
 
 // One wave: the blocks of one (group, band).  Entries [s, e) of the group (columns ascending, all
 // inside the band), band_cols = the band's columns (ncols of them).  With out == nullptr only
@@ -106,6 +109,9 @@ __device__ __forceinline__ int32_t band_blocks_of(const int32_t* __restrict__ ro
     int32_t words = 0;
     int32_t cur = s;
     bool first_block = true;
+    // the band's columns, one per lane (ascending; lanes past the end hold a column no entry has):
+    // the slot of an entry's column is then found with lane exchanges instead of reads of memory
+    const int32_t band_col_of_lane = (out && lane < ncols) ? band_cols[lane] : INT32_MAX;
     do {
         // A run here is at most kBandRunCap entries of one column (an input that repeats a
         // coordinate can hold more: they form several runs).  The segment takes the runs that
@@ -129,23 +135,36 @@ __device__ __forceinline__ int32_t band_blocks_of(const int32_t* __restrict__ ro
         // per entry (two tiles of 64 lanes): type of its piece, head or not
         int type[2] = {0, 0}, in_piece[2] = {0, 0};
         int32_t head[2] = {0, 0};                         // entry index of the piece's first entry, relative to cur
+        int32_t col_of[2] = {0, 0};
         uint64_t heads[2][4];
+        const bool two_tiles = seg_end - cur > 64;        // the same in every lane: the second tile is skipped as a whole
 #pragma unroll
         for (int t = 0; t < 2; ++t) {
             const int32_t i = cur + t * 64 + lane;
-            if (i < seg_end) {
+            if ((t == 0 || two_tiles) && i < seg_end) {
+                // the entry's column and its two neighbours in one go (three independent reads); the
+                // loops read on only inside runs of three and more
                 const int32_t c = cols[i];
+                const int32_t before = i > cur ? cols[i - 1] : -1;
+                const int32_t after = i + 1 < seg_end ? cols[i + 1] : -1;
+                col_of[t] = c;
                 int32_t rs = i, re = i + 1;
-                while (rs > cur && cols[rs - 1] == c) --rs;
+                if (before == c) {
+                    --rs;
+                    while (rs > cur && cols[rs - 1] == c) --rs;
+                }
                 rs += (i - rs) / kBandRunCap * kBandRunCap;
-                while (re < seg_end && re < rs + kBandRunCap && cols[re] == c) ++re;
+                if (after == c && re < rs + kBandRunCap) {
+                    ++re;
+                    while (re < seg_end && re < rs + kBandRunCap && cols[re] == c) ++re;
+                }
                 int pf;
                 type[t] = band_piece_of(re - rs, i - rs, &pf);
                 head[t] = rs + pf - cur;
                 in_piece[t] = i - rs - pf;
             }
 #pragma unroll
-            for (int ti = 0; ti < 4; ++ti) heads[t][ti] = __ballot(type[t] == (1 << ti) && in_piece[t] == 0);
+            for (int ti = 0; ti < 4; ++ti) heads[t][ti] = (t == 0 || two_tiles) ? __ballot(type[t] == (1 << ti) && in_piece[t] == 0) : 0ull;
         }
         // Pieces per type as cut from the runs (nat), then after the pieces of 4 and of 2 that
         // would leave a chunk partly filled have been halved into the next smaller type (cnt).
@@ -183,13 +202,24 @@ __device__ __forceinline__ int32_t band_blocks_of(const int32_t* __restrict__ ro
 #pragma unroll
             for (int t = 0; t < 2; ++t) {
                 const int32_t i = cur + t * 64 + lane;
+                // slot of the entry's column inside the band = how many of the band's columns are smaller:
+                // a lower bound over the 64 lanes, six exchanges, every lane takes part
+                int32_t slot = 0;
+                if (t == 0 || two_tiles) {
+#pragma unroll
+                    for (int step = 32; step >= 1; step >>= 1) {
+                        const int32_t probe = __shfl(band_col_of_lane, slot + step - 1, 64);
+                        if (probe < col_of[t]) slot += step;
+                    }
+                }
                 if (i < seg_end) {
                     int T = type[t], u = in_piece[t];
                     const int nti = band_type_index(T);
                     const int32_t h = head[t];
                     int32_t rank;                                 // of the piece among the pieces of its type, in entry order
-                    if (h < 64) rank = __popcll(heads[0][nti] & ((1ull << h) - 1ull));
-                    else rank = __popcll(heads[0][nti]) + __popcll(heads[1][nti] & ((1ull << (h - 64)) - 1ull));
+                    const uint64_t heads0 = band_pick(heads[0], nti), heads1 = band_pick(heads[1], nti);
+                    if (h < 64) rank = __popcll(heads0 & ((1ull << h) - 1ull));
+                    else rank = __popcll(heads0) + __popcll(heads1 & ((1ull << (h - 64)) - 1ull));
                     if (T == 4 && rank >= cnt[2]) {               // halved: two 2s behind the 2s cut from the runs
                         rank = nat[1] + 2 * (rank - cnt[2]) + (u >> 1);
                         u &= 1;
@@ -201,20 +231,11 @@ __device__ __forceinline__ int32_t band_blocks_of(const int32_t* __restrict__ ro
                         T = 1;
                     }
                     const int ti = band_type_index(T), J = band_pieces_per_chunk(T);
-                    uint32_t* ch = blk + off[ti] + (rank / J) * band_chunk_words(T);
+                    uint32_t* ch = blk + band_pick(off, ti) + (rank / J) * band_chunk_words(T);
                     const int j = rank % J;
                     reinterpret_cast<uint8_t*>(ch + band_chunk_rows_at(T))[j * T + u] = (uint8_t)(rows[i] - row0);
                     ch[band_chunk_vals_at(T) + j * T + u] = __float_as_uint(values[i]);
-                    if (u == 0) {
-                        // slot of the column inside the band
-                        const int32_t c = cols[i];
-                        int32_t lo = 0, hi = ncols;
-                        while (lo < hi) {
-                            const int32_t mid = (lo + hi) >> 1;
-                            if (band_cols[mid] < c) lo = mid + 1; else hi = mid;
-                        }
-                        reinterpret_cast<uint16_t*>(ch)[j] = (uint16_t)(lo * 1024);
-                    }
+                    if (u == 0) reinterpret_cast<uint16_t*>(ch)[j] = (uint16_t)(slot * 1024);
                 }
             }
             // unused piece slots of the last chunk of every type
@@ -251,7 +272,7 @@ __device__ __forceinline__ int32_t band_blocks_of(const int32_t* __restrict__ ro
 // (wave v takes b = v, v + 16, ...); prefix sum over the bands; pass 2: the same waves write the
 // blocks.  Dynamic LDS: 2 * (NBmax + 1) words with NBmax = ceil(k / 64).
 // ---------------------------------------------------------------------------------------------
-__global__ __launch_bounds__(kBandBuildThreads) void band_fill(const int32_t* __restrict__ gIdxes, const int32_t* __restrict__ rows,
+__global__ __launch_bounds__(kBandBuildThreads, 8) void band_fill(const int32_t* __restrict__ gIdxes, const int32_t* __restrict__ rows,
                                                               const int32_t* __restrict__ cols, const float* __restrict__ values,
                                                               int32_t p, int64_t g, int64_t k, int32_t W,
                                                               const int32_t* __restrict__ ucols, const int32_t* __restrict__ ucount,
