@@ -60,13 +60,14 @@ typedef struct gcoo_matrix gcoo_matrix;
  * per lane); on MI355X it was the fastest of {4, 8, 16, 32, 64} for that kernel for uniform random
  * matrices of density 0.001 .. 0.5, for a power-law row-length matrix and for a diagonal one.
  * 16 is returned where the workgroup-shared kernel with sixteen waves (GCOO_VARIANT_BAND, groups
- * of at most 16 rows) was measured faster than that: N a multiple of 4, density at most 6 %, at
- * least 192 blocks of 256 rows x 256 columns of C that fill their rounds over the 256 compute
- * units to 80 % or more, and 9000 columns or more at 0.4 % density or more - or 7000 at 0.8 % or
- * more with rounds filled to 90 %.  (Conversion plus product is what was compared; a caller that
- * converts once and multiplies often gains from 16 already from 4000 columns on between 1 % and 6 %.)  Such
- * a caller can do better still by timing a few values (the Python binding has gcoo_tune_p for
- * that).  Pure host arithmetic; 0 for invalid arguments.
+ * of at most 16 rows) was measured faster than that, conversion included: N a multiple of 4,
+ * density at most 6 %, at least 192 blocks of 256 rows x 256 columns of C, and
+ *   9000 columns or more at 0.4 % density or more, the blocks filling their rounds over the 256
+ *     compute units to 80 % or more; or
+ *   7000 columns or more at 0.8 % or more, rounds filled to 90 %; or
+ *   3500 columns or more between 0.9 % and 5 %, rounds filled to 95 %.
+ * A caller that multiplies the same matrix many times can do better by timing a few values (the
+ * Python binding has gcoo_tune_p for that).  Pure host arithmetic; 0 for invalid arguments.
  */
 int32_t gcoo_default_p(int64_t m, int64_t k, int64_t nnz, int64_t N);
 
@@ -164,7 +165,8 @@ int gcoo_spdm(const gcoo_matrix* A, const float* B_dev, int64_t ldb, int64_t N,
  * gcoo_set_band_policy()); needs B, C, ldb, ldc, N multiples of 4 elements (16-byte aligned rows),
  * else GCOO_EINVAL.  gcoo_spdm() picks it where the matrix has that schedule by the automatic
  * rule, the operands are so aligned and C has at least 192 blocks of (256 rows of such groups) x
- * 256 columns */
+ * 256 columns - below 9000 columns of A also only if those blocks fill their rounds over the
+ * 256 compute units to 80 % */
 #define GCOO_VARIANT_BAND 3
 int gcoo_spdm_variant(const gcoo_matrix* A, const float* B_dev, int64_t ldb, int64_t N,
                       float* C_dev, int64_t ldc, void* stream, int variant);

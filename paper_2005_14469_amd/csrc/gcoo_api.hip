@@ -126,12 +126,12 @@ double band_fill_of_rounds(int64_t items)
     return (double)items / (double)(rounds * 256);
 }
 
-// Group height 16 with the band kernel against 32 with the register kernel (same grid of
-// measurements, conversion included: the band schedule costs about as much again as the rest of
-// the conversion): 16 wins from 9000 columns on at 0.4 % density or more, and from 7000 on at
-// 0.8 % or more, where the workgroups fill their rounds.  (The band kernel alone is 1.1x .. 1.2x
-// faster already from 4000 columns on between 1 % and 6 %, but not with its share of the
-// conversion; at 0.1 % the two are level even at 14000 columns.)
+// Group height 16 with the band kernel against 32 with the register kernel, conversion included
+// (whole steps of bench.py, uniform random, n = 4000 .. 14000): 16 wins from 9000 columns on at
+// 0.4 % density or more; from 7000 on at 0.8 % or more (n = 8000: by 15 .. 31 % between 1 % and 5 %);
+// from 3500 on between 0.9 % and 5 % (n = 4000: by 4 .. 20 %) - the two smaller regions only where the
+// workgroups fill their rounds (n = 6000 and 7000, at 75 % and 77 %, lose by up to 10 %).  At 0.5 %
+// and below the two are level or 32 wins up to 8000 columns; at 0.1 % even at 14000.
 bool short_groups_preferred(int64_t m, int64_t k, int64_t nnz, int64_t N)
 {
     if (N % 4 != 0 || N <= 0 || !band_kernel_preferred(m, k, nnz, 16)) return false;
@@ -140,7 +140,8 @@ bool short_groups_preferred(int64_t m, int64_t k, int64_t nnz, int64_t N)
     const double fill = band_fill_of_rounds(items);
     if (items < 192) return false;
     if (k >= 9000 && density >= 0.004) return fill >= 0.8;
-    return k >= 7000 && density >= 0.008 && fill >= 0.9;
+    if (k >= 7000 && density >= 0.008) return fill >= 0.9;
+    return k >= 3500 && density >= 0.009 && density <= 0.05 && fill >= 0.95;
 }
 
 bool band_schedule_wanted(int64_t m, int64_t k, int64_t nnz, int32_t p)
@@ -628,8 +629,11 @@ int gcoo_spdm_pick(const gcoo_matrix* A, const float* B_dev, int64_t ldb, int64_
     int rc = check_spdm_args(A, B_dev, ldb, N, C_dev, ldc);
     if (rc != GCOO_OK) return rc;
     const Shape sh = shape_of(B_dev, ldb, N, C_dev, ldc);
-    // the band kernel wants enough workgroups to occupy the chip: one per 256 rows and 256 columns
-    if (A->band_preferred && sh.al4 && !sh.wide_pitch && A->super_groups() * ((N + 255) / 256) >= 192) return GCOO_VARIANT_BAND;
+    // the band kernel wants enough workgroups to occupy the chip (one per 256 rows and 256 columns), and
+    // below 9000 columns its margin does not survive a last round that is mostly idle
+    const int64_t items = A->super_groups() * ((N + 255) / 256);
+    if (A->band_preferred && sh.al4 && !sh.wide_pitch && items >= 192 && (A->k >= 9000 || band_fill_of_rounds(items) >= 0.8))
+        return GCOO_VARIANT_BAND;
     return sched_width(A->p, sh) ? GCOO_VARIANT_REG : GCOO_VARIANT_LDS;
 }
 

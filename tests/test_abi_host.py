@@ -121,7 +121,7 @@ def test_default_p_rule(L):
     assert dp(8000, 0.995) == 32            # the headline workload: 8000 columns at 0.5 %
     assert dp(8000, 0.98) == 16 and dp(8000, 0.99) == 16
     assert dp(8000, 0.9) == 32              # too dense for the band schedule
-    assert dp(4000, 0.98) == 32 and dp(4000, 0.995) == 32 and dp(6999, 0.98) == 32
+    assert dp(4000, 0.98) == 16 and dp(4000, 0.995) == 32 and dp(4000, 0.94) == 32 and dp(5000, 0.98) == 32
     assert dp(6000, 0.98) == 32             # 24 x 24 blocks fill 2.25 rounds of 256: 75 %
     assert dp(12000, 0.995) == 16 and dp(14000, 0.999) == 32 and dp(10000, 0.996) == 16 and dp(10000, 0.997) == 32
     assert dp(2000, 0.98) == 32
