@@ -272,6 +272,23 @@ def test_band_variant(band_always, m, k, N, p, sparsity):
     assert np.array_equal(c1, c2)
 
 
+@pytest.mark.parametrize("p", [16, 32])
+def test_band_variant_skewed_rows_and_diagonal(band_always, p):
+    """Power-law row lengths (a few groups with thousands of entries in one band: chains of further blocks) and a
+    diagonal matrix (every band of every super-group has exactly one entry per column), both shapes."""
+    w = workloads.zipf_rows(700, 3000, 260, seed=17, row_max=2500)
+    _say(f"band variant, skewed rows p={p} nnz={w.nnz}")
+    assert w.nnz <= 0.06 * w.m * w.k
+    err, A, c1 = _check_product(w, p, binding.VARIANT_BAND)
+    assert err < 2e-6
+    _, _, c2 = _check_product(w, p, binding.VARIANT_BAND, A=A)
+    assert np.array_equal(c1, c2)
+    d = workloads.diagonal(1000, 516, seed=3)
+    _say(f"band variant, diagonal p={p}")
+    err, _, _ = _check_product(d, p, binding.VARIANT_BAND)
+    assert err < 2e-6
+
+
 def test_band_variant_repeated_coordinates_and_strides(band_always):
     from tests.test_band_model import repeated_coordinates_workload
     m, k, N, row_ptr, col_idx, vals, B = repeated_coordinates_workload()
