@@ -66,6 +66,9 @@ typedef struct gcoo_matrix gcoo_matrix;
  *     compute units to 80 % or more; or
  *   7000 columns or more at 0.8 % or more, rounds filled to 90 %; or
  *   3500 columns or more between 0.9 % and 5 %, rounds filled to 95 %.
+ * 38, the tallest group the register kernel holds with four columns per lane (its second
+ * accumulator layout), is returned between 6 % and 12 % density from 5000 columns on (N a multiple
+ * of 4): there most groups touch most columns and fewer, taller groups fetch fewer rows of B.
  * A caller that multiplies the same matrix many times can do better by timing a few values (the
  * Python binding has gcoo_tune_p for that).  Pure host arithmetic; 0 for invalid arguments.
  */
@@ -158,7 +161,9 @@ int gcoo_spdm(const gcoo_matrix* A, const float* B_dev, int64_t ldb, int64_t N,
 #define GCOO_VARIANT_AUTO 0
 #define GCOO_VARIANT_LDS  1  /* partial sums in LDS, reads the five arrays directly; any p, any alignment */
 /* partial sums in VGPRs, reads the run schedule built at conversion; needs p <= 64 and B, C, ldb,
- * ldc, N all even (8-byte aligned rows), else GCOO_EINVAL */
+ * ldc, N all even (8-byte aligned rows), else GCOO_EINVAL.  Four columns per lane for p <= 38 where
+ * the rows are 16-byte aligned (N, ldb, ldc multiples of 4), two otherwise; groups with very many
+ * entries are shared by the waves of a workgroup except for 33 <= p <= 38 */
 #define GCOO_VARIANT_REG  2
 /* the groups of a workgroup (sixteen of at most 16 rows, or eight of 17..32 rows) share the rows of
  * B through LDS; reads the band schedule built at conversion (gcoo_band_words() > 0, see

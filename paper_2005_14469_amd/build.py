@@ -53,6 +53,14 @@ def _compile(src: str) -> str:
     return obj
 
 
+def sched_kernel_names(stem: str):
+    """Mangled name prefixes of the kernels in spdm_sched_v<V>[t].hip (t = the tall accumulator layout)."""
+    v = stem.rsplit("v", 1)[1]
+    if v.endswith("t"):                  # that layout has no workgroup-shared kernel
+        return (f"_ZN4gcoo8acc_tall10spdm_schedILi{v[:-1]}E",)
+    return (f"_ZN4gcoo7acc_std10spdm_schedILi{v}E", f"_ZN4gcoo7acc_std15spdm_sched_coopILi{v}E")
+
+
 def verify_generated_code() -> None:
     """Refuse to link a library whose asm-issued loads are not provably safe.
 
@@ -71,8 +79,7 @@ def verify_generated_code() -> None:
         if stem == "spdm_band":
             verify_band_code(stem, text)
             continue
-        v = stem.rsplit("v", 1)[1]
-        for kernel in (f"_ZN4gcoo10spdm_schedILi{v}E", f"_ZN4gcoo15spdm_sched_coopILi{v}E"):
+        for kernel in sched_kernel_names(stem):
             regs, bad = isa_check.check(text, kernel)
             if not regs:
                 raise RuntimeError(f"{stem}: no asm-issued loads found in {kernel} (check is blind)")

@@ -299,7 +299,16 @@ int gcoo_set_band_policy(int policy)
 int32_t gcoo_default_p(int64_t m, int64_t k, int64_t nnz, int64_t N)
 {
     if (m < 0 || k < 0 || nnz < 0 || N < 0) return 0;
-    return short_groups_preferred(m, k, nnz, N) ? 16 : 32;
+    if (short_groups_preferred(m, k, nnz, N)) return 16;
+    // Between 6 % and 12 % density most groups touch most columns, and what the register kernel
+    // fetches falls with the number of groups: 38 rows (the tall accumulator file) beat 32 by
+    // 8 .. 28 % from 6000 columns on (whole steps, n = 6000 .. 14000, s = 0.9 and 0.93); at 20 % and
+    // more, and at n = 4000, the two are within a few per cent either way.
+    if (m > 0 && k >= 5000 && N % 4 == 0) {
+        const double density = (double)nnz / ((double)m * (double)k);
+        if (density > 0.06 && density <= 0.12) return 38;
+    }
+    return 32;
 }
 
 size_t gcoo_device_bytes(int64_t m, int64_t k, int64_t nnz, int32_t p)
@@ -553,11 +562,14 @@ Shape shape_of(const float* B, int64_t ldb, int64_t N, const float* C, int64_t l
     return s;
 }
 
-// Columns per lane of the register kernel that serves this p and alignment; 0 if none does.
+// Instance of the register kernel that serves this p and alignment: its columns per lane, 0 if
+// none does; kTallInstance for four columns per lane with the tall accumulator file (33 <= p <= 38).
+constexpr int kTallInstance = 38;
 int sched_width(int32_t p, const Shape& sh)
 {
     if (sh.wide_pitch) return 0;
     if (p <= 32 && sh.al4) return 4;
+    if (p <= 38 && sh.al4) return kTallInstance;
     if (p <= 64 && sh.al2) return 2;
     // The one-column-per-lane instance (65 <= p <= 128, or operands aligned to 4 bytes only) is
     // switched off: a run of it on an 8000 x 8000 matrix with p = 128 ended in a GPU memory
@@ -604,6 +616,7 @@ namespace gcoo {
 hipError_t launch_spdm_sched(int V, const SpdmArgs& a, hipStream_t s)
 {
     if (V == 4) return launch_spdm_sched_v4(a, s);
+    if (V == 38) return launch_spdm_sched_v4_tall(a, s);
     if (V == 2) return launch_spdm_sched_v2(a, s);
     if (V == 1) return launch_spdm_sched_v1(a, s);
     return hipErrorInvalidValue;
@@ -671,8 +684,10 @@ int gcoo_spdm_variant(const gcoo_matrix* A, const float* B_dev, int64_t ldb, int
         int rc = launch_build_reg_schedule(A, s);
         if (rc != GCOO_OK) return rc;
     }
+    const int cols_per_lane = V == kTallInstance ? 4 : V;
+    // (heavy groups are shared by a workgroup in the standard instances only)
     gcoo::SpdmArgs a{A->sched_hdr(), A->sched(), A->gIdxes(), A->m, A->p, A->g, A->nw, B_dev, ldb, N, C_dev, ldc,
-                     heavy_group_min(A, (N + 64 * V - 1) / (64 * V), s)};
+                     V == kTallInstance ? INT32_MAX : heavy_group_min(A, (N + 64 * cols_per_lane - 1) / (64 * cols_per_lane), s)};
     hipError_t e = gcoo::launch_spdm_sched(V, a, s);
     if (e != hipSuccess) return hip_fail(e, "spdm_sched launch");
     return GCOO_OK;

@@ -16,7 +16,22 @@
 #include "gcoo_sched.hpp"
 #include "gcoo_spdm_launch.hpp"
 
+// Two layouts of the accumulator file, one per translation unit (everything below is compiled
+// inside an inline namespace named after the layout, so the two sets of kernels do not collide):
+//   standard  v[124:255]: 33 x 4, 65 x 2 or 129 x 1 partial sums (p <= 32 / 64 / 128)
+//   tall      v[100:255]: 39 x 4 partial sums (p <= 38), for which the compiler is left 100 VGPRs
+//             (with fewer it parks values in AGPRs, also ones whose load is still in flight, which
+//             the build's check of the generated code refuses);
+//             taller groups mean fewer fetched B rows per multiply-add where groups are dense
+//             enough to touch most columns (Section 3.3)
+#ifdef GCOO_ACC_TALL
+#define GCOO_ACC_NS acc_tall
+#else
+#define GCOO_ACC_NS acc_std
+#endif
+
 namespace gcoo {
+inline namespace GCOO_ACC_NS {
 
 // ---------------------------------------------------------------------------------------------
 // Accumulator file.  The (p+1) x V partial sums of a lane sit in the fixed VGPR range v[124:255]:
@@ -33,6 +48,53 @@ typedef float f32x32 __attribute__((ext_vector_type(32)));
 typedef float f32x4 __attribute__((ext_vector_type(4)));
 typedef float f32x2 __attribute__((ext_vector_type(2)));
 
+#ifdef GCOO_ACC_TALL
+typedef float f32x16 __attribute__((ext_vector_type(16)));
+typedef float f32x8 __attribute__((ext_vector_type(8)));
+struct AccFile {
+    f32x4 t0;                 // v[100:103]
+    f32x32 t1, t2, t3, t4;    // v[104:135] v[136:167] v[168:199] v[200:231]
+    f32x16 t5;                // v[232:247]
+    f32x8 t6;                 // v[248:255]
+};
+constexpr int kAccFirst = 100;
+
+#define GCOO_ACC_OPERANDS(acc)                                                                                      \
+    "+{v[100:103]}"((acc).t0), "+{v[104:135]}"((acc).t1), "+{v[136:167]}"((acc).t2), "+{v[168:199]}"((acc).t3),   \
+        "+{v[200:231]}"((acc).t4), "+{v[232:247]}"((acc).t5), "+{v[248:255]}"((acc).t6)
+
+template <int V>
+__host__ __device__ constexpr int acc_stride()
+{
+    static_assert(V == 4, "the tall layout exists for four columns per lane only");
+    return 39;
+}
+
+__device__ __forceinline__ void acc_clear(AccFile& acc)
+{
+    acc.t0 = 0.0f; acc.t1 = 0.0f; acc.t2 = 0.0f; acc.t3 = 0.0f; acc.t4 = 0.0f; acc.t5 = 0.0f; acc.t6 = 0.0f;
+}
+
+__device__ __forceinline__ float acc_get(const AccFile& acc, int reg)
+{
+    const int s = reg - kAccFirst;
+    if (s < 4) return acc.t0[s];
+    if (s >= 148) return acc.t6[s - 148];
+    if (s >= 132) return acc.t5[s - 132];
+    const int t = (s - 4) >> 5, i = (s - 4) & 31;
+    return t == 0 ? acc.t1[i] : (t == 1 ? acc.t2[i] : (t == 2 ? acc.t3[i] : acc.t4[i]));
+}
+
+__device__ __forceinline__ void acc_add(AccFile& acc, int reg, float x)
+{
+    const int s = reg - kAccFirst;
+    if (s < 4) { acc.t0[s] += x; return; }
+    if (s >= 148) { acc.t6[s - 148] += x; return; }
+    if (s >= 132) { acc.t5[s - 132] += x; return; }
+    const int t = (s - 4) >> 5, i = (s - 4) & 31;
+    if (t == 0) acc.t1[i] += x; else if (t == 1) acc.t2[i] += x; else if (t == 2) acc.t3[i] += x; else acc.t4[i] += x;
+}
+#else
 struct AccFile {
     f32x4 t0;                 // v[124:127]
     f32x32 t1, t2, t3, t4;    // v[128:159] v[160:191] v[192:223] v[224:255]
@@ -47,6 +109,11 @@ template <int V>
 __host__ __device__ constexpr int acc_stride()
 {
     return V == 4 ? 33 : (V == 2 ? 65 : 129);
+}
+
+__device__ __forceinline__ void acc_clear(AccFile& acc)
+{
+    acc.t0 = 0.0f; acc.t1 = 0.0f; acc.t2 = 0.0f; acc.t3 = 0.0f; acc.t4 = 0.0f;
 }
 
 __device__ __forceinline__ float acc_get(const AccFile& acc, int reg)
@@ -64,9 +131,19 @@ __device__ __forceinline__ void acc_add(AccFile& acc, int reg, float x)
     const int t = (s - 4) >> 5, i = (s - 4) & 31;
     if (t == 0) acc.t1[i] += x; else if (t == 1) acc.t2[i] += x; else if (t == 2) acc.t3[i] += x; else acc.t4[i] += x;
 }
+#endif
 
 // Instruction text.  GCOO_FMA_Vn(i): the V multiply-adds of entry i of a run (operands a<i> =
 // the entry's value, the same in every lane of a VGPR; b0..b3 = the run's B segment).  GCOO_ENT(i) = select row c<i>, then those.
+#ifdef GCOO_ACC_TALL
+// (the one- and two-column texts are parsed but never instantiated in this layout: acc_stride refuses them)
+#define GCOO_FMA_V1(i) "v_fma_f32 v100, %[a" #i "], %[b0], v100\n\t"
+#define GCOO_FMA_V2(i) GCOO_FMA_V1(i) "v_fma_f32 v139, %[a" #i "], %[b1], v139\n\t"
+#define GCOO_FMA_V4(i)                                  \
+    GCOO_FMA_V2(i)                                      \
+    "v_fma_f32 v178, %[a" #i "], %[b2], v178\n\t"        \
+    "v_fma_f32 v217, %[a" #i "], %[b3], v217\n\t"
+#else
 #define GCOO_FMA_V1(i) "v_fma_f32 v124, %[a" #i "], %[b0], v124\n\t"
 #define GCOO_FMA_V2(i) GCOO_FMA_V1(i) "v_fma_f32 v189, %[a" #i "], %[b1], v189\n\t"
 #define GCOO_FMA_V4(i)                                  \
@@ -74,6 +151,7 @@ __device__ __forceinline__ void acc_add(AccFile& acc, int reg, float x)
     "v_fma_f32 v157, %[a" #i "], %[b1], v157\n\t"        \
     "v_fma_f32 v190, %[a" #i "], %[b2], v190\n\t"        \
     "v_fma_f32 v223, %[a" #i "], %[b3], v223\n\t"
+#endif
 #define GCOO_ENT0(FMA) "s_set_gpr_idx_on %[c0], gpr_idx(SRC2,DST)\n\t" FMA(0)
 #define GCOO_ENT(FMA, i) "s_set_gpr_idx_idx %[c" #i "]\n\t" FMA(i)
 #define GCOO_RUN1(FMA) GCOO_ENT0(FMA)
@@ -319,7 +397,7 @@ __global__ __launch_bounds__(64) void spdm_sched(const SchedClass* __restrict__ 
     const uint32_t ldb4 = (uint32_t)ldb * 4u;              // the launcher checks that ldb*4 fits 32 bits
 
     AccFile acc;
-    acc.t0 = 0.0f; acc.t1 = 0.0f; acc.t2 = 0.0f; acc.t3 = 0.0f; acc.t4 = 0.0f;
+    acc_clear(acc);
 
     // the wave's ring of stream lines (one wave per workgroup)
     __shared__ __attribute__((aligned(16))) uint32_t ring_mem[kRing * kLineWords];
@@ -411,7 +489,7 @@ __global__ __launch_bounds__(64 * kCoopWaves) void spdm_sched_coop(const SchedCl
     const uint32_t ldb4 = (uint32_t)ldb * 4u;
 
     AccFile acc;
-    acc.t0 = 0.0f; acc.t1 = 0.0f; acc.t2 = 0.0f; acc.t3 = 0.0f; acc.t4 = 0.0f;
+    acc_clear(acc);
 
     const lds_u32* ring = (const lds_u32*)ring_mem[wv];
     const uint32_t ring_lds = (uint32_t)(uintptr_t)ring;
@@ -491,9 +569,16 @@ hipError_t launch_spdm_sched_instance(const SpdmArgs& a, hipStream_t s)
                                                             a.C, a.ldc, total, a.heavy_min);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess || a.heavy_min == INT32_MAX) return e;
+#ifdef GCOO_ACC_TALL
+    // no workgroup-shared kernel in this layout: with 100 VGPRs it does not fit without spilling
+    // registers whose loads are in flight
+    return hipErrorInvalidValue;
+#else
     spdm_sched_coop<V><<<dim3((unsigned)total), dim3(64 * kCoopWaves), 0, s>>>(a.hdr, a.stream, a.gIdxes, a.m, a.p, a.g, a.nw, a.B,
                                                                               a.ldb, a.N, a.C, a.ldc, total, a.heavy_min);
     return hipGetLastError();
+#endif
 }
 
+}  // inline namespace
 }  // namespace gcoo

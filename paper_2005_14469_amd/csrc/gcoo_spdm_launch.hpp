@@ -25,11 +25,13 @@ struct SpdmArgs {
     int32_t heavy_min;         // groups with this many entries or more go to the workgroup-shared kernel (INT32_MAX: none)
 };
 
-// V = 4 needs p <= 32, V = 2 needs p <= 64, V = 1 needs p <= 128; N, ldb, ldc and both base
-// addresses must be multiples of V elements.  Anything else returns hipErrorInvalidValue.
+// V = 4 needs p <= 32, V = 38 (four columns per lane, tall accumulator file) p <= 38, V = 2 needs
+// p <= 64, V = 1 needs p <= 128; N, ldb, ldc and both base addresses must be multiples of the
+// columns per lane.  Anything else returns hipErrorInvalidValue.
 hipError_t launch_spdm_sched(int V, const SpdmArgs& a, hipStream_t s);
 
 hipError_t launch_spdm_sched_v4(const SpdmArgs& a, hipStream_t s);
+hipError_t launch_spdm_sched_v4_tall(const SpdmArgs& a, hipStream_t s);
 hipError_t launch_spdm_sched_v2(const SpdmArgs& a, hipStream_t s);
 hipError_t launch_spdm_sched_v1(const SpdmArgs& a, hipStream_t s);
 

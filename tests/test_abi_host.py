@@ -120,7 +120,8 @@ def test_default_p_rule(L):
         return L.gcoo_default_p(m, n, int(m * n * (1 - s)), n if N is None else N)
     assert dp(8000, 0.995) == 32            # the headline workload: 8000 columns at 0.5 %
     assert dp(8000, 0.98) == 16 and dp(8000, 0.99) == 16
-    assert dp(8000, 0.9) == 32              # too dense for the band schedule
+    assert dp(8000, 0.9) == 38 and dp(8000, 0.93) == 38 and dp(14000, 0.9) == 38      # 6 .. 12 % dense: the tall register instance
+    assert dp(8000, 0.8) == 32 and dp(4000, 0.9) == 32 and dp(8000, 0.9, N=8002) == 32
     assert dp(4000, 0.98) == 16 and dp(4000, 0.995) == 32 and dp(4000, 0.94) == 32 and dp(5000, 0.98) == 32
     assert dp(6000, 0.98) == 32             # 24 x 24 blocks fill 2.25 rounds of 256: 75 %
     assert dp(12000, 0.995) == 16 and dp(14000, 0.999) == 32 and dp(10000, 0.996) == 16 and dp(10000, 0.997) == 32

@@ -196,7 +196,7 @@ def test_band_schedule_bit_exact_with_repeated_coordinates(band_always):
 
 # ------------------------------------------------------------------ product
 
-@pytest.mark.parametrize("p", [1, 2, 8, 16, 32, 64, 128, 256])
+@pytest.mark.parametrize("p", [1, 2, 8, 16, 32, 33, 38, 39, 64, 128, 256])
 def test_config0_all_variants(p):
     w = workloads.config(0)
     for variant in _variants_for(p, w.N):
@@ -208,6 +208,7 @@ def test_config0_all_variants(p):
 @pytest.mark.parametrize("m,k,N,p", [
     (1, 1, 1, 1), (5, 7, 3, 2), (33, 65, 64, 32), (100, 90, 260, 32), (129, 257, 516, 64),
     (300, 200, 1028, 16), (77, 500, 250, 128), (64, 64, 4, 8), (130, 40, 1000, 20), (513, 100, 768, 32),
+    (400, 300, 516, 38), (77, 90, 260, 36), (1000, 2000, 256, 38),
 ])
 def test_ragged_shapes_all_variants(m, k, N, p):
     w = workloads.uniform_random(m, k, N, 0.8, seed=m * 1000 + N)
@@ -409,31 +410,34 @@ def test_mid_size_configs_full_check(index, p):
 
 @pytest.mark.parametrize("index", [2, 3])
 def test_full_size_configs_sampled_rows(index):
-    """8000^2 at s=0.9 and s=0.995 in the launch configuration the benchmark times (p=32, automatic
-    variant); the oracle recomputes a sample of row bands: the first, the last (ragged tile
-    columns are in every row) and random ones."""
+    """8000^2 at s=0.9 and s=0.995 in the launch configuration the benchmark times (group height from
+    gcoo_default_p: 38 and 32, automatic variant); the oracle recomputes a sample of row bands: the first,
+    the last (ragged tile columns are in every row) and random ones."""
     w = workloads.config(index)
-    _say(f"config{index} nnz={w.nnz}")
-    A = binding.gcoo_from_csr(w.m, w.k, w.row_ptr, w.col_idx, w.vals, 32, device=DEV)
+    p = binding.gcoo_default_p(w.m, w.k, w.nnz, w.N)
+    assert p == (38 if index == 2 else 32)
+    _say(f"config{index} nnz={w.nnz} p={p}")
+    A = binding.gcoo_from_csr(w.m, w.k, w.row_ptr, w.col_idx, w.vals, p, device=DEV)
     G = A.export()
+    g = A.info()["g"]
     assert int(G["gIdxes"][-1]) == w.nnz and int(G["nnzPerGroup"].sum()) == w.nnz
     # conversion at full size: group q is the CSR range of its rows, sorted by (col,row)
     rng = np.random.default_rng(index)
-    for q in [0, A.info()["g"] - 1] + rng.integers(0, A.info()["g"], 6).tolist():
-        r0, r1 = q * 32, min(q * 32 + 32, w.m)
+    for q in [0, g - 1] + rng.integers(0, g, 6).tolist():
+        r0, r1 = q * p, min(q * p + p, w.m)
         sub = orc.gcoo_from_csr(r1 - r0, w.k, w.row_ptr[r0:r1 + 1] - w.row_ptr[r0],
-                                w.col_idx[w.row_ptr[r0]:w.row_ptr[r1]], w.vals[w.row_ptr[r0]:w.row_ptr[r1]], 32)
+                                w.col_idx[w.row_ptr[r0]:w.row_ptr[r1]], w.vals[w.row_ptr[r0]:w.row_ptr[r1]], p)
         s, e = int(G["gIdxes"][q]), int(G["gIdxes"][q + 1])
         assert np.array_equal(G["cols"][s:e], sub.cols) and np.array_equal(G["rows"][s:e], sub.rows + r0)
         assert np.array_equal(G["values"][s:e].view(np.uint32), sub.values.view(np.uint32))
     Bt = torch.from_numpy(w.B).to(DEV)
     Cg = torch.full((w.m, w.N), float("nan"), dtype=torch.float32, device=DEV)
+    assert binding.gcoo_spdm_pick(A, Bt, Cg) == binding.VARIANT_REG
     binding.gcoo_spdm(A, Bt, Cg)
     torch.cuda.synchronize()
     assert not torch.isnan(Cg).any()
-    bands = [0, (w.m - 1) // 32] + rng.integers(0, (w.m + 31) // 32, 6).tolist()
-    for q in bands:
-        r0, r1 = q * 32, min(q * 32 + 32, w.m)
+    for q in [0, g - 1] + rng.integers(0, g, 6).tolist():
+        r0, r1 = q * p, min(q * p + p, w.m)
         C64, D64 = orc.spdm_csr(w.k, w.N, w.row_ptr, w.col_idx, w.vals, w.B, r0, r1)
         err, bad = orc.max_scaled_error(Cg[r0:r1].cpu().numpy(), C64, D64)
         assert bad == 0 and err <= TOL, (q, err, bad)

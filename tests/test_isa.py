@@ -17,7 +17,14 @@ CSRC = build.CSRC
 ROOT = build.ROOT
 
 
-def _compile(v: int) -> str:
+INSTANCES = ("4", "4t", "2", "1")        # columns per lane; t = the tall accumulator file
+
+
+def _kernels(v: str):
+    return build.sched_kernel_names(f"spdm_sched_v{v}")
+
+
+def _compile(v: str) -> str:
     src = os.path.join(CSRC, f"spdm_sched_v{v}.hip")
     out = os.path.join(tempfile.mkdtemp(prefix="gcoo_isa_"), f"v{v}.s")
     subprocess.check_call(["hipcc", *build.FLAGS, "-I", os.path.join(ROOT, "include"), "-I", CSRC, "-S",
@@ -27,19 +34,20 @@ def _compile(v: int) -> str:
 
 @pytest.fixture(scope="module")
 def asm():
-    with ThreadPoolExecutor(max_workers=3) as ex:
-        texts = list(ex.map(_compile, (4, 2, 1)))
-    return dict(zip((4, 2, 1), texts))
+    with ThreadPoolExecutor(max_workers=4) as ex:
+        texts = list(ex.map(_compile, INSTANCES))
+    return dict(zip(INSTANCES, texts))
 
 
-@pytest.mark.parametrize("v", [4, 2, 1])
+@pytest.mark.parametrize("v", INSTANCES)
 def test_no_compiler_instruction_touches_a_register_with_a_load_in_flight(asm, v):
-    regs, bad = isa_check.check(asm[v], f"_ZN4gcoo10spdm_schedILi{v}E")
-    assert len(regs) >= 4 * v          # the check found the asm loads
-    assert not bad, bad[:10]
+    for kernel in _kernels(v):
+        regs, bad = isa_check.check(asm[v], kernel)
+        assert len(regs) >= 4 * int(v.rstrip("t"))          # the check found the asm loads
+        assert not bad, bad[:10]
 
 
-@pytest.mark.parametrize("v", [4, 2, 1])
+@pytest.mark.parametrize("v", INSTANCES)
 def test_no_scratch_and_two_waves_per_simd(asm, v):
     text = asm[v]
     meta = text[text.index("amdhsa.kernels"):]
@@ -53,22 +61,23 @@ def test_no_scratch_and_two_waves_per_simd(asm, v):
 def test_checker_sees_a_planted_violation(asm):
     """The checker itself: a compiler-style copy out of a load destination, planted right after the
     first asm load, must be reported."""
-    text = asm[4]
-    regs, bad = isa_check.check(text, "_ZN4gcoo10spdm_schedILi4E")
+    text = asm["4"]
+    K = _kernels("4")[0]
+    regs, bad = isa_check.check(text, K)
     assert not bad
     first = text.index("global_load_dwordx4")
     dst = int(re.match(r"global_load_dwordx4 v\[(\d+):", text[first:]).group(1))
     end_asm = text.index("#ASMEND", first)
     eol = text.index("\n", end_asm)
     planted = text[:eol + 1] + f"\tv_mov_b32_e32 v0, v{dst}\n" + text[eol + 1:]
-    _, bad2 = isa_check.check(planted, "_ZN4gcoo10spdm_schedILi4E")
+    _, bad2 = isa_check.check(planted, K)
     assert bad2
     # a wait that lets one load too many stay in flight is seen as well
     waits = sorted({int(n) for n in re.findall(r"s_waitcnt vmcnt\((\d+)\)", text)})
     assert len(waits) >= 3
     n = waits[-1]
     loosened = text.replace(f"s_waitcnt vmcnt({n})", f"s_waitcnt vmcnt({n + 1})")
-    _, bad3 = isa_check.check(loosened, "_ZN4gcoo10spdm_schedILi4E")
+    _, bad3 = isa_check.check(loosened, K)
     assert bad3
 
 
