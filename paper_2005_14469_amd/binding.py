@@ -268,7 +268,7 @@ def gcoo_default_p(m: int, k: int, nnz: int, N: int) -> int:
     return int(lib().gcoo_default_p(m, k, nnz, N))
 
 
-def gcoo_tune_p(m: int, k: int, row_ptr, col_idx, vals, B: torch.Tensor, candidates=(8, 16, 32, 64), reps: int = 5,
+def gcoo_tune_p(m: int, k: int, row_ptr, col_idx, vals, B: torch.Tensor, candidates=(8, 16, 32, 38, 64), reps: int = 5,
                 include_conversion: bool = False):
     """Times conversion + product for each group height and returns (best p, {p: ms}).
 
