@@ -122,10 +122,16 @@ __global__ __launch_bounds__(kSortWaves * kWave) void sort_groups_by_col_digit(
 {
     __shared__ int32_t slot_of[kSortWaves][256];      // counts, then running slots, per wave and digit
     __shared__ int32_t total[256];
+    __shared__ int32_t rp_s[FIRST ? 257 : 1];         // FIRST: row_ptr of the group's rows (at most 256 + 1), searched per entry
     const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
     const int64_t q = blockIdx.x;
     const int32_t beg = gIdxes[q], end = gIdxes[q + 1];
     if (beg >= end) return;
+    if (FIRST) {
+        const int64_t r_lo = q * p;
+        const int64_t r_hi = (r_lo + p < m) ? r_lo + p : m;
+        if (tid <= r_hi - r_lo) rp_s[tid] = row_ptr[r_lo + tid];     // p + 1 <= 257 <= threads; the barriers below publish it
+    }
     // part of wave wv: whole 64-entry tiles
     const int32_t tiles = (end - beg + kWave - 1) / kWave;
     const int32_t tiles_per = (tiles + kSortWaves - 1) / kSortWaves;
@@ -183,12 +189,12 @@ __global__ __launch_bounds__(kSortWaves * kWave) void sort_groups_by_col_digit(
             val = src_vals[e];
             if (FIRST) {
                 // row r with row_ptr[r] <= e < row_ptr[r+1]; empty rows are skipped by the upper bound
-                int64_t lo = r_lo, hi = r_hi;          // answer in [lo, hi)
+                int32_t lo = 0, hi = (int32_t)(r_hi - r_lo);      // answer in [lo, hi), relative to the group's first row
                 while (hi - lo > 1) {
-                    const int64_t mid = (lo + hi) >> 1;
-                    if (row_ptr[mid] <= e) lo = mid; else hi = mid;
+                    const int32_t mid = (lo + hi) >> 1;
+                    if (rp_s[mid] <= e) lo = mid; else hi = mid;
                 }
-                row = (int32_t)lo;
+                row = (int32_t)r_lo + lo;
             } else {
                 row = src_rows[e];
             }
