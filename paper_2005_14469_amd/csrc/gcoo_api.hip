@@ -416,17 +416,25 @@ int from_csr(int64_t m, int64_t k, const int32_t* row_ptr, const int32_t* col_id
         int32_t* tmp_r = reinterpret_cast<int32_t*>(base + L.tmp_rows);
         float* tmp_v = reinterpret_cast<float*>(base + L.tmp_vals);
         const int32_t* src_c = d_cols; const int32_t* src_r = nullptr; const float* src_v = d_vals;
+        // Two passes and large groups: high digit first, then the low digit bucket by bucket (see the
+        // kernel); otherwise low digit first, whole groups.
+        const int64_t buckets = (k + 255) / 256;
+        const bool high_first = passes == 2 && nnz / g >= 8192 && g * buckets <= 0x7fffffffLL;
         for (int pass = 0; pass < passes; ++pass) {
             const bool to_final = ((passes - 1 - pass) % 2) == 0;
             int32_t* dc = to_final ? fin_c : tmp_c;
             int32_t* dr = to_final ? fin_r : tmp_r;
             float* dv = to_final ? fin_v : tmp_v;
+            const int shift = high_first ? 8 * (1 - pass) : 8 * pass;
             if (pass == 0)
                 gcoo::sort_groups_by_col_digit<true><<<dim3((unsigned)g), dim3(gcoo::kSortWaves * gcoo::kWave), 0, s>>>(
-                    h->gIdxes(), d_row_ptr, m, p, src_c, src_r, src_v, dc, dr, dv, 8 * pass);
+                    h->gIdxes(), d_row_ptr, m, p, src_c, src_r, src_v, dc, dr, dv, shift, 0);
+            else if (high_first)
+                gcoo::sort_groups_by_col_digit<false><<<dim3((unsigned)(g * buckets)), dim3(gcoo::kSortWaves * gcoo::kWave), 0, s>>>(
+                    h->gIdxes(), d_row_ptr, m, p, src_c, src_r, src_v, dc, dr, dv, shift, (int32_t)buckets);
             else
                 gcoo::sort_groups_by_col_digit<false><<<dim3((unsigned)g), dim3(gcoo::kSortWaves * gcoo::kWave), 0, s>>>(
-                    h->gIdxes(), d_row_ptr, m, p, src_c, src_r, src_v, dc, dr, dv, 8 * pass);
+                    h->gIdxes(), d_row_ptr, m, p, src_c, src_r, src_v, dc, dr, dv, shift, 0);
             hipError_t e = hipGetLastError();
             if (e != hipSuccess) { delete h; return hip_fail(e, "sort_groups_by_col_digit"); }
             src_c = dc; src_r = dr; src_v = dv;

@@ -111,6 +111,14 @@ __device__ __forceinline__ uint64_t match_digit(uint32_t d, bool is_active)
 //
 // FIRST: the source is the CSR input itself (row of an entry = search in row_ptr); otherwise the
 // source is the (cols, rows, values) triple written by the previous pass.
+//
+// nb > 0: the workgroup sorts one bucket of one group instead of a whole group.  The pass before
+// it has sorted the group by the digit above (col >> 8, nb values); bucket b of group q is the
+// stretch of the group with that digit equal to b, found by two binary searches, and it is sorted
+// in place (inside its own stretch of the destination) by the low digit.  High digit first keeps
+// the stores of both passes close together: consecutive entries of a CSR row fall into the same
+// bucket in the first pass, and a bucket's stretch is a few kilobytes in the second, where the
+// low digit first scatters every store of both passes over the whole group.
 // ---------------------------------------------------------------------------------------------
 constexpr int kSortWaves = 16;
 
@@ -118,15 +126,32 @@ template <bool FIRST>
 __global__ __launch_bounds__(kSortWaves * kWave) void sort_groups_by_col_digit(
     const int32_t* __restrict__ gIdxes, const int32_t* __restrict__ row_ptr, int64_t m, int32_t p,
     const int32_t* __restrict__ src_cols, const int32_t* __restrict__ src_rows, const float* __restrict__ src_vals,
-    int32_t* __restrict__ dst_cols, int32_t* __restrict__ dst_rows, float* __restrict__ dst_vals, int shift)
+    int32_t* __restrict__ dst_cols, int32_t* __restrict__ dst_rows, float* __restrict__ dst_vals, int shift, int32_t nb)
 {
     __shared__ int32_t slot_of[kSortWaves][256];      // counts, then running slots, per wave and digit
     __shared__ int32_t total[256];
     __shared__ int32_t rp_s[FIRST ? 257 : 1];         // FIRST: row_ptr of the group's rows (at most 256 + 1), searched per entry
+    __shared__ int32_t range_s[2];
     const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
-    const int64_t q = blockIdx.x;
-    const int32_t beg = gIdxes[q], end = gIdxes[q + 1];
+    const int64_t q = nb > 0 ? blockIdx.x / nb : blockIdx.x;
+    int32_t beg = gIdxes[q], end = gIdxes[q + 1];
     if (beg >= end) return;
+    if (nb > 0) {
+        // threads 0 and 1: first entry of the group whose high digit is >= b, and >= b + 1
+        if (tid < 2) {
+            const int32_t want = (int32_t)(blockIdx.x - q * nb) + tid;
+            int32_t lo = beg, hi = end;
+            while (lo < hi) {
+                const int32_t mid = lo + (hi - lo) / 2;
+                if ((src_cols[mid] >> 8) < want) lo = mid + 1; else hi = mid;
+            }
+            range_s[tid] = lo;
+        }
+        __syncthreads();
+        beg = range_s[0];
+        end = range_s[1];
+        if (beg >= end) return;                      // the whole workgroup
+    }
     if (FIRST) {
         const int64_t r_lo = q * p;
         const int64_t r_hi = (r_lo + p < m) ? r_lo + p : m;
