@@ -427,13 +427,13 @@ int from_csr(int64_t m, int64_t k, const int32_t* row_ptr, const int32_t* col_id
             float* dv = to_final ? fin_v : tmp_v;
             const int shift = high_first ? 8 * (1 - pass) : 8 * pass;
             if (pass == 0)
-                gcoo::sort_groups_by_col_digit<true><<<dim3((unsigned)g), dim3(gcoo::kSortWaves * gcoo::kWave), 0, s>>>(
+                gcoo::sort_groups_by_col_digit<true, gcoo::kSortWaves><<<dim3((unsigned)g), dim3(gcoo::kSortWaves * gcoo::kWave), 0, s>>>(
                     h->gIdxes(), d_row_ptr, m, p, src_c, src_r, src_v, dc, dr, dv, shift, 0);
             else if (high_first)
-                gcoo::sort_groups_by_col_digit<false><<<dim3((unsigned)(g * buckets)), dim3(gcoo::kSortWaves * gcoo::kWave), 0, s>>>(
+                gcoo::sort_groups_by_col_digit<false, gcoo::kSortBucketWaves><<<dim3((unsigned)(g * buckets)), dim3(gcoo::kSortBucketWaves * gcoo::kWave), 0, s>>>(
                     h->gIdxes(), d_row_ptr, m, p, src_c, src_r, src_v, dc, dr, dv, shift, (int32_t)buckets);
             else
-                gcoo::sort_groups_by_col_digit<false><<<dim3((unsigned)g), dim3(gcoo::kSortWaves * gcoo::kWave), 0, s>>>(
+                gcoo::sort_groups_by_col_digit<false, gcoo::kSortWaves><<<dim3((unsigned)g), dim3(gcoo::kSortWaves * gcoo::kWave), 0, s>>>(
                     h->gIdxes(), d_row_ptr, m, p, src_c, src_r, src_v, dc, dr, dv, shift, 0);
             hipError_t e = hipGetLastError();
             if (e != hipSuccess) { delete h; return hip_fail(e, "sort_groups_by_col_digit"); }

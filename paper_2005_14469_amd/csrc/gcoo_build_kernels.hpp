@@ -120,15 +120,16 @@ __device__ __forceinline__ uint64_t match_digit(uint32_t d, bool is_active)
 // bucket in the first pass, and a bucket's stretch is a few kilobytes in the second, where the
 // low digit first scatters every store of both passes over the whole group.
 // ---------------------------------------------------------------------------------------------
-constexpr int kSortWaves = 16;
+constexpr int kSortWaves = 16;          // waves of the workgroup that sorts a whole group
+constexpr int kSortBucketWaves = 4;     // and of the one that sorts one bucket of a group (about a thousand entries)
 
-template <bool FIRST>
-__global__ __launch_bounds__(kSortWaves * kWave) void sort_groups_by_col_digit(
+template <bool FIRST, int WAVES>
+__global__ __launch_bounds__(WAVES * kWave) void sort_groups_by_col_digit(
     const int32_t* __restrict__ gIdxes, const int32_t* __restrict__ row_ptr, int64_t m, int32_t p,
     const int32_t* __restrict__ src_cols, const int32_t* __restrict__ src_rows, const float* __restrict__ src_vals,
     int32_t* __restrict__ dst_cols, int32_t* __restrict__ dst_rows, float* __restrict__ dst_vals, int shift, int32_t nb)
 {
-    __shared__ int32_t slot_of[kSortWaves][256];      // counts, then running slots, per wave and digit
+    __shared__ int32_t slot_of[WAVES][256];      // counts, then running slots, per wave and digit
     __shared__ int32_t total[256];
     __shared__ int32_t rp_s[FIRST ? 257 : 1];         // FIRST: row_ptr of the group's rows (at most 256 + 1), searched per entry
     __shared__ int32_t range_s[2];
@@ -155,22 +156,23 @@ __global__ __launch_bounds__(kSortWaves * kWave) void sort_groups_by_col_digit(
     if (FIRST) {
         const int64_t r_lo = q * p;
         const int64_t r_hi = (r_lo + p < m) ? r_lo + p : m;
-        if (tid <= r_hi - r_lo) rp_s[tid] = row_ptr[r_lo + tid];     // p + 1 <= 257 <= threads; the barriers below publish it
+        static_assert(!FIRST || WAVES * kWave >= 257, "one thread per row of the group, and one more");
+        if (tid <= r_hi - r_lo) rp_s[tid] = row_ptr[r_lo + tid];     // the barriers below publish it
     }
     // part of wave wv: whole 64-entry tiles
     const int32_t tiles = (end - beg + kWave - 1) / kWave;
-    const int32_t tiles_per = (tiles + kSortWaves - 1) / kSortWaves;
+    const int32_t tiles_per = (tiles + WAVES - 1) / WAVES;
     const int32_t pb = beg + wv * tiles_per * kWave;
     const int32_t pe = (pb + tiles_per * kWave < end) ? pb + tiles_per * kWave : end;
 
-    for (int i = tid; i < kSortWaves * 256; i += kSortWaves * kWave) (&slot_of[0][0])[i] = 0;
+    for (int i = tid; i < WAVES * 256; i += WAVES * kWave) (&slot_of[0][0])[i] = 0;
     __syncthreads();
     for (int32_t e = pb + lane; e < pe; e += kWave)
         atomicAdd(&slot_of[wv][((uint32_t)src_cols[e] >> shift) & 255u], 1);   // counts only: order-free
     __syncthreads();
     if (tid < 256) {
         int32_t run = 0;
-        for (int w = 0; w < kSortWaves; ++w) {
+        for (int w = 0; w < WAVES; ++w) {
             const int32_t c = slot_of[w][tid];
             slot_of[w][tid] = run;
             run += c;
@@ -195,7 +197,7 @@ __global__ __launch_bounds__(kSortWaves * kWave) void sort_groups_by_col_digit(
         total[4 * lane + 3] = ex + c0 + c1 + c2;
     }
     __syncthreads();
-    for (int i = tid; i < kSortWaves * 256; i += kSortWaves * kWave) (&slot_of[0][0])[i] += total[i & 255];
+    for (int i = tid; i < WAVES * 256; i += WAVES * kWave) (&slot_of[0][0])[i] += total[i & 255];
     __syncthreads();
 
     // From here on the waves do not meet again: a wave's LDS operations execute in order, and the
