@@ -419,7 +419,7 @@ int from_csr(int64_t m, int64_t k, const int32_t* row_ptr, const int32_t* col_id
         // Two passes and large groups: high digit first, then the low digit bucket by bucket (see the
         // kernel); otherwise low digit first, whole groups.
         const int64_t buckets = (k + 255) / 256;
-        const bool high_first = passes == 2 && nnz / g >= 16384 && g * buckets <= 0x7fffffffLL;
+        const bool high_first = passes == 2 && nnz / g >= 6000 && g * buckets <= 0x7fffffffLL;
         for (int pass = 0; pass < passes; ++pass) {
             const bool to_final = ((passes - 1 - pass) % 2) == 0;
             int32_t* dc = to_final ? fin_c : tmp_c;
