@@ -60,11 +60,7 @@ constexpr int64_t kWindowCols = 2048;
 
 void pick_windows(int64_t k, int64_t g, int32_t* nw, int32_t* window_cols)
 {
-    int64_t wc = kWindowCols;
-    if (const char* e = std::getenv("GCOO_WINDOW_COLS")) {
-        const long v = std::atol(e);
-        if (v >= 64) wc = v;
-    }
+    const int64_t wc = kWindowCols;
     int64_t n = (k + wc - 1) / wc;
     const int64_t cap_groups = g > 0 ? (int64_t(1) << 22) / g : gcoo::kMaxWindows;
     int64_t cap = gcoo::kMaxWindows;
