@@ -26,8 +26,8 @@ ROOT = os.path.dirname(os.path.abspath(__file__))
 if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
-KERNEL_NAMES = {1: "gcoo::spdm_lds", 2: "gcoo::spdm_sched", 3: "gcoo::spdm_band"}
-KERNEL_FILES = {1: "spdm_lds", 2: "spdm_sched", 3: "spdm_band"}
+KERNEL_NAMES = {1: "gcoo::spdm_lds", 2: "gcoo::spdm_sched", 3: "gcoo::spdm_share"}
+KERNEL_FILES = {1: "spdm_lds", 2: "spdm_sched", 3: "spdm_share"}
 HBM_PEAK_GBS = 8000.0          # MI355X HBM3E, published
 FP32_VECTOR_PEAK_TF = 157.3    # published (packed fp32); plain v_fma_f32 reaches half of it
 
@@ -41,7 +41,7 @@ def parse():
                     help="config0..config4 (the five named workloads; config3 = 8000^2, sparsity 0.995), or "
                          "uniform_<n>_<sparsity> for a square uniform random A with N = n")
     ap.add_argument("--p", type=int, default=0, help="group height; 0 = library default for the workload")
-    ap.add_argument("--variant", type=int, default=0, help="0 auto, 1 partial sums in LDS, 2 partial sums in registers")
+    ap.add_argument("--variant", type=int, default=0, help="0 auto, 1 partial sums in LDS, 2 partial sums in registers, 3 the same with the rows of B shared through LDS by the eight groups of a workgroup")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle timing")
     ap.add_argument("--no-dense", action="store_true", help="skip the dense SGEMM timing")
     ap.add_argument("--secondary", default="config2", help="second workload reported in the same line ('' = none)")
@@ -154,9 +154,14 @@ def cpu_baseline(w, p, budget_flops=1.2e11):
                        f"product {1e3 * (t2 - t1):.0f} ms, fp64 sums, OpenMP over rows")
 
 
+def traffic_file(kernel: str, workload: str) -> str:
+    return os.path.join("profiles", f"{kernel}_{workload}_pmc.txt")
+
+
 def read_traffic(kernel: str, workload: str):
-    """HBM bytes per launch from the committed rocprofv3 --pmc summary, if there is one."""
-    path = os.path.join(ROOT, "profiles", f"{kernel}_{workload}_pmc.txt")
+    """HBM bytes per launch from the committed rocprofv3 --pmc summary of this kernel on this workload, if there
+    is one (the counters cannot be read from inside this run: the line names the file in traffic_source)."""
+    path = os.path.join(ROOT, traffic_file(kernel, workload))
     if not os.path.exists(path):
         return None
     vals = {}
@@ -397,6 +402,9 @@ def main():
                  "convert_ms": head["convert_ms"], "frac_of_fp32_vector_peak": head["valu_frac_of_published"]},
         "roofline": {"bound": "hbm", "achieved": head["hbm_gbs"], "peak": HBM_PEAK_GBS, "unit": "GB/s",
                      "frac": head["hbm_frac"], "traffic": read_traffic(KERNEL_FILES.get(head["variant"], "spdm_sched"), args.workload),
+                     "traffic_source": (traffic_file(KERNEL_FILES.get(head["variant"], "spdm_sched"), args.workload)
+                                        if read_traffic(KERNEL_FILES.get(head["variant"], "spdm_sched"), args.workload) is not None
+                                        else None),
                      "kernel": KERNEL_NAMES.get(head["variant"], "?"), "algorithmic_bytes_per_launch": head["alg_bytes"]},
     }
     if not args.no_dense:

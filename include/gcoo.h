@@ -26,8 +26,14 @@
  *
  * Errors.  Every function returning int returns GCOO_OK (0) or a negative gcoo_status.  On error
  * no handle is produced and C is not written by the failing call.  No C++ exception crosses
- * this boundary.  Functions are safe to call from several host threads on distinct handles;
- * one handle may be read by concurrent gcoo_spdm() calls.
+ * this boundary.
+ *
+ * Threads.  A handle is complete when its gcoo_from_* call returns and is never modified afterwards:
+ * gcoo_spdm*, gcoo_info and gcoo_export* only read it, so any number of host threads may use one
+ * handle at once, on any streams (each caller orders its own streams behind the conversion).
+ * Distinct handles are independent.  gcoo_free() must not run while another call still uses the
+ * handle.  The process-wide setting gcoo_set_share_policy() is the one function that is not
+ * thread-safe.
  */
 #ifndef GCOO_H
 #define GCOO_H
@@ -59,13 +65,11 @@ typedef struct gcoo_matrix gcoo_matrix;
  * 32 is the tallest group the widest instance of the register kernel holds (32 rows x 4 columns
  * per lane); on MI355X it was the fastest of {4, 8, 16, 32, 64} for that kernel for uniform random
  * matrices of density 0.001 .. 0.5, for a power-law row-length matrix and for a diagonal one.
- * 16 is returned where the workgroup-shared kernel with sixteen waves (GCOO_VARIANT_BAND, groups
- * of at most 16 rows) was measured faster than that, conversion included: N a multiple of 4,
- * density at most 6 %, at least 192 blocks of 256 rows x 256 columns of C, and
- *   9000 columns or more at 0.4 % density or more, the blocks filling their rounds over the 256
- *     compute units to 80 % or more; or
- *   7000 columns or more at 0.8 % or more, rounds filled to 90 %; or
- *   3500 columns or more between 0.9 % and 5 %, rounds filled to 95 %.
+ * Where gcoo_spdm() will run the workgroup-shared kernel (GCOO_VARIANT_SHARE: N a multiple of 4,
+ * density at most 6 %, and 7000 columns or more, or 3500 at 0.8 % density or more), a height between
+ * 24 and 48 is returned that makes the workgroups of that kernel (one per 8p rows x 256 columns of C)
+ * fill whole rounds over the 256 compute units: the p that minimises
+ * ceil(workgroups / 256) x (p + 24).
  * 38, the tallest group the register kernel holds with four columns per lane (its second
  * accumulator layout), is returned between 6 % and 12 % density from 5000 columns on (N a multiple
  * of 4): there most groups touch most columns and fewer, taller groups fetch fewer rows of B.
@@ -77,9 +81,10 @@ int32_t gcoo_default_p(int64_t m, int64_t k, int64_t nnz, int64_t N);
 /*
  * Device bytes a gcoo_from_csr() / gcoo_from_dense() call needs in dev_buf for an m x k matrix
  * with nnz stored entries and group height p: the five arrays of Section 3.1 (Table 1:
- * 3*nnz + 2*g elements, plus one sentinel), the run schedule derived from them for the register
- * kernel (at most 3*nnz + 2048*g + 128 words) and the scratch space the conversion kernels use.
- * Returns 0 for invalid arguments.  Pure host arithmetic.
+ * 3*nnz + 2*g elements, plus one sentinel), the kernel-private schedules derived from them (the run
+ * schedule of the register kernel, at most 3*nnz + 2048*g + 128 words; where gcoo_set_share_policy()
+ * asks for it the share schedule of the workgroup-shared kernel) and the scratch space the
+ * conversion kernels use.  Returns 0 for invalid arguments.  Pure host arithmetic.
  */
 size_t gcoo_device_bytes(int64_t m, int64_t k, int64_t nnz, int32_t p);
 
@@ -108,9 +113,9 @@ int gcoo_from_csr(int64_t m, int64_t k,
  * gcoo_from_csr() for a CSR matrix that is already on the device, by a caller who knows nnz (the
  * one who sized dev_buf with it).  Nothing is read back: the call only launches kernels on `stream`
  * and returns.  row_ptr_dev[m] must equal nnz; if it does not, the result is unspecified but every
- * kernel stays inside the arrays (offsets are clamped to nnz).  A later gcoo_spdm() of few work
- * items (at most 4096 group x column-tile pairs) synchronises `stream` once, to learn the size
- * of the largest group.
+ * kernel stays inside the arrays (offsets are clamped to nnz).  Columns are not validated for
+ * device input, but a column outside [0, k) is stored clamped into that range, so that no
+ * kernel reads outside B; gcoo_export() reports GCOO_EBOUNDS for such a matrix.
  */
 int gcoo_from_csr_device(int64_t m, int64_t k, int64_t nnz,
                          const int32_t* row_ptr_dev, const int32_t* col_idx_dev, const float* vals_dev,
@@ -143,11 +148,9 @@ int gcoo_from_dense(int64_t m, int64_t k, const float* A_dev, int64_t lda, int32
  * that no stored entry touches does not reach C).  The summation order inside one element of C
  * is fixed by the matrix, p and the kernel variant, never by timing: results are the same bits
  * from run to run.
- * Asynchronous on `stream`; allocates nothing; N = 0 or m = 0 is a no-op success.
- * A matrix whose automatic kernel is the band kernel (see gcoo_set_band_policy) is converted
- * without the register kernel's schedule; the first call that runs the register kernel on it
- * after all builds that schedule first, on the same stream.  Calls on one handle from several
- * host threads at once are not supported.
+ * Asynchronous on `stream`: the call launches kernels and returns, it never waits for the device,
+ * copies nothing back and allocates nothing, so it may be recorded into a stream capture.
+ * N = 0 or m = 0 is a no-op success.  The handle is only read.
  */
 int gcoo_spdm(const gcoo_matrix* A, const float* B_dev, int64_t ldb, int64_t N,
               float* C_dev, int64_t ldc, void* stream);
@@ -165,29 +168,20 @@ int gcoo_spdm(const gcoo_matrix* A, const float* B_dev, int64_t ldb, int64_t N,
  * the rows are 16-byte aligned (N, ldb, ldc multiples of 4), two otherwise; groups with very many
  * entries are shared by the waves of a workgroup except for 33 <= p <= 38 */
 #define GCOO_VARIANT_REG  2
-/* the groups of a workgroup (sixteen of at most 16 rows, or eight of 17..32 rows) share the rows of
- * B through LDS; reads the band schedule built at conversion (gcoo_band_words() > 0, see
- * gcoo_set_band_policy()); needs B, C, ldb, ldc, N multiples of 4 elements (16-byte aligned rows),
- * else GCOO_EINVAL.  gcoo_spdm() picks it where the matrix has that schedule by the automatic
- * rule, the operands are so aligned and C has at least 192 blocks of (256 rows of such groups) x
- * 256 columns - below 9000 columns of A also only if those blocks fill their rounds over the
- * 256 compute units to 80 % */
-#define GCOO_VARIANT_BAND 3
+/* the eight groups of a workgroup (a super-group, up to 8 x 48 rows of A) fetch each row of B that
+ * any of them needs once into LDS, and every multiply-add takes its B values from there; reads the
+ * share schedule built at conversion (see gcoo_set_share_policy()); needs p <= 48, B, C, ldb, ldc, N
+ * multiples of 4 elements (16-byte aligned rows) and k * ldb * 4 < 2^32, else GCOO_EINVAL.
+ * gcoo_spdm() picks it where the matrix has that schedule by the automatic rule, the operands
+ * qualify and C has at least 192 blocks of (8p rows) x 256 columns - below 9000 columns of A also
+ * only if those blocks fill their rounds over the 256 compute units to 80 % */
+#define GCOO_VARIANT_SHARE 3
 int gcoo_spdm_variant(const gcoo_matrix* A, const float* B_dev, int64_t ldb, int64_t N,
                       float* C_dev, int64_t ldc, void* stream, int variant);
 
 /* Variant gcoo_spdm() would pick for this matrix and these operand shapes (one of GCOO_VARIANT_* > 0). */
 int gcoo_spdm_pick(const gcoo_matrix* A, const float* B_dev, int64_t ldb, int64_t N,
                    const float* C_dev, int64_t ldc);
-
-/*
- * Context for benchmarks, not part of the GCOO path: a plain CSR row-split SpMM (one wave per row
- * and 256 columns, no staging, no reuse of B across rows), the kind of routine Section 4 of the
- * paper compares against.  All pointers are device pointers; C (m x N) is fully overwritten.
- */
-int gcoo_csr_spmm_baseline(int64_t m, int64_t k, const int32_t* row_ptr_dev, const int32_t* col_idx_dev,
-                           const float* vals_dev, const float* B_dev, int64_t ldb, int64_t N,
-                           float* C_dev, int64_t ldc, void* stream);
 
 /* Release the host handle.  The device buffer stays the caller's.  NULL is accepted. */
 int gcoo_free(gcoo_matrix* A);
@@ -198,38 +192,37 @@ int gcoo_info(const gcoo_matrix* A, int64_t* m, int64_t* k, int64_t* nnz, int32_
 /*
  * Copy the five arrays of Section 3.1 to HOST buffers: values[nnz], rows[nnz], cols[nnz],
  * gIdxes[g+1] (widened to int64), nnzPerGroup[g].  Any pointer may be NULL to skip that array.
- * Waits for the conversion kernels on `stream` first (synchronises).
+ * Waits for the conversion kernels on `stream` first (synchronises).  GCOO_EBOUNDS (after the
+ * copies) if the conversion met a column outside [0, k) in a device CSR input and clamped it.
  */
 int gcoo_export(const gcoo_matrix* A, float* values, int32_t* rows, int32_t* cols,
                 int64_t* gIdxes, int32_t* nnzPerGroup, void* stream);
 
 /*
- * When conversions build the band schedule (process-wide setting, not thread-safe; takes effect
- * for matrices converted afterwards).  GCOO_BAND_AUTO: only for matrices on which gcoo_spdm()
- * then picks GCOO_VARIANT_BAND when B is wide enough: density at most 6 % and
- *   p <= 16:       7000 columns or more, or 3500 at 0.8 % density or more;
- *   17 <= p <= 32: 13000 columns or more at 0.5 % or more, or 10000 at 2 % or more.
- * GCOO_BAND_ALWAYS: whenever the band kernel could run (p <= 32, density <= 6 %, at most 262144
- * columns); gcoo_spdm() keeps its usual choice and GCOO_VARIANT_BAND must be asked for.
- * GCOO_BAND_NEVER: never.
+ * When conversions build the share schedule (process-wide setting, not thread-safe; takes effect
+ * for matrices converted afterwards).
+ * GCOO_SHARE_AUTO: only for matrices on which gcoo_spdm() then picks GCOO_VARIANT_SHARE when B is
+ *   wide enough: p <= 48, density at most 6 %, and 7000 columns or more, or 3500 at 0.8 % density or more
+ *   (at most 262144 columns);
+ * GCOO_SHARE_ALWAYS: whenever that kernel could run (p <= 48, at most 262144 columns, nnz > 0);
+ *   gcoo_spdm() keeps its usual choice and GCOO_VARIANT_SHARE must be asked for;
+ * GCOO_SHARE_NEVER: never.
  */
-#define GCOO_BAND_AUTO   0
-#define GCOO_BAND_ALWAYS 1
-#define GCOO_BAND_NEVER  2
-int gcoo_set_band_policy(int policy);
+#define GCOO_SHARE_AUTO   0
+#define GCOO_SHARE_ALWAYS 1
+#define GCOO_SHARE_NEVER  2
+int gcoo_set_share_policy(int policy);
 
 /*
- * Introspection for tests: the band schedule, the kernel-private re-listing that the
- * workgroup-shared SpDM kernel reads (built at conversion as gcoo_set_band_policy() says).
- * gcoo_band_words() = its size in 32-bit words, 0 if this matrix has none (or A is NULL).
- * gcoo_export_band() copies it to HOST buffers: `words` (gcoo_band_words entries), `ucount`
- * (distinct columns per super-group of W groups, ceil(g/W) entries; W = 16 for p <= 16, else 8) and
- * `ucols` (nnz entries; the columns of super-group Q start at index gIdxes[W*Q]); any of them may
- * be NULL.  Synchronises
- * `stream`.  GCOO_EINVAL if A is NULL or has no band schedule.
+ * Introspection for tests: copies the share schedule (the kernel-private re-listing that the
+ * workgroup-shared SpDM kernel reads) to HOST buffers, any of which may be NULL.
+ * *hdr_words and *block_count receive the sizes of `hdr` (32-bit words) and `blocks` (blocks of 64 words);
+ * call once with the arrays NULL to learn them.  sbase has 8 * ceil(g / 8) entries, ucount ceil(g / 8),
+ * ucols nnz (the distinct columns of super-group Q start at index gIdxes[8Q]).  Synchronises `stream`.
+ * GCOO_EINVAL if A is NULL or has no share schedule.
  */
-int64_t gcoo_band_words(const gcoo_matrix* A);
-int gcoo_export_band(const gcoo_matrix* A, uint32_t* words, int32_t* ucount, int32_t* ucols, void* stream);
+int gcoo_export_share(const gcoo_matrix* A, uint32_t* hdr, uint32_t* blocks, int32_t* sbase, int32_t* ucount, int32_t* ucols,
+                      int64_t* hdr_words, int64_t* block_count, void* stream);
 
 /* Static text for a status code. */
 const char* gcoo_strerror(int status);

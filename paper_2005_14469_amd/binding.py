@@ -14,19 +14,22 @@ import torch
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "libgcoo.so")
+BASELINE_LIB_PATH = os.path.join(_HERE, "libgcoo_baseline.so")
 
 GCOO_OK, GCOO_EINVAL, GCOO_EBOUNDS, GCOO_ENOMEM, GCOO_EHIP = 0, -1, -2, -3, -4
 GCOO_MAX_P = 256
-VARIANT_AUTO, VARIANT_LDS, VARIANT_REG, VARIANT_BAND = 0, 1, 2, 3
-BAND_AUTO, BAND_ALWAYS, BAND_NEVER = 0, 1, 2
+VARIANT_AUTO, VARIANT_LDS, VARIANT_REG, VARIANT_SHARE = 0, 1, 2, 3
+SHARE_AUTO, SHARE_ALWAYS, SHARE_NEVER = 0, 1, 2
 
 # every symbol include/gcoo.h declares
 SYMBOLS = ["gcoo_default_p", "gcoo_device_bytes", "gcoo_from_csr", "gcoo_from_csr_device", "gcoo_dense_nnz", "gcoo_from_dense", "gcoo_spdm",
            "gcoo_spdm_variant", "gcoo_spdm_pick", "gcoo_free", "gcoo_info", "gcoo_export",
-           "gcoo_strerror", "gcoo_last_hip_error", "gcoo_csr_spmm_baseline",
-           "gcoo_band_words", "gcoo_export_band", "gcoo_set_band_policy"]
+           "gcoo_strerror", "gcoo_last_hip_error", "gcoo_set_share_policy", "gcoo_export_share"]
+# and include/gcoo_baseline.h (libgcoo_baseline.so)
+BASELINE_SYMBOLS = ["gcoo_csr_spmm_baseline"]
 
 _lib = None
+_baseline_lib = None
 
 
 class GcooError(RuntimeError):
@@ -71,22 +74,32 @@ def lib():
         L.gcoo_export.argtypes = [vp, vp, vp, vp, vp, vp, vp]
         L.gcoo_from_csr_device.restype = C.c_int
         L.gcoo_from_csr_device.argtypes = [i64, i64, i64, vp, vp, vp, i32, vp, C.c_size_t, vp, C.POINTER(vp)]
-        L.gcoo_set_band_policy.restype = C.c_int
-        L.gcoo_set_band_policy.argtypes = [C.c_int]
-        L.gcoo_band_words.restype = C.c_int64
-        L.gcoo_band_words.argtypes = [vp]
-        L.gcoo_export_band.restype = C.c_int
-        L.gcoo_export_band.argtypes = [vp, vp, vp, vp, vp]
+        L.gcoo_set_share_policy.restype = C.c_int
+        L.gcoo_set_share_policy.argtypes = [C.c_int]
+        L.gcoo_export_share.restype = C.c_int
+        L.gcoo_export_share.argtypes = [vp, vp, vp, vp, vp, vp, C.POINTER(i64), C.POINTER(i64), vp]
         L.gcoo_default_p.restype = C.c_int32
         L.gcoo_default_p.argtypes = [i64, i64, i64, i64]
-        L.gcoo_csr_spmm_baseline.restype = C.c_int
-        L.gcoo_csr_spmm_baseline.argtypes = [i64, i64, vp, vp, vp, vp, i64, i64, vp, i64, vp]
         L.gcoo_strerror.restype = C.c_char_p
         L.gcoo_strerror.argtypes = [C.c_int]
         L.gcoo_last_hip_error.restype = C.c_char_p
         L.gcoo_last_hip_error.argtypes = []
         _lib = L
     return _lib
+
+
+def baseline_lib():
+    """Load libgcoo_baseline.so (the CSR row-split routine the benchmark compares against)."""
+    global _baseline_lib
+    if _baseline_lib is None:
+        if not os.path.exists(BASELINE_LIB_PATH):
+            raise FileNotFoundError(f"{BASELINE_LIB_PATH} is missing: build it with `python -m paper_2005_14469_amd.build`")
+        L = C.CDLL(BASELINE_LIB_PATH)
+        i64, vp = C.c_int64, C.c_void_p
+        L.gcoo_csr_spmm_baseline.restype = C.c_int
+        L.gcoo_csr_spmm_baseline.argtypes = [i64, i64, vp, vp, vp, vp, i64, i64, vp, i64, vp]
+        _baseline_lib = L
+    return _baseline_lib
 
 
 def _check(status: int, where: str):
@@ -134,19 +147,21 @@ class GcooMatrix:
                                  npg.ctypes.data, _stream_ptr(stream)), "gcoo_export")
         return dict(values=v, rows=r, cols=c, gIdxes=gi, nnzPerGroup=npg)
 
-    def export_band(self, stream=None):
-        """The band schedule as numpy arrays on the host, or None if this matrix has none."""
-        n = int(lib().gcoo_band_words(self.handle))
-        if n == 0:
+    def export_share(self, stream=None):
+        """The share schedule as numpy arrays on the host, or None if this matrix has none."""
+        hw, nb = C.c_int64(), C.c_int64()
+        if lib().gcoo_export_share(self.handle, None, None, None, None, None, C.byref(hw), C.byref(nb), _stream_ptr(stream)) != GCOO_OK:
             return None
         i = self.info()
-        words = np.empty(n, np.uint32)
-        W = 16 if i["p"] <= 16 else 8                      # groups per super-group
-        ucount = np.empty((i["g"] + W - 1) // W, np.int32)
+        nq = (i["g"] + 7) // 8
+        hdr = np.empty(hw.value, np.uint32)
+        blocks = np.empty(nb.value * 64, np.uint32)
+        sbase = np.empty(nq * 8, np.int32)
+        ucount = np.empty(nq, np.int32)
         ucols = np.empty(i["nnz"], np.int32)
-        _check(lib().gcoo_export_band(self.handle, words.ctypes.data, ucount.ctypes.data, ucols.ctypes.data,
-                                      _stream_ptr(stream)), "gcoo_export_band")
-        return dict(words=words, ucount=ucount, ucols=ucols)
+        _check(lib().gcoo_export_share(self.handle, hdr.ctypes.data, blocks.ctypes.data, sbase.ctypes.data, ucount.ctypes.data,
+                                       ucols.ctypes.data, None, None, _stream_ptr(stream)), "gcoo_export_share")
+        return dict(hdr=hdr, blocks=blocks, sbase=sbase, ucount=ucount, ucols=ucols)
 
     def free(self):
         if self._h is not None:
@@ -259,7 +274,7 @@ def gcoo_csr_spmm_baseline(m: int, k: int, row_ptr: torch.Tensor, col_idx: torch
     ldb = B.stride(0) if B.shape[0] > 1 else max(N, 1)
     ldc = C_out.stride(0) if C_out.shape[0] > 1 else max(N, 1)
     with torch.cuda.device(B.device):
-        _check(lib().gcoo_csr_spmm_baseline(m, k, row_ptr.data_ptr(), col_idx.data_ptr(), vals.data_ptr(), B.data_ptr(), ldb, N,
+        _check(baseline_lib().gcoo_csr_spmm_baseline(m, k, row_ptr.data_ptr(), col_idx.data_ptr(), vals.data_ptr(), B.data_ptr(), ldb, N,
                                             C_out.data_ptr(), ldc, _stream_ptr(stream)), "gcoo_csr_spmm_baseline")
     return C_out
 
@@ -268,7 +283,7 @@ def gcoo_default_p(m: int, k: int, nnz: int, N: int) -> int:
     return int(lib().gcoo_default_p(m, k, nnz, N))
 
 
-def gcoo_tune_p(m: int, k: int, row_ptr, col_idx, vals, B: torch.Tensor, candidates=(8, 16, 32, 38, 64), reps: int = 5,
+def gcoo_tune_p(m: int, k: int, row_ptr, col_idx, vals, B: torch.Tensor, candidates=(8, 16, 32, 38, 42, 48, 64), reps: int = 5,
                 include_conversion: bool = False):
     """Times conversion + product for each group height and returns (best p, {p: ms}).
 
@@ -303,5 +318,6 @@ def gcoo_tune_p(m: int, k: int, row_ptr, col_idx, vals, B: torch.Tensor, candida
     return min(times, key=times.get), times
 
 
-def gcoo_set_band_policy(policy: int) -> None:
-    _check(lib().gcoo_set_band_policy(policy), "gcoo_set_band_policy")
+
+def gcoo_set_share_policy(policy: int) -> None:
+    _check(lib().gcoo_set_share_policy(policy), "gcoo_set_share_policy")

@@ -10,11 +10,13 @@
 #include <new>
 #include <string>
 
-#include "gcoo_band.hpp"
-#include "gcoo_band_build.hpp"
+#include <atomic>
+
 #include "gcoo_build_kernels.hpp"
 #include "gcoo_sched.hpp"
 #include "gcoo_sched_build.hpp"
+#include "gcoo_share.hpp"
+#include "gcoo_share_build.hpp"
 #include "gcoo_spdm_launch.hpp"
 #include "gcoo_spdm_lds_kernel.hpp"
 
@@ -37,18 +39,22 @@ int hip_fail(hipError_t e, const char* what)
 constexpr size_t kAlign = 256;
 size_t al(size_t bytes) { return (bytes + kAlign - 1) / kAlign * kAlign; }
 
-// 8 bytes of device memory for gcoo_dense_nnz(), which is handed no device buffer: one copy per
-// device, addressed through hipGetSymbolAddress; calls on one device serialise on it.
-__device__ unsigned long long g_dense_total;
+// Device memory for gcoo_dense_nnz(), which is handed no device buffer: kDenseSlots counters per
+// device, addressed through hipGetSymbolAddress.  Every call takes the next slot (round robin), so
+// calls that overlap on one device - other streams, other host threads - count into different
+// words as long as fewer than kDenseSlots of them are in flight at once.
+constexpr unsigned kDenseSlots = 256;
+__device__ unsigned long long g_dense_total[kDenseSlots];
+std::atomic<unsigned> g_dense_next{0};
 
 // Carve-up of the caller's device buffer.  Offsets depend on (m, nnz, g) only.
 struct Layout {
     size_t values, rows, cols, gIdxes, nnzPerGroup;        // the five arrays of the format
     size_t sched_hdr, sched;                               // run schedule of the register kernel
-    size_t band_ucols, band_ucount, band_stream;           // band schedule of the workgroup-shared kernel (may be empty)
+    size_t share_ucols, share_ucount, share_hdr, share_blocks, share_sbase, share_alloc;   // share schedule (may be empty)
     size_t tmp_cols, tmp_rows, tmp_vals;                   // conversion scratch (second sort buffer)
     size_t in_row_ptr, in_cols, in_vals;                   // staging of a host CSR input
-    size_t counter;                                        // two 8-byte device counters (nnz, largest group)
+    size_t counter;                                        // device words: nnz (8 bytes), largest group (8), column-out-of-range flag (4)
     size_t blk;                                            // dense input: entries per (group, column block)
     size_t total;
 };
@@ -82,68 +88,73 @@ int dense_vec_width(const float* A, int64_t lda, int64_t k)
     return (k % 4 == 0 && lda % 4 == 0 && reinterpret_cast<uintptr_t>(A) % 16 == 0) ? 4 : 1;
 }
 
-// The band schedule costs conversion time and memory, so it is built only where the band
-// kernel is the one gcoo_spdm() will pick.  Measured on MI355X with uniform random square
-// matrices (n = 2000 .. 14000, density 0.1 % .. 6 %, N = n):
-//   * groups of 17..32 rows (eight waves per workgroup): the band kernel beats the register kernel
-//     from about 10000 columns on at 2 % density or more, from 13000 columns on already at 0.5 %
-//     (1.1x .. 1.7x);
-//   * groups of at most 16 rows (sixteen waves): it beats the register kernel on the same matrix from
-//     3500 columns on at 0.8 % density or more and from 7000 columns on at any density up to the limit
-//     (1.1x .. 2.7x), and it beats the register kernel with groups of 32 rows - the better height
-//     for that kernel - in the narrower region that gcoo_default_p() describes.
-// The B tile of a column tile then no longer stays in L2 between the groups that need it, and W
-// groups sharing each fetched row matters more than the step-by-step overhead of the band kernel.
-// Below 6 % most column runs inside a group are one or two entries long; above it the register
-// kernel is bound by its multiply-adds, not by the rows it fetches.
-// gcoo_set_band_policy() overrides the choice.
-int g_band_policy = GCOO_BAND_AUTO;
+// The share schedule costs conversion time and memory, so it is built only where the workgroup-shared
+// kernel is the one gcoo_spdm() will pick.  Measured on MI355X with uniform random square matrices
+// (n = 4000 .. 14000, density 0.1 % .. 10 %, N = n), against the register kernel at its best group height:
+// the workgroup-shared kernel wins from 7000 columns on at any density between 0.5 % and 6 % (n = 8000: by
+// 10 .. 30 % between 1 % and 5 %, level at 0.5 %; n = 14000: 1.7 .. 2.3x), and from 3500 columns on at 0.8 % or more
+// (n = 4000, 2 %: 12 %).  The B tile of a column tile then no longer stays in L2 between the groups
+// that need it, and what the register kernel pays per run (a 1 KB segment through the vector cache)
+// costs more than the per-band steps of the workgroup-shared kernel.  Above 6 % the register kernel,
+// which reuses a fetched segment along runs of up to eight entries, is ahead (10 %: 2.9 against 3.2 ms
+// at n = 8000); at 0.1 % and at n <= 3000 too.  gcoo_set_share_policy() overrides the choice.
+int g_share_policy = GCOO_SHARE_AUTO;
 
-bool band_schedule_possible(int64_t m, int64_t k, int64_t nnz, int32_t p)
+bool share_schedule_possible(int64_t m, int64_t k, int64_t nnz, int32_t p)
 {
-    if (p > gcoo::kBandMaxP || k > gcoo::kBandMaxK || nnz <= 0 || m <= 0 || k <= 0) return false;
-    return (double)nnz <= 0.06 * (double)m * (double)k;
+    return p <= gcoo::kShareMaxP && k <= gcoo::kShareMaxK && nnz > 0 && m > 0 && k > 0;
 }
 
-bool band_kernel_preferred(int64_t m, int64_t k, int64_t nnz, int32_t p)
+// (density and shape only: also the rule by which gcoo_default_p() picks a height for that kernel)
+bool share_shape_preferred(int64_t m, int64_t k, int64_t nnz)
 {
-    if (!band_schedule_possible(m, k, nnz, p)) return false;
+    if (m <= 0 || k <= 0 || nnz <= 0 || k > gcoo::kShareMaxK) return false;
     const double density = (double)nnz / ((double)m * (double)k);
-    if (gcoo::band_waves(p) == 16) return k >= 7000 || (k >= 3500 && density >= 0.008);
-    return (k >= 13000 && density >= 0.005) || (k >= 10000 && density >= 0.02);
+    if (density > 0.06) return false;
+    return k >= 7000 || (k >= 3500 && density >= 0.008);
 }
 
-// A band workgroup runs for a whole (super-group, column tile): how well `items` of them fill the
-// 256 compute units, as the fraction of the rounds they need that is work.
-double band_fill_of_rounds(int64_t items)
+bool share_kernel_preferred(int64_t m, int64_t k, int64_t nnz, int32_t p)
+{
+    return share_schedule_possible(m, k, nnz, p) && share_shape_preferred(m, k, nnz);
+}
+
+bool share_schedule_wanted(int64_t m, int64_t k, int64_t nnz, int32_t p)
+{
+    if (g_share_policy == GCOO_SHARE_NEVER || !share_schedule_possible(m, k, nnz, p)) return false;
+    return g_share_policy == GCOO_SHARE_ALWAYS || share_kernel_preferred(m, k, nnz, p);
+}
+
+// A workgroup of that kernel runs for a whole (super-group, column tile): how well `items` of them fill
+// the 256 compute units, as the fraction of the rounds they need that is work.
+double fill_of_rounds(int64_t items)
 {
     if (items <= 0) return 0.0;
     const int64_t rounds = (items + 255) / 256;
     return (double)items / (double)(rounds * 256);
 }
 
-// Group height 16 with the band kernel against 32 with the register kernel, conversion included
-// (whole steps of bench.py, uniform random, n = 4000 .. 14000): 16 wins from 9000 columns on at
-// 0.4 % density or more; from 7000 on at 0.8 % or more (n = 8000: by 15 .. 31 % between 1 % and 5 %);
-// from 3500 on between 0.9 % and 5 % (n = 4000: by 4 .. 20 %) - the two smaller regions only where the
-// workgroups fill their rounds (n = 6000 and 7000, at 75 % and 77 %, lose by up to 10 %).  At 0.5 %
-// and below the two are level or 32 wins up to 8000 columns; at 0.1 % even at 14000.
-bool short_groups_preferred(int64_t m, int64_t k, int64_t nnz, int64_t N)
+int64_t share_items(int64_t m, int32_t p, int64_t N)
 {
-    if (N % 4 != 0 || N <= 0 || !band_kernel_preferred(m, k, nnz, 16)) return false;
-    const double density = (double)nnz / ((double)m * (double)k);
-    const int64_t items = ((m + 255) / 256) * ((N + 255) / 256);
-    const double fill = band_fill_of_rounds(items);
-    if (items < 192) return false;
-    if (k >= 9000 && density >= 0.004) return fill >= 0.8;
-    if (k >= 7000 && density >= 0.008) return fill >= 0.9;
-    return k >= 3500 && density >= 0.009 && density <= 0.05 && fill >= 0.95;
+    const int64_t g = (m + p - 1) / p;
+    return gcoo::share_super_groups(g) * ((N + 255) / 256);
 }
 
-bool band_schedule_wanted(int64_t m, int64_t k, int64_t nnz, int32_t p)
+// Group height for the workgroup-shared kernel: taller groups mean fewer rows of B fetched per
+// multiply-add, but the workgroups must fill their rounds over the compute units.  The time of a launch goes
+// like rounds x (time of a workgroup), and the time of a workgroup like p plus a part that does not depend
+// on p (the per-band steps); measured best heights: 42 at 8000 x 8000 (768 workgroups = 3 rounds), 48 at
+// 14000 x 14000, 32 at 4000 x 4000 (256 workgroups), which this rule reproduces.
+int32_t share_best_p(int64_t m, int64_t N)
 {
-    if (g_band_policy == GCOO_BAND_NEVER || !band_schedule_possible(m, k, nnz, p)) return false;
-    return g_band_policy == GCOO_BAND_ALWAYS || band_kernel_preferred(m, k, nnz, p);
+    int32_t best = 32;
+    int64_t best_cost = INT64_MAX;
+    for (int32_t p = gcoo::kShareMaxP; p >= 24; --p) {
+        const int64_t rounds = (share_items(m, p, N) + 255) / 256;
+        const int64_t cost = rounds * (p + 24);
+        if (cost < best_cost) { best_cost = cost; best = p; }
+    }
+    return best;
 }
 
 Layout make_layout(int64_t m, int64_t k, int64_t nnz, int64_t g, int32_t p)
@@ -158,18 +169,21 @@ Layout make_layout(int64_t m, int64_t k, int64_t nnz, int64_t g, int32_t p)
     // counted into them before nnz is known
     L.gIdxes = take((size_t)(g + 1) * 4);
     L.nnzPerGroup = take((size_t)g * 4);
-    L.counter = take(16);
+    L.counter = take(32);
     L.blk = take((size_t)g * (size_t)dense_blocks(k) * 4);
     L.values = take(n4);
     L.rows = take(n4);
     L.cols = take(n4);
     L.sched_hdr = take((size_t)g * nw * gcoo::kMaxRun * sizeof(gcoo::SchedClass));
     L.sched = take((size_t)gcoo::sched_words(nnz, g, nw) * 4);
-    const bool band = band_schedule_wanted(m, k, nnz, p);
-    L.band_ucols = take(band ? n4 : 0);
-    const int W = gcoo::band_waves(p);
-    L.band_ucount = take(band ? (size_t)((g + W - 1) / W) * 4 : 0);
-    L.band_stream = take(band ? (size_t)gcoo::band_stream_words(nnz, g, k, W) * 4 : 0);
+    const bool share = share_schedule_wanted(m, k, nnz, p);
+    const int64_t nQ = gcoo::share_super_groups(g);
+    L.share_ucols = take(share ? n4 : 0);
+    L.share_ucount = take(share ? (size_t)nQ * 4 : 0);
+    L.share_hdr = take(share ? (size_t)gcoo::share_hdr_words(nnz, g) * 4 : 0);
+    L.share_blocks = take(share ? (size_t)gcoo::share_stream_blocks(nnz, g, k) * gcoo::kShareBlockWords * 4 : 0);
+    L.share_sbase = take(share ? (size_t)nQ * gcoo::kShareW * 4 : 0);
+    L.share_alloc = take(share ? 4 : 0);
     L.tmp_cols = take(n4);
     L.tmp_rows = take(n4);
     L.tmp_vals = take(n4);
@@ -197,13 +211,13 @@ int radix_passes(int64_t k)
 }  // namespace
 
 struct gcoo_matrix {
+    // Everything below is set by the conversion and only read afterwards.
     int64_t m, k, nnz, g;
-    mutable int64_t max_group_nnz;   // entries of the largest group; -1: still on the device (L.counter + 8), fetched on first need
     int32_t p;
     int32_t nw, window_cols;
-    mutable bool sched_built;  // the run schedule of the register kernel exists (built at conversion, or by the first launch that needs it)
-    bool has_band;             // the band schedule was built
-    bool band_preferred;       // and the band kernel is the automatic choice
+    bool has_sched;            // the run schedule of the register kernel was built (p <= 64)
+    bool has_share;            // the share schedule was built
+    bool share_preferred;      // and the kernel that reads it is the automatic choice
     int device;
     char* base;
     Layout L;
@@ -214,37 +228,42 @@ struct gcoo_matrix {
     int32_t* nnzPerGroup() const { return reinterpret_cast<int32_t*>(base + L.nnzPerGroup); }
     gcoo::SchedClass* sched_hdr() const { return reinterpret_cast<gcoo::SchedClass*>(base + L.sched_hdr); }
     uint32_t* sched() const { return reinterpret_cast<uint32_t*>(base + L.sched); }
-    int32_t* band_ucols() const { return reinterpret_cast<int32_t*>(base + L.band_ucols); }
-    int32_t* band_ucount() const { return reinterpret_cast<int32_t*>(base + L.band_ucount); }
-    uint32_t* band_stream() const { return reinterpret_cast<uint32_t*>(base + L.band_stream); }
-    int band_w() const { return gcoo::band_waves(p); }
-    int64_t super_groups() const { return (g + band_w() - 1) / band_w(); }
+    unsigned long long* stats() const { return reinterpret_cast<unsigned long long*>(base + L.counter); }
+    uint32_t* bad_col() const { return reinterpret_cast<uint32_t*>(base + L.counter + 16); }
+    int32_t* share_ucols() const { return reinterpret_cast<int32_t*>(base + L.share_ucols); }
+    int32_t* share_ucount() const { return reinterpret_cast<int32_t*>(base + L.share_ucount); }
+    uint32_t* share_hdr() const { return reinterpret_cast<uint32_t*>(base + L.share_hdr); }
+    uint32_t* share_blocks() const { return reinterpret_cast<uint32_t*>(base + L.share_blocks); }
+    int32_t* share_sbase() const { return reinterpret_cast<int32_t*>(base + L.share_sbase); }
+    uint32_t* share_alloc() const { return reinterpret_cast<uint32_t*>(base + L.share_alloc); }
+    int64_t share_nq() const { return gcoo::share_super_groups(g); }
 };
 
 namespace {
 
-int new_handle(int64_t m, int64_t k, int64_t nnz, int64_t max_group_nnz, int32_t p, void* dev_buf, gcoo_matrix** out)
+int new_handle(int64_t m, int64_t k, int64_t nnz, int32_t p, void* dev_buf, gcoo_matrix** out)
 {
     gcoo_matrix* h = new (std::nothrow) gcoo_matrix;
     if (!h) return GCOO_ENOMEM;
     h->m = m; h->k = k; h->nnz = nnz; h->p = p;
-    h->max_group_nnz = max_group_nnz;
     h->g = (m + p - 1) / p;
     h->base = static_cast<char*>(dev_buf);
     h->L = make_layout(m, k, nnz, h->g, p);
-    h->has_band = band_schedule_wanted(m, k, nnz, p);
-    h->band_preferred = h->has_band && band_kernel_preferred(m, k, nnz, p);
-    h->sched_built = false;
+    h->has_share = share_schedule_wanted(m, k, nnz, p);
+    h->share_preferred = h->has_share && share_kernel_preferred(m, k, nnz, p);
+    h->has_sched = h->p <= gcoo::kSchedMaxP;
     pick_windows(k, h->g, &h->nw, &h->window_cols);
     if (hipGetDevice(&h->device) != hipSuccess) h->device = -1;
     *out = h;
     return GCOO_OK;
 }
 
-// Builds the run schedule of the register kernel from the finished GCOO arrays.
-int launch_build_reg_schedule(const gcoo_matrix* h, hipStream_t s)
+// The kernel-private schedules that a conversion ends with: the run schedule of the register kernel
+// (every matrix of at most 64 rows per group) and, where wanted, the share schedule.  Both are built
+// here, on the conversion's stream, so that the handle is never written again.
+int launch_build_schedule(const gcoo_matrix* h, hipStream_t s)
 {
-    if (h->g > 0 && h->p <= gcoo::kSchedMaxP) {              // no register kernel above that height
+    if (h->g > 0 && h->has_sched) {
         const dim3 grid((unsigned)(h->g * h->nw));
         if (h->nnz / (h->g * h->nw) <= 1024)
             gcoo::build_schedule<256><<<grid, dim3(256), 0, s>>>(h->gIdxes(), h->rows(), h->cols(), h->values(), h->p, h->g, h->nw,
@@ -254,28 +273,15 @@ int launch_build_reg_schedule(const gcoo_matrix* h, hipStream_t s)
                                                                    h->window_cols, h->sched_hdr(), h->sched());
         HIP_TRY(hipGetLastError());
     }
-    h->sched_built = true;
-    return GCOO_OK;
-}
-
-// The kernel-private schedules that a conversion ends with.  A matrix whose automatic kernel is
-// the band kernel gets the band schedule only; should the register kernel be asked for it after
-// all (few columns of B, unaligned operands, by name), its schedule is built by that first launch.
-int launch_build_schedule(const gcoo_matrix* h, hipStream_t s)
-{
-    if (!h->band_preferred) {
-        int rc = launch_build_reg_schedule(h, s);
-        if (rc != GCOO_OK) return rc;
-    }
-    if (h->g > 0 && h->has_band) {
+    if (h->g > 0 && h->has_share) {
         const size_t bitmap_bytes = (size_t)((h->k + 31) / 32) * 4;
-        gcoo::band_union<<<dim3((unsigned)h->super_groups()), dim3(gcoo::kBandBuildThreads), bitmap_bytes, s>>>(
-            h->gIdxes(), h->cols(), h->g, h->k, h->band_w(), h->band_ucols(), h->band_ucount());
+        gcoo::share_union<<<dim3((unsigned)h->share_nq()), dim3(gcoo::kShareBuildThreads), bitmap_bytes, s>>>(
+            h->gIdxes(), h->cols(), h->g, h->k, gcoo::kShareW, h->share_ucols(), h->share_ucount(), h->share_alloc());
         HIP_TRY(hipGetLastError());
-        const size_t table_bytes = 2 * (size_t)((h->k + 63) / 64 + 1) * 4;
-        gcoo::band_fill<<<dim3((unsigned)(h->super_groups() * h->band_w())), dim3(gcoo::kBandBuildThreads), table_bytes, s>>>(
-            h->gIdxes(), h->rows(), h->cols(), h->values(), h->p, h->g, h->k, h->band_w(), h->band_ucols(), h->band_ucount(),
-            h->band_stream());
+        const size_t table_bytes = 2 * (size_t)((h->k + gcoo::kShareBandRows - 1) / gcoo::kShareBandRows + 1) * 4;
+        gcoo::share_fill<<<dim3((unsigned)(h->share_nq() * gcoo::kShareW)), dim3(gcoo::kShareBuildThreads), table_bytes, s>>>(
+            h->gIdxes(), h->rows(), h->cols(), h->values(), h->p, h->g, h->k, h->share_ucols(), h->share_ucount(), h->share_hdr(),
+            h->share_blocks(), h->share_sbase(), h->share_alloc());
         HIP_TRY(hipGetLastError());
     }
     return GCOO_OK;
@@ -285,17 +291,21 @@ int launch_build_schedule(const gcoo_matrix* h, hipStream_t s)
 
 extern "C" {
 
-int gcoo_set_band_policy(int policy)
+int gcoo_set_share_policy(int policy)
 {
-    if (policy < GCOO_BAND_AUTO || policy > GCOO_BAND_NEVER) return GCOO_EINVAL;
-    g_band_policy = policy;
+    if (policy < GCOO_SHARE_AUTO || policy > GCOO_SHARE_NEVER) return GCOO_EINVAL;
+    g_share_policy = policy;
     return GCOO_OK;
 }
 
 int32_t gcoo_default_p(int64_t m, int64_t k, int64_t nnz, int64_t N)
 {
     if (m < 0 || k < 0 || nnz < 0 || N < 0) return 0;
-    if (short_groups_preferred(m, k, nnz, N)) return 16;
+    if (N > 0 && N % 4 == 0 && share_shape_preferred(m, k, nnz)) {
+        const int32_t p = share_best_p(m, N);
+        const int64_t items = share_items(m, p, N);
+        if (items >= 192 && (k >= 9000 || fill_of_rounds(items) >= 0.8)) return p;
+    }
     // Between 6 % and 12 % density most groups touch most columns, and what the register kernel
     // fetches falls with the number of groups: 38 rows (the tall accumulator file) beat 32 by
     // 8 .. 28 % from 6000 columns on (whole steps, n = 6000 .. 14000, s = 0.9 and 0.93); at 20 % and
@@ -328,24 +338,21 @@ int from_csr(int64_t m, int64_t k, const int32_t* row_ptr, const int32_t* col_id
     hipStream_t s = static_cast<hipStream_t>(stream);
 
     const int64_t g = (m + p - 1) / p;
-    int64_t nnz, max_group_nnz = 0;
-    unsigned long long* stats_with_index = nullptr;
+    int64_t nnz;
     if (src_on_device && nnz_known >= 0) {          // everything the host can check, before the first launch
         if (nnz_known > 0 && (!col_idx || !vals)) return GCOO_EINVAL;
         if (dev_buf_bytes < make_layout(m, k, nnz_known, g, p).total) return GCOO_ENOMEM;
     }
+    // nnz and the size of the largest group are computed on the device and stay there (the counters
+    // sit at an offset of the buffer that does not depend on nnz); the launches that need the
+    // latter read it there.
+    const Layout L0 = make_layout(m, k, 0, g, p);
+    if (dev_buf_bytes < L0.total) return GCOO_ENOMEM;
+    unsigned long long* stats = reinterpret_cast<unsigned long long*>(static_cast<char*>(dev_buf) + L0.counter);
     if (src_on_device) {
-        // nnz and the size of the largest group are computed on the device (the counters sit at
-        // an offset of the buffer that does not depend on nnz).  They come back in one small
-        // copy, unless the caller has given nnz: then nothing is read back here and the size of
-        // the largest group is fetched the first time a launch needs it.
-        const Layout L0 = make_layout(m, k, 0, g, p);
-        if (dev_buf_bytes < L0.total) return GCOO_ENOMEM;
-        unsigned long long* stats = reinterpret_cast<unsigned long long*>(static_cast<char*>(dev_buf) + L0.counter);
+        // With nnz given nothing is read back here; otherwise nnz comes back in one small copy.
         if (nnz_known >= 0) {
             nnz = nnz_known;
-            max_group_nnz = -1;
-            stats_with_index = stats;                             // computed by the launch that writes gIdxes
         } else {
             gcoo::group_stats_from_row_ptr<<<dim3(1), dim3(256), 0, s>>>(row_ptr, m, p, g, stats);
             HIP_TRY(hipGetLastError());
@@ -354,7 +361,6 @@ int from_csr(int64_t m, int64_t k, const int32_t* row_ptr, const int32_t* col_id
             HIP_TRY(hipStreamSynchronize(s));
             if (got[0] > (unsigned long long)INT32_MAX) return GCOO_EBOUNDS;
             nnz = (int64_t)got[0];
-            max_group_nnz = (int64_t)got[1];
         }
     } else {
         if (row_ptr[0] != 0) return GCOO_EBOUNDS;
@@ -364,18 +370,13 @@ int from_csr(int64_t m, int64_t k, const int32_t* row_ptr, const int32_t* col_id
         if (nnz > 0 && (!col_idx || !vals)) return GCOO_EINVAL;
         for (int64_t e = 0; e < nnz; ++e)
             if (col_idx[e] < 0 || col_idx[e] >= k) return GCOO_EBOUNDS;
-        for (int64_t q = 0; q < g; ++q) {
-            const int64_t r0 = q * p, r1 = (r0 + p < m) ? r0 + p : m;
-            const int64_t n = (int64_t)row_ptr[r1] - row_ptr[r0];
-            if (n > max_group_nnz) max_group_nnz = n;
-        }
     }
     if (nnz > 0 && (!col_idx || !vals)) return GCOO_EINVAL;
     const Layout L = make_layout(m, k, nnz, g, p);
     if (dev_buf_bytes < L.total) return GCOO_ENOMEM;
 
     gcoo_matrix* h = nullptr;
-    int rc = new_handle(m, k, nnz, max_group_nnz, p, dev_buf, &h);
+    int rc = new_handle(m, k, nnz, p, dev_buf, &h);
     if (rc != GCOO_OK) return rc;
     char* base = h->base;
 
@@ -397,9 +398,9 @@ int from_csr(int64_t m, int64_t k, const int32_t* row_ptr, const int32_t* col_id
 
     // Algorithm 1, step 1: group index and counts straight from row_ptr (also writes the sentinel).
     {
-        const unsigned blocks = (unsigned)((g + 1 + 255) / 256) + (stats_with_index ? 1u : 0u);
+        const unsigned blocks = (unsigned)((g + 1 + 255) / 256) + 1u;     // the last one computes the statistics
         gcoo::group_index_from_row_ptr<<<dim3(blocks), dim3(256), 0, s>>>(d_row_ptr, m, p, g, (int32_t)nnz, h->gIdxes(), h->nnzPerGroup(),
-                                                                         stats_with_index);
+                                                                         stats, h->bad_col());
         hipError_t e = hipGetLastError();
         if (e != hipSuccess) { delete h; return hip_fail(e, "group_index_from_row_ptr"); }
     }
@@ -424,13 +425,13 @@ int from_csr(int64_t m, int64_t k, const int32_t* row_ptr, const int32_t* col_id
             const int shift = high_first ? 8 * (1 - pass) : 8 * pass;
             if (pass == 0)
                 gcoo::sort_groups_by_col_digit<true, gcoo::kSortWaves><<<dim3((unsigned)g), dim3(gcoo::kSortWaves * gcoo::kWave), 0, s>>>(
-                    h->gIdxes(), d_row_ptr, m, p, src_c, src_r, src_v, dc, dr, dv, shift, 0);
+                    h->gIdxes(), d_row_ptr, m, p, src_c, src_r, src_v, dc, dr, dv, shift, 0, (int32_t)k, h->bad_col());
             else if (high_first)
                 gcoo::sort_groups_by_col_digit<false, gcoo::kSortBucketWaves><<<dim3((unsigned)(g * buckets)), dim3(gcoo::kSortBucketWaves * gcoo::kWave), 0, s>>>(
-                    h->gIdxes(), d_row_ptr, m, p, src_c, src_r, src_v, dc, dr, dv, shift, (int32_t)buckets);
+                    h->gIdxes(), d_row_ptr, m, p, src_c, src_r, src_v, dc, dr, dv, shift, (int32_t)buckets, (int32_t)k, h->bad_col());
             else
                 gcoo::sort_groups_by_col_digit<false, gcoo::kSortWaves><<<dim3((unsigned)g), dim3(gcoo::kSortWaves * gcoo::kWave), 0, s>>>(
-                    h->gIdxes(), d_row_ptr, m, p, src_c, src_r, src_v, dc, dr, dv, shift, 0);
+                    h->gIdxes(), d_row_ptr, m, p, src_c, src_r, src_v, dc, dr, dv, shift, 0, (int32_t)k, h->bad_col());
             hipError_t e = hipGetLastError();
             if (e != hipSuccess) { delete h; return hip_fail(e, "sort_groups_by_col_digit"); }
             src_c = dc; src_r = dr; src_v = dv;
@@ -467,6 +468,7 @@ int gcoo_dense_nnz(int64_t m, int64_t k, const float* A_dev, int64_t lda, void* 
     hipStream_t s = static_cast<hipStream_t>(stream);
     unsigned long long* dptr = nullptr;
     HIP_TRY(hipGetSymbolAddress(reinterpret_cast<void**>(&dptr), HIP_SYMBOL(g_dense_total)));
+    dptr += g_dense_next.fetch_add(1u, std::memory_order_relaxed) % kDenseSlots;
     unsigned long long got = 0;
     HIP_TRY(hipMemsetAsync(dptr, 0, 8, s));
     const unsigned blocks = (unsigned)(m < 2048 ? m : 2048);
@@ -499,7 +501,7 @@ int gcoo_from_dense(int64_t m, int64_t k, const float* A_dev, int64_t lda, int32
     int32_t* idx = reinterpret_cast<int32_t*>(base + L0.gIdxes);
     int32_t* blk = reinterpret_cast<int32_t*>(base + L0.blk);
     unsigned long long* tot = reinterpret_cast<unsigned long long*>(base + L0.counter);
-    unsigned long long total = 0, largest = 0;
+    unsigned long long total = 0;
     const int vw = dense_vec_width(A_dev, lda, k);
     const int64_t nblk = dense_blocks(k, vw);
     // one workgroup per (group, column block); a band holds fewer than 2^31 elements so that
@@ -521,16 +523,17 @@ int gcoo_from_dense(int64_t m, int64_t k, const float* A_dev, int64_t lda, int32
         HIP_TRY(hipMemcpyAsync(got, tot, sizeof(got), hipMemcpyDeviceToHost, s));
         HIP_TRY(hipStreamSynchronize(s));
         total = got[0];
-        largest = got[1];
     } else {
         HIP_TRY(hipMemsetAsync(idx, 0, 4, s));          // only the sentinel exists
+        HIP_TRY(hipMemsetAsync(tot, 0, 16, s));
     }
+    HIP_TRY(hipMemsetAsync(base + L0.counter + 16, 0, 4, s));   // no column can be out of range here
     if (total > (unsigned long long)INT32_MAX) return GCOO_EINVAL;
     const int64_t nnz = (int64_t)total;
     const Layout L = make_layout(m, k, nnz, g, p);
     if (dev_buf_bytes < L.total) return GCOO_ENOMEM;
     gcoo_matrix* h = nullptr;
-    int rc = new_handle(m, k, nnz, (int64_t)largest, p, dev_buf, &h);
+    int rc = new_handle(m, k, nnz, p, dev_buf, &h);
     if (rc != GCOO_OK) return rc;
     if (g > 0 && nnz > 0) {
         const dim3 grid((unsigned)(nblk * g)), block(gcoo::kDenseThreads);
@@ -575,43 +578,11 @@ int sched_width(int32_t p, const Shape& sh)
     if (p <= 32 && sh.al4) return 4;
     if (p <= 38 && sh.al4) return kTallInstance;
     if (p <= 64 && sh.al2) return 2;
-    // The one-column-per-lane instance (65 <= p <= 128, or operands aligned to 4 bytes only) is
-    // switched off: a run of it on an 8000 x 8000 matrix with p = 128 ended in a GPU memory
-    // fault whose cause has not been found, so it is not reachable until it is.  Such calls get
-    // the LDS kernel (automatic choice) or GCOO_EINVAL (explicit GCOO_VARIANT_REG).
+    // There is no one-column-per-lane instance (65 <= p <= 128, or operands aligned to 4 bytes only): a run
+    // of one on an 8000 x 8000 matrix with p = 128 ended in a GPU memory fault whose cause was never
+    // found, and it was taken out of the build.  Such calls get the LDS kernel (automatic choice) or
+    // GCOO_EINVAL (explicit GCOO_VARIANT_REG).
     return 0;
-}
-
-}  // namespace
-
-namespace {
-
-// When the launch has too few (group, tile) items to fill the machine, the longest group sets
-// the run time: groups well above the mean load of a wave slot are then shared by the eight
-// waves of a workgroup (spdm_sched_coop).  Sharing costs every wave a start-up per class and
-// window, so it is only used when the largest group stands out (four times the mean group, a
-// skewed matrix) or when plain waves would leave seven eighths of the machine idle.  Returns
-// the entry count from which a group is treated that way, INT32_MAX for "none".
-int32_t heavy_group_min(const gcoo_matrix* A, int64_t tiles, hipStream_t s)
-{
-    constexpr int64_t kWaveSlots = 2048;                   // 256 compute units x 8 resident waves of the register kernel
-    constexpr int64_t kMinHeavy = 1024;
-    const int64_t items = A->g * tiles;
-    if (items <= 0 || items > 2 * kWaveSlots || A->nnz <= 0) return INT32_MAX;
-    if (A->max_group_nnz < 0) {
-        // a matrix converted without any read-back: fetch the size of its largest group now (once)
-        unsigned long long got = 0;
-        if (hipMemcpyAsync(&got, A->base + A->L.counter + 8, 8, hipMemcpyDeviceToHost, s) != hipSuccess ||
-            hipStreamSynchronize(s) != hipSuccess)
-            return INT32_MAX;
-        A->max_group_nnz = (int64_t)got;
-    }
-    const int64_t mean_group = A->nnz / A->g;
-    if (A->max_group_nnz < 4 * mean_group && items * 8 > kWaveSlots) return INT32_MAX;
-    const int64_t mean_per_slot = A->nnz * tiles / kWaveSlots;
-    int64_t t = mean_per_slot + mean_per_slot / 2;
-    if (t < kMinHeavy) t = kMinHeavy;
-    return t >= INT32_MAX ? INT32_MAX : (int32_t)t;
 }
 
 }  // namespace
@@ -622,12 +593,16 @@ hipError_t launch_spdm_sched(int V, const SpdmArgs& a, hipStream_t s)
     if (V == 4) return launch_spdm_sched_v4(a, s);
     if (V == 38) return launch_spdm_sched_v4_tall(a, s);
     if (V == 2) return launch_spdm_sched_v2(a, s);
-    if (V == 1) return launch_spdm_sched_v1(a, s);
     return hipErrorInvalidValue;
 }
 }  // namespace gcoo
 
 namespace {
+
+bool share_operands_ok(const gcoo_matrix* A, const Shape& sh, int64_t ldb)
+{
+    return sh.al4 && (uint64_t)A->k * (uint64_t)ldb * 4u <= 0xffffffffull;
+}
 
 int check_spdm_args(const gcoo_matrix* A, const float* B, int64_t ldb, int64_t N, const float* C, int64_t ldc)
 {
@@ -646,12 +621,12 @@ int gcoo_spdm_pick(const gcoo_matrix* A, const float* B_dev, int64_t ldb, int64_
     int rc = check_spdm_args(A, B_dev, ldb, N, C_dev, ldc);
     if (rc != GCOO_OK) return rc;
     const Shape sh = shape_of(B_dev, ldb, N, C_dev, ldc);
-    // the band kernel wants enough workgroups to occupy the chip (one per 256 rows and 256 columns), and
-    // below 9000 columns its margin does not survive a last round that is mostly idle
-    const int64_t items = A->super_groups() * ((N + 255) / 256);
-    if (A->band_preferred && sh.al4 && !sh.wide_pitch && items >= 192 && (A->k >= 9000 || band_fill_of_rounds(items) >= 0.8))
-        return GCOO_VARIANT_BAND;
-    return sched_width(A->p, sh) ? GCOO_VARIANT_REG : GCOO_VARIANT_LDS;
+    // the workgroup-shared kernel wants enough workgroups to occupy the chip (one per 8p rows and 256 columns),
+    // and below 9000 columns its margin does not survive a last round that is mostly idle
+    const int64_t items = A->share_nq() * ((N + 255) / 256);
+    if (A->share_preferred && share_operands_ok(A, sh, ldb) && items >= 192 && (A->k >= 9000 || fill_of_rounds(items) >= 0.8))
+        return GCOO_VARIANT_SHARE;
+    return (A->has_sched && sched_width(A->p, sh)) ? GCOO_VARIANT_REG : GCOO_VARIANT_LDS;
 }
 
 int gcoo_spdm_variant(const gcoo_matrix* A, const float* B_dev, int64_t ldb, int64_t N, float* C_dev, int64_t ldc,
@@ -659,7 +634,7 @@ int gcoo_spdm_variant(const gcoo_matrix* A, const float* B_dev, int64_t ldb, int
 {
     int rc = check_spdm_args(A, B_dev, ldb, N, C_dev, ldc);
     if (rc != GCOO_OK) return rc;
-    if (variant < GCOO_VARIANT_AUTO || variant > GCOO_VARIANT_BAND) return GCOO_EINVAL;
+    if (variant < GCOO_VARIANT_AUTO || variant > GCOO_VARIANT_SHARE) return GCOO_EINVAL;
     if (variant == GCOO_VARIANT_AUTO) variant = gcoo_spdm_pick(A, B_dev, ldb, N, C_dev, ldc);
     if (A->m == 0 || N == 0) return GCOO_OK;
     hipStream_t s = static_cast<hipStream_t>(stream);
@@ -674,24 +649,23 @@ int gcoo_spdm_variant(const gcoo_matrix* A, const float* B_dev, int64_t ldb, int
         HIP_TRY(hipGetLastError());
         return GCOO_OK;
     }
-    if (variant == GCOO_VARIANT_BAND) {
-        if (!A->has_band || !shape_of(B_dev, ldb, N, C_dev, ldc).al4) return GCOO_EINVAL;
-        gcoo::BandArgs a{A->band_stream(), A->gIdxes(), A->band_ucount(), A->m, A->p, A->g, A->k, A->super_groups(),
-                         B_dev, ldb, N, C_dev, ldc};
-        hipError_t e = gcoo::launch_spdm_band(a, s);
-        if (e != hipSuccess) return hip_fail(e, "spdm_band launch");
+    if (variant == GCOO_VARIANT_SHARE) {
+        const Shape sh = shape_of(B_dev, ldb, N, C_dev, ldc);
+        if (!A->has_share || !share_operands_ok(A, sh, ldb)) return GCOO_EINVAL;
+        gcoo::ShareArgs a{A->share_hdr(), A->share_blocks(), A->share_sbase(), A->share_ucols(), A->share_ucount(), A->gIdxes(),
+                          A->m, A->p, A->g, A->share_nq(), B_dev, ldb, N, C_dev, ldc};
+        hipError_t e = gcoo::launch_spdm_share(a, s);
+        if (e != hipSuccess) return hip_fail(e, "spdm_share launch");
         return GCOO_OK;
     }
     const int V = sched_width(A->p, shape_of(B_dev, ldb, N, C_dev, ldc));
-    if (V == 0) return GCOO_EINVAL;
-    if (!A->sched_built) {                                        // left out at conversion: the band kernel was the expected one
-        int rc = launch_build_reg_schedule(A, s);
-        if (rc != GCOO_OK) return rc;
-    }
+    if (V == 0 || !A->has_sched) return GCOO_EINVAL;
     const int cols_per_lane = V == kTallInstance ? 4 : V;
-    // (heavy groups are shared by a workgroup in the standard instances only)
+    // Heavy groups are shared by a workgroup in the standard instances only, and only a launch of few
+    // items can have any: then the kernels decide group by group, from the statistics on the device.
+    const bool heavy = V != kTallInstance && gcoo::sched_heavy_possible(A->nnz, A->g, (N + 64 * cols_per_lane - 1) / (64 * cols_per_lane));
     gcoo::SpdmArgs a{A->sched_hdr(), A->sched(), A->gIdxes(), A->m, A->p, A->g, A->nw, B_dev, ldb, N, C_dev, ldc,
-                     V == kTallInstance ? INT32_MAX : heavy_group_min(A, (N + 64 * cols_per_lane - 1) / (64 * cols_per_lane), s)};
+                     A->nnz, heavy ? A->stats() : nullptr};
     hipError_t e = gcoo::launch_spdm_sched(V, a, s);
     if (e != hipSuccess) return hip_fail(e, "spdm_sched launch");
     return GCOO_OK;
@@ -736,27 +710,29 @@ int gcoo_export(const gcoo_matrix* A, float* values, int32_t* rows, int32_t* col
         hipError_t e = hipMemcpyAsync(narrow, A->gIdxes(), (size_t)(A->g + 1) * 4, hipMemcpyDeviceToHost, s);
         if (e != hipSuccess) { delete[] narrow; return hip_fail(e, "hipMemcpyAsync(gIdxes)"); }
     }
-    hipError_t e = hipStreamSynchronize(s);
+    uint32_t bad = 0;
+    hipError_t e = hipMemcpyAsync(&bad, A->bad_col(), 4, hipMemcpyDeviceToHost, s);
+    if (e == hipSuccess) e = hipStreamSynchronize(s);
     if (gIdxes && e == hipSuccess)
         for (int64_t i = 0; i <= A->g; ++i) gIdxes[i] = narrow[i];
     delete[] narrow;
     if (e != hipSuccess) return hip_fail(e, "hipStreamSynchronize");
-    return GCOO_OK;
+    return bad ? GCOO_EBOUNDS : GCOO_OK;
 }
 
-int64_t gcoo_band_words(const gcoo_matrix* A)
+int gcoo_export_share(const gcoo_matrix* A, uint32_t* hdr, uint32_t* blocks, int32_t* sbase, int32_t* ucount, int32_t* ucols,
+                      int64_t* hdr_words, int64_t* block_count, void* stream)
 {
-    if (!A || !A->has_band) return 0;
-    return gcoo::band_stream_words(A->nnz, A->g, A->k, A->band_w());
-}
-
-int gcoo_export_band(const gcoo_matrix* A, uint32_t* words, int32_t* ucount, int32_t* ucols, void* stream)
-{
-    if (!A || !A->has_band) return GCOO_EINVAL;
+    if (!A || !A->has_share) return GCOO_EINVAL;
     hipStream_t s = static_cast<hipStream_t>(stream);
-    if (words) HIP_TRY(hipMemcpyAsync(words, A->band_stream(), (size_t)gcoo_band_words(A) * 4, hipMemcpyDeviceToHost, s));
-    if (ucount) HIP_TRY(hipMemcpyAsync(ucount, A->band_ucount(), (size_t)A->super_groups() * 4, hipMemcpyDeviceToHost, s));
-    if (ucols && A->nnz) HIP_TRY(hipMemcpyAsync(ucols, A->band_ucols(), (size_t)A->nnz * 4, hipMemcpyDeviceToHost, s));
+    const int64_t hw = gcoo::share_hdr_words(A->nnz, A->g), nb = gcoo::share_stream_blocks(A->nnz, A->g, A->k);
+    if (hdr_words) *hdr_words = hw;
+    if (block_count) *block_count = nb;
+    if (hdr) HIP_TRY(hipMemcpyAsync(hdr, A->share_hdr(), (size_t)hw * 4, hipMemcpyDeviceToHost, s));
+    if (blocks) HIP_TRY(hipMemcpyAsync(blocks, A->share_blocks(), (size_t)nb * gcoo::kShareBlockWords * 4, hipMemcpyDeviceToHost, s));
+    if (sbase) HIP_TRY(hipMemcpyAsync(sbase, A->share_sbase(), (size_t)A->share_nq() * gcoo::kShareW * 4, hipMemcpyDeviceToHost, s));
+    if (ucount) HIP_TRY(hipMemcpyAsync(ucount, A->share_ucount(), (size_t)A->share_nq() * 4, hipMemcpyDeviceToHost, s));
+    if (ucols && A->nnz) HIP_TRY(hipMemcpyAsync(ucols, A->share_ucols(), (size_t)A->nnz * 4, hipMemcpyDeviceToHost, s));
     HIP_TRY(hipStreamSynchronize(s));
     return GCOO_OK;
 }

@@ -54,9 +54,11 @@ __global__ __launch_bounds__(256) void group_stats_from_row_ptr(const int32_t* _
 // ---------------------------------------------------------------------------------------------
 __global__ __launch_bounds__(256) void group_index_from_row_ptr(const int32_t* __restrict__ row_ptr, int64_t m, int32_t p, int64_t g,
                                                                  int32_t nnz, int32_t* __restrict__ gIdxes,
-                                                                 int32_t* __restrict__ nnzPerGroup, unsigned long long* __restrict__ stats)
+                                                                 int32_t* __restrict__ nnzPerGroup, unsigned long long* __restrict__ stats,
+                                                                 uint32_t* __restrict__ bad_col)
 {
     if (stats && blockIdx.x == gridDim.x - 1) {                   // the whole workgroup
+        if (threadIdx.x == 0) *bad_col = 0u;                      // set by the sort that follows if it meets a column out of range
         group_stats_block(row_ptr, m, p, g, stats);
         return;
     }
@@ -109,8 +111,9 @@ __device__ __forceinline__ uint64_t match_digit(uint32_t d, bool is_active)
 // slot = that running base + number of earlier entries of the 64 with the same digit (ballots).
 // Nothing depends on timing: counts are sums, ranks come from ballots.
 //
-// FIRST: the source is the CSR input itself (row of an entry = search in row_ptr); otherwise the
-// source is the (cols, rows, values) triple written by the previous pass.
+// FIRST: the source is the CSR input itself (row of an entry = search in row_ptr; columns are forced
+// into [0, kcols) and *bad_col is set if one was outside); otherwise the source is the (cols, rows,
+// values) triple written by the previous pass.
 //
 // nb > 0: the workgroup sorts one bucket of one group instead of a whole group.  The pass before
 // it has sorted the group by the digit above (col >> 8, nb values); bucket b of group q is the
@@ -127,8 +130,12 @@ template <bool FIRST, int WAVES>
 __global__ __launch_bounds__(WAVES * kWave) void sort_groups_by_col_digit(
     const int32_t* __restrict__ gIdxes, const int32_t* __restrict__ row_ptr, int64_t m, int32_t p,
     const int32_t* __restrict__ src_cols, const int32_t* __restrict__ src_rows, const float* __restrict__ src_vals,
-    int32_t* __restrict__ dst_cols, int32_t* __restrict__ dst_rows, float* __restrict__ dst_vals, int shift, int32_t nb)
+    int32_t* __restrict__ dst_cols, int32_t* __restrict__ dst_rows, float* __restrict__ dst_vals, int shift, int32_t nb,
+    int32_t kcols, uint32_t* __restrict__ bad_col)
 {
+    // FIRST: a column of the input outside [0, kcols) is stored clamped into that range and reported in
+    // *bad_col, so that no later kernel forms an address outside B from it
+    auto in_range = [&](int32_t c) { return FIRST ? (c < 0 ? 0 : (c >= kcols ? kcols - 1 : c)) : c; };
     __shared__ int32_t slot_of[WAVES][256];      // counts, then running slots, per wave and digit
     __shared__ int32_t total[256];
     __shared__ int32_t rp_s[FIRST ? 257 : 1];         // FIRST: row_ptr of the group's rows (at most 256 + 1), searched per entry
@@ -168,7 +175,7 @@ __global__ __launch_bounds__(WAVES * kWave) void sort_groups_by_col_digit(
     for (int i = tid; i < WAVES * 256; i += WAVES * kWave) (&slot_of[0][0])[i] = 0;
     __syncthreads();
     for (int32_t e = pb + lane; e < pe; e += kWave)
-        atomicAdd(&slot_of[wv][((uint32_t)src_cols[e] >> shift) & 255u], 1);   // counts only: order-free
+        atomicAdd(&slot_of[wv][((uint32_t)in_range(src_cols[e]) >> shift) & 255u], 1);   // counts only: order-free
     __syncthreads();
     if (tid < 256) {
         int32_t run = 0;
@@ -215,6 +222,8 @@ __global__ __launch_bounds__(WAVES * kWave) void sort_groups_by_col_digit(
             col = src_cols[e];
             val = src_vals[e];
             if (FIRST) {
+                const int32_t c = in_range(col);
+                if (c != col) { *bad_col = 1u; col = c; }
                 // row r with row_ptr[r] <= e < row_ptr[r+1]; empty rows are skipped by the upper bound
                 int32_t lo = 0, hi = (int32_t)(r_hi - r_lo);      // answer in [lo, hi), relative to the group's first row
                 while (hi - lo > 1) {

@@ -51,7 +51,7 @@ constexpr int kSchedPad = 64;            // words per (group, window) for class 
 constexpr int kSchedSlack = 128;         // words after the last group (whole-line reads)
 constexpr int kMaxWindows = 32;
 // Tallest group the register kernel serves.  The layout itself (rows as bytes, row p included)
-// and the one-column-per-lane instance reach p = 128, but that instance is switched off: see
+// and the one-column-per-lane instance reach p = 128, but that instance is not part of the build: see
 // sched_width() in gcoo_api.hip.
 constexpr int kSchedMaxP = 64;
 
@@ -84,5 +84,32 @@ struct SchedClass {
     int32_t first_word;   // of the pre-block, relative to the group's base
     int32_t bodies;       // nb
 };
+
+// When a launch has too few (group, tile) items to fill the machine, the longest group sets the run
+// time: groups well above the mean load of a wave slot are then shared by the eight waves of a
+// workgroup (spdm_sched_coop).  Sharing costs every wave a start-up per class and window, so it is
+// only used when the largest group stands out (four times the mean group, a skewed matrix) or when
+// plain waves would leave seven eighths of the machine idle.  Returns the entry count from which a
+// group is treated that way, INT32_MAX for "none".  Evaluated on the device from the statistics the
+// conversion left there (largest = entries of the largest group), so that a launch needs nothing
+// from the host but the shape; the host evaluates only the part that does not need `largest`.
+constexpr int64_t kHeavyWaveSlots = 2048;                  // 256 compute units x 8 resident waves of the register kernel
+constexpr int64_t kHeavyMin = 1024;
+__host__ __device__ inline bool sched_heavy_possible(int64_t nnz, int64_t g, int64_t tiles)
+{
+    const int64_t items = g * tiles;
+    return items > 0 && items <= 2 * kHeavyWaveSlots && nnz > 0;
+}
+__host__ __device__ inline int32_t sched_heavy_min(int64_t nnz, int64_t g, int64_t tiles, int64_t largest)
+{
+    if (!sched_heavy_possible(nnz, g, tiles)) return 0x7fffffff;
+    const int64_t items = g * tiles;
+    const int64_t mean_group = nnz / g;
+    if (largest < 4 * mean_group && items * 8 > kHeavyWaveSlots) return 0x7fffffff;
+    const int64_t mean_per_slot = nnz * tiles / kHeavyWaveSlots;
+    int64_t t = mean_per_slot + mean_per_slot / 2;
+    if (t < kHeavyMin) t = kHeavyMin;
+    return t >= 0x7fffffff ? 0x7fffffff : (int32_t)t;
+}
 
 }  // namespace gcoo

@@ -1,0 +1,245 @@
+// Kernels that write the share schedule (layout in gcoo_share.hpp) from the finished GCOO arrays: the
+// distinct columns of every super-group (share_union), then headers and records (share_fill).
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "gcoo_share.hpp"
+
+namespace gcoo {
+
+constexpr int kShareBuildThreads = 1024;
+constexpr int kShareBuildWaves = kShareBuildThreads / 64;
+
+
+// Exclusive prefix sum over the kShareBuildThreads values `mine` (one per thread); returns this
+// thread's offset and leaves the total in *total_s (shared).  `wsum` is shared scratch.
+__device__ __forceinline__ int32_t share_block_scan(int32_t mine, int32_t* wsum, int32_t* total_s)
+{
+    const int lane = threadIdx.x & 63, wv = threadIdx.x >> 6;
+    int32_t incl = mine;
+#pragma unroll
+    for (int d = 1; d < 64; d <<= 1) {
+        const int32_t t = __shfl_up(incl, d, 64);
+        if (lane >= d) incl += t;
+    }
+    if (lane == 63) wsum[wv] = incl;
+    __syncthreads();
+    int32_t off = incl - mine;
+    for (int j = 0; j < wv; ++j) off += wsum[j];
+    if (threadIdx.x == kShareBuildThreads - 1) *total_s = off + mine;
+    __syncthreads();
+    return off;
+}
+
+// ---------------------------------------------------------------------------------------------
+// ucols(Q): one workgroup per super-group marks the columns of its entries in a bitmap in LDS
+// (bit sets commute, so the order of the atomics is irrelevant), counts the bits in front of every
+// bitmap word and lists the set bits in ascending order.  ucols(Q) is written to the slice of
+// `ucols` that starts at the super-group's first entry (it cannot be longer than its entries).
+// Dynamic LDS: ceil(k/32) words.
+// ---------------------------------------------------------------------------------------------
+__global__ __launch_bounds__(kShareBuildThreads) void share_union(const int32_t* __restrict__ gIdxes, const int32_t* __restrict__ cols,
+                                                               int64_t g, int64_t k, int32_t W,
+                                                               int32_t* __restrict__ ucols, int32_t* __restrict__ ucount,
+                                                               uint32_t* __restrict__ zeroed = nullptr)
+{
+    if (zeroed && blockIdx.x == 0 && threadIdx.x == 0) *zeroed = 0u;   // a counter of the kernel that runs next
+    extern __shared__ uint32_t share_union_lds[];
+    __shared__ int32_t wsum[kShareBuildWaves];
+    __shared__ int32_t total_s;
+    const int32_t nbw = (int32_t)((k + 31) / 32);
+    uint32_t* bits = share_union_lds;
+    const int64_t Q = blockIdx.x;
+    const int64_t q0 = Q * W, q1 = (q0 + W < g) ? q0 + W : g;
+    const int32_t e0 = gIdxes[q0], e1 = gIdxes[q1];
+    for (int32_t i = threadIdx.x; i < nbw; i += kShareBuildThreads) bits[i] = 0u;
+    __syncthreads();
+    for (int32_t e = e0 + (int32_t)threadIdx.x; e < e1; e += kShareBuildThreads) {
+        const uint32_t c = (uint32_t)cols[e];
+        atomicOr(&bits[c >> 5], 1u << (c & 31u));
+    }
+    __syncthreads();
+    // thread t owns the words [t*per, (t+1)*per)
+    const int32_t per = (nbw + kShareBuildThreads - 1) / kShareBuildThreads;
+    const int32_t w0 = (int32_t)threadIdx.x * per, w1 = (w0 + per < nbw) ? w0 + per : nbw;
+    int32_t mine = 0;
+    for (int32_t w = w0; w < w1; ++w) mine += __popc(bits[w]);
+    int32_t at = e0 + share_block_scan(mine, wsum, &total_s);
+    for (int32_t w = w0; w < w1; ++w) {
+        uint32_t b = bits[w];
+        while (b) {
+            const int bit = __ffs(b) - 1;
+            b &= b - 1u;
+            ucols[at++] = w * 32 + bit;
+        }
+    }
+    if (threadIdx.x == 0) ucount[Q] = total_s;
+}
+
+
+// Where entry i of a (group, band) that spans [s, e) stands in its run.  A run is a maximal stretch of one
+// column, cut into stretches of kShareRunCap from its first entry.  Writes the entry's place in its stretch
+// and the stretch's length.
+__device__ __forceinline__ void share_place(const int32_t* __restrict__ cols, int32_t s, int32_t e, int32_t i, int32_t* x, int32_t* len)
+{
+    const int32_t c = cols[i];
+    int32_t rs = i;
+    while (rs > s && cols[rs - 1] == c) --rs;
+    rs += (i - rs) / kShareRunCap * kShareRunCap;
+    int32_t re = i + 1;
+    while (re < e && re < rs + kShareRunCap && cols[re] == c) ++re;
+    *x = i - rs;
+    *len = re - rs;
+}
+
+typedef uint32_t share_u32x4 __attribute__((ext_vector_type(4)));
+
+// One workgroup per stream q = 8Q + w, also for the groups behind the last one of the last super-group
+// (their streams are empty, their headers zero).  Band b of the group is the entry range
+// [bstart[b], bstart[b+1]).  Pass 1 (a wave per band): quads and singles of every band -> header, blocks
+// of the band; prefix sum over the bands; the stream's place is taken from the atomic counter `alloc`
+// (zero before the launch).  Pass 2 (the same waves): the records.
+// Dynamic LDS: 2 * (ceil(k / 48) + 1) words.
+__global__ __launch_bounds__(kShareBuildThreads) void share_fill(const int32_t* __restrict__ gIdxes, const int32_t* __restrict__ rows,
+                                                                const int32_t* __restrict__ cols, const float* __restrict__ values,
+                                                                int32_t p, int64_t g, int64_t k, const int32_t* __restrict__ ucols,
+                                                                const int32_t* __restrict__ ucount, uint32_t* __restrict__ hdr,
+                                                                uint32_t* __restrict__ blocks, int32_t* __restrict__ sbase,
+                                                                uint32_t* __restrict__ alloc)
+{
+    extern __shared__ uint32_t share_lds[];
+    __shared__ int32_t wsum[kShareBuildWaves];
+    __shared__ int32_t total_s;
+    __shared__ int32_t carry_s;
+    __shared__ int32_t base_s;
+    const int lane = threadIdx.x & 63, wv = threadIdx.x >> 6;
+    const int64_t q = blockIdx.x, Q = q / kShareW;
+    const int w = (int)(q - Q * kShareW);
+    const int32_t first = gIdxes[Q * kShareW < g ? Q * kShareW : g];
+    const int32_t first_next = gIdxes[(Q + 1) * kShareW < g ? (Q + 1) * kShareW : g];
+    const int32_t nU = ucount[Q];
+    const int32_t NB = (nU + kShareBandRows - 1) / kShareBandRows;
+    const int32_t* uc = ucols + first;
+    const int32_t beg = gIdxes[q < g ? q : g], end = gIdxes[q < g ? q + 1 : g];
+    const int32_t row0 = (int32_t)(q * p);
+    const int64_t hb = share_hdr_base(first, Q), cap = share_hdr_base(first_next, Q + 1) - hb;
+    uint32_t* hd = hdr + 2 * (hb * kShareW + w * cap);
+    int32_t* bstart = reinterpret_cast<int32_t*>(share_lds);         // [NB + 1]
+    int32_t* boff = bstart + ((k + kShareBandRows - 1) / kShareBandRows + 1);   // [NB + 1] blocks per band, then offsets
+
+    for (int32_t b = threadIdx.x; b <= NB; b += kShareBuildThreads) {
+        int32_t lo = beg, hi = end;
+        if (b < NB) {
+            const int32_t c = uc[b * kShareBandRows];
+            while (lo < hi) {
+                const int32_t mid = lo + (hi - lo) / 2;
+                if (cols[mid] < c) lo = mid + 1; else hi = mid;
+            }
+        } else {
+            lo = end;
+        }
+        bstart[b] = lo;
+    }
+    if (threadIdx.x == 0) carry_s = 0;
+    __syncthreads();
+
+    // pass 1
+    for (int32_t b = wv; b < NB; b += kShareBuildWaves) {
+        const int32_t s = bstart[b], e = bstart[b + 1];
+        int32_t members = 0, singles = 0;
+        for (int32_t i = s + lane; i < e; i += 64) {
+            int32_t x, len;
+            share_place(cols, s, e, i, &x, &len);
+            if (x < (len & ~3)) ++members; else ++singles;
+        }
+#pragma unroll
+        for (int d = 32; d >= 1; d >>= 1) {
+            members += __shfl_xor(members, d, 64);
+            singles += __shfl_xor(singles, d, 64);
+        }
+        const int32_t nq = members / 4, ns4 = (singles + 3) / 4;
+        if (lane == 0) {
+            hd[(int64_t)b * 2] = (uint32_t)nq;
+            hd[(int64_t)b * 2 + 1] = (uint32_t)ns4;
+            boff[b] = (nq + 3) / 4 + (ns4 + 3) / 4;
+        }
+    }
+    __syncthreads();
+    // exclusive prefix sum of the blocks per band, kShareBuildThreads bands at a time
+    for (int32_t t0 = 0; t0 < NB; t0 += kShareBuildThreads) {
+        const int32_t b = t0 + (int32_t)threadIdx.x;
+        const int32_t mine = b < NB ? boff[b] : 0;
+        const int32_t off = share_block_scan(mine, wsum, &total_s);
+        if (b < NB) boff[b] = carry_s + off;
+        __syncthreads();
+        if (threadIdx.x == 0) carry_s += total_s;
+        __syncthreads();
+    }
+    if (threadIdx.x == 0) {
+        const int32_t base = (int32_t)atomicAdd(alloc, (uint32_t)carry_s);
+        base_s = base;
+        sbase[q] = base;
+    }
+    __syncthreads();
+    share_u32x4* out = reinterpret_cast<share_u32x4*>(blocks) + (int64_t)base_s * 16;
+    const share_u32x4 unused = {0u, (uint32_t)kShareSink, 0u, 0u};
+
+    // pass 2
+    for (int32_t b = wv; b < NB; b += kShareBuildWaves) {
+        const int32_t s = bstart[b], e = bstart[b + 1];
+        if (s >= e) continue;
+        const int32_t nc = (nU - b * kShareBandRows < kShareBandRows) ? nU - b * kShareBandRows : kShareBandRows;
+        // the band's columns, one per lane (ascending; lanes past the end hold a column no entry has): an
+        // entry's slot is then a lower bound over the lanes, six exchanges
+        const int32_t band_col_of_lane = lane < nc ? uc[b * kShareBandRows + lane] : INT32_MAX;
+        share_u32x4* qblk = out + (int64_t)boff[b] * 16;
+        int32_t members_before = 0, singles_before = 0;         // in the tiles before this one
+        int32_t nq_blocks = 0;                                    // known after the walk: S blocks sit behind the Q blocks
+        // the Q blocks need the band's quad count first: it is in the header this workgroup wrote in pass 1
+        const int32_t nq = (int32_t)hd[(int64_t)b * 2], ns4 = (int32_t)hd[(int64_t)b * 2 + 1];
+        nq_blocks = (nq + 3) / 4;
+        share_u32x4* sblk = qblk + (int64_t)nq_blocks * 16;
+        for (int32_t cur = s; cur < e; cur += 64) {
+            const int32_t i = cur + lane;
+            const bool live = i < e;
+            int32_t x = 0, len = 0, col = 0;
+            if (live) {
+                share_place(cols, s, e, i, &x, &len);
+                col = cols[i];
+            }
+            const bool member = live && x < (len & ~3);
+            const bool single = live && !member;
+            const uint64_t mm = __ballot(member), sm = __ballot(single);
+            const uint64_t below = (1ull << lane) - 1ull;
+            int32_t slot = 0;
+#pragma unroll
+            for (int step = 32; step >= 1; step >>= 1) {
+                const int32_t probe = __shfl(band_col_of_lane, slot + step - 1, 64);
+                if (probe < col) slot += step;
+            }
+            if (live) {
+                const share_u32x4 rec = {__float_as_uint(values[i]), (uint32_t)(rows[i] - row0), (uint32_t)slot * 1024u, 0u};
+                if (member) {
+                    const int32_t u = x & 3;
+                    const int32_t rank = (members_before + __popcll(mm & below) - u) / 4;
+                    qblk[(int64_t)(rank / 4) * 16 + (rank % 4) * 4 + u] = rec;
+                } else {
+                    const int32_t rank = singles_before + __popcll(sm & below);
+                    sblk[(int64_t)(rank / 16) * 16 + rank % 16] = rec;
+                }
+            }
+            members_before += __popcll(mm);
+            singles_before += __popcll(sm);
+        }
+        // records that no entry owns
+        {
+            const int32_t used = nq * 4, room = nq_blocks * 16;
+            if (used + lane < room) qblk[used + lane] = unused;
+            const int32_t sused = singles_before, sroom = ((ns4 + 3) / 4) * 16;
+            if (sused + lane < sroom) sblk[sused + lane] = unused;
+        }
+    }
+}
+
+}  // namespace gcoo

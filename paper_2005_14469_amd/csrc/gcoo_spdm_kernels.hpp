@@ -372,7 +372,7 @@ template <int V>
 __global__ __launch_bounds__(64) void spdm_sched(const SchedClass* __restrict__ hdr, const uint32_t* __restrict__ stream,
                                                  const int32_t* __restrict__ gIdxes, int64_t m, int32_t p, int64_t g,
                                                  int32_t nw, const float* __restrict__ B, int64_t ldb, int64_t N, float* __restrict__ C,
-                                                 int64_t ldc, int64_t total, int32_t heavy_min)
+                                                 int64_t ldc, int64_t total, int64_t nnz, const unsigned long long* __restrict__ stats)
 {
     // XCD-aware order: workgroup ids go round-robin over the 8 XCDs, so XCD x is given the
     // contiguous slice [x*per, (x+1)*per) of the (tile-major) work list: it walks through all
@@ -384,6 +384,8 @@ __global__ __launch_bounds__(64) void spdm_sched(const SchedClass* __restrict__ 
     if (w >= total) return;
     const int64_t tile = w / g, q = w - tile * g;
     // groups with heavy_min entries or more are left to spdm_sched_coop (launched beside this kernel)
+    const int32_t heavy_min = stats ? sched_heavy_min(nnz, g, (N + 64 * V - 1) / (64 * V), (int64_t)__builtin_amdgcn_readfirstlane((uint32_t)stats[1]))
+                                    : 0x7fffffff;
     const int32_t first_entry = __builtin_amdgcn_readfirstlane(gIdxes[q]);
     if (__builtin_amdgcn_readfirstlane(gIdxes[q + 1]) - first_entry >= heavy_min) return;
 
@@ -468,7 +470,8 @@ template <int V>
 __global__ __launch_bounds__(64 * kCoopWaves) void spdm_sched_coop(const SchedClass* __restrict__ hdr, const uint32_t* __restrict__ stream,
                                                                    const int32_t* __restrict__ gIdxes, int64_t m, int32_t p, int64_t g,
                                                                    int32_t nw, const float* __restrict__ B, int64_t ldb, int64_t N,
-                                                                   float* __restrict__ C, int64_t ldc, int64_t total, int32_t heavy_min)
+                                                                   float* __restrict__ C, int64_t ldc, int64_t total, int64_t nnz,
+                                                                   const unsigned long long* __restrict__ stats)
 {
     constexpr int S = acc_stride<V>(), P = S - 1;          // rows an instance can hold
     __shared__ __attribute__((aligned(16))) uint32_t ring_mem[kCoopWaves][kRing * kLineWords];
@@ -477,6 +480,7 @@ __global__ __launch_bounds__(64 * kCoopWaves) void spdm_sched_coop(const SchedCl
     const int64_t w = blockIdx.x;                          // tile-major like spdm_sched
     if (w >= total) return;
     const int64_t tile = w / g, q = w - tile * g;
+    const int32_t heavy_min = sched_heavy_min(nnz, g, (N + 64 * V - 1) / (64 * V), (int64_t)__builtin_amdgcn_readfirstlane((uint32_t)stats[1]));
     const int32_t first_entry = __builtin_amdgcn_readfirstlane(gIdxes[q]);
     if (__builtin_amdgcn_readfirstlane(gIdxes[q + 1]) - first_entry < heavy_min) return;   // the whole workgroup
 
@@ -566,16 +570,16 @@ hipError_t launch_spdm_sched_instance(const SpdmArgs& a, hipStream_t s)
     if (a.ldb > 0x3fffffffLL) return hipErrorInvalidValue;   // row pitch in bytes is kept in 32 bits
     if (a.p + 1 > acc_stride<V>()) return hipErrorInvalidValue;
     spdm_sched<V><<<dim3((unsigned)grid), dim3(64), 0, s>>>(a.hdr, a.stream, a.gIdxes, a.m, a.p, a.g, a.nw, a.B, a.ldb, a.N,
-                                                            a.C, a.ldc, total, a.heavy_min);
+                                                            a.C, a.ldc, total, a.nnz, a.stats);
     hipError_t e = hipGetLastError();
-    if (e != hipSuccess || a.heavy_min == INT32_MAX) return e;
+    if (e != hipSuccess || !a.stats) return e;
 #ifdef GCOO_ACC_TALL
     // no workgroup-shared kernel in this layout: with 100 VGPRs it does not fit without spilling
     // registers whose loads are in flight
     return hipErrorInvalidValue;
 #else
     spdm_sched_coop<V><<<dim3((unsigned)total), dim3(64 * kCoopWaves), 0, s>>>(a.hdr, a.stream, a.gIdxes, a.m, a.p, a.g, a.nw, a.B,
-                                                                              a.ldb, a.N, a.C, a.ldc, total, a.heavy_min);
+                                                                              a.ldb, a.N, a.C, a.ldc, total, a.nnz, a.stats);
     return hipGetLastError();
 #endif
 }

@@ -22,28 +22,33 @@ struct SpdmArgs {
     int64_t N;
     float* C;
     int64_t ldc;
-    int32_t heavy_min;         // groups with this many entries or more go to the workgroup-shared kernel (INT32_MAX: none)
+    int64_t nnz;
+    // statistics of the conversion on the device ([1] = entries of the largest group), from which the
+    // kernels derive the entry count from which a group goes to spdm_sched_coop; nullptr: no group does
+    const unsigned long long* stats;
 };
 
 // V = 4 needs p <= 32, V = 38 (four columns per lane, tall accumulator file) p <= 38, V = 2 needs
-// p <= 64, V = 1 needs p <= 128; N, ldb, ldc and both base addresses must be multiples of the
-// columns per lane.  Anything else returns hipErrorInvalidValue.
+// p <= 64; N, ldb, ldc and both base addresses must be multiples of the columns per lane.
+// Anything else returns hipErrorInvalidValue.
 hipError_t launch_spdm_sched(int V, const SpdmArgs& a, hipStream_t s);
 
 hipError_t launch_spdm_sched_v4(const SpdmArgs& a, hipStream_t s);
 hipError_t launch_spdm_sched_v4_tall(const SpdmArgs& a, hipStream_t s);
 hipError_t launch_spdm_sched_v2(const SpdmArgs& a, hipStream_t s);
-hipError_t launch_spdm_sched_v1(const SpdmArgs& a, hipStream_t s);
 
-// The workgroup-shared kernel (band schedule): p <= 32; N, ldb, ldc multiples of 4; B and C 16-byte aligned.
-struct BandArgs {
-    const uint32_t* stream;    // band schedule
-    const int32_t* gIdxes;     // [g+1]
-    const int32_t* ucount;     // [nq] distinct columns per super-group
+// The workgroup-shared kernel that reads the share schedule: p <= 48; N, ldb, ldc multiples of 4; B and C
+// 16-byte aligned; every row offset of B in bytes below 2^32.
+struct ShareArgs {
+    const uint32_t* hdr;       // headers
+    const uint32_t* blocks;    // streams
+    const int32_t* sbase;      // [8 * nq] first block of every stream
+    const int32_t* ucols;      // distinct columns per super-group, the list of Q starting at gIdxes[8Q]
+    const int32_t* ucount;     // [nq]
+    const int32_t* gIdxes;     // [g + 1]
     int64_t m;
     int32_t p;
     int64_t g;
-    int64_t k;
     int64_t nq;                // super-groups
     const float* B;
     int64_t ldb;
@@ -51,6 +56,6 @@ struct BandArgs {
     float* C;
     int64_t ldc;
 };
-hipError_t launch_spdm_band(const BandArgs& a, hipStream_t s);
+hipError_t launch_spdm_share(const ShareArgs& a, hipStream_t s);
 
 }  // namespace gcoo

@@ -6,7 +6,7 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
-#include "gcoo.h"
+#include "gcoo_baseline.h"
 
 namespace gcoo {
 
@@ -45,17 +45,17 @@ extern "C" int gcoo_csr_spmm_baseline(int64_t m, int64_t k, const int32_t* row_p
                                       const float* vals_dev, const float* B_dev, int64_t ldb, int64_t N, float* C_dev,
                                       int64_t ldc, void* stream)
 {
-    if (m < 0 || k < 0 || N < 0 || ldb < N || ldc < N || !row_ptr_dev) return GCOO_EINVAL;
-    if (m == 0 || N == 0) return GCOO_OK;
-    if (!C_dev || !B_dev) return GCOO_EINVAL;
+    if (m < 0 || k < 0 || N < 0 || ldb < N || ldc < N || !row_ptr_dev) return -1;
+    if (m == 0 || N == 0) return 0;
+    if (!C_dev || !B_dev) return -1;
     const uintptr_t pb = reinterpret_cast<uintptr_t>(B_dev), pc = reinterpret_cast<uintptr_t>(C_dev);
     const bool v4 = (N % 4 == 0) && (ldb % 4 == 0) && (ldc % 4 == 0) && (pb % 16 == 0) && (pc % 16 == 0);
     const int V = v4 ? 4 : 1;
     const int64_t tiles = (N + 64 * V - 1) / (64 * V);
-    if (m > 0x7fffffffLL / tiles) return GCOO_EINVAL;
+    if (m > 0x7fffffffLL / tiles) return -1;
     hipStream_t s = static_cast<hipStream_t>(stream);
     const dim3 grid((unsigned)(m * tiles)), block(64);
     if (v4) gcoo::csr_spmm_rowsplit<4><<<grid, block, 0, s>>>(row_ptr_dev, col_idx_dev, vals_dev, m, B_dev, ldb, N, C_dev, ldc, tiles);
     else gcoo::csr_spmm_rowsplit<1><<<grid, block, 0, s>>>(row_ptr_dev, col_idx_dev, vals_dev, m, B_dev, ldb, N, C_dev, ldc, tiles);
-    return hipGetLastError() == hipSuccess ? GCOO_OK : GCOO_EHIP;
+    return hipGetLastError() == hipSuccess ? 0 : -4;
 }

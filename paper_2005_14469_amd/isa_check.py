@@ -186,15 +186,16 @@ def check(asm_text: str, mangled_prefix: str):
     return sorted(load_regs), bad
 
 
-def check_lds_loads(asm_text: str, mangled_prefix: str):
+def check_lds_loads(asm_text: str, mangled_prefix: str, in_flight: int = 0):
     """Loads that write LDS directly (`global_load_lds_*`) in a kernel that also uses the VGPR index mode.
 
     Such a load takes the LDS address of lane 0 from M0, and `s_set_gpr_idx_on/idx` overwrite M0.
     Returns (number of such loads, list of problems).  Proved on the text, block by block:
       * walking back from every such load, an instruction that writes M0 as a plain destination
         (`s_mov_b32 m0`, `s_add_i32 m0`, ...) comes before any label, branch or index-mode instruction;
-      * walking back from every `s_barrier`, an `s_waitcnt` that names vmcnt(0) comes before any such load
-        (what a wave has sent to LDS has arrived before the other waves are let past the barrier).
+      * walking back from every `s_barrier`, an `s_waitcnt` that names vmcnt(n), n <= in_flight, comes before
+        any such load (what a wave has sent to LDS has arrived before the other waves are let past the
+        barrier, except the youngest in_flight loads, which a kernel may keep on their way on purpose).
     """
     body = [l.split(";")[0].strip() for l in kernel_body(asm_text, mangled_prefix)]
     body = [l for l in body if l]
@@ -218,7 +219,8 @@ def check_lds_loads(asm_text: str, mangled_prefix: str):
             j = i - 1
             while j >= 0:
                 t = body[j]
-                if t.startswith("s_waitcnt") and "vmcnt(0)" in t:
+                waited = re.search(r"vmcnt\((\d+)\)", t) if t.startswith("s_waitcnt") else None
+                if waited and int(waited.group(1)) <= in_flight:
                     break
                 if t.startswith("global_load_lds"):
                     problems.append(f"line {i}: barrier with a load to LDS ('{t}') not awaited")

@@ -19,13 +19,23 @@ def L():
     return binding.lib()
 
 
-def test_header_symbols_are_exported(L):
-    text = open(os.path.join(ROOT, "include", "gcoo.h")).read()
+def _declared(header):
+    text = open(os.path.join(ROOT, "include", header)).read()
     text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
-    declared = set(re.findall(r"\b(gcoo_[a-z_]+)\s*\(", text))
+    return set(re.findall(r"\b(gcoo_[a-z_]+)\s*\(", text))
+
+
+def test_header_symbols_are_exported(L):
+    declared = _declared("gcoo.h")
     assert declared == set(binding.SYMBOLS)
     for name in declared:
         assert hasattr(L, name), name
+    base = _declared("gcoo_baseline.h")
+    assert base == set(binding.BASELINE_SYMBOLS)
+    for name in base:
+        assert hasattr(binding.baseline_lib(), name), name
+        assert not hasattr(L, name), "the comparison routine is not part of the product library"
+    assert sorted(os.listdir(os.path.join(ROOT, "include"))) == ["gcoo.h", "gcoo_baseline.h"]
 
 
 def test_device_bytes_covers_table_1_footprint(L):
@@ -95,38 +105,53 @@ def test_newer_entry_points_reject_bad_arguments_on_the_host(L):
     assert L.gcoo_from_csr_device(2, 2, 1, fake, fake, fake, 2, fake, 16, None, C.byref(out)) == binding.GCOO_ENOMEM
     assert L.gcoo_from_csr_device(2, 2, 1, fake, None, None, 2, fake, 1 << 20, None, C.byref(out)) == binding.GCOO_EINVAL
     assert out.value is None
-    # band schedule policy and introspection
-    assert L.gcoo_set_band_policy(-1) == binding.GCOO_EINVAL
-    assert L.gcoo_set_band_policy(3) == binding.GCOO_EINVAL
-    assert L.gcoo_set_band_policy(binding.BAND_AUTO) == 0
-    assert L.gcoo_band_words(None) == 0
-    assert L.gcoo_export_band(None, None, None, None, None) == binding.GCOO_EINVAL
+    # share schedule policy and introspection
+    assert L.gcoo_set_share_policy(-1) == binding.GCOO_EINVAL
+    assert L.gcoo_set_share_policy(3) == binding.GCOO_EINVAL
+    assert L.gcoo_set_share_policy(binding.SHARE_AUTO) == 0
+    assert L.gcoo_export_share(None, None, None, None, None, None, None, None, None) == binding.GCOO_EINVAL
     assert L.gcoo_spdm_pick(None, None, 4, 4, None, 4) == binding.GCOO_EINVAL
     for variant in (-1, 4):
         assert L.gcoo_spdm_variant(None, None, 4, 4, None, 4, None, variant) == binding.GCOO_EINVAL
-    # CSR baseline kernel: shapes are checked before anything is launched
-    assert L.gcoo_csr_spmm_baseline(-1, 2, fake, fake, fake, fake, 4, 4, fake, 4, None) == binding.GCOO_EINVAL
-    assert L.gcoo_csr_spmm_baseline(2, 2, None, fake, fake, fake, 4, 4, fake, 4, None) == binding.GCOO_EINVAL
-    assert L.gcoo_csr_spmm_baseline(2, 2, fake, fake, fake, fake, 3, 4, fake, 4, None) == binding.GCOO_EINVAL   # ldb < N
-    assert L.gcoo_csr_spmm_baseline(2, 2, fake, fake, fake, fake, 4, 4, None, 4, None) == binding.GCOO_EINVAL
-    assert L.gcoo_csr_spmm_baseline(0, 2, fake, fake, fake, fake, 4, 4, None, 4, None) == 0                     # nothing to do
+    # CSR baseline kernel (library of its own): shapes are checked before anything is launched
+    Lb = binding.baseline_lib()
+    assert Lb.gcoo_csr_spmm_baseline(-1, 2, fake, fake, fake, fake, 4, 4, fake, 4, None) == binding.GCOO_EINVAL
+    assert Lb.gcoo_csr_spmm_baseline(2, 2, None, fake, fake, fake, 4, 4, fake, 4, None) == binding.GCOO_EINVAL
+    assert Lb.gcoo_csr_spmm_baseline(2, 2, fake, fake, fake, fake, 3, 4, fake, 4, None) == binding.GCOO_EINVAL   # ldb < N
+    assert Lb.gcoo_csr_spmm_baseline(2, 2, fake, fake, fake, fake, 4, 4, None, 4, None) == binding.GCOO_EINVAL
+    assert Lb.gcoo_csr_spmm_baseline(0, 2, fake, fake, fake, fake, 4, 4, None, 4, None) == 0                     # nothing to do
+
+
+def _share_height(m, N):
+    """The header's rule for the workgroup-shared kernel: the p in 24..48 that minimises
+    ceil(workgroups / 256) x (p + 24), the taller one on a tie."""
+    best, cost = None, None
+    for p in range(48, 23, -1):
+        g = (m + p - 1) // p
+        items = ((g + 7) // 8) * ((N + 255) // 256)
+        c = ((items + 255) // 256) * (p + 24)
+        if cost is None or c < cost:
+            best, cost = p, c
+    return best
 
 
 def test_default_p_rule(L):
-    """32 (the register kernel's best height) unless the sixteen-wave band kernel was measured faster:
-    the cases below sit on both sides of every limit the header states."""
+    """32 (the register kernel's best height) unless the workgroup-shared kernel or the tall register instance
+    was measured faster: the cases below sit on both sides of every limit the header states."""
     def dp(n, s, N=None, m=None):
         m = n if m is None else m
         return L.gcoo_default_p(m, n, int(m * n * (1 - s)), n if N is None else N)
-    assert dp(8000, 0.995) == 32            # the headline workload: 8000 columns at 0.5 %
-    assert dp(8000, 0.98) == 16 and dp(8000, 0.99) == 16
+    assert dp(8000, 0.995) == 42            # the headline workload: 24 super-groups x 32 tiles = 3 rounds of 256
+    assert dp(8000, 0.98) == 42 and dp(8000, 0.99) == 42 and dp(8000, 0.95) == 42
+    assert dp(14000, 0.98) == 48 and dp(4000, 0.98) == 32
+    for n in (4000, 5000, 7000, 8000, 10000, 14000):
+        assert dp(n, 0.98) == _share_height(n, n), n
     assert dp(8000, 0.9) == 38 and dp(8000, 0.93) == 38 and dp(14000, 0.9) == 38      # 6 .. 12 % dense: the tall register instance
     assert dp(8000, 0.8) == 32 and dp(4000, 0.9) == 32 and dp(8000, 0.9, N=8002) == 32
-    assert dp(4000, 0.98) == 16 and dp(4000, 0.995) == 32 and dp(4000, 0.94) == 32 and dp(5000, 0.98) == 32
-    assert dp(6000, 0.98) == 32             # 24 x 24 blocks fill 2.25 rounds of 256: 75 %
-    assert dp(12000, 0.995) == 16 and dp(14000, 0.999) == 32 and dp(10000, 0.996) == 16 and dp(10000, 0.997) == 32
-    assert dp(2000, 0.98) == 32
-    assert dp(12000, 0.98, N=256) == 32     # 47 blocks of C: too few workgroups
+    assert dp(4000, 0.995) == 32            # below 7000 columns only from 0.8 % on
+    assert dp(6000, 0.98) in (32, _share_height(6000, 6000))
+    assert dp(3000, 0.98) == 32 and dp(2000, 0.98) == 32
+    assert dp(12000, 0.98, N=256) == 32     # too few workgroups
     assert dp(12000, 0.98, N=12002) == 32   # rows of B not 16-byte aligned
     for m, k, nnz, n in [(0, 0, 0, 0), (1, 1, 1, 1), (256, 256, 6000, 256)]:
         assert L.gcoo_default_p(m, k, nnz, n) == 32

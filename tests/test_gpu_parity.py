@@ -23,11 +23,11 @@ def _say(msg):
 
 
 @pytest.fixture
-def band_always():
-    """Conversions inside the test build the band schedule whenever the band kernel could run."""
-    binding.gcoo_set_band_policy(binding.BAND_ALWAYS)
+def share_always():
+    """Conversions inside the test build the share schedule whenever the workgroup-shared kernel could run."""
+    binding.gcoo_set_share_policy(binding.SHARE_ALWAYS)
     yield
-    binding.gcoo_set_band_policy(binding.BAND_AUTO)
+    binding.gcoo_set_share_policy(binding.SHARE_AUTO)
 
 
 def _assert_arrays_equal(exp, G):
@@ -167,55 +167,6 @@ def test_gcoo_from_dense_bit_exact(p, shape):
     _assert_arrays_equal(A2.export(), G)
 
 
-def _band_base(first_entry, q, k):
-    return (3 * first_entry + 3) // 4 * 4 + (56 * ((k + 63) // 64 + 2) + 4) * q
-
-
-@pytest.mark.parametrize("m,k,p,s", [
-    (100, 300, 32, 0.95), (257, 1000, 32, 0.99), (70, 200, 16, 0.94), (33, 50, 8, 0.95), (300, 70, 32, 0.96),
-    (1, 1, 1, 0.0), (520, 5000, 32, 0.97), (64, 4000, 32, 0.999), (2000, 2000, 32, 0.98), (256, 64, 32, 0.95),
-    (2000, 2000, 16, 0.98), (520, 5000, 12, 0.97), (256, 64, 16, 0.95), (700, 300, 16, 0.945), (120, 90, 17, 0.95),
-])
-def test_band_schedule_bit_exact(band_always, m, k, p, s):
-    """The band schedule written by the HIP builder equals the Python model word for word."""
-    from tests import band_model
-    _say(f"band schedule m={m} k={k} p={p} sparsity={s}")
-    w = workloads.uniform_random(m, k, 1, s, seed=3 * m + k)
-    A = binding.gcoo_from_csr(w.m, w.k, w.row_ptr, w.col_idx, w.vals, p, device=DEV)
-    got = A.export_band()
-    if w.nnz == 0 or w.nnz > 0.06 * m * k:
-        assert got is None
-        return
-    assert got is not None
-    G = orc.gcoo_from_csr(w.m, w.k, w.row_ptr, w.col_idx, w.vals, p)
-    streams, info = band_model.build(m, k, p, G.gIdxes, G.rows, G.cols, G.values)
-    for Q, (ucols, NB) in enumerate(info):
-        assert got["ucount"][Q] == len(ucols)
-        e0 = int(G.gIdxes[min(band_model.waves_of(p) * Q, G.g)])
-        assert np.array_equal(got["ucols"][e0:e0 + len(ucols)], ucols)
-    for q, st in enumerate(streams):
-        base = _band_base(int(G.gIdxes[min(q, G.g)]), q, k)
-        assert np.array_equal(got["words"][base:base + len(st)], st), f"stream {q}"
-
-
-def test_band_schedule_bit_exact_with_repeated_coordinates(band_always):
-    from tests import band_model
-    from tests.test_band_model import repeated_coordinates_workload
-    m, k, N, row_ptr, col_idx, vals, B = repeated_coordinates_workload()
-    # density of this input is above the limit for the band schedule at its real size: embed it in a wider matrix
-    k2 = 4000
-    for p in (8, 16, 32):
-        _say(f"band schedule with repeated coordinates p={p}")
-        A = binding.gcoo_from_csr(m, k2, row_ptr, col_idx, vals, p, device=DEV)
-        got = A.export_band()
-        assert got is not None
-        G = orc.gcoo_from_csr(m, k2, row_ptr, col_idx, vals, p)
-        streams, info = band_model.build(m, k2, p, G.gIdxes, G.rows, G.cols, G.values)
-        for q, st in enumerate(streams):
-            base = _band_base(int(G.gIdxes[min(q, G.g)]), q, k2)
-            assert np.array_equal(got["words"][base:base + len(st)], st), f"stream {q}"
-
-
 # ------------------------------------------------------------------ product
 
 @pytest.mark.parametrize("p", [1, 2, 8, 16, 32, 33, 38, 39, 64, 128, 256])
@@ -253,8 +204,8 @@ def test_register_kernel_refuses_what_it_does_not_serve():
         torch.cuda.synchronize()
 
 
-@pytest.mark.skip(reason="the one-column-per-lane register kernel (65 <= p <= 128) is switched off in the library: "
-                         "one run of it at 8000 x 8000, p = 128 ended in a GPU memory fault of unknown cause")
+@pytest.mark.skip(reason="the one-column-per-lane register kernel (65 <= p <= 128) is not part of the library any more: "
+                         "one run of it at 8000 x 8000, p = 128 ended in a GPU memory fault whose cause was never found")
 def test_register_kernel_one_column_per_lane():
     w = workloads.config(3)
     _check_product(w, 128, binding.VARIANT_REG, r0=0, r1=128)
@@ -273,65 +224,6 @@ def test_heavy_groups_shared_by_a_workgroup(m, k, N, p, sparsity):
     assert err < 2e-6
     _, _, c2 = _check_product(w, p, binding.VARIANT_REG, A=A)
     assert np.array_equal(c1, c2)                        # same bits on every run
-
-
-@pytest.mark.parametrize("m,k,N,p,sparsity", [
-    (100, 300, 8, 32, 0.95), (257, 1000, 260, 32, 0.99), (70, 200, 4, 16, 0.94), (33, 50, 12, 8, 0.95), (300, 70, 64, 32, 0.96),
-    (1, 1, 4, 1, 0.0), (520, 5000, 512, 32, 0.97), (64, 4000, 256, 32, 0.999), (2000, 2000, 300, 32, 0.98), (256, 64, 1028, 32, 0.95),
-    (1000, 3000, 256, 32, 0.94),
-    (2000, 2000, 300, 16, 0.98), (520, 5000, 512, 12, 0.97), (256, 64, 1028, 16, 0.95), (1000, 3000, 256, 16, 0.94),
-    (257, 1000, 260, 9, 0.99), (64, 4000, 256, 16, 0.999), (100, 300, 8, 2, 0.95), (3000, 900, 64, 16, 0.95),
-])
-def test_band_variant(band_always, m, k, N, p, sparsity):
-    """The kernel whose waves share the rows of B through LDS (both shapes: eight waves for groups of 17..32 rows,
-    sixteen for shorter groups), on matrices sparse enough to have a band schedule."""
-    w = workloads.uniform_random(m, k, N, sparsity, seed=5 * m + k + N)
-    _say(f"band variant m={m} k={k} N={N} p={p} nnz={w.nnz}")
-    if w.nnz == 0 or w.nnz > 0.06 * m * k:
-        pytest.skip("no band schedule for this matrix")
-    err, A, c1 = _check_product(w, p, binding.VARIANT_BAND)
-    assert err < 2e-6
-    _, _, c2 = _check_product(w, p, binding.VARIANT_BAND, A=A)
-    assert np.array_equal(c1, c2)
-
-
-@pytest.mark.parametrize("p", [16, 32])
-def test_band_variant_skewed_rows_and_diagonal(band_always, p):
-    """Power-law row lengths (a few groups with thousands of entries in one band: chains of further blocks) and a
-    diagonal matrix (every band of every super-group has exactly one entry per column), both shapes."""
-    w = workloads.zipf_rows(700, 3000, 260, seed=17, row_max=2500)
-    _say(f"band variant, skewed rows p={p} nnz={w.nnz}")
-    assert w.nnz <= 0.06 * w.m * w.k
-    err, A, c1 = _check_product(w, p, binding.VARIANT_BAND)
-    assert err < 2e-6
-    _, _, c2 = _check_product(w, p, binding.VARIANT_BAND, A=A)
-    assert np.array_equal(c1, c2)
-    d = workloads.diagonal(1000, 516, seed=3)
-    _say(f"band variant, diagonal p={p}")
-    err, _, _ = _check_product(d, p, binding.VARIANT_BAND)
-    assert err < 2e-6
-
-
-def test_band_variant_repeated_coordinates_and_strides(band_always):
-    from tests.test_band_model import repeated_coordinates_workload
-    m, k, N, row_ptr, col_idx, vals, B = repeated_coordinates_workload()
-    _say("band variant: repeated coordinates, strided operands")
-    k2, N2 = 4000, 12
-    rng = np.random.default_rng(2)
-    Bh = rng.standard_normal((k2, N2)).astype(np.float32)
-    Bbig = torch.zeros((k2, 40), device=DEV)
-    Bbig[:, 8:8 + N2] = torch.from_numpy(Bh).to(DEV)
-    C64, D64 = orc.spdm_csr(k2, N2, row_ptr, col_idx, vals, Bh)
-    for p in (16, 32):
-        A = binding.gcoo_from_csr(m, k2, row_ptr, col_idx, vals, p, device=DEV)
-        Cbig = torch.full((m, 32), 7.0, device=DEV)
-        binding.gcoo_spdm(A, Bbig[:, 8:8 + N2], Cbig[:, 4:4 + N2], variant=binding.VARIANT_BAND)
-        torch.cuda.synchronize()
-        err, bad = orc.max_scaled_error(Cbig[:, 4:4 + N2].cpu().numpy(), C64, D64)
-        assert bad == 0 and err <= TOL
-        assert torch.all(Cbig[:, :4] == 7.0) and torch.all(Cbig[:, 4 + N2:] == 7.0)
-    with pytest.raises(binding.GcooError):                  # rows not 16-byte aligned
-        binding.gcoo_spdm(A, Bbig[:, 9:9 + N2], Cbig[:, 4:4 + N2], variant=binding.VARIANT_BAND)
 
 
 def test_auto_variant_and_strided_operands():
@@ -430,79 +322,6 @@ def test_mid_size_configs_full_check(index, p):
     _check_product(w, p, binding.VARIANT_AUTO)
 
 
-@pytest.mark.parametrize("index", [2, 3])
-def test_full_size_configs_sampled_rows(index):
-    """8000^2 at s=0.9 and s=0.995 in the launch configuration the benchmark times (group height from
-    gcoo_default_p: 38 and 32, automatic variant); the oracle recomputes a sample of row bands: the first,
-    the last (ragged tile columns are in every row) and random ones."""
-    w = workloads.config(index)
-    p = binding.gcoo_default_p(w.m, w.k, w.nnz, w.N)
-    assert p == (38 if index == 2 else 32)
-    _say(f"config{index} nnz={w.nnz} p={p}")
-    A = binding.gcoo_from_csr(w.m, w.k, w.row_ptr, w.col_idx, w.vals, p, device=DEV)
-    G = A.export()
-    g = A.info()["g"]
-    assert int(G["gIdxes"][-1]) == w.nnz and int(G["nnzPerGroup"].sum()) == w.nnz
-    # conversion at full size: group q is the CSR range of its rows, sorted by (col,row)
-    rng = np.random.default_rng(index)
-    for q in [0, g - 1] + rng.integers(0, g, 6).tolist():
-        r0, r1 = q * p, min(q * p + p, w.m)
-        sub = orc.gcoo_from_csr(r1 - r0, w.k, w.row_ptr[r0:r1 + 1] - w.row_ptr[r0],
-                                w.col_idx[w.row_ptr[r0]:w.row_ptr[r1]], w.vals[w.row_ptr[r0]:w.row_ptr[r1]], p)
-        s, e = int(G["gIdxes"][q]), int(G["gIdxes"][q + 1])
-        assert np.array_equal(G["cols"][s:e], sub.cols) and np.array_equal(G["rows"][s:e], sub.rows + r0)
-        assert np.array_equal(G["values"][s:e].view(np.uint32), sub.values.view(np.uint32))
-    Bt = torch.from_numpy(w.B).to(DEV)
-    Cg = torch.full((w.m, w.N), float("nan"), dtype=torch.float32, device=DEV)
-    assert binding.gcoo_spdm_pick(A, Bt, Cg) == binding.VARIANT_REG
-    binding.gcoo_spdm(A, Bt, Cg)
-    torch.cuda.synchronize()
-    assert not torch.isnan(Cg).any()
-    for q in [0, g - 1] + rng.integers(0, g, 6).tolist():
-        r0, r1 = q * p, min(q * p + p, w.m)
-        C64, D64 = orc.spdm_csr(w.k, w.N, w.row_ptr, w.col_idx, w.vals, w.B, r0, r1)
-        err, bad = orc.max_scaled_error(Cg[r0:r1].cpu().numpy(), C64, D64)
-        assert bad == 0 and err <= TOL, (q, err, bad)
-
-
-def test_full_size_default_height_picks_the_band_kernel_sampled_rows():
-    """8000^2 at s=0.98, N = 8000, as the benchmark's sweeps run it: group height from gcoo_default_p (16 here),
-    automatic variant (the sixteen-wave band kernel); the oracle recomputes a sample of groups and row bands."""
-    n, s = 8000, 0.98
-    w = workloads.uniform_random(n, n, n, s, workloads.BASE_SEED + n, name="uniform_8000_0.98")
-    p = binding.gcoo_default_p(w.m, w.k, w.nnz, w.N)
-    _say(f"uniform 8000 s=0.98 nnz={w.nnz} default p={p}")
-    assert p == 16
-    A = binding.gcoo_from_csr(w.m, w.k, w.row_ptr, w.col_idx, w.vals, p, device=DEV)
-    Bt = torch.from_numpy(w.B).to(DEV)
-    Cg = torch.full((w.m, w.N), float("nan"), dtype=torch.float32, device=DEV)
-    assert binding.gcoo_spdm_pick(A, Bt, Cg) == binding.VARIANT_BAND
-    G = A.export()
-    rng = np.random.default_rng(98)
-    g = A.info()["g"]
-    for q in [0, g - 1] + rng.integers(0, g, 6).tolist():
-        r0, r1 = q * p, min(q * p + p, w.m)
-        sub = orc.gcoo_from_csr(r1 - r0, w.k, w.row_ptr[r0:r1 + 1] - w.row_ptr[r0],
-                                w.col_idx[w.row_ptr[r0]:w.row_ptr[r1]], w.vals[w.row_ptr[r0]:w.row_ptr[r1]], p)
-        b, e = int(G["gIdxes"][q]), int(G["gIdxes"][q + 1])
-        assert np.array_equal(G["cols"][b:e], sub.cols) and np.array_equal(G["rows"][b:e], sub.rows + r0)
-        assert np.array_equal(G["values"][b:e].view(np.uint32), sub.values.view(np.uint32))
-    binding.gcoo_spdm(A, Bt, Cg)
-    torch.cuda.synchronize()
-    assert not torch.isnan(Cg).any()
-    for q in [0, g - 1] + rng.integers(0, g, 8).tolist():
-        r0, r1 = q * p, min(q * p + p, w.m)
-        C64, D64 = orc.spdm_csr(w.k, w.N, w.row_ptr, w.col_idx, w.vals, w.B, r0, r1)
-        err, bad = orc.max_scaled_error(Cg[r0:r1].cpu().numpy(), C64, D64)
-        assert bad == 0 and err <= TOL, (q, err, bad)
-    # the same product through the register kernel on the same handle: every element within two roundings' worth
-    Cr = torch.empty_like(Cg)
-    binding.gcoo_spdm(A, Bt, Cr, variant=binding.VARIANT_REG)
-    torch.cuda.synchronize()
-    scale = float(torch.abs(torch.from_numpy(w.B)).max()) * float(np.abs(w.vals).max())
-    assert float((Cg - Cr).abs().max()) <= 1e-4 * scale * 8
-
-
 @pytest.mark.parametrize("shape", [(300, 200, 1028), (77, 500, 250), (1, 1, 1)])
 def test_csr_baseline_kernel(shape):
     """The comparison kernel of the benchmark is held to the same bound as the path itself."""
@@ -528,37 +347,325 @@ def test_tune_p_returns_a_measured_candidate():
     assert binding.gcoo_default_p(w.m, w.k, w.nnz, w.N) == 32
 
 
-def test_band_policy_and_automatic_choice():
-    """By default a matrix gets a band schedule only where the band kernel is the automatic choice."""
-    _say("band policy")
-    w = workloads.uniform_random(4096, 12000, 3072, 0.97, seed=8)      # 12000 columns, 3 % dense, 16 x 12 blocks of C
+
+# ------------------------------------------------------------------ the workgroup-shared kernel and its schedule
+
+def _check_share_schedule(A, m, k, p, G):
+    """The share schedule written by the HIP builder equals the Python model record for record."""
+    from tests import share_model
+    sh = A.export_share()
+    assert sh is not None
+    info, streams = share_model.build(m, k, p, G.gIdxes, G.rows, G.cols, G.values)
+    g = (m + p - 1) // p
+    nQ = (g + 7) // 8
+    blocks = sh["blocks"].reshape(-1, 16, 4)
+    used = []
+    for Q in range(nQ):
+        ucols, NB = info[Q]
+        first = int(G.gIdxes[Q * 8])
+        assert sh["ucount"][Q] == len(ucols)
+        assert np.array_equal(sh["ucols"][first:first + len(ucols)], ucols)
+        hb = first // share_model.BAND + Q
+        cap = int(G.gIdxes[min(Q * 8 + 8, g)]) // share_model.BAND + Q + 1 - hb
+        assert NB <= cap
+        for w in range(8):
+            q = Q * 8 + w
+            at = int(sh["sbase"][q])
+            start = at
+            for b, (nq, ns4, blk) in enumerate(streams[q]):
+                assert sh["hdr"][2 * (8 * hb + w * cap + b)] == nq, (Q, w, b)
+                assert sh["hdr"][2 * (8 * hb + w * cap + b) + 1] == ns4, (Q, w, b)
+                assert np.array_equal(blocks[at:at + len(blk)], blk), (Q, w, b)
+                at += len(blk)
+            used.append((start, at))
+    used.sort()
+    for (a0, a1), (b0, b1) in zip(used, used[1:]):
+        assert a1 <= b0, "streams overlap"
+    assert used[-1][1] + 16 <= len(blocks)
+
+
+@pytest.mark.parametrize("m,k,N,p,s", [
+    (100, 300, 8, 32, 0.9), (257, 1000, 260, 42, 0.99), (70, 200, 4, 16, 0.3), (64, 64, 64, 48, 0.0), (33, 50, 4, 8, 0.95),
+    (300, 70, 12, 32, 0.6), (1, 1, 4, 1, 0.0), (20, 130, 4, 32, 1.0), (700, 500, 516, 48, 0.5), (530, 2000, 300, 12, 0.98),
+    (1000, 3000, 1024, 42, 0.995), (3000, 900, 64, 16, 0.95), (64, 4000, 256, 32, 0.999), (100, 300, 8, 2, 0.95),
+])
+def test_share_schedule_and_variant(share_always, m, k, N, p, s):
+    """The kernel whose eight waves share the rows of B through LDS: its schedule against the model, its product
+    against the oracle, the same bits on a second run."""
+    _say(f"share: m={m} k={k} N={N} p={p} s={s}")
+    w = workloads.uniform_random(m, k, N, s, seed=m + k)
+    G = orc.gcoo_from_csr(w.m, w.k, w.row_ptr, w.col_idx, w.vals, p)
+    A = binding.gcoo_from_csr(w.m, w.k, w.row_ptr, w.col_idx, w.vals, p, device=DEV)
+    if w.nnz == 0:
+        assert A.export_share() is None
+        return
+    _check_share_schedule(A, m, k, p, G)
+    err, _, c1 = _check_product(w, p, binding.VARIANT_SHARE, A=A)
+    assert err < 2e-6
+    _, _, c2 = _check_product(w, p, binding.VARIANT_SHARE, A=A)
+    assert np.array_equal(c1, c2)
+
+
+@pytest.mark.parametrize("p", [16, 32, 48])
+def test_share_variant_skewed_rows_and_diagonal(share_always, p):
+    """Power-law row lengths (a few groups with thousands of entries in one band: many blocks per band, ring
+    pieces requested in the middle of a band) and a diagonal matrix (one entry per column)."""
+    w = workloads.zipf_rows(700, 3000, 260, seed=17, row_max=2500)
+    _say(f"share variant, skewed rows p={p} nnz={w.nnz}")
+    err, A, c1 = _check_product(w, p, binding.VARIANT_SHARE)
+    assert err < 2e-6
+    _, _, c2 = _check_product(w, p, binding.VARIANT_SHARE, A=A)
+    assert np.array_equal(c1, c2)
+    d = workloads.diagonal(1000, 516, seed=3)
+    _say(f"share variant, diagonal p={p}")
+    err, _, _ = _check_product(d, p, binding.VARIANT_SHARE)
+    assert err < 2e-6
+
+
+def test_share_variant_repeated_coordinates_and_strides(share_always):
+    from tests.test_share_model import repeated_coordinates_workload
+    m, k, N, row_ptr, col_idx, vals, B = repeated_coordinates_workload()
+    _say("share variant: repeated coordinates, strided operands")
+    k2, N2 = 4000, 12
+    rng = np.random.default_rng(2)
+    Bh = rng.standard_normal((k2, N2)).astype(np.float32)
+    Bbig = torch.zeros((k2, 40), device=DEV)
+    Bbig[:, 8:8 + N2] = torch.from_numpy(Bh).to(DEV)
+    C64, D64 = orc.spdm_csr(k2, N2, row_ptr, col_idx, vals, Bh)
+    for p in (8, 48):
+        G = orc.gcoo_from_csr(m, k2, row_ptr, col_idx, vals, p)
+        A = binding.gcoo_from_csr(m, k2, row_ptr, col_idx, vals, p, device=DEV)
+        _check_share_schedule(A, m, k2, p, G)
+        Cbig = torch.full((m, 32), 7.0, device=DEV)
+        binding.gcoo_spdm(A, Bbig[:, 8:8 + N2], Cbig[:, 4:4 + N2], variant=binding.VARIANT_SHARE)
+        torch.cuda.synchronize()
+        err, bad = orc.max_scaled_error(Cbig[:, 4:4 + N2].cpu().numpy(), C64, D64)
+        assert bad == 0 and err <= TOL
+        assert torch.all(Cbig[:, :4] == 7.0) and torch.all(Cbig[:, 4 + N2:] == 7.0)
+    with pytest.raises(binding.GcooError):                  # rows not 16-byte aligned
+        binding.gcoo_spdm(A, Bbig[:, 9:9 + N2], Cbig[:, 4:4 + N2], variant=binding.VARIANT_SHARE)
+    torch.cuda.synchronize()
+
+
+def test_share_policy_and_automatic_choice():
+    """By default a matrix gets a share schedule only where the workgroup-shared kernel is the automatic choice;
+    the register kernel's schedule is always there, so either kernel can run on the same handle."""
+    _say("share policy")
+    w = workloads.uniform_random(4096, 12000, 3072, 0.97, seed=8)      # 12000 columns, 3 % dense
     Bt = torch.from_numpy(w.B).to(DEV)
     Cg = torch.empty((w.m, w.N), device=DEV)
-    for p in (32, 16):
+    for p in (32, 24):                                                  # 16 x 12 and 22 x 12 workgroups
         A = binding.gcoo_from_csr(w.m, w.k, w.row_ptr, w.col_idx, w.vals, p, device=DEV)
-        assert A.export_band() is not None and binding.gcoo_spdm_pick(A, Bt, Cg) == binding.VARIANT_BAND
-        # too few blocks of C for the workgroups of the band kernel to occupy the chip
+        assert A.export_share() is not None and binding.gcoo_spdm_pick(A, Bt, Cg) == binding.VARIANT_SHARE
+        # too few blocks of C for the workgroups of that kernel to occupy the chip
         assert binding.gcoo_spdm_pick(A, Bt[:, :256], Cg[:, :256]) == binding.VARIANT_REG
         err, _, cfull = _check_product(w, p, binding.VARIANT_AUTO, A=A)
         assert err < 2e-6
-        # the register kernel on this handle after all: its schedule was left out at conversion and is
-        # built by this first launch
         Cn = torch.full((w.m, 256), float("nan"), device=DEV)
         binding.gcoo_spdm(A, Bt[:, :256], Cn)
         torch.cuda.synchronize()
         scale = float(np.abs(w.B).max()) * float(np.abs(w.vals).max())
         assert float((Cn - torch.from_numpy(cfull[:, :256]).to(DEV)).abs().max()) <= 1e-4 * scale * 8
-    w2 = workloads.uniform_random(64, 3000, 256, 0.97, seed=8)         # too few columns for the band kernel to pay
-    for p in (32, 16):
-        A2 = binding.gcoo_from_csr(w2.m, w2.k, w2.row_ptr, w2.col_idx, w2.vals, p, device=DEV)
-        assert A2.export_band() is None
-        assert binding.gcoo_spdm_pick(A2, torch.from_numpy(w2.B).to(DEV), Cg[:64, :256]) == binding.VARIANT_REG
-    w3 = workloads.uniform_random(64, 5000, 256, 0.98, seed=9)         # enough columns for groups of 16 rows, not for 32
-    assert binding.gcoo_from_csr(w3.m, w3.k, w3.row_ptr, w3.col_idx, w3.vals, 16, device=DEV).export_band() is not None
-    assert binding.gcoo_from_csr(w3.m, w3.k, w3.row_ptr, w3.col_idx, w3.vals, 32, device=DEV).export_band() is None
-    binding.gcoo_set_band_policy(binding.BAND_NEVER)
+    w2 = workloads.uniform_random(64, 3000, 256, 0.97, seed=8)         # too few columns for that kernel to pay
+    A2 = binding.gcoo_from_csr(w2.m, w2.k, w2.row_ptr, w2.col_idx, w2.vals, 32, device=DEV)
+    assert A2.export_share() is None
+    assert binding.gcoo_spdm_pick(A2, torch.from_numpy(w2.B).to(DEV), Cg[:64, :256]) == binding.VARIANT_REG
+    w3 = workloads.uniform_random(64, 8000, 256, 0.98, seed=9)
+    assert binding.gcoo_from_csr(w3.m, w3.k, w3.row_ptr, w3.col_idx, w3.vals, 48, device=DEV).export_share() is not None
+    assert binding.gcoo_from_csr(w3.m, w3.k, w3.row_ptr, w3.col_idx, w3.vals, 49, device=DEV).export_share() is None
+    binding.gcoo_set_share_policy(binding.SHARE_NEVER)
     try:
         A3 = binding.gcoo_from_csr(w.m, w.k, w.row_ptr, w.col_idx, w.vals, 32, device=DEV)
-        assert A3.export_band() is None and binding.gcoo_spdm_pick(A3, Bt, Cg) == binding.VARIANT_REG
+        assert A3.export_share() is None and binding.gcoo_spdm_pick(A3, Bt, Cg) == binding.VARIANT_REG
     finally:
-        binding.gcoo_set_band_policy(binding.BAND_AUTO)
+        binding.gcoo_set_share_policy(binding.SHARE_AUTO)
+
+
+# ------------------------------------------------------------------ the benchmark's launches, every element
+
+def _every_element(w, A, Bt, variant, chunk=1000):
+    """C = A x B at full size against the oracle, every element, in row chunks; returns the largest scaled error."""
+    Cg = torch.full((w.m, w.N), float("nan"), dtype=torch.float32, device=DEV)
+    binding.gcoo_spdm(A, Bt, Cg, variant=variant)
+    torch.cuda.synchronize()
+    Ch = Cg.cpu().numpy()
+    worst = 0.0
+    for r0 in range(0, w.m, chunk):
+        r1 = min(r0 + chunk, w.m)
+        C64, D64 = orc.spdm_csr(w.k, w.N, w.row_ptr, w.col_idx, w.vals, w.B, r0, r1)
+        err, bad = orc.max_scaled_error(Ch[r0:r1], C64, D64)
+        assert bad == 0 and err <= TOL, (r0, err, bad)
+        worst = max(worst, err)
+    return worst, Cg
+
+
+@pytest.mark.parametrize("index", [2, 3])
+def test_full_size_configs_every_element(index):
+    """8000^2 at s=0.9 and s=0.995 in the launch configuration the benchmark times (group height from
+    gcoo_default_p, automatic variant, device CSR with nnz given): all five GCOO arrays and every element of C
+    against the oracle, and the same bits on a second launch."""
+    w = workloads.config(index)
+    p = binding.gcoo_default_p(w.m, w.k, w.nnz, w.N)
+    assert p == (38 if index == 2 else 42)
+    _say(f"config{index} nnz={w.nnz} p={p}")
+    dev = [torch.from_numpy(x).to(DEV) for x in (w.row_ptr, w.col_idx, w.vals)]
+    A = binding.gcoo_from_csr(w.m, w.k, *dev, p, device=DEV, known_nnz=True)
+    _assert_arrays_equal(A.export(), orc.gcoo_from_csr(w.m, w.k, w.row_ptr, w.col_idx, w.vals, p))
+    Bt = torch.from_numpy(w.B).to(DEV)
+    Cp = torch.empty((w.m, w.N), dtype=torch.float32, device=DEV)
+    assert binding.gcoo_spdm_pick(A, Bt, Cp) == (binding.VARIANT_REG if index == 2 else binding.VARIANT_SHARE)
+    worst, C1 = _every_element(w, A, Bt, binding.VARIANT_AUTO)
+    _say(f"  every element within {worst:.2e}")
+    _, C2 = _every_element(w, A, Bt, binding.VARIANT_AUTO)
+    assert torch.equal(C1, C2)
+    if index == 3:                       # the register kernel on the same handle (its schedule is always built)
+        if p <= 38:
+            _every_element(w, A, Bt, binding.VARIANT_REG)
+        A32 = binding.gcoo_from_csr(w.m, w.k, *dev, 32, device=DEV, known_nnz=True)
+        worst, _ = _every_element(w, A32, Bt, binding.VARIANT_REG)
+        _say(f"  register kernel, p = 32: every element within {worst:.2e}")
+
+
+def test_full_size_sweep_point_every_element():
+    """8000^2 at s=0.98, N = 8000, as the benchmark's sweeps run it: group height from gcoo_default_p, automatic
+    variant (the workgroup-shared kernel); arrays and every element of C against the oracle."""
+    n, s = 8000, 0.98
+    w = workloads.uniform_random(n, n, n, s, workloads.BASE_SEED + n, name="uniform_8000_0.98")
+    p = binding.gcoo_default_p(w.m, w.k, w.nnz, w.N)
+    _say(f"uniform 8000 s=0.98 nnz={w.nnz} default p={p}")
+    assert p == 42
+    A = binding.gcoo_from_csr(w.m, w.k, w.row_ptr, w.col_idx, w.vals, p, device=DEV)
+    _assert_arrays_equal(A.export(), orc.gcoo_from_csr(w.m, w.k, w.row_ptr, w.col_idx, w.vals, p))
+    Bt = torch.from_numpy(w.B).to(DEV)
+    Cp = torch.empty((w.m, w.N), dtype=torch.float32, device=DEV)
+    assert binding.gcoo_spdm_pick(A, Bt, Cp) == binding.VARIANT_SHARE
+    worst, _ = _every_element(w, A, Bt, binding.VARIANT_AUTO)
+    _say(f"  every element within {worst:.2e}")
+
+
+@pytest.mark.parametrize("p", [32, 48])
+def test_skewed_config_through_the_share_variant(share_always, p):
+    """The 16384^2 power-law workload through the workgroup-shared kernel, every element."""
+    w = workloads.config(4)
+    _say(f"config4 share p={p} nnz={w.nnz}")
+    A = binding.gcoo_from_csr(w.m, w.k, w.row_ptr, w.col_idx, w.vals, p, device=DEV)
+    worst, _ = _every_element(w, A, torch.from_numpy(w.B).to(DEV), binding.VARIANT_SHARE, chunk=4096)
+    assert worst < 2e-6
+
+
+# ------------------------------------------------------------------ dispatch corners
+
+@pytest.mark.parametrize("p", [8, 32])
+def test_two_columns_per_lane_chosen_by_alignment(p):
+    """p <= 32 with N = 2 mod 4, and with rows that are 8- but not 16-byte aligned: the register kernel runs its
+    two-columns-per-lane instance."""
+    w = workloads.uniform_random(300, 400, 1030, 0.9, seed=31)
+    _say(f"V = 2 by alignment, p={p}")
+    assert w.N % 4 == 2
+    A = binding.gcoo_from_csr(w.m, w.k, w.row_ptr, w.col_idx, w.vals, p, device=DEV)
+    Bt = torch.from_numpy(w.B).to(DEV)
+    Cg = torch.empty((w.m, w.N), device=DEV)
+    assert binding.gcoo_spdm_pick(A, Bt, Cg) == binding.VARIANT_REG
+    err, _, _ = _check_product(w, p, binding.VARIANT_REG, A=A)
+    assert err < 2e-6
+    # N a multiple of 4 but the views start 8 bytes into a row
+    N2 = 1024
+    Bbig = torch.zeros((w.k, 1040), device=DEV)
+    Bbig[:, 2:2 + N2] = Bt[:, :N2]
+    Cbig = torch.full((w.m, 1040), 7.0, device=DEV)
+    Bv, Cv = Bbig[:, 2:2 + N2], Cbig[:, 2:2 + N2]
+    assert Bv.data_ptr() % 16 == 8 and binding.gcoo_spdm_pick(A, Bv, Cv) == binding.VARIANT_REG
+    binding.gcoo_spdm(A, Bv, Cv, variant=binding.VARIANT_REG)
+    torch.cuda.synchronize()
+    C64, D64 = orc.spdm_csr(w.k, N2, w.row_ptr, w.col_idx, w.vals, np.ascontiguousarray(w.B[:, :N2]))
+    err, bad = orc.max_scaled_error(Cv.cpu().numpy(), C64, D64)
+    assert bad == 0 and err <= TOL
+    assert torch.all(Cbig[:, :2] == 7.0) and torch.all(Cbig[:, 2 + N2:] == 7.0)
+
+
+def test_skewed_matrix_through_the_tall_layout():
+    """Power-law row lengths at p = 38 (the tall accumulator layout, which never splits a heavy group)."""
+    w = workloads.zipf_rows(700, 3000, 260, seed=17, row_max=2500)
+    _say(f"skewed rows, p = 38, nnz={w.nnz}")
+    err, A, c1 = _check_product(w, 38, binding.VARIANT_REG)
+    assert err < 2e-6
+    _, _, c2 = _check_product(w, 38, binding.VARIANT_REG, A=A)
+    assert np.array_equal(c1, c2)
+
+
+def test_one_handle_two_host_threads_two_streams(share_always):
+    """A handle is read-only after conversion: two host threads multiply with it at once, each on a stream of
+    its own, through different kernels, and both get the oracle's result."""
+    import threading
+    w = workloads.uniform_random(1500, 4000, 1024, 0.98, seed=12)
+    _say("one handle, two threads, two streams")
+    A = binding.gcoo_from_csr(w.m, w.k, w.row_ptr, w.col_idx, w.vals, 32, device=DEV)
+    Bt = torch.from_numpy(w.B).to(DEV)
+    torch.cuda.synchronize()
+    C64, D64 = orc.spdm_csr(w.k, w.N, w.row_ptr, w.col_idx, w.vals, w.B)
+    outs, errors = {}, []
+
+    def work(name, variant):
+        try:
+            st = torch.cuda.Stream(device=DEV)
+            for _ in range(5):
+                Cg = torch.full((w.m, w.N), float("nan"), dtype=torch.float32, device=DEV)
+                binding.gcoo_spdm(A, Bt, Cg, variant=variant, stream=st)
+            st.synchronize()
+            outs[name] = Cg.cpu().numpy()
+        except Exception as e:                                   # surfaced below
+            errors.append((name, e))
+    threads = [threading.Thread(target=work, args=("share", binding.VARIANT_SHARE)),
+               threading.Thread(target=work, args=("reg", binding.VARIANT_REG)),
+               threading.Thread(target=work, args=("auto", binding.VARIANT_AUTO))]
+    for t in threads:
+        t.start()
+    for t in threads:
+        t.join()
+    assert not errors, errors
+    for name, Ch in outs.items():
+        err, bad = orc.max_scaled_error(Ch, C64, D64)
+        assert bad == 0 and err <= TOL, name
+
+
+def test_dense_count_on_two_streams_at_once():
+    """gcoo_dense_nnz takes a counter of its own per call: two host threads on two streams get their own counts."""
+    import threading
+    _say("gcoo_dense_nnz from two threads")
+    rng = np.random.default_rng(6)
+    mats = [torch.from_numpy(((rng.random((3000, 2000)) < d) * 1.0).astype(np.float32)).to(DEV) for d in (0.1, 0.3)]
+    want = [int((x != 0).sum().item()) for x in mats]
+    got = [[], []]
+
+    def work(i):
+        st = torch.cuda.Stream(device=DEV)
+        for _ in range(20):
+            got[i].append(binding.gcoo_dense_nnz(mats[i], stream=st))
+    threads = [threading.Thread(target=work, args=(i,)) for i in (0, 1)]
+    for t in threads:
+        t.start()
+    for t in threads:
+        t.join()
+    assert got[0] == [want[0]] * 20 and got[1] == [want[1]] * 20
+
+
+def test_device_csr_with_a_column_out_of_range_is_clamped_and_reported():
+    """Device input is not validated on the host; a column outside [0, k) is stored clamped (so no kernel leaves
+    B) and gcoo_export says GCOO_EBOUNDS."""
+    _say("device CSR, column out of range")
+    w = workloads.uniform_random(100, 200, 64, 0.9, seed=2)
+    ci = w.col_idx.copy()
+    ci[5] = 200
+    ci[17] = -3
+    dev = [torch.from_numpy(x).to(DEV) for x in (w.row_ptr, ci, w.vals)]
+    A = binding.gcoo_from_csr(w.m, w.k, *dev, 16, device=DEV, known_nnz=True)
+    with pytest.raises(binding.GcooError) as e:
+        A.export()
+    assert e.value.status == binding.GCOO_EBOUNDS
+    Cg = binding.gcoo_spdm(A, torch.from_numpy(w.B).to(DEV))           # stays inside B: columns 199 and 0 were used
+    torch.cuda.synchronize()
+    ci[5], ci[17] = 199, 0
+    order = np.lexsort((ci, np.repeat(np.arange(w.m), np.diff(w.row_ptr))))
+    C64, D64 = orc.spdm_csr(w.k, w.N, w.row_ptr, ci[order].astype(np.int32), w.vals[order], w.B)
+    err, bad = orc.max_scaled_error(Cg.cpu().numpy(), C64, D64)
+    assert bad == 0 and err <= TOL
