@@ -51,7 +51,8 @@ typedef enum gcoo_status {
                            nnz or a dimension above INT32_MAX, unknown variant */
     GCOO_EBOUNDS = -2,  /* host-side validation: row_ptr not non-decreasing from 0, or a column outside [0, k) */
     GCOO_ENOMEM = -3,   /* dev_buf smaller than gcoo_device_bytes() for this input */
-    GCOO_EHIP = -4      /* a HIP runtime call failed; gcoo_last_hip_error() holds its text */
+    GCOO_EHIP = -4,     /* a HIP runtime call failed; gcoo_last_hip_error() holds its text */
+    GCOO_ELIMIT = -5    /* gcoo_from_csr_device_static(): more stored entries than its fixed scratch serves */
 } gcoo_status;
 
 /* Largest supported group height p (rows per group). */
@@ -121,6 +122,27 @@ int gcoo_from_csr_device(int64_t m, int64_t k, int64_t nnz,
                          const int32_t* row_ptr_dev, const int32_t* col_idx_dev, const float* vals_dev,
                          int32_t p, void* dev_buf, size_t dev_buf_bytes, void* stream,
                          gcoo_matrix** out);
+
+/*
+ * gcoo_from_csr_device() for callers that may not allocate device memory beyond what they hand over as
+ * output - code under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.  out_buf
+ * (256-byte aligned, >= gcoo_static_handle_bytes(m, k, nnz, p)) receives only what the handle keeps:
+ * the five arrays, the statistics and the schedules.  What the conversion needs beyond that (the second
+ * buffer of the radix sort, 12 bytes per stored entry, and a counter) is a fixed array inside the
+ * library, 24 MiB + 256 bytes per device, held until the process ends; hence the limit
+ *   nnz <= GCOO_STATIC_MAX_NNZ, else GCOO_ELIMIT (gcoo_static_handle_bytes() then returns 0).
+ * The call allocates and frees no device memory and copies nothing back; it launches the same
+ * kernels as gcoo_from_csr_device() and produces the same arrays, schedules and products.
+ * Every call on a device uses that device's one array: two such conversions that overlap in time on
+ * one GPU (other streams, other threads) race on it and give unspecified arrays; a second call
+ * may start once the kernels of the first have finished.
+ */
+#define GCOO_STATIC_MAX_NNZ 2097152
+size_t gcoo_static_handle_bytes(int64_t m, int64_t k, int64_t nnz, int32_t p);
+int gcoo_from_csr_device_static(int64_t m, int64_t k, int64_t nnz,
+                                const int32_t* row_ptr_dev, const int32_t* col_idx_dev, const float* vals_dev,
+                                int32_t p, void* out_buf, size_t out_buf_bytes, void* stream,
+                                gcoo_matrix** out);
 
 /*
  * Algorithm 1, step 1: count the entries of a dense device matrix A_dev (m x k, row-major,

@@ -16,7 +16,8 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "libgcoo.so")
 BASELINE_LIB_PATH = os.path.join(_HERE, "libgcoo_baseline.so")
 
-GCOO_OK, GCOO_EINVAL, GCOO_EBOUNDS, GCOO_ENOMEM, GCOO_EHIP = 0, -1, -2, -3, -4
+GCOO_OK, GCOO_EINVAL, GCOO_EBOUNDS, GCOO_ENOMEM, GCOO_EHIP, GCOO_ELIMIT = 0, -1, -2, -3, -4, -5
+GCOO_STATIC_MAX_NNZ = 2097152
 GCOO_MAX_P = 256
 VARIANT_AUTO, VARIANT_LDS, VARIANT_REG, VARIANT_SHARE = 0, 1, 2, 3
 SHARE_AUTO, SHARE_ALWAYS, SHARE_NEVER = 0, 1, 2
@@ -24,7 +25,8 @@ SHARE_AUTO, SHARE_ALWAYS, SHARE_NEVER = 0, 1, 2
 # every symbol include/gcoo.h declares
 SYMBOLS = ["gcoo_default_p", "gcoo_device_bytes", "gcoo_from_csr", "gcoo_from_csr_device", "gcoo_dense_nnz", "gcoo_from_dense", "gcoo_spdm",
            "gcoo_spdm_variant", "gcoo_spdm_pick", "gcoo_free", "gcoo_info", "gcoo_export",
-           "gcoo_strerror", "gcoo_last_hip_error", "gcoo_set_share_policy", "gcoo_export_share"]
+           "gcoo_strerror", "gcoo_last_hip_error", "gcoo_set_share_policy", "gcoo_export_share",
+           "gcoo_static_handle_bytes", "gcoo_from_csr_device_static"]
 # and include/gcoo_baseline.h (libgcoo_baseline.so)
 BASELINE_SYMBOLS = ["gcoo_csr_spmm_baseline"]
 
@@ -74,6 +76,10 @@ def lib():
         L.gcoo_export.argtypes = [vp, vp, vp, vp, vp, vp, vp]
         L.gcoo_from_csr_device.restype = C.c_int
         L.gcoo_from_csr_device.argtypes = [i64, i64, i64, vp, vp, vp, i32, vp, C.c_size_t, vp, C.POINTER(vp)]
+        L.gcoo_static_handle_bytes.restype = sz
+        L.gcoo_static_handle_bytes.argtypes = [i64, i64, i64, i32]
+        L.gcoo_from_csr_device_static.restype = C.c_int
+        L.gcoo_from_csr_device_static.argtypes = [i64, i64, i64, vp, vp, vp, i32, vp, C.c_size_t, vp, C.POINTER(vp)]
         L.gcoo_set_share_policy.restype = C.c_int
         L.gcoo_set_share_policy.argtypes = [C.c_int]
         L.gcoo_export_share.restype = C.c_int
@@ -214,6 +220,26 @@ def gcoo_from_csr(m: int, k: int, row_ptr, col_idx, vals, p: int, device="cuda:0
             _check(lib().gcoo_from_csr(m, k, ptrs[0], ptrs[1], ptrs[2], 1 if on_dev else 0, p, buf.data_ptr(),
                                        buf.numel(), _stream_ptr(stream), C.byref(out)), "gcoo_from_csr")
     return GcooMatrix(out.value, buf)
+
+
+def gcoo_from_csr_device_static(m: int, k: int, row_ptr: torch.Tensor, col_idx: torch.Tensor, vals: torch.Tensor, p: int,
+                                out_buf: torch.Tensor | None = None, stream=None) -> GcooMatrix:
+    """gcoo_from_csr_device_static: the conversion that allocates no device memory.  out_buf (a uint8 device
+    tensor the caller already owns) receives what the handle keeps; without one, a tensor of
+    gcoo_static_handle_bytes is made here first (the C call itself allocates nothing either way)."""
+    assert row_ptr.is_cuda and row_ptr.dtype == torch.int32 and col_idx.dtype == torch.int32 and vals.dtype == torch.float32
+    nnz = int(col_idx.numel())
+    need = int(lib().gcoo_static_handle_bytes(m, k, nnz, p))
+    with torch.cuda.device(row_ptr.device):
+        if out_buf is None:
+            if need == 0:
+                raise GcooError(GCOO_ELIMIT if nnz > GCOO_STATIC_MAX_NNZ else GCOO_EINVAL, "gcoo_static_handle_bytes")
+            out_buf = _alloc(need, row_ptr.device)
+        out = C.c_void_p()
+        _check(lib().gcoo_from_csr_device_static(m, k, nnz, row_ptr.data_ptr(), col_idx.data_ptr(), vals.data_ptr(), p,
+                                                 out_buf.data_ptr(), out_buf.numel(), _stream_ptr(stream), C.byref(out)),
+               "gcoo_from_csr_device_static")
+    return GcooMatrix(out.value, out_buf)
 
 
 def gcoo_dense_nnz(A: torch.Tensor, stream=None) -> int:

@@ -11,6 +11,7 @@
 #include <string>
 
 #include <atomic>
+#include <mutex>
 
 #include "gcoo_build_kernels.hpp"
 #include "gcoo_sched.hpp"
@@ -47,6 +48,35 @@ constexpr unsigned kDenseSlots = 256;
 __device__ unsigned long long g_dense_total[kDenseSlots];
 std::atomic<unsigned> g_dense_next{0};
 
+// Scratch of gcoo_from_csr_device_static(), the conversion for callers that may not allocate device
+// memory: the second buffer of the per-group radix sort (3 arrays of nnz words) and the counter from
+// which the share schedule's streams take their place.  One copy per device, held until the process
+// ends.  Host code never uses the array's name as an address: static_scratch() asks the runtime for
+// the address on the current device, once per device, and everything goes through that pointer.
+constexpr int64_t kStaticMaxNnz = 2 * 1024 * 1024;
+constexpr size_t kStaticSortBytes = (size_t)kStaticMaxNnz * 4;        // each of the three arrays, a multiple of 256
+constexpr size_t kStaticScratchBytes = 3 * kStaticSortBytes + 256;
+static __device__ __align__(256) unsigned char g_static_scratch[kStaticScratchBytes];
+constexpr int kMaxDevices = 64;
+std::mutex g_static_mutex;
+unsigned char* g_static_ptr[kMaxDevices] = {};
+
+int static_scratch(unsigned char** out)
+{
+    int dev = -1;
+    HIP_TRY(hipGetDevice(&dev));
+    if (dev < 0 || dev >= kMaxDevices) return GCOO_EINVAL;
+    std::lock_guard<std::mutex> lock(g_static_mutex);
+    if (!g_static_ptr[dev]) {
+        unsigned char* ptr = nullptr;
+        HIP_TRY(hipGetSymbolAddress(reinterpret_cast<void**>(&ptr), HIP_SYMBOL(g_static_scratch)));
+        if (!ptr) return GCOO_EHIP;
+        g_static_ptr[dev] = ptr;
+    }
+    *out = g_static_ptr[dev];
+    return GCOO_OK;
+}
+
 // Carve-up of the caller's device buffer.  Offsets depend on (m, nnz, g) only.
 struct Layout {
     size_t values, rows, cols, gIdxes, nnzPerGroup;        // the five arrays of the format
@@ -55,6 +85,9 @@ struct Layout {
     size_t tmp_cols, tmp_rows, tmp_vals;                   // conversion scratch (second sort buffer)
     size_t in_row_ptr, in_cols, in_vals;                   // staging of a host CSR input
     size_t counter;                                        // device words: nnz (8 bytes), largest group (8), column-out-of-range flag (4)
+    size_t persistent;                                     // bytes up to here stay in use after the conversion
+    // offsets from here on are relative to the scratch area: the caller's buffer from `persistent` on, or the
+    // library's static scratch
     size_t blk;                                            // dense input: entries per (group, column block)
     size_t total;
 };
@@ -157,7 +190,7 @@ int32_t share_best_p(int64_t m, int64_t N)
     return best;
 }
 
-Layout make_layout(int64_t m, int64_t k, int64_t nnz, int64_t g, int32_t p)
+Layout make_layout(int64_t m, int64_t k, int64_t nnz, int64_t g, int32_t p, bool scratch_inside = true)
 {
     int32_t nw, wc;
     pick_windows(k, g, &nw, &wc);
@@ -183,6 +216,18 @@ Layout make_layout(int64_t m, int64_t k, int64_t nnz, int64_t g, int32_t p)
     L.share_hdr = take(share ? (size_t)gcoo::share_hdr_words(nnz, g) * 4 : 0);
     L.share_blocks = take(share ? (size_t)gcoo::share_stream_blocks(nnz, g, k) * gcoo::kShareBlockWords * 4 : 0);
     L.share_sbase = take(share ? (size_t)nQ * gcoo::kShareW * 4 : 0);
+    L.persistent = at;
+    if (!scratch_inside) {
+        // the fixed carve-up of the static scratch (no staging of a host input there)
+        L.tmp_cols = 0;
+        L.tmp_rows = kStaticSortBytes;
+        L.tmp_vals = 2 * kStaticSortBytes;
+        L.share_alloc = 3 * kStaticSortBytes;
+        L.in_row_ptr = L.in_cols = L.in_vals = 0;
+        L.total = L.persistent;
+        return L;
+    }
+    at = 0;
     L.share_alloc = take(share ? 4 : 0);
     L.tmp_cols = take(n4);
     L.tmp_rows = take(n4);
@@ -190,7 +235,7 @@ Layout make_layout(int64_t m, int64_t k, int64_t nnz, int64_t g, int32_t p)
     L.in_row_ptr = take((size_t)(m + 1) * 4);
     L.in_cols = take(n4);
     L.in_vals = take(n4);
-    L.total = at;
+    L.total = L.persistent + at;
     return L;
 }
 
@@ -235,20 +280,19 @@ struct gcoo_matrix {
     uint32_t* share_hdr() const { return reinterpret_cast<uint32_t*>(base + L.share_hdr); }
     uint32_t* share_blocks() const { return reinterpret_cast<uint32_t*>(base + L.share_blocks); }
     int32_t* share_sbase() const { return reinterpret_cast<int32_t*>(base + L.share_sbase); }
-    uint32_t* share_alloc() const { return reinterpret_cast<uint32_t*>(base + L.share_alloc); }
     int64_t share_nq() const { return gcoo::share_super_groups(g); }
 };
 
 namespace {
 
-int new_handle(int64_t m, int64_t k, int64_t nnz, int32_t p, void* dev_buf, gcoo_matrix** out)
+int new_handle(int64_t m, int64_t k, int64_t nnz, int32_t p, void* dev_buf, gcoo_matrix** out, bool scratch_inside = true)
 {
     gcoo_matrix* h = new (std::nothrow) gcoo_matrix;
     if (!h) return GCOO_ENOMEM;
     h->m = m; h->k = k; h->nnz = nnz; h->p = p;
     h->g = (m + p - 1) / p;
     h->base = static_cast<char*>(dev_buf);
-    h->L = make_layout(m, k, nnz, h->g, p);
+    h->L = make_layout(m, k, nnz, h->g, p, scratch_inside);
     h->has_share = share_schedule_wanted(m, k, nnz, p);
     h->share_preferred = h->has_share && share_kernel_preferred(m, k, nnz, p);
     h->has_sched = h->p <= gcoo::kSchedMaxP;
@@ -261,8 +305,10 @@ int new_handle(int64_t m, int64_t k, int64_t nnz, int32_t p, void* dev_buf, gcoo
 // The kernel-private schedules that a conversion ends with: the run schedule of the register kernel
 // (every matrix of at most 64 rows per group) and, where wanted, the share schedule.  Both are built
 // here, on the conversion's stream, so that the handle is never written again.
-int launch_build_schedule(const gcoo_matrix* h, hipStream_t s)
+// `scratch`: the conversion's scratch area (the counter of share_fill sits in it).
+int launch_build_schedule(const gcoo_matrix* h, char* scratch, hipStream_t s)
 {
+    uint32_t* share_alloc = reinterpret_cast<uint32_t*>(scratch + h->L.share_alloc);
     if (h->g > 0 && h->has_sched) {
         const dim3 grid((unsigned)(h->g * h->nw));
         if (h->nnz / (h->g * h->nw) <= 1024)
@@ -276,12 +322,12 @@ int launch_build_schedule(const gcoo_matrix* h, hipStream_t s)
     if (h->g > 0 && h->has_share) {
         const size_t bitmap_bytes = (size_t)((h->k + 31) / 32) * 4;
         gcoo::share_union<<<dim3((unsigned)h->share_nq()), dim3(gcoo::kShareBuildThreads), bitmap_bytes, s>>>(
-            h->gIdxes(), h->cols(), h->g, h->k, gcoo::kShareW, h->share_ucols(), h->share_ucount(), h->share_alloc());
+            h->gIdxes(), h->cols(), h->g, h->k, gcoo::kShareW, h->share_ucols(), h->share_ucount(), share_alloc);
         HIP_TRY(hipGetLastError());
         const size_t table_bytes = 2 * (size_t)((h->k + gcoo::kShareBandRows - 1) / gcoo::kShareBandRows + 1) * 4;
         gcoo::share_fill<<<dim3((unsigned)(h->share_nq() * gcoo::kShareW)), dim3(gcoo::kShareBuildThreads), table_bytes, s>>>(
             h->gIdxes(), h->rows(), h->cols(), h->values(), h->p, h->g, h->k, h->share_ucols(), h->share_ucount(), h->share_hdr(),
-            h->share_blocks(), h->share_sbase(), h->share_alloc());
+            h->share_blocks(), h->share_sbase(), share_alloc);
         HIP_TRY(hipGetLastError());
     }
     return GCOO_OK;
@@ -328,9 +374,13 @@ size_t gcoo_device_bytes(int64_t m, int64_t k, int64_t nnz, int32_t p)
 namespace {
 
 // gcoo_from_csr() and gcoo_from_csr_device().  nnz_known < 0: learn nnz from the input.
+// static_scratch_ptr != nullptr: the conversion's scratch is that area instead of the tail of dev_buf (device input with
+// nnz given only).
 int from_csr(int64_t m, int64_t k, const int32_t* row_ptr, const int32_t* col_idx, const float* vals, int src_on_device,
-             int64_t nnz_known, int32_t p, void* dev_buf, size_t dev_buf_bytes, void* stream, gcoo_matrix** out)
+             int64_t nnz_known, int32_t p, void* dev_buf, size_t dev_buf_bytes, void* stream, gcoo_matrix** out,
+             unsigned char* static_scratch_ptr = nullptr)
 {
+    const bool inside = static_scratch_ptr == nullptr;
     if (!out) return GCOO_EINVAL;
     *out = nullptr;
     if (!row_ptr || !dev_buf || !dims_ok(m, k, 0, p)) return GCOO_EINVAL;
@@ -341,12 +391,12 @@ int from_csr(int64_t m, int64_t k, const int32_t* row_ptr, const int32_t* col_id
     int64_t nnz;
     if (src_on_device && nnz_known >= 0) {          // everything the host can check, before the first launch
         if (nnz_known > 0 && (!col_idx || !vals)) return GCOO_EINVAL;
-        if (dev_buf_bytes < make_layout(m, k, nnz_known, g, p).total) return GCOO_ENOMEM;
+        if (dev_buf_bytes < make_layout(m, k, nnz_known, g, p, inside).total) return GCOO_ENOMEM;
     }
     // nnz and the size of the largest group are computed on the device and stay there (the counters
     // sit at an offset of the buffer that does not depend on nnz); the launches that need the
     // latter read it there.
-    const Layout L0 = make_layout(m, k, 0, g, p);
+    const Layout L0 = make_layout(m, k, 0, g, p, inside);
     if (dev_buf_bytes < L0.total) return GCOO_ENOMEM;
     unsigned long long* stats = reinterpret_cast<unsigned long long*>(static_cast<char*>(dev_buf) + L0.counter);
     if (src_on_device) {
@@ -372,21 +422,22 @@ int from_csr(int64_t m, int64_t k, const int32_t* row_ptr, const int32_t* col_id
             if (col_idx[e] < 0 || col_idx[e] >= k) return GCOO_EBOUNDS;
     }
     if (nnz > 0 && (!col_idx || !vals)) return GCOO_EINVAL;
-    const Layout L = make_layout(m, k, nnz, g, p);
+    const Layout L = make_layout(m, k, nnz, g, p, inside);
     if (dev_buf_bytes < L.total) return GCOO_ENOMEM;
 
     gcoo_matrix* h = nullptr;
-    int rc = new_handle(m, k, nnz, p, dev_buf, &h);
+    int rc = new_handle(m, k, nnz, p, dev_buf, &h, inside);
     if (rc != GCOO_OK) return rc;
     char* base = h->base;
+    char* scratch = inside ? base + L.persistent : reinterpret_cast<char*>(static_scratch_ptr);
 
     const int32_t* d_row_ptr = row_ptr;
     const int32_t* d_cols = col_idx;
     const float* d_vals = vals;
     if (!src_on_device) {
-        int32_t* sp = reinterpret_cast<int32_t*>(base + L.in_row_ptr);
-        int32_t* sc = reinterpret_cast<int32_t*>(base + L.in_cols);
-        float* sv = reinterpret_cast<float*>(base + L.in_vals);
+        int32_t* sp = reinterpret_cast<int32_t*>(scratch + L.in_row_ptr);
+        int32_t* sc = reinterpret_cast<int32_t*>(scratch + L.in_cols);
+        float* sv = reinterpret_cast<float*>(scratch + L.in_vals);
         hipError_t e = hipMemcpyAsync(sp, row_ptr, (size_t)(m + 1) * 4, hipMemcpyHostToDevice, s);
         if (e == hipSuccess && nnz > 0) e = hipMemcpyAsync(sc, col_idx, (size_t)nnz * 4, hipMemcpyHostToDevice, s);
         if (e == hipSuccess && nnz > 0) e = hipMemcpyAsync(sv, vals, (size_t)nnz * 4, hipMemcpyHostToDevice, s);
@@ -409,9 +460,9 @@ int from_csr(int64_t m, int64_t k, const int32_t* row_ptr, const int32_t* col_id
     if (g > 0 && nnz > 0) {
         const int passes = radix_passes(k);
         int32_t* fin_c = h->cols(); int32_t* fin_r = h->rows(); float* fin_v = h->values();
-        int32_t* tmp_c = reinterpret_cast<int32_t*>(base + L.tmp_cols);
-        int32_t* tmp_r = reinterpret_cast<int32_t*>(base + L.tmp_rows);
-        float* tmp_v = reinterpret_cast<float*>(base + L.tmp_vals);
+        int32_t* tmp_c = reinterpret_cast<int32_t*>(scratch + L.tmp_cols);
+        int32_t* tmp_r = reinterpret_cast<int32_t*>(scratch + L.tmp_rows);
+        float* tmp_v = reinterpret_cast<float*>(scratch + L.tmp_vals);
         const int32_t* src_c = d_cols; const int32_t* src_r = nullptr; const float* src_v = d_vals;
         // Two passes and large groups: high digit first, then the low digit bucket by bucket (see the
         // kernel); otherwise low digit first, whole groups.
@@ -437,7 +488,7 @@ int from_csr(int64_t m, int64_t k, const int32_t* row_ptr, const int32_t* col_id
             src_c = dc; src_r = dr; src_v = dv;
         }
     }
-    rc = launch_build_schedule(h, s);
+    rc = launch_build_schedule(h, scratch, s);
     if (rc != GCOO_OK) { delete h; return rc; }
     *out = h;
     return GCOO_OK;
@@ -446,6 +497,25 @@ int from_csr(int64_t m, int64_t k, const int32_t* row_ptr, const int32_t* col_id
 }  // namespace
 
 extern "C" {
+
+size_t gcoo_static_handle_bytes(int64_t m, int64_t k, int64_t nnz, int32_t p)
+{
+    if (!dims_ok(m, k, nnz, p) || nnz > kStaticMaxNnz) return 0;
+    return make_layout(m, k, nnz, (m + p - 1) / p, p, false).total;
+}
+
+int gcoo_from_csr_device_static(int64_t m, int64_t k, int64_t nnz, const int32_t* row_ptr_dev, const int32_t* col_idx_dev,
+                                const float* vals_dev, int32_t p, void* out_buf, size_t out_buf_bytes, void* stream,
+                                gcoo_matrix** out)
+{
+    if (out) *out = nullptr;
+    if (nnz < 0 || nnz > INT32_MAX) return GCOO_EINVAL;
+    if (nnz > kStaticMaxNnz) return GCOO_ELIMIT;
+    unsigned char* scratch = nullptr;
+    int rc = static_scratch(&scratch);
+    if (rc != GCOO_OK) return rc;
+    return from_csr(m, k, row_ptr_dev, col_idx_dev, vals_dev, 1, nnz, p, out_buf, out_buf_bytes, stream, out, scratch);
+}
 
 int gcoo_from_csr(int64_t m, int64_t k, const int32_t* row_ptr, const int32_t* col_idx, const float* vals,
                   int src_on_device, int32_t p, void* dev_buf, size_t dev_buf_bytes, void* stream, gcoo_matrix** out)
@@ -544,7 +614,7 @@ int gcoo_from_dense(int64_t m, int64_t k, const float* A_dev, int64_t lda, int32
         hipError_t e = hipGetLastError();
         if (e != hipSuccess) { delete h; return hip_fail(e, "fill_dense_blocks"); }
     }
-    rc = launch_build_schedule(h, s);
+    rc = launch_build_schedule(h, h->base + h->L.persistent, s);
     if (rc != GCOO_OK) { delete h; return rc; }
     *out = h;
     return GCOO_OK;
@@ -745,6 +815,7 @@ const char* gcoo_strerror(int status)
         case GCOO_EBOUNDS: return "malformed CSR input (row_ptr not non-decreasing from 0, or column out of range)";
         case GCOO_ENOMEM: return "device buffer too small (see gcoo_device_bytes) or host allocation failed";
         case GCOO_EHIP: return "HIP runtime error (see gcoo_last_hip_error)";
+        case GCOO_ELIMIT: return "input larger than the fixed scratch of gcoo_from_csr_device_static (at most 2097152 stored entries)";
         default: return "unknown status";
     }
 }

@@ -110,6 +110,13 @@ def test_newer_entry_points_reject_bad_arguments_on_the_host(L):
     assert L.gcoo_set_share_policy(3) == binding.GCOO_EINVAL
     assert L.gcoo_set_share_policy(binding.SHARE_AUTO) == 0
     assert L.gcoo_export_share(None, None, None, None, None, None, None, None, None) == binding.GCOO_EINVAL
+    # the conversion without device allocations: its limit is checked on the host, before any device call
+    big = binding.GCOO_STATIC_MAX_NNZ + 1
+    assert L.gcoo_static_handle_bytes(4000, 4000, big, 32) == 0
+    assert L.gcoo_from_csr_device_static(4000, 4000, big, fake, fake, fake, 32, fake, 1 << 40, None, C.byref(out)) \
+        == binding.GCOO_ELIMIT
+    assert out.value is None and b"2097152" in L.gcoo_strerror(binding.GCOO_ELIMIT)
+    assert 0 < L.gcoo_static_handle_bytes(4000, 4000, 1000, 32) < L.gcoo_device_bytes(4000, 4000, 1000, 32)
     assert L.gcoo_spdm_pick(None, None, 4, 4, None, 4) == binding.GCOO_EINVAL
     for variant in (-1, 4):
         assert L.gcoo_spdm_variant(None, None, 4, 4, None, 4, None, variant) == binding.GCOO_EINVAL
