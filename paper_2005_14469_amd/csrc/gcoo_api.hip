@@ -121,16 +121,17 @@ int dense_vec_width(const float* A, int64_t lda, int64_t k)
     return (k % 4 == 0 && lda % 4 == 0 && reinterpret_cast<uintptr_t>(A) % 16 == 0) ? 4 : 1;
 }
 
-// The share schedule costs conversion time and memory, so it is built only where the workgroup-shared
-// kernel is the one gcoo_spdm() will pick.  Measured on MI355X with uniform random square matrices
-// (n = 4000 .. 14000, density 0.1 % .. 10 %, N = n), against the register kernel at its best group height:
-// the workgroup-shared kernel wins from 7000 columns on at any density between 0.5 % and 6 % (n = 8000: by
-// 10 .. 30 % between 1 % and 5 %, level at 0.5 %; n = 14000: 1.7 .. 2.3x), and from 3500 columns on at 0.8 % or more
-// (n = 4000, 2 %: 12 %).  The B tile of a column tile then no longer stays in L2 between the groups
-// that need it, and what the register kernel pays per run (a 1 KB segment through the vector cache)
-// costs more than the per-band steps of the workgroup-shared kernel.  Above 6 % the register kernel,
-// which reuses a fetched segment along runs of up to eight entries, is ahead (10 %: 2.9 against 3.2 ms
-// at n = 8000); at 0.1 % and at n <= 3000 too.  gcoo_set_share_policy() overrides the choice.
+// The share schedule costs conversion time (0.05 ms at 320 000 entries) and memory, so it is built only where
+// the workgroup-shared kernel is the one gcoo_spdm() will pick.  Measured on MI355X with uniform random square
+// matrices (n = 4000 .. 14000, density 0.1 % .. 10 %, N = n), against the register kernel at its best group height:
+// the workgroup-shared kernel wins from 3500 columns on at 0.8 % density or more (n = 8000: by 10 .. 30 % between
+// 1 % and 5 %; n = 4000, 2 %: 12 %) and from 12000 columns on already at 0.4 % (n = 14000: 1.7 .. 2.3x between 0.5 %
+// and 2 %); at n = 8000 and 0.5 % the two kernels are level and the schedule's cost decides for the register
+// kernel.  The B tile of a column tile then no longer stays in L2 between the groups that need it, and what
+// the register kernel pays per run (a 1 KB segment through the vector cache) costs more than the per-band steps
+// of the workgroup-shared kernel.  Above 6 % the register kernel, which reuses a fetched segment along runs of
+// up to eight entries, is ahead (10 %: 2.9 against 3.2 ms at n = 8000); at 0.1 % and at n <= 3000 too.
+// gcoo_set_share_policy() overrides the choice.
 int g_share_policy = GCOO_SHARE_AUTO;
 
 bool share_schedule_possible(int64_t m, int64_t k, int64_t nnz, int32_t p)
@@ -144,7 +145,7 @@ bool share_shape_preferred(int64_t m, int64_t k, int64_t nnz)
     if (m <= 0 || k <= 0 || nnz <= 0 || k > gcoo::kShareMaxK) return false;
     const double density = (double)nnz / ((double)m * (double)k);
     if (density > 0.06) return false;
-    return k >= 7000 || (k >= 3500 && density >= 0.008);
+    return (k >= 12000 && density >= 0.004) || (k >= 3500 && density >= 0.008);
 }
 
 bool share_kernel_preferred(int64_t m, int64_t k, int64_t nnz, int32_t p)
