@@ -42,6 +42,9 @@ def parse():
                          "uniform_<n>_<sparsity> for a square uniform random A with N = n")
     ap.add_argument("--p", type=int, default=0, help="group height; 0 = library default for the workload")
     ap.add_argument("--variant", type=int, default=0, help="0 auto, 1 partial sums in LDS, 2 partial sums in registers, 3 the same with the rows of B shared through LDS by the eight groups of a workgroup")
+    ap.add_argument("--share", choices=["auto", "always", "never"], default="auto",
+                    help="when the conversion also builds the schedule of variant 3: where the library expects that kernel to be "
+                         "picked (auto), wherever it can run (always: needed to force --variant 3 elsewhere), or never")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle timing")
     ap.add_argument("--no-dense", action="store_true", help="skip the dense SGEMM timing")
     ap.add_argument("--secondary", default="config2", help="second workload reported in the same line ('' = none)")
@@ -372,6 +375,7 @@ def main():
         sys.exit(3)
     dev = torch.device("cuda:0")
     torch.cuda.set_device(dev)
+    binding.gcoo_set_share_policy({"auto": binding.SHARE_AUTO, "always": binding.SHARE_ALWAYS, "never": binding.SHARE_NEVER}[args.share])
     if args.copy_calibration:
         src = torch.ones(64 * 1024 * 1024, dtype=torch.float32, device=dev)
         dst = torch.empty_like(src)
