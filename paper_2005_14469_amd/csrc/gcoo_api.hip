@@ -306,6 +306,22 @@ int new_handle(int64_t m, int64_t k, int64_t nnz, int32_t p, void* dev_buf, gcoo
 // The kernel-private schedules that a conversion ends with: the run schedule of the register kernel
 // (every matrix of at most 64 rows per group) and, where wanted, the share schedule.  Both are built
 // here, on the conversion's stream, so that the handle is never written again.
+// share_fill may ask for more dynamic LDS than a kernel gets by default: raised once per device (a compute unit
+// has 160 KB; the kernel's static variables take a little of it).
+constexpr int kShareFillMaxLds = 156 * 1024;
+hipError_t share_fill_lds_limit()
+{
+    static std::atomic<unsigned> done[64];
+    int dev = 0;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return e;
+    if (dev < 0 || dev >= 64) return hipErrorInvalidDevice;
+    if (done[dev].load(std::memory_order_acquire)) return hipSuccess;
+    e = hipFuncSetAttribute(reinterpret_cast<const void*>(&gcoo::share_fill), hipFuncAttributeMaxDynamicSharedMemorySize, kShareFillMaxLds);
+    if (e == hipSuccess) done[dev].store(1u, std::memory_order_release);
+    return e;
+}
+
 // `scratch`: the conversion's scratch area (the counter of share_fill sits in it).
 int launch_build_schedule(const gcoo_matrix* h, char* scratch, hipStream_t s)
 {
@@ -325,10 +341,17 @@ int launch_build_schedule(const gcoo_matrix* h, char* scratch, hipStream_t s)
         gcoo::share_union<<<dim3((unsigned)h->share_nq()), dim3(gcoo::kShareBuildThreads), bitmap_bytes, s>>>(
             h->gIdxes(), h->cols(), h->g, h->k, gcoo::kShareW, h->share_ucols(), h->share_ucount(), share_alloc);
         HIP_TRY(hipGetLastError());
-        const size_t table_bytes = 2 * (size_t)((h->k + gcoo::kShareBandRows - 1) / gcoo::kShareBandRows + 1) * 4;
-        gcoo::share_fill<<<dim3((unsigned)(h->share_nq() * gcoo::kShareW)), dim3(gcoo::kShareBuildThreads), table_bytes, s>>>(
+        // LDS of share_fill: its per-band tables and room for the columns of a group of up to twice the mean size
+        // (between 8 K and 28 K entries: two workgroups share a compute unit up to 80 KB each)
+        const size_t table_bytes = 4 * (size_t)((h->k + gcoo::kShareBandRows - 1) / gcoo::kShareBandRows + 1) * 4;
+        int64_t stage_cap = 2 * (h->nnz / h->g + 1);
+        stage_cap = stage_cap < 8192 ? 8192 : (stage_cap > 28672 ? 28672 : stage_cap);
+        if (table_bytes + (size_t)stage_cap * 4 > (size_t)kShareFillMaxLds) stage_cap = 0;
+        const size_t fill_lds = table_bytes + (size_t)stage_cap * 4;
+        HIP_TRY(share_fill_lds_limit());
+        gcoo::share_fill<<<dim3((unsigned)(h->share_nq() * gcoo::kShareW)), dim3(gcoo::kShareBuildThreads), fill_lds, s>>>(
             h->gIdxes(), h->rows(), h->cols(), h->values(), h->p, h->g, h->k, h->share_ucols(), h->share_ucount(), h->share_hdr(),
-            h->share_blocks(), h->share_sbase(), share_alloc);
+            h->share_blocks(), h->share_sbase(), share_alloc, (int32_t)stage_cap);
         HIP_TRY(hipGetLastError());
     }
     return GCOO_OK;

@@ -27,10 +27,21 @@ __device__ __forceinline__ void sched_put_piece(uint32_t* __restrict__ seg, int 
     uint32_t* blk = seg + sched_block_word(L, x);
     uint8_t* rp = reinterpret_cast<uint8_t*>(blk + blk_rowpack(L, c));
     uint32_t* vp = blk + blk_val(L, c);
-    for (int i = 0; i < L; ++i) {
-        rp[j * L + i] = (uint8_t)(rows ? rows[e + i] - row0 : p);
-        vp[j * L + i] = rows ? __float_as_uint(values[e + i]) : 0u;
+    // all loads first: the stores below may alias them for all the compiler knows, and a load behind every store
+    // makes a piece of eight entries a chain of eight memory latencies
+    int32_t r[kMaxRun];
+    uint32_t v[kMaxRun];
+#pragma unroll
+    for (int i = 0; i < kMaxRun; ++i) {
+        r[i] = (rows && i < L) ? rows[e + i] - row0 : p;
+        v[i] = (rows && i < L) ? __float_as_uint(values[e + i]) : 0u;
     }
+#pragma unroll
+    for (int i = 0; i < kMaxRun; ++i)
+        if (i < L) {
+            rp[j * L + i] = (uint8_t)r[i];
+            vp[j * L + i] = v[i];
+        }
     (void)J;
 }
 
@@ -43,6 +54,11 @@ __device__ __forceinline__ void sched_put_piece(uint32_t* __restrict__ seg, int 
 // per window) makes disjoint.
 // kBuildThreads = 256 or 1024: the launcher takes the small workgroup when a window holds few
 // entries, so that eight of them share a compute unit instead of two.
+// Finding the piece of an entry is a chain of dependent reads of neighbouring columns, and the window's
+// bounds come from searches in the group's columns: from global memory every step of either is a memory
+// latency (config 2: 0.25 ms for 6.4 M entries, seven times what the traffic needs).  So the bounds are
+// found by a wave each, 64 probes per step, and a window of at most kStage entries copies its columns to
+// LDS first and reads them there.
 template <int kBuildThreads>
 __global__ __launch_bounds__(kBuildThreads) void build_schedule(const int32_t* __restrict__ gIdxes, const int32_t* __restrict__ rows,
                                                       const int32_t* __restrict__ cols, const float* __restrict__ values,
@@ -56,6 +72,8 @@ __global__ __launch_bounds__(kBuildThreads) void build_schedule(const int32_t* _
     __shared__ int32_t base[kMaxRun];             // pieces of the class already placed
     constexpr int kBuildWaves = kBuildThreads / 64;
     __shared__ int32_t wcnt[kBuildWaves][kMaxRun];          // per wave, per class, in the current tile
+    constexpr int kStage = kBuildThreads == 256 ? 1536 : 12288;
+    __shared__ int32_t stage[kStage];
     const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
     const int64_t q = blockIdx.x / nw;
     const int32_t w = (int32_t)(blockIdx.x - q * nw);
@@ -66,14 +84,24 @@ __global__ __launch_bounds__(kBuildThreads) void build_schedule(const int32_t* _
     SchedClass* __restrict__ h = hdr + q * nw * kMaxRun;
 
     // window w = the entries whose column is in [w*window_cols, (w+1)*window_cols); the last window takes the rest
-    if (tid < 2) {
-        const int64_t lim = (int64_t)(w + tid) * window_cols;
+    if (wv < 2) {
+        // first entry of the group whose column is >= lim: the probes of a step split [lo, hi) into 64 parts
+        const int64_t lim = (int64_t)(w + wv) * window_cols;
         int32_t lo = beg, hi = end;
         while (lo < hi) {
-            const int32_t mid = lo + (hi - lo) / 2;
-            if ((int64_t)cols[mid] < lim) lo = mid + 1; else hi = mid;
+            const int32_t stride = (hi - lo + 63) / 64;
+            const int32_t at = lo + lane * stride;
+            const bool less = at < hi && (int64_t)cols[at] < lim;
+            const int below = __popcll(__ballot(less));          // the columns ascend: the probes that are less come first
+            if (below == 0) {
+                hi = lo;
+            } else {
+                const int32_t up = lo + below * stride;
+                lo = lo + (below - 1) * stride + 1;
+                hi = up < hi ? up : hi;
+            }
         }
-        wstart[tid] = (w + tid == nw) ? end : lo;
+        if (lane == 0) wstart[wv] = (w + wv == nw) ? end : lo;
     }
     if (tid < kMaxRun) { cnt[tid] = 0; base[tid] = 0; demote[tid] = 0; }
     __syncthreads();
@@ -81,17 +109,23 @@ __global__ __launch_bounds__(kBuildThreads) void build_schedule(const int32_t* _
     const uint64_t lt = (1ull << lane) - 1ull;
     {
         const int32_t wb = wstart[0], we = wstart[1];
+        const bool staged = we - wb <= kStage;
+        if (staged) {
+            for (int32_t e = wb + tid; e < we; e += kBuildThreads) stage[e - wb] = cols[e];
+            __syncthreads();
+        }
+        auto col_at = [&](int32_t e) -> int32_t { return staged ? stage[e - wb] : cols[e]; };
 
         // Length of the natural piece (run cut every kMaxRun entries) that entry e belongs to,
         // and e's place in it.  A run has one column, so it lies inside one window.
         auto natural_piece = [&](int32_t e, int& pos) -> int {
-            const int32_t c = cols[e];
+            const int32_t c = col_at(e);
             int32_t rs = e;                               // first entry of the run
-            while (rs > wb && cols[rs - 1] == c) --rs;
+            while (rs > wb && col_at(rs - 1) == c) --rs;
             pos = (e - rs) % kMaxRun;
             const int32_t ps = e - pos;                   // first entry of the piece
             int len = pos + 1;
-            while (len < kMaxRun && ps + len < we && cols[ps + len] == c) ++len;
+            while (len < kMaxRun && ps + len < we && col_at(ps + len) == c) ++len;
             return len;
         };
 
@@ -140,7 +174,7 @@ __global__ __launch_bounds__(kBuildThreads) void build_schedule(const int32_t* _
                 int32_t rank = base[L - 1] + before;
                 for (int x = 0; x < wv; ++x) rank += wcnt[x][L - 1];
                 const int J = runs_per_chunk(L);
-                sched_put_piece(out + seg[L - 1], L, rank / J, rank % J, (uint32_t)cols[e], rows, values, e, row0, p);
+                sched_put_piece(out + seg[L - 1], L, rank / J, rank % J, (uint32_t)col_at(e), rows, values, e, row0, p);
             }
             __syncthreads();
             if (tid < kMaxRun) {
@@ -156,7 +190,7 @@ __global__ __launch_bounds__(kBuildThreads) void build_schedule(const int32_t* _
         if (tid < kMaxRun && cnt[tid] > 0) {
             const int L = tid + 1, J = runs_per_chunk(L), per_body = kBody * J;
             const int32_t padded = (cnt[tid] + per_body - 1) / per_body * per_body;
-            const uint32_t any_col = (uint32_t)cols[wb];
+            const uint32_t any_col = (uint32_t)col_at(wb);
             uint32_t* sg = out + seg[tid];
             for (int32_t r = cnt[tid]; r < padded; ++r) sched_put_piece(sg, L, r / J, r % J, any_col, nullptr, nullptr, 0, row0, p);
             const int32_t nch = padded / J;

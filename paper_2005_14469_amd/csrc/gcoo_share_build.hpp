@@ -55,9 +55,27 @@ __global__ __launch_bounds__(kShareBuildThreads) void share_union(const int32_t*
     const int32_t e0 = gIdxes[q0], e1 = gIdxes[q1];
     for (int32_t i = threadIdx.x; i < nbw; i += kShareBuildThreads) bits[i] = 0u;
     __syncthreads();
-    for (int32_t e = e0 + (int32_t)threadIdx.x; e < e1; e += kShareBuildThreads) {
-        const uint32_t c = (uint32_t)cols[e];
-        atomicOr(&bits[c >> 5], 1u << (c & 31u));
+    // A thread takes eight consecutive entries at a time and collects the bits of one bitmap word in a register
+    // while the word stays the same (the columns of a group ascend, so it mostly does): one atomic per word
+    // and thread instead of one per entry, and the lanes of a wave, 8 entries apart, rarely meet in a word.
+    // (One atomic per entry cost 110 clocks per wave instruction: most of its lanes hit the same two or three words.)
+    constexpr int kChunk = 8;
+    for (int32_t e = e0 + kChunk * (int32_t)threadIdx.x; e < e1; e += kChunk * kShareBuildThreads) {
+        uint32_t c[kChunk];
+#pragma unroll
+        for (int u = 0; u < kChunk; ++u) c[u] = e + u < e1 ? (uint32_t)cols[e + u] : 0xFFFFFFFFu;
+        uint32_t word = c[0] >> 5, acc = 0u;
+#pragma unroll
+        for (int u = 0; u < kChunk; ++u) {
+            if (c[u] == 0xFFFFFFFFu) break;
+            if ((c[u] >> 5) != word) {
+                atomicOr(&bits[word], acc);
+                word = c[u] >> 5;
+                acc = 0u;
+            }
+            acc |= 1u << (c[u] & 31u);
+        }
+        if (acc) atomicOr(&bits[word], acc);
     }
     __syncthreads();
     // thread t owns the words [t*per, (t+1)*per)
@@ -81,14 +99,16 @@ __global__ __launch_bounds__(kShareBuildThreads) void share_union(const int32_t*
 // Where entry i of a (group, band) that spans [s, e) stands in its run.  A run is a maximal stretch of one
 // column, cut into stretches of kShareRunCap from its first entry.  Writes the entry's place in its stretch
 // and the stretch's length.
-__device__ __forceinline__ void share_place(const int32_t* __restrict__ cols, int32_t s, int32_t e, int32_t i, int32_t* x, int32_t* len)
+// `col_at(i)` = column of entry i.
+template <typename ColAt>
+__device__ __forceinline__ void share_place(ColAt col_at, int32_t s, int32_t e, int32_t i, int32_t* x, int32_t* len)
 {
-    const int32_t c = cols[i];
+    const int32_t c = col_at(i);
     int32_t rs = i;
-    while (rs > s && cols[rs - 1] == c) --rs;
+    while (rs > s && col_at(rs - 1) == c) --rs;
     rs += (i - rs) / kShareRunCap * kShareRunCap;
     int32_t re = i + 1;
-    while (re < e && re < rs + kShareRunCap && cols[re] == c) ++re;
+    while (re < e && re < rs + kShareRunCap && col_at(re) == c) ++re;
     *x = i - rs;
     *len = re - rs;
 }
@@ -100,13 +120,17 @@ typedef uint32_t share_u32x4 __attribute__((ext_vector_type(4)));
 // [bstart[b], bstart[b+1]).  Pass 1 (a wave per band): quads and singles of every band -> header, blocks
 // of the band; prefix sum over the bands; the stream's place is taken from the atomic counter `alloc`
 // (zero before the launch).  Pass 2 (the same waves): the records.
-// Dynamic LDS: 2 * (ceil(k / 48) + 1) words.
+// The walk over a band is a chain of dependent reads of neighbouring columns (where does the run of this entry
+// begin and end), and the band starts come from binary searches: from global memory each step is a memory
+// latency and a stream of 170 bands took 60 us.  A group of at most `stage_cap` entries therefore copies its columns
+// to LDS first and reads them there; a larger one reads global memory.
+// Dynamic LDS: 4 * (ceil(k / 48) + 1) + stage_cap words.
 __global__ __launch_bounds__(kShareBuildThreads) void share_fill(const int32_t* __restrict__ gIdxes, const int32_t* __restrict__ rows,
                                                                 const int32_t* __restrict__ cols, const float* __restrict__ values,
                                                                 int32_t p, int64_t g, int64_t k, const int32_t* __restrict__ ucols,
                                                                 const int32_t* __restrict__ ucount, uint32_t* __restrict__ hdr,
                                                                 uint32_t* __restrict__ blocks, int32_t* __restrict__ sbase,
-                                                                uint32_t* __restrict__ alloc)
+                                                                uint32_t* __restrict__ alloc, int32_t stage_cap)
 {
     extern __shared__ uint32_t share_lds[];
     __shared__ int32_t wsum[kShareBuildWaves];
@@ -126,7 +150,17 @@ __global__ __launch_bounds__(kShareBuildThreads) void share_fill(const int32_t* 
     const int64_t hb = share_hdr_base(first, Q), cap = share_hdr_base(first_next, Q + 1) - hb;
     uint32_t* hd = hdr + 2 * (hb * kShareW + w * cap);
     int32_t* bstart = reinterpret_cast<int32_t*>(share_lds);         // [NB + 1]
-    int32_t* boff = bstart + ((k + kShareBandRows - 1) / kShareBandRows + 1);   // [NB + 1] blocks per band, then offsets
+    const int32_t table = (int32_t)((k + kShareBandRows - 1) / kShareBandRows + 1);
+    int32_t* boff = bstart + table;      // [NB + 1] blocks per band, then offsets
+    int32_t* hq = boff + table;          // quads of band b
+    int32_t* hs = hq + table;            // groups of four singles of band b
+    int32_t* stage = hs + table;         // columns of the group's entries, if they fit
+    const bool staged = end - beg <= stage_cap;
+    if (staged) {
+        for (int32_t i = beg + (int32_t)threadIdx.x; i < end; i += kShareBuildThreads) stage[i - beg] = cols[i];
+        __syncthreads();
+    }
+    auto col_at = [&](int32_t i) -> int32_t { return staged ? stage[i - beg] : cols[i]; };
 
     for (int32_t b = threadIdx.x; b <= NB; b += kShareBuildThreads) {
         int32_t lo = beg, hi = end;
@@ -134,7 +168,7 @@ __global__ __launch_bounds__(kShareBuildThreads) void share_fill(const int32_t* 
             const int32_t c = uc[b * kShareBandRows];
             while (lo < hi) {
                 const int32_t mid = lo + (hi - lo) / 2;
-                if (cols[mid] < c) lo = mid + 1; else hi = mid;
+                if (col_at(mid) < c) lo = mid + 1; else hi = mid;
             }
         } else {
             lo = end;
@@ -150,7 +184,7 @@ __global__ __launch_bounds__(kShareBuildThreads) void share_fill(const int32_t* 
         int32_t members = 0, singles = 0;
         for (int32_t i = s + lane; i < e; i += 64) {
             int32_t x, len;
-            share_place(cols, s, e, i, &x, &len);
+            share_place(col_at, s, e, i, &x, &len);
             if (x < (len & ~3)) ++members; else ++singles;
         }
 #pragma unroll
@@ -162,6 +196,8 @@ __global__ __launch_bounds__(kShareBuildThreads) void share_fill(const int32_t* 
         if (lane == 0) {
             hd[(int64_t)b * 2] = (uint32_t)nq;
             hd[(int64_t)b * 2 + 1] = (uint32_t)ns4;
+            hq[b] = nq;
+            hs[b] = ns4;
             boff[b] = (nq + 3) / 4 + (ns4 + 3) / 4;
         }
     }
@@ -196,8 +232,8 @@ __global__ __launch_bounds__(kShareBuildThreads) void share_fill(const int32_t* 
         share_u32x4* qblk = out + (int64_t)boff[b] * 16;
         int32_t members_before = 0, singles_before = 0;         // in the tiles before this one
         int32_t nq_blocks = 0;                                    // known after the walk: S blocks sit behind the Q blocks
-        // the Q blocks need the band's quad count first: it is in the header this workgroup wrote in pass 1
-        const int32_t nq = (int32_t)hd[(int64_t)b * 2], ns4 = (int32_t)hd[(int64_t)b * 2 + 1];
+        // the Q blocks need the band's quad count first: pass 1 left it
+        const int32_t nq = hq[b], ns4 = hs[b];
         nq_blocks = (nq + 3) / 4;
         share_u32x4* sblk = qblk + (int64_t)nq_blocks * 16;
         for (int32_t cur = s; cur < e; cur += 64) {
@@ -205,8 +241,8 @@ __global__ __launch_bounds__(kShareBuildThreads) void share_fill(const int32_t* 
             const bool live = i < e;
             int32_t x = 0, len = 0, col = 0;
             if (live) {
-                share_place(cols, s, e, i, &x, &len);
-                col = cols[i];
+                share_place(col_at, s, e, i, &x, &len);
+                col = col_at(i);
             }
             const bool member = live && x < (len & ~3);
             const bool single = live && !member;
