@@ -185,10 +185,13 @@ int gcoo_spdm(const gcoo_matrix* A, const float* B_dev, int64_t ldb, int64_t N,
  */
 #define GCOO_VARIANT_AUTO 0
 #define GCOO_VARIANT_LDS  1  /* partial sums in LDS, reads the five arrays directly; any p, any alignment */
-/* partial sums in VGPRs, reads the run schedule built at conversion; needs p <= 64 and B, C, ldb,
- * ldc, N all even (8-byte aligned rows), else GCOO_EINVAL.  Four columns per lane for p <= 38 where
- * the rows are 16-byte aligned (N, ldb, ldc multiples of 4), two otherwise; groups with very many
- * entries are shared by the waves of a workgroup except for 33 <= p <= 38 */
+/* partial sums in VGPRs, reads the run schedule built at conversion; needs p <= 64 and N >= 4 (p <= 38:
+ * four columns per lane) or N >= 2 (39 <= p <= 64: two), else GCOO_EINVAL.  Any N, ldb, ldc and base
+ * addresses: where N is not a multiple of the columns per lane, the lane at the end of a row computes the
+ * last columns of the row instead of reaching beyond N, and rows aligned to 4 bytes only are read and
+ * written with unaligned 16-byte accesses (a few per cent slower than aligned ones).  No access leaves
+ * the first N columns of a row.  Groups with very many entries are shared by the waves of a workgroup
+ * except for 33 <= p <= 38 */
 #define GCOO_VARIANT_REG  2
 /* the eight groups of a workgroup (a super-group, up to 8 x 48 rows of A) fetch each row of B that
  * any of them needs once into LDS, and every multiply-add takes its B values from there; reads the

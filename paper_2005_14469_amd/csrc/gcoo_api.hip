@@ -649,8 +649,10 @@ int gcoo_from_dense(int64_t m, int64_t k, const float* A_dev, int64_t lda, int32
 namespace {
 
 struct Shape {
-    bool al4, al2;
+    bool al4;          // N, both leading dimensions and both base addresses fit 16-byte accesses: what the
+                       // workgroup-shared kernel's loads straight to LDS need
     bool wide_pitch;   // row pitch of B in bytes does not fit 32 bits: LDS variant only
+    int64_t N;
 };
 
 Shape shape_of(const float* B, int64_t ldb, int64_t N, const float* C, int64_t ldc)
@@ -659,23 +661,25 @@ Shape shape_of(const float* B, int64_t ldb, int64_t N, const float* C, int64_t l
     Shape s;
     s.al4 = (N % 4 == 0) && (ldb % 4 == 0) && (ldc % 4 == 0) && (pb % 16 == 0) && (pc % 16 == 0);
     s.wide_pitch = ldb > 0x3fffffffLL;
-    s.al2 = (N % 2 == 0) && (ldb % 2 == 0) && (ldc % 2 == 0) && (pb % 8 == 0) && (pc % 8 == 0);
+    s.N = N;
     return s;
 }
 
-// Instance of the register kernel that serves this p and alignment: its columns per lane, 0 if
-// none does; kTallInstance for four columns per lane with the tall accumulator file (33 <= p <= 38).
+// Instance of the register kernel that serves this p and N: its columns per lane, 0 if none does;
+// kTallInstance for four columns per lane with the tall accumulator file (33 <= p <= 38).  The instances
+// take any N of at least their columns per lane and any leading dimensions and base addresses: the one lane that
+// would reach beyond N computes the last columns of the row instead (lane_cols() in gcoo_spdm_kernels.hpp), and
+// rows that are aligned to 4 bytes only are read and written with unaligned 16-byte accesses.
 constexpr int kTallInstance = 38;
 int sched_width(int32_t p, const Shape& sh)
 {
     if (sh.wide_pitch) return 0;
-    if (p <= 32 && sh.al4) return 4;
-    if (p <= 38 && sh.al4) return kTallInstance;
-    if (p <= 64 && sh.al2) return 2;
-    // There is no one-column-per-lane instance (65 <= p <= 128, or operands aligned to 4 bytes only): a run
-    // of one on an 8000 x 8000 matrix with p = 128 ended in a GPU memory fault whose cause was never
-    // found, and it was taken out of the build.  Such calls get the LDS kernel (automatic choice) or
-    // GCOO_EINVAL (explicit GCOO_VARIANT_REG).
+    if (p <= 32 && sh.N >= 4) return 4;
+    if (p <= 38 && sh.N >= 4) return kTallInstance;
+    if (p <= 64 && sh.N >= 2) return 2;
+    // There is no one-column-per-lane instance (65 <= p <= 128, or N = 1): a run of one on an 8000 x 8000
+    // matrix with p = 128 ended in a GPU memory fault whose cause was never found, and it was taken out of
+    // the build.  Such calls get the LDS kernel (automatic choice) or GCOO_EINVAL (explicit GCOO_VARIANT_REG).
     return 0;
 }
 

@@ -368,6 +368,42 @@ __device__ __forceinline__ void run_class(AccFile& acc, const uint32_t* seg, int
     wait_vm<0>();                                                          // the loads of chunks past the end
 }
 
+// The V adjacent columns a lane computes.  Lane l of tile t owns columns j0 = t*64V + l*V .. j0+V-1.  When N is not
+// a multiple of V, the last lane with a column inside C would reach beyond N: it computes columns N-V .. N-1 instead
+// and stores only those of them that are its own (first_own .. V-1 of its vector); lanes wholly beyond N compute some
+// columns inside B and store nothing.  So every 4V-byte access stays inside the N columns of a row, whatever ldb and
+// ldc are; it may then be aligned to 4 bytes only, which the hardware serves (the compiler itself emits 16-byte
+// accesses for data aligned to 4).  The launcher checks N >= V.
+struct LaneCols {
+    bool in;             // the lane owns at least one column of C
+    int64_t jc;          // first column it computes
+    int first_own;       // elements [first_own, V) of its vector are its own
+};
+template <int V>
+__device__ __forceinline__ LaneCols lane_cols(int64_t tile, int lane, int64_t N)
+{
+    const int64_t j0 = tile * (64 * V) + (int64_t)lane * V;
+    LaneCols c;
+    c.in = j0 < N;
+    const int64_t want = c.in ? j0 : tile * (64 * V);
+    c.jc = want + V <= N ? want : N - V;
+    c.first_own = c.in ? (int)(j0 - c.jc) : V;
+    return c;
+}
+
+// Stores one row of a lane's columns (o[v] = column jc + v) with the non-temporal hint.
+template <int V, typename Vec>
+__device__ __forceinline__ void store_lane_row(float* __restrict__ dst, const Vec& o, int first_own)
+{
+    if (first_own == 0) {
+        __builtin_nontemporal_store(o, reinterpret_cast<Vec*>(dst));
+    } else {
+#pragma unroll
+        for (int v = 1; v < V; ++v)
+            if (v >= first_own) __builtin_nontemporal_store(o[v], dst + v);
+    }
+}
+
 template <int V>
 __global__ __launch_bounds__(64) void spdm_sched(const SchedClass* __restrict__ hdr, const uint32_t* __restrict__ stream,
                                                  const int32_t* __restrict__ gIdxes, int64_t m, int32_t p, int64_t g,
@@ -390,13 +426,12 @@ __global__ __launch_bounds__(64) void spdm_sched(const SchedClass* __restrict__ 
     if (__builtin_amdgcn_readfirstlane(gIdxes[q + 1]) - first_entry >= heavy_min) return;
 
     const int lane = threadIdx.x;
-    const int64_t j0 = tile * (64 * V) + (int64_t)lane * V;
-    const bool in = j0 < N;                                // N % V == 0: a lane is all in or all out
-    // Row bases are wave-uniform (SGPRs); the lane's place inside the tile is a 32-bit byte
-    // offset.  Lanes beyond N read the first columns of the tile instead (always inside B).
-    const char* Bbytes = reinterpret_cast<const char*>(B + tile * (64 * V));
-    const uint32_t lane_off = in ? (uint32_t)(lane * V * 4) : 0u;
-    const uint32_t ldb4 = (uint32_t)ldb * 4u;              // the launcher checks that ldb*4 fits 32 bits
+    const LaneCols lc = lane_cols<V>(tile, lane, N);
+    const bool in = lc.in;
+    // Row bases are wave-uniform (SGPRs); the lane's place inside the row is a 32-bit byte offset.
+    const char* Bbytes = reinterpret_cast<const char*>(B);
+    const uint32_t lane_off = (uint32_t)(lc.jc * 4);       // the launcher checks that ldb*4 fits 32 bits
+    const uint32_t ldb4 = (uint32_t)ldb * 4u;
 
     AccFile acc;
     acc_clear(acc);
@@ -435,7 +470,7 @@ __global__ __launch_bounds__(64) void spdm_sched(const SchedClass* __restrict__ 
     if (in) {
         constexpr int S = acc_stride<V>();
         const int64_t row0 = q * p;
-        float* __restrict__ Cl = C + j0;
+        float* __restrict__ Cl = C + lc.jc;
 #pragma unroll
         for (int r = 0; r < S - 1; ++r) {
             if (r < p && row0 + r < m) {
@@ -443,12 +478,11 @@ __global__ __launch_bounds__(64) void spdm_sched(const SchedClass* __restrict__ 
                 if constexpr (V == 4) {
                     f32x4 o = {acc_get(acc, kAccFirst + r), acc_get(acc, kAccFirst + S + r), acc_get(acc, kAccFirst + 2 * S + r),
                                acc_get(acc, kAccFirst + 3 * S + r)};
-                    __builtin_nontemporal_store(o, reinterpret_cast<f32x4*>(dst));
-                } else if constexpr (V == 2) {
-                    f32x2 o = {acc_get(acc, kAccFirst + r), acc_get(acc, kAccFirst + S + r)};
-                    __builtin_nontemporal_store(o, reinterpret_cast<f32x2*>(dst));
+                    store_lane_row<4>(dst, o, lc.first_own);
                 } else {
-                    __builtin_nontemporal_store(acc_get(acc, kAccFirst + r), dst);
+                    static_assert(V == 2, "");
+                    f32x2 o = {acc_get(acc, kAccFirst + r), acc_get(acc, kAccFirst + S + r)};
+                    store_lane_row<2>(dst, o, lc.first_own);
                 }
             }
         }
@@ -486,10 +520,10 @@ __global__ __launch_bounds__(64 * kCoopWaves) void spdm_sched_coop(const SchedCl
 
     const int lane = threadIdx.x & 63;
     const int wv = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
-    const int64_t j0 = tile * (64 * V) + (int64_t)lane * V;
-    const bool in = j0 < N;
-    const char* Bbytes = reinterpret_cast<const char*>(B + tile * (64 * V));
-    const uint32_t lane_off = in ? (uint32_t)(lane * V * 4) : 0u;
+    const LaneCols lc = lane_cols<V>(tile, lane, N);
+    const bool in = lc.in;
+    const char* Bbytes = reinterpret_cast<const char*>(B);
+    const uint32_t lane_off = (uint32_t)(lc.jc * 4);
     const uint32_t ldb4 = (uint32_t)ldb * 4u;
 
     AccFile acc;
@@ -540,7 +574,7 @@ __global__ __launch_bounds__(64 * kCoopWaves) void spdm_sched_coop(const SchedCl
 
     if (wv == 0 && in) {
         const int64_t row0 = q * p;
-        float* __restrict__ Cl = C + j0;
+        float* __restrict__ Cl = C + lc.jc;
 #pragma unroll
         for (int r = 0; r < P; ++r) {
             if (r < p && row0 + r < m) {
@@ -548,12 +582,11 @@ __global__ __launch_bounds__(64 * kCoopWaves) void spdm_sched_coop(const SchedCl
                 if constexpr (V == 4) {
                     f32x4 o = {acc_get(acc, kAccFirst + r), acc_get(acc, kAccFirst + S + r), acc_get(acc, kAccFirst + 2 * S + r),
                                acc_get(acc, kAccFirst + 3 * S + r)};
-                    __builtin_nontemporal_store(o, reinterpret_cast<f32x4*>(dst));
-                } else if constexpr (V == 2) {
-                    f32x2 o = {acc_get(acc, kAccFirst + r), acc_get(acc, kAccFirst + S + r)};
-                    __builtin_nontemporal_store(o, reinterpret_cast<f32x2*>(dst));
+                    store_lane_row<4>(dst, o, lc.first_own);
                 } else {
-                    __builtin_nontemporal_store(acc_get(acc, kAccFirst + r), dst);
+                    static_assert(V == 2, "");
+                    f32x2 o = {acc_get(acc, kAccFirst + r), acc_get(acc, kAccFirst + S + r)};
+                    store_lane_row<2>(dst, o, lc.first_own);
                 }
             }
         }
@@ -569,6 +602,7 @@ hipError_t launch_spdm_sched_instance(const SpdmArgs& a, hipStream_t s)
     if (grid <= 0 || grid > 0x7fffffffLL) return hipErrorInvalidConfiguration;
     if (a.ldb > 0x3fffffffLL) return hipErrorInvalidValue;   // row pitch in bytes is kept in 32 bits
     if (a.p + 1 > acc_stride<V>()) return hipErrorInvalidValue;
+    if (a.N < V) return hipErrorInvalidValue;               // lane_cols() places a lane's columns inside [0, N)
     spdm_sched<V><<<dim3((unsigned)grid), dim3(64), 0, s>>>(a.hdr, a.stream, a.gIdxes, a.m, a.p, a.g, a.nw, a.B, a.ldb, a.N,
                                                             a.C, a.ldc, total, a.nnz, a.stats);
     hipError_t e = hipGetLastError();

@@ -60,7 +60,7 @@ REG_MAX_P = 64
 def _variants_for(p, N):
     """The kernels that serve group height p and N columns (torch tensors are 16-byte aligned)."""
     v = [binding.VARIANT_LDS]
-    if p <= REG_MAX_P and N % 2 == 0:
+    if (p <= 38 and N >= 4) or (p <= REG_MAX_P and N >= 2):       # four columns per lane, or two
         v += [binding.VARIANT_REG]
     return v
 
@@ -182,6 +182,9 @@ def test_config0_all_variants(p):
     (1, 1, 1, 1), (5, 7, 3, 2), (33, 65, 64, 32), (100, 90, 260, 32), (129, 257, 516, 64),
     (300, 200, 1028, 16), (77, 500, 250, 128), (64, 64, 4, 8), (130, 40, 1000, 20), (513, 100, 768, 32),
     (400, 300, 516, 38), (77, 90, 260, 36), (1000, 2000, 256, 38),
+    # N not a multiple of the columns per lane: the lane at the end of a row computes the last columns instead
+    (100, 90, 261, 32), (300, 200, 1027, 16), (400, 300, 517, 38), (129, 257, 515, 64), (64, 64, 5, 8), (50, 60, 4, 32),
+    (90, 70, 257, 32), (90, 70, 258, 24), (90, 70, 259, 38), (40, 30, 2, 48), (40, 30, 3, 64), (70, 50, 7, 3), (300, 300, 769, 40),
 ])
 def test_ragged_shapes_all_variants(m, k, N, p):
     w = workloads.uniform_random(m, k, N, 0.8, seed=m * 1000 + N)
@@ -191,10 +194,10 @@ def test_ragged_shapes_all_variants(m, k, N, p):
 
 
 def test_register_kernel_refuses_what_it_does_not_serve():
-    _say("REG variant: p > 64 and odd N are refused, AUTO falls back to the LDS kernel")
+    _say("REG variant: p > 64 and a single column are refused, AUTO falls back to the LDS kernel")
     w = workloads.uniform_random(256, 256, 64, 0.9, seed=5)
     Bt = torch.from_numpy(w.B).to(DEV)
-    for p, N in [(128, 64), (65, 64), (32, 63)]:
+    for p, N in [(128, 64), (65, 64), (32, 1), (48, 1)]:
         A = binding.gcoo_from_csr(w.m, w.k, w.row_ptr, w.col_idx, w.vals, p, device=DEV)
         Bv = Bt[:, :N].contiguous()
         Cv = torch.empty((w.m, N), device=DEV)
@@ -557,32 +560,28 @@ def test_skewed_config_through_the_share_variant(share_always, p):
 
 # ------------------------------------------------------------------ dispatch corners
 
-@pytest.mark.parametrize("p", [8, 32])
-def test_two_columns_per_lane_chosen_by_alignment(p):
-    """p <= 32 with N = 2 mod 4, and with rows that are 8- but not 16-byte aligned: the register kernel runs its
-    two-columns-per-lane instance."""
-    w = workloads.uniform_random(300, 400, 1030, 0.9, seed=31)
-    _say(f"V = 2 by alignment, p={p}")
-    assert w.N % 4 == 2
+@pytest.mark.parametrize("p", [8, 32, 38, 48])
+def test_register_kernel_with_any_n_and_alignment(p):
+    """N that is no multiple of the columns per lane, and views that start 4, 8 or 12 bytes into a row with odd leading
+    dimensions: the register kernel serves them all (unaligned 16-byte accesses, the last lane of a row shifted
+    inside), and nothing outside the N columns of C is written."""
+    w = workloads.uniform_random(300, 400, 1031, 0.9, seed=31)
+    _say(f"register kernel, ragged N and alignment, p={p}")
     A = binding.gcoo_from_csr(w.m, w.k, w.row_ptr, w.col_idx, w.vals, p, device=DEV)
     Bt = torch.from_numpy(w.B).to(DEV)
-    Cg = torch.empty((w.m, w.N), device=DEV)
-    assert binding.gcoo_spdm_pick(A, Bt, Cg) == binding.VARIANT_REG
-    err, _, _ = _check_product(w, p, binding.VARIANT_REG, A=A)
-    assert err < 2e-6
-    # N a multiple of 4 but the views start 8 bytes into a row
-    N2 = 1024
-    Bbig = torch.zeros((w.k, 1040), device=DEV)
-    Bbig[:, 2:2 + N2] = Bt[:, :N2]
-    Cbig = torch.full((w.m, 1040), 7.0, device=DEV)
-    Bv, Cv = Bbig[:, 2:2 + N2], Cbig[:, 2:2 + N2]
-    assert Bv.data_ptr() % 16 == 8 and binding.gcoo_spdm_pick(A, Bv, Cv) == binding.VARIANT_REG
-    binding.gcoo_spdm(A, Bv, Cv, variant=binding.VARIANT_REG)
-    torch.cuda.synchronize()
-    C64, D64 = orc.spdm_csr(w.k, N2, w.row_ptr, w.col_idx, w.vals, np.ascontiguousarray(w.B[:, :N2]))
-    err, bad = orc.max_scaled_error(Cv.cpu().numpy(), C64, D64)
-    assert bad == 0 and err <= TOL
-    assert torch.all(Cbig[:, :2] == 7.0) and torch.all(Cbig[:, 2 + N2:] == 7.0)
+    for N2, shift, pitch in [(1031, 0, 1031), (1030, 0, 1030), (1029, 1, 1041), (1024, 2, 1040), (1027, 3, 1039), (1024, 1, 1027),
+                             (513, 5, 1031)]:
+        Bbig = torch.zeros((w.k, pitch), device=DEV)
+        Bbig[:, shift:shift + N2] = Bt[:, :N2]
+        Cbig = torch.full((w.m, pitch), 7.0, device=DEV)
+        Bv, Cv = Bbig[:, shift:shift + N2], Cbig[:, shift:shift + N2]
+        assert binding.gcoo_spdm_pick(A, Bv, Cv) == binding.VARIANT_REG
+        binding.gcoo_spdm(A, Bv, Cv, variant=binding.VARIANT_AUTO)
+        torch.cuda.synchronize()
+        C64, D64 = orc.spdm_csr(w.k, N2, w.row_ptr, w.col_idx, w.vals, np.ascontiguousarray(w.B[:, :N2]))
+        err, bad = orc.max_scaled_error(Cv.cpu().numpy(), C64, D64)
+        assert bad == 0 and err <= TOL, (N2, shift, pitch, err, bad)
+        assert torch.all(Cbig[:, :shift] == 7.0) and torch.all(Cbig[:, shift + N2:] == 7.0), (N2, shift, pitch)
 
 
 def test_skewed_matrix_through_the_tall_layout():
