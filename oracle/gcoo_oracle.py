@@ -19,13 +19,22 @@ _lib = None
 
 
 def build(force: bool = False) -> str:
-    """Compile gcoo_oracle.c into libgcoo_oracle.so (plain gcc, -O2, OpenMP)."""
-    if force or not os.path.exists(_LIB) or os.path.getmtime(_LIB) < os.path.getmtime(_SRC):
-        tmp = _LIB + f".tmp{os.getpid()}"
-        subprocess.check_call(["gcc", "-O2", "-fopenmp", "-fPIC", "-shared", "-std=c99",
+    """Compile gcoo_oracle.c into libgcoo_oracle.so (plain gcc, -O2, OpenMP).
+
+    With GCOO_ORACLE_SANITIZE=1 in the environment the library is libgcoo_oracle_san.so instead, built with
+    -O0 -g -fsanitize=address,undefined: a checking build for one pass of the CPU tests,
+        GCOO_ORACLE_SANITIZE=1 LD_PRELOAD=$(gcc -print-file-name=libasan.so) ASAN_OPTIONS=detect_leaks=0 \
+            UBSAN_OPTIONS=halt_on_error=1 python -m pytest tests -m "not gpu" -q
+    (the address sanitizer's runtime has to be loaded before the interpreter's own libraries)."""
+    sanitize = os.environ.get("GCOO_ORACLE_SANITIZE", "") == "1"
+    out = os.path.join(_HERE, "libgcoo_oracle_san.so") if sanitize else _LIB
+    flags = ["-O0", "-g", "-fsanitize=address,undefined", "-fno-omit-frame-pointer"] if sanitize else ["-O2"]
+    if force or not os.path.exists(out) or os.path.getmtime(out) < os.path.getmtime(_SRC):
+        tmp = out + f".tmp{os.getpid()}"
+        subprocess.check_call(["gcc", *flags, "-fopenmp", "-fPIC", "-shared", "-std=c99",
                                "-Wall", "-Wextra", "-o", tmp, _SRC, "-lm"])
-        os.replace(tmp, _LIB)
-    return _LIB
+        os.replace(tmp, out)
+    return out
 
 
 def lib():

@@ -13,7 +13,8 @@ import numpy as np
 import torch
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
-LIB_PATH = os.path.join(_HERE, "libgcoo.so")
+# GCOO_LIBRARY names another build of the same library (the host-sanitized one of build.py --host-sanitize)
+LIB_PATH = os.environ.get("GCOO_LIBRARY") or os.path.join(_HERE, "libgcoo.so")
 BASELINE_LIB_PATH = os.path.join(_HERE, "libgcoo_baseline.so")
 
 GCOO_OK, GCOO_EINVAL, GCOO_EBOUNDS, GCOO_ENOMEM, GCOO_EHIP, GCOO_ELIMIT = 0, -1, -2, -3, -4, -5

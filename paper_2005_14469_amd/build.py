@@ -124,5 +124,33 @@ def build(force: bool = True, jobs: int = 8) -> str:
     return LIB
 
 
+def build_host_sanitized(jobs: int = 8) -> str:
+    """A checking build: the same sources with the address and undefined-behaviour sanitizers on the HOST
+    code only (the device code is compiled as usual), as _build/san/libgcoo.so.  For one pass of the tests that
+    need no GPU; the command is printed by `python -m paper_2005_14469_amd.build --host-sanitize`."""
+    out_dir = os.path.join(OBJ, "san")
+    os.makedirs(out_dir, exist_ok=True)
+    san = ["-Xarch_host", "-fsanitize=address", "-Xarch_host", "-fsanitize=undefined", "-Xarch_host", "-fno-omit-frame-pointer"]
+    flags = [f if f != "-O3" else "-O1" for f in FLAGS] + ["-g"]
+
+    def one(src):
+        obj = os.path.join(out_dir, os.path.basename(src)[:-4] + ".o")
+        subprocess.check_call(["hipcc", *flags, *san, "-I", os.path.join(ROOT, "include"), "-I", CSRC, "-c", src, "-o", obj])
+        return obj
+    with ThreadPoolExecutor(max_workers=jobs) as ex:
+        objs = list(ex.map(one, sources()))
+    lib = os.path.join(out_dir, "libgcoo.so")
+    subprocess.check_call(["hipcc", "--offload-arch=gfx950", "-shared", "-fPIC", *san[:4], "-shared-libsan", "-o", lib, *objs])
+    return lib
+
+
 if __name__ == "__main__":
-    print(build())
+    import sys
+    if "--host-sanitize" in sys.argv[1:]:
+        lib = build_host_sanitized()
+        rt = glob.glob("/opt/rocm/lib/llvm/lib/clang/*/lib/linux/libclang_rt.asan-x86_64.so")
+        print(lib)
+        print(f"run: GCOO_LIBRARY={lib} LD_PRELOAD={rt[0] if rt else '<libclang_rt.asan-x86_64.so>'} ASAN_OPTIONS=detect_leaks=0 "
+              "UBSAN_OPTIONS=halt_on_error=1 python -m pytest tests/test_abi_host.py -q")
+    else:
+        print(build())
