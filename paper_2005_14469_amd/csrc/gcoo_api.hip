@@ -81,6 +81,7 @@ int static_scratch(unsigned char** out)
 struct Layout {
     size_t values, rows, cols, gIdxes, nnzPerGroup;        // the five arrays of the format
     size_t sched_hdr, sched;                               // run schedule of the register kernel
+    size_t order;                                          // groups by falling size, then those sizes (matrices of few groups)
     size_t share_ucols, share_ucount, share_hdr, share_blocks, share_sbase, share_alloc;   // share schedule (may be empty)
     size_t tmp_cols, tmp_rows, tmp_vals;                   // conversion scratch (second sort buffer)
     size_t in_row_ptr, in_cols, in_vals;                   // staging of a host CSR input
@@ -210,6 +211,7 @@ Layout make_layout(int64_t m, int64_t k, int64_t nnz, int64_t g, int32_t p, bool
     L.cols = take(n4);
     L.sched_hdr = take((size_t)g * nw * gcoo::kMaxRun * sizeof(gcoo::SchedClass));
     L.sched = take((size_t)gcoo::sched_words(nnz, g, nw) * 4);
+    L.order = take(g <= gcoo::kOrderMaxGroups && p <= gcoo::kSchedMaxP ? (size_t)g * 8 : 0);
     const bool share = share_schedule_wanted(m, k, nnz, p);
     const int64_t nQ = gcoo::share_super_groups(g);
     L.share_ucols = take(share ? n4 : 0);
@@ -274,6 +276,8 @@ struct gcoo_matrix {
     int32_t* nnzPerGroup() const { return reinterpret_cast<int32_t*>(base + L.nnzPerGroup); }
     gcoo::SchedClass* sched_hdr() const { return reinterpret_cast<gcoo::SchedClass*>(base + L.sched_hdr); }
     uint32_t* sched() const { return reinterpret_cast<uint32_t*>(base + L.sched); }
+    bool has_order() const { return has_sched && g > 0 && g <= gcoo::kOrderMaxGroups; }
+    int32_t* order() const { return reinterpret_cast<int32_t*>(base + L.order); }
     unsigned long long* stats() const { return reinterpret_cast<unsigned long long*>(base + L.counter); }
     uint32_t* bad_col() const { return reinterpret_cast<uint32_t*>(base + L.counter + 16); }
     int32_t* share_ucols() const { return reinterpret_cast<int32_t*>(base + L.share_ucols); }
@@ -335,6 +339,10 @@ int launch_build_schedule(const gcoo_matrix* h, char* scratch, hipStream_t s)
             gcoo::build_schedule<1024><<<grid, dim3(1024), 0, s>>>(h->gIdxes(), h->rows(), h->cols(), h->values(), h->p, h->g, h->nw,
                                                                    h->window_cols, h->sched_hdr(), h->sched());
         HIP_TRY(hipGetLastError());
+        if (h->has_order()) {
+            gcoo::group_order_by_size<<<dim3(1), dim3(1024), 0, s>>>(h->gIdxes(), (int32_t)h->g, h->order(), h->order() + h->g);
+            HIP_TRY(hipGetLastError());
+        }
     }
     if (h->g > 0 && h->has_share) {
         const size_t bitmap_bytes = (size_t)((h->k + 31) / 32) * 4;
@@ -763,7 +771,7 @@ int gcoo_spdm_variant(const gcoo_matrix* A, const float* B_dev, int64_t ldb, int
     // items can have any: then the kernels decide group by group, from the statistics on the device.
     const bool heavy = V != kTallInstance && gcoo::sched_heavy_possible(A->nnz, A->g, (N + 64 * cols_per_lane - 1) / (64 * cols_per_lane));
     gcoo::SpdmArgs a{A->sched_hdr(), A->sched(), A->gIdxes(), A->m, A->p, A->g, A->nw, B_dev, ldb, N, C_dev, ldc,
-                     A->nnz, heavy ? A->stats() : nullptr};
+                     A->nnz, heavy ? A->stats() : nullptr, (heavy && A->has_order()) ? A->order() : nullptr};
     hipError_t e = gcoo::launch_spdm_sched(V, a, s);
     if (e != hipSuccess) return hip_fail(e, "spdm_sched launch");
     return GCOO_OK;

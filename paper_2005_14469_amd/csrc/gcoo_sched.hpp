@@ -95,6 +95,7 @@ struct SchedClass {
 // from the host but the shape; the host evaluates only the part that does not need `largest`.
 constexpr int64_t kHeavyWaveSlots = 2048;                  // 256 compute units x 8 resident waves of the register kernel
 constexpr int64_t kHeavyMin = 1024;
+constexpr int64_t kOrderMaxGroups = 2 * kHeavyWaveSlots;   // a launch of few items has at most that many groups
 __host__ __device__ inline bool sched_heavy_possible(int64_t nnz, int64_t g, int64_t tiles)
 {
     const int64_t items = g * tiles;

@@ -202,4 +202,25 @@ __global__ __launch_bounds__(kBuildThreads) void build_schedule(const int32_t* _
     }
 }
 
+// The groups in order of falling size (ties: the lower index first), and those sizes: what the kernel for
+// launches of few items takes its work from.  One workgroup; every group counts the groups that come before
+// it in that order (g <= kOrderMaxGroups, so the sizes fit LDS and the count is a short loop over them).
+__global__ __launch_bounds__(1024) void group_order_by_size(const int32_t* __restrict__ gIdxes, int32_t g,
+                                                            int32_t* __restrict__ order, int32_t* __restrict__ osize)
+{
+    __shared__ int32_t size_s[kOrderMaxGroups];
+    for (int32_t i = threadIdx.x; i < g; i += 1024) size_s[i] = gIdxes[i + 1] - gIdxes[i];
+    __syncthreads();
+    for (int32_t i = threadIdx.x; i < g; i += 1024) {
+        const int32_t mine = size_s[i];
+        int32_t before = 0;
+        for (int32_t j = 0; j < g; ++j) {
+            const int32_t other = size_s[j];
+            before += (other > mine || (other == mine && j < i)) ? 1 : 0;
+        }
+        order[before] = i;
+        osize[before] = mine;
+    }
+}
+
 }  // namespace gcoo

@@ -419,11 +419,10 @@ __global__ __launch_bounds__(64) void spdm_sched(const SchedClass* __restrict__ 
     const int64_t w = (int64_t)(bid & 7u) * per + (bid >> 3);
     if (w >= total) return;
     const int64_t tile = w / g, q = w - tile * g;
-    // groups with heavy_min entries or more are left to spdm_sched_coop (launched beside this kernel)
-    const int32_t heavy_min = stats ? sched_heavy_min(nnz, g, (N + 64 * V - 1) / (64 * V), (int64_t)__builtin_amdgcn_readfirstlane((uint32_t)stats[1]))
-                                    : 0x7fffffff;
+    // a matrix with heavy groups (a launch of few items, `stats` given) is left to spdm_sched_coop altogether
+    if (stats && sched_heavy_min(nnz, g, (N + 64 * V - 1) / (64 * V), (int64_t)__builtin_amdgcn_readfirstlane((uint32_t)stats[1])) != 0x7fffffff)
+        return;
     const int32_t first_entry = __builtin_amdgcn_readfirstlane(gIdxes[q]);
-    if (__builtin_amdgcn_readfirstlane(gIdxes[q + 1]) - first_entry >= heavy_min) return;
 
     const int lane = threadIdx.x;
     const LaneCols lc = lane_cols<V>(tile, lane, N);
@@ -490,36 +489,87 @@ __global__ __launch_bounds__(64) void spdm_sched(const SchedClass* __restrict__ 
 }
 
 // ---------------------------------------------------------------------------------------------
-// A group with many entries, shared by the kCoopWaves waves of one workgroup (the nnz-balanced
-// splitting that the paper leaves as future work, Section 5).  All waves work on the same
-// (group, column tile): wave w takes the w-th part of the bodies of every class segment, keeps
-// partial sums of its own, and the partial sums are added up through LDS in wave order
-// (((w0 + w1) + w2) + ...), so the result does not depend on timing.  Wave 0 stores C.
-// One workgroup per (tile, group); workgroups of groups below heavy_min return at once (those
-// groups are computed by spdm_sched).
+// Launches of few (group, tile) items, where the longest group would set the run time (the nnz-balanced
+// splitting that the paper leaves as future work, Section 5).  One kernel serves all groups; its workgroups
+// have kCoopWaves waves and take their work from the groups in order of falling size (`order`, `osize`: written
+// at conversion), so that the hardware's dispatcher hands the long items out first:
+//   * a heavy group (heavy_min entries or more) has a workgroup to itself: its class segments, laid end to
+//     end, are cut into kCoopWaves stretches of equal entries, each wave keeps partial sums of its own, and the
+//     partial sums are added up through LDS in a fixed tree order, so the result does not depend on timing.
+//     Wave 0 stores C.
+//   * the other groups go `bundle` to a workgroup, one wave each, neighbours in size (bundle = 1 .. 8: as few as
+//     keeps every compute unit busy, chosen by the launcher from the number of items).
+// A matrix without a heavy group is not served here but by spdm_sched, which keeps the groups of a column tile
+// together on an XCD: both kernels are launched, and each decides from the statistics on the device whether the
+// launch is its own (the other returns at once).
+// Workgroup b < nheavy * tiles (nheavy = number of heavy groups) takes heavy group order[b / tiles], tile b % tiles; the
+// workgroups after those take bundles of eight.  The launch has g * tiles workgroups, which is enough for any count of heavy groups;
+// the rest return at once.
 // ---------------------------------------------------------------------------------------------
 constexpr int kCoopWaves = 8;
+// entries of one body (kBody chunks) of class L, padding included
+__host__ __device__ constexpr int body_entries(int L) { return kBody * runs_per_chunk(L) * L; }
 
 template <int V>
 __global__ __launch_bounds__(64 * kCoopWaves) void spdm_sched_coop(const SchedClass* __restrict__ hdr, const uint32_t* __restrict__ stream,
                                                                    const int32_t* __restrict__ gIdxes, int64_t m, int32_t p, int64_t g,
                                                                    int32_t nw, const float* __restrict__ B, int64_t ldb, int64_t N,
                                                                    float* __restrict__ C, int64_t ldc, int64_t total, int64_t nnz,
-                                                                   const unsigned long long* __restrict__ stats)
+                                                                   const unsigned long long* __restrict__ stats,
+                                                                   const int32_t* __restrict__ order, const int32_t* __restrict__ osize,
+                                                                   int32_t bundle)
 {
     constexpr int S = acc_stride<V>(), P = S - 1;          // rows an instance can hold
     __shared__ __attribute__((aligned(16))) uint32_t ring_mem[kCoopWaves][kRing * kLineWords];
-    __shared__ __attribute__((aligned(16))) float part[P * 64 * V];        // one wave's partial sums: [row][lane][V]
-
-    const int64_t w = blockIdx.x;                          // tile-major like spdm_sched
-    if (w >= total) return;
-    const int64_t tile = w / g, q = w - tile * g;
-    const int32_t heavy_min = sched_heavy_min(nnz, g, (N + 64 * V - 1) / (64 * V), (int64_t)__builtin_amdgcn_readfirstlane((uint32_t)stats[1]));
-    const int32_t first_entry = __builtin_amdgcn_readfirstlane(gIdxes[q]);
-    if (__builtin_amdgcn_readfirstlane(gIdxes[q + 1]) - first_entry < heavy_min) return;   // the whole workgroup
+    // partial sums on their way from wave to wave: [wave][row][lane][V].  Four columns per lane: a tree, the upper
+    // half of the waves writes at a time; two columns per lane: one wave at a time (the tree, compiled for that
+    // instance, made the compiler move partial sums through registers that still have loads in flight: the
+    // build's check of the generated code refused it)
+    constexpr int kParts = V == 4 ? kCoopWaves / 2 : 1;
+    __shared__ __attribute__((aligned(16))) float part[kParts][P * 64 * V];
 
     const int lane = threadIdx.x & 63;
     const int wv = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const int64_t tiles = (N + 64 * V - 1) / (64 * V);
+    const int32_t heavy_min = sched_heavy_min(nnz, g, tiles, (int64_t)__builtin_amdgcn_readfirstlane((uint32_t)stats[1]));
+    // nheavy = groups of heavy_min entries or more = first place in the falling list osize[] that is smaller:
+    // two steps of 64 probes (g <= 4096)
+    if (heavy_min == 0x7fffffff) return;                   // no heavy group: spdm_sched, launched beside this kernel, does it all
+    int32_t nheavy = 0;
+    {
+        int32_t lo = 0, hi = (int32_t)g;
+        while (lo < hi) {
+            const int32_t stride = (hi - lo + 63) / 64;
+            const int32_t at = lo + lane * stride;
+            const bool big = at < hi && osize[at] >= heavy_min;
+            const int n = __popcll(__ballot(big));             // the sizes fall: the probes that are big come first
+            if (n == 0) {
+                hi = lo;
+            } else {
+                const int32_t up = lo + n * stride;
+                lo = lo + (n - 1) * stride + 1;
+                hi = up < hi ? up : hi;
+            }
+        }
+        nheavy = lo;
+    }
+    const int64_t b = blockIdx.x;
+    const bool heavy = b < (int64_t)nheavy * tiles;
+    int64_t tile, q;
+    if (heavy) {
+        tile = b % tiles;
+        q = order[b / tiles];
+    } else {
+        const int64_t bb = b - (int64_t)nheavy * tiles;
+        tile = bb % tiles;
+        const int64_t at = nheavy + (bb / tiles) * bundle + wv;
+        if (wv >= bundle || at >= g) return;               // a wave without a group, or a workgroup without work: no barrier follows on this path
+        q = order[at];
+    }
+    q = __builtin_amdgcn_readfirstlane((int32_t)q);
+    (void)total;
+    const int32_t first_entry = __builtin_amdgcn_readfirstlane(gIdxes[q]);
+
     const LaneCols lc = lane_cols<V>(tile, lane, N);
     const bool in = lc.in;
     const char* Bbytes = reinterpret_cast<const char*>(B);
@@ -534,14 +584,35 @@ __global__ __launch_bounds__(64 * kCoopWaves) void spdm_sched_coop(const SchedCl
 
     const uint32_t* gs = stream + sched_group_base(first_entry, q, nw);
     const SchedClass* h = hdr + q * nw * kMaxRun;
+    // The group's class segments, window after window, laid end to end and measured in entries, are cut into
+    // kCoopWaves equal stretches: wave wv takes the bodies that begin in [lo, hi).  A wave then works through one
+    // or two long pieces of segments instead of a sliver of every segment (each piece costs a start and a drain
+    // of the load pipeline), and the waves carry equal numbers of entries wherever the group's columns lie.
+    int64_t all = 0;
+    for (int32_t i = lane; i < nw * kMaxRun; i += 64) all += (int64_t)h[i].bodies * body_entries(i % kMaxRun + 1);
+#pragma unroll
+    for (int d = 32; d >= 1; d >>= 1) all += __shfl_xor(all, d, 64);
+    const int64_t total_entries = ((int64_t)__builtin_amdgcn_readfirstlane((uint32_t)(all >> 32)) << 32) |
+                                  (uint32_t)__builtin_amdgcn_readfirstlane((uint32_t)all);
+    const int64_t lo = heavy ? total_entries * wv / kCoopWaves : 0, hi = heavy ? total_entries * (wv + 1) / kCoopWaves : total_entries;
+    int64_t seg_lo = 0;                                    // entries in the segments before this one
     for (int32_t w8 = 0; w8 < nw * kMaxRun; w8 += kMaxRun) {
         int32_t fw[kMaxRun], b0[kMaxRun], b1[kMaxRun];
 #pragma unroll
         for (int i = 0; i < kMaxRun; ++i) {
             fw[i] = __builtin_amdgcn_readfirstlane(h[w8 + i].first_word);
             const int32_t nb = __builtin_amdgcn_readfirstlane(h[w8 + i].bodies);
-            b0[i] = (int32_t)((int64_t)nb * wv / kCoopWaves);
-            b1[i] = (int32_t)((int64_t)nb * (wv + 1) / kCoopWaves);
+            const int32_t per = body_entries(i + 1);
+            // bodies of this segment that begin before entry x of the whole: ceil((x - seg_lo) / per), within [0, nb]
+            auto before = [&](int64_t x) -> int32_t {
+                const int64_t d = x - seg_lo;
+                if (d <= 0) return 0;
+                if (d >= (int64_t)nb * per) return nb;
+                return (int32_t)(((uint32_t)d + (uint32_t)per - 1u) / (uint32_t)per);   // a constant divisor
+            };
+            b0[i] = before(lo);
+            b1[i] = before(hi);
+            seg_lo += (int64_t)nb * per;
         }
         run_class<1, V, true>(acc, gs + fw[0], b0[0], b1[0], Bbytes, ldb4, lane_off, ring, ring_lds, lane);
         run_class<2, V, true>(acc, gs + fw[1], b0[1], b1[1], Bbytes, ldb4, lane_off, ring, ring_lds, lane);
@@ -553,26 +624,54 @@ __global__ __launch_bounds__(64 * kCoopWaves) void spdm_sched_coop(const SchedCl
         run_class<8, V, true>(acc, gs + fw[7], b0[7], b1[7], Bbytes, ldb4, lane_off, ring, ring_lds, lane);
     }
 
-    // partial sums of waves 1 .. kCoopWaves-1 into wave 0, one wave at a time (every wave of the
-    // workgroup reaches every barrier: nothing above or below leaves the kernel early)
-    for (int src = 1; src < kCoopWaves; ++src) {
-        if (wv == src) {
+    // The look-ahead loads of the last class may still be on their way into registers that the compiler is free
+    // to use from here on.
+    wait_vm<0>();
+    // The partial sums of the eight waves are added up in a fixed order, so the bits are the same on every run;
+    // every wave of a heavy group's workgroup reaches every barrier (nothing above or below leaves the kernel
+    // early on this path).
+    if constexpr (V == 4) {
+        // a tree, in three rounds: the upper half of the waves still in the round writes, the lower half adds its
+        // partner's: ((w0 + w4) + (w2 + w6)) + ((w1 + w5) + (w3 + w7))
+        for (int half = kCoopWaves / 2; heavy && half >= 1; half >>= 1) {
+            if (wv >= half && wv < 2 * half) {
+                float* mine = part[wv - half];
 #pragma unroll
-            for (int r = 0; r < P; ++r)
+                for (int r = 0; r < P; ++r)
 #pragma unroll
-                for (int v = 0; v < V; ++v) part[(r * 64 + lane) * V + v] = acc_get(acc, kAccFirst + v * S + r);
+                    for (int v = 0; v < V; ++v) mine[(r * 64 + lane) * V + v] = acc_get(acc, kAccFirst + v * S + r);
+            }
+            __syncthreads();
+            if (wv < half) {
+                const float* theirs = part[wv];
+#pragma unroll
+                for (int r = 0; r < P; ++r)
+#pragma unroll
+                    for (int v = 0; v < V; ++v) acc_add(acc, kAccFirst + v * S + r, theirs[(r * 64 + lane) * V + v]);
+            }
+            __syncthreads();
         }
-        __syncthreads();
-        if (wv == 0) {
+    } else {
+        // one wave after the other into wave 0: ((w0 + w1) + w2) + ...
+        for (int src = 1; heavy && src < kCoopWaves; ++src) {
+            if (wv == src) {
 #pragma unroll
-            for (int r = 0; r < P; ++r)
+                for (int r = 0; r < P; ++r)
 #pragma unroll
-                for (int v = 0; v < V; ++v) acc_add(acc, kAccFirst + v * S + r, part[(r * 64 + lane) * V + v]);
+                    for (int v = 0; v < V; ++v) part[0][(r * 64 + lane) * V + v] = acc_get(acc, kAccFirst + v * S + r);
+            }
+            __syncthreads();
+            if (wv == 0) {
+#pragma unroll
+                for (int r = 0; r < P; ++r)
+#pragma unroll
+                    for (int v = 0; v < V; ++v) acc_add(acc, kAccFirst + v * S + r, part[0][(r * 64 + lane) * V + v]);
+            }
+            __syncthreads();
         }
-        __syncthreads();
     }
 
-    if (wv == 0 && in) {
+    if ((wv == 0 || !heavy) && in) {
         const int64_t row0 = q * p;
         float* __restrict__ Cl = C + lc.jc;
 #pragma unroll
@@ -603,19 +702,23 @@ hipError_t launch_spdm_sched_instance(const SpdmArgs& a, hipStream_t s)
     if (a.ldb > 0x3fffffffLL) return hipErrorInvalidValue;   // row pitch in bytes is kept in 32 bits
     if (a.p + 1 > acc_stride<V>()) return hipErrorInvalidValue;
     if (a.N < V) return hipErrorInvalidValue;               // lane_cols() places a lane's columns inside [0, N)
+#ifndef GCOO_ACC_TALL
+    // A launch of few items, on a matrix that carries the list of its groups by size: the kernel that splits heavy
+    // groups and bundles the others (no version of it in the tall layout: with 100 VGPRs it does not fit without
+    // spilling registers whose loads are in flight)
+    if (a.stats && a.order) {
+        int64_t bundle = (total + 255) / 256;              // light groups per workgroup: one workgroup per compute unit and round
+        bundle = bundle < 1 ? 1 : (bundle > kCoopWaves ? kCoopWaves : bundle);
+        spdm_sched_coop<V><<<dim3((unsigned)total), dim3(64 * kCoopWaves), 0, s>>>(a.hdr, a.stream, a.gIdxes, a.m, a.p, a.g, a.nw, a.B,
+                                                                                  a.ldb, a.N, a.C, a.ldc, total, a.nnz, a.stats,
+                                                                                  a.order, a.order + a.g, (int32_t)bundle);
+        hipError_t e = hipGetLastError();
+        if (e != hipSuccess) return e;
+    }
+#endif
     spdm_sched<V><<<dim3((unsigned)grid), dim3(64), 0, s>>>(a.hdr, a.stream, a.gIdxes, a.m, a.p, a.g, a.nw, a.B, a.ldb, a.N,
                                                             a.C, a.ldc, total, a.nnz, a.stats);
-    hipError_t e = hipGetLastError();
-    if (e != hipSuccess || !a.stats) return e;
-#ifdef GCOO_ACC_TALL
-    // no workgroup-shared kernel in this layout: with 100 VGPRs it does not fit without spilling
-    // registers whose loads are in flight
-    return hipErrorInvalidValue;
-#else
-    spdm_sched_coop<V><<<dim3((unsigned)total), dim3(64 * kCoopWaves), 0, s>>>(a.hdr, a.stream, a.gIdxes, a.m, a.p, a.g, a.nw, a.B,
-                                                                              a.ldb, a.N, a.C, a.ldc, total, a.nnz, a.stats);
     return hipGetLastError();
-#endif
 }
 
 }  // inline namespace

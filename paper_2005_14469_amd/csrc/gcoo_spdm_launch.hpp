@@ -24,8 +24,12 @@ struct SpdmArgs {
     int64_t ldc;
     int64_t nnz;
     // statistics of the conversion on the device ([1] = entries of the largest group), from which the
-    // kernels derive the entry count from which a group goes to spdm_sched_coop; nullptr: no group does
+    // kernel derives the entry count from which a group is split over the waves of a workgroup; nullptr: the
+    // launch has too many items for that to pay
     const unsigned long long* stats;
+    // order[0..g): the groups by falling size; order[g..2g): those sizes.  nullptr: not built (more than
+    // kOrderMaxGroups groups)
+    const int32_t* order;
 };
 
 // V = 4 needs p <= 32, V = 38 (four columns per lane, tall accumulator file) p <= 38, V = 2 needs

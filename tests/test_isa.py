@@ -65,7 +65,8 @@ def test_checker_sees_a_planted_violation(asm):
     K = _kernels("4")[0]
     regs, bad = isa_check.check(text, K)
     assert not bad
-    first = text.index("global_load_dwordx4")
+    start = re.search(rf"^{re.escape(K)}\w*:", text, re.M).start()          # inside the kernel that is checked
+    first = text.index("global_load_dwordx4", start)
     dst = int(re.match(r"global_load_dwordx4 v\[(\d+):", text[first:]).group(1))
     end_asm = text.index("#ASMEND", first)
     eol = text.index("\n", end_asm)
