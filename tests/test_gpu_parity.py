@@ -558,6 +558,35 @@ def test_skewed_config_through_the_share_variant(share_always, p):
     assert worst < 2e-6
 
 
+def test_zipf_config_every_element_default_path():
+    """The 16384^2 power-law workload as the benchmark runs it (library default height, automatic variant): a launch of
+    few items, so the register kernel takes the groups in order of falling size, splits the heavy ones over the
+    waves of a workgroup and bundles the others.  Every element against the oracle; the same bits twice."""
+    w = workloads.config(4)
+    p = binding.gcoo_default_p(w.m, w.k, w.nnz, w.N)
+    _say(f"config4 default path p={p} nnz={w.nnz}")
+    A = binding.gcoo_from_csr(w.m, w.k, w.row_ptr, w.col_idx, w.vals, p, device=DEV)
+    Bt = torch.from_numpy(w.B).to(DEV)
+    assert binding.gcoo_spdm_pick(A, Bt, torch.empty((w.m, w.N), device=DEV)) == binding.VARIANT_REG
+    worst, C1 = _every_element(w, A, Bt, binding.VARIANT_AUTO, chunk=4096)
+    assert worst < 2e-6
+    _, C2 = _every_element(w, A, Bt, binding.VARIANT_AUTO, chunk=4096)
+    assert torch.equal(C1, C2)
+
+
+@pytest.mark.parametrize("p", [4, 16, 32, 64])
+@pytest.mark.parametrize("N", [64, 260, 1031])
+def test_skewed_rows_few_items(p, N):
+    """Power-law rows in launches of few items, from all groups heavy (one tile, tall groups) to a mix of heavy
+    groups and bundles of light ones, with N that is no multiple of the columns per lane."""
+    w = workloads.zipf_rows(900, 5000, N, seed=23 + p, row_max=3000)
+    _say(f"skewed rows, few items: p={p} N={N} nnz={w.nnz}")
+    err, A, c1 = _check_product(w, p, binding.VARIANT_REG)
+    assert err < 2e-6
+    _, _, c2 = _check_product(w, p, binding.VARIANT_REG, A=A)
+    assert np.array_equal(c1, c2)
+
+
 # ------------------------------------------------------------------ dispatch corners
 
 @pytest.mark.parametrize("p", [8, 32, 38, 48])
