@@ -1,0 +1,371 @@
+// Stand-alone micro-benchmarks behind the ceilings that the design notes quote for the SpDM kernels on MI355X.
+// They measure what the machine delivers for the three things the kernels do per entry and per band, with
+// nothing else in the way:
+//   1. lds      ds_read_b128 bandwidth of a compute unit (the B values of the workgroup-shared kernel come from LDS)
+//   2. issue    the workgroup-shared kernel's own instruction sequence for a block of 16 singles / 4 quads
+//               (the macros of gcoo_spdm_share_kernel.hpp, so it is the same text), looped with no band
+//               bookkeeping, no fills and no barrier: the rate at which a compute unit issues it
+//   3. fill     48-row bands of a B tile fetched straight to LDS by eight waves, three buffers, one barrier per
+//               band with the loads of the band after next still in flight: the kernel's fetch pattern alone
+//   4. sweep    the register kernel's fetch pattern alone: every wave walks the rows of its B tile in ascending
+//               order and loads a random share of them, 1 KB per row, four loads per step, three steps in flight
+// Each line gives the time that the headline workload (8000 x 8000, 0.5 % density, N = 8000: 10.24 M entries x
+// column tiles) would need at the measured rate.
+// Build and run: python -m paper_2005_14469_amd.microbench
+#include <hip/hip_runtime.h>
+
+#include <cstdio>
+#include <cstdlib>
+#include <vector>
+
+#include "gcoo_spdm_share_kernel.hpp"
+
+#define CK(x)                                                                          \
+    do {                                                                               \
+        hipError_t e_ = (x);                                                           \
+        if (e_ != hipSuccess) {                                                        \
+            printf("HIP error %s at line %d\n", hipGetErrorString(e_), __LINE__);      \
+            exit(1);                                                                   \
+        }                                                                              \
+    } while (0)
+
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+constexpr double kEntryTiles = 320000.0 * 32.0;      // headline workload: entries x column tiles of 256
+constexpr int kCUs = 256;
+
+// ---------------------------------------------------------------- 1. LDS read bandwidth
+__global__ __launch_bounds__(512) void lds_read(int iters, unsigned* sink)
+{
+    extern __shared__ __attribute__((aligned(16))) float lds[];
+    const int lane = threadIdx.x & 63;
+    for (int i = threadIdx.x; i < 32768; i += 512) lds[i] = (float)i;
+    __syncthreads();
+    const unsigned base = lane * 16 + ((threadIdx.x >> 6) * 7 % 16) * 4096;
+    unsigned acc = 0;
+    for (int it = 0; it < iters; ++it) {
+        f32x4 r0, r1, r2, r3, r4, r5, r6, r7;
+        const unsigned a = (base + (it * 37 % 13) * 8192u) % 122880u;      // + 7168 + 16 stays below 131072
+        asm volatile("ds_read_b128 %0, %8\n\tds_read_b128 %1, %8 offset:1024\n\tds_read_b128 %2, %8 offset:3072\n\t"
+                     "ds_read_b128 %3, %8 offset:2048\n\tds_read_b128 %4, %8 offset:5120\n\tds_read_b128 %5, %8 offset:4096\n\t"
+                     "ds_read_b128 %6, %8 offset:7168\n\tds_read_b128 %7, %8 offset:6144\n\ts_waitcnt lgkmcnt(0)"
+                     : "=&v"(r0), "=&v"(r1), "=&v"(r2), "=&v"(r3), "=&v"(r4), "=&v"(r5), "=&v"(r6), "=&v"(r7)
+                     : "v"(a));
+        acc += __float_as_uint(r0.x) ^ __float_as_uint(r7.x);
+    }
+    if (acc == 0x12345u) sink[0] = acc;
+}
+
+// ---------------------------------------------------------------- 2. issue rate of the per-entry sequence
+// MODE 0: sixteen singles (SH_GROUP x 4), 1: four quads, 2: the multiply-adds of sixteen entries with their
+// index-mode switches and nothing else, 3: 64 plain v_fmac_f32 (no index mode, no LDS)
+template <int MODE>
+__global__ __launch_bounds__(512) void issue(int iters, float* out)
+{
+    extern __shared__ __attribute__((aligned(16))) float lds[];
+    const int lane = threadIdx.x & 63;
+    for (int i = threadIdx.x; i < 3 * 12288; i += 512) lds[i] = 1.0f + (float)(i & 7);
+    __syncthreads();
+    gcoo::ShareAcc acc;
+    acc.t0 = 0.0f; acc.t1 = 0.0f; acc.t2 = 0.0f; acc.t3 = 0.0f; acc.t4 = 0.0f; acc.t5 = 0.0f; acc.t6 = 0.0f;
+    const unsigned rec = lane & 15;
+    const float value = 0.5f;
+    // rows of the four records of a group of four, one byte each (all below 48); slot of the record's B row
+    const unsigned g4 = rec & ~3u;
+    const unsigned rows = ((g4 * 3) % 48) | (((g4 * 3 + 7) % 48) << 8) | (((g4 * 3 + 19) % 48) << 16) | (((g4 * 3 + 31) % 48) << 24);
+    const unsigned off = ((rec * 11) % 48) * 1024u;
+    const unsigned l16 = lane * 16u;
+    if constexpr (MODE == 0) {
+        asm volatile(
+            "v_mov_b32 v40, %[val]\n\t"
+            "v_mov_b32 v41, %[rows]\n\t"
+            "v_mov_b32 v42, %[off]\n\t"
+            "v_mov_b32 v46, %[off]\n\t"
+            "v_mov_b32 v48, %[l16]\n\t"
+            "s_mov_b32 s74, %[iters]\n"
+            ".Lq_loop_%=:\n\t"
+            "s_mov_b32 s73, 1000\n\t"
+            SH_ROWS(s70, 0)
+            SH_ADDR(v36, v42, 0) SH_ADDR(v37, v42, 1) SH_ADDR(v38, v42, 2) SH_ADDR(v39, v42, 3)
+            SH_READ_SET0 SH_READ_SET1 SH_READ_SET2 SH_READ_SET3
+            SH_GROUP(v42, 4, 5, 6, 7, SH_ROWS(s86, 4), 0, 1, 2, 3, s70)
+            SH_GROUP(v42, 8, 9, 10, 11, SH_ROWS(s70, 8), 4, 5, 6, 7, s86)
+            SH_GROUP(v42, 12, 13, 14, 15, SH_ROWS(s86, 12), 8, 9, 10, 11, s70)
+            SH_GROUP(v46, 0, 1, 2, 3, "", 12, 13, 14, 15, s86)
+            "s_waitcnt lgkmcnt(0)\n\t"
+            "s_sub_u32 s74, s74, 1\n\t"
+            "s_cmp_lg_u32 s74, 0\n\t"
+            "s_cbranch_scc1 .Lq_loop_%=\n"
+            ".Lsh_send_%=:\n\t"
+            "s_waitcnt lgkmcnt(0)\n\t"
+            : "+{v[60:63]}"(acc.t0), "+{v[64:95]}"(acc.t1), "+{v[96:127]}"(acc.t2), "+{v[128:159]}"(acc.t3),
+              "+{v[160:191]}"(acc.t4), "+{v[192:223]}"(acc.t5), "+{v[224:255]}"(acc.t6)
+            : [iters] "s"(iters), [val] "v"(value), [rows] "v"(rows), [off] "v"(off), [l16] "v"(l16)
+            : "m0", "scc", "memory", "v20", "v21", "v22", "v23", "v24", "v25", "v26", "v27", "v28", "v29", "v30", "v31", "v32", "v33",
+              "v34", "v35", "v36", "v37", "v38", "v39", "v40", "v41", "v42", "v46", "v48", "s70", "s73", "s74", "s86");
+    } else if constexpr (MODE == 1) {
+        asm volatile(
+            "v_mov_b32 v40, %[val]\n\t"
+            "v_mov_b32 v41, %[rows]\n\t"
+            "v_mov_b32 v42, %[off]\n\t"
+            "v_mov_b32 v46, %[off]\n\t"
+            "v_mov_b32 v48, %[l16]\n\t"
+            "s_mov_b32 s74, %[iters]\n"
+            ".Lq_loop_%=:\n\t"
+            SH_ROWS(s70, 0)
+            SH_ROWS(s86, 4)
+            SH_ADDR(v36, v42, 0) SH_ADDR(v37, v42, 4) SH_ADDR(v38, v42, 8) SH_ADDR(v39, v42, 12)
+            SH_READ_SET0 SH_READ_SET1 SH_READ_SET2 SH_READ_SET3
+            SH_WAIT3
+            SH_FMAC_SET0(0, s70) SH_FMAC_SET0(1, s70) SH_FMAC_SET0(2, s70) SH_FMAC_SET0(3, s70)
+            SH_OFF
+            SH_ROWS(s70, 8)
+            "s_waitcnt lgkmcnt(2)\n\t"
+            SH_FMAC_SET1(4, s86) SH_FMAC_SET1(5, s86) SH_FMAC_SET1(6, s86) SH_FMAC_SET1(7, s86)
+            SH_OFF
+            SH_ROWS(s86, 12)
+            "s_waitcnt lgkmcnt(1)\n\t"
+            SH_FMAC_SET2(8, s70) SH_FMAC_SET2(9, s70) SH_FMAC_SET2(10, s70) SH_FMAC_SET2(11, s70)
+            SH_OFF
+            "s_waitcnt lgkmcnt(0)\n\t"
+            SH_FMAC_SET3(12, s86) SH_FMAC_SET3(13, s86) SH_FMAC_SET3(14, s86) SH_FMAC_SET3(15, s86)
+            SH_OFF
+            "s_sub_u32 s74, s74, 1\n\t"
+            "s_cmp_lg_u32 s74, 0\n\t"
+            "s_cbranch_scc1 .Lq_loop_%=\n\t"
+            : "+{v[60:63]}"(acc.t0), "+{v[64:95]}"(acc.t1), "+{v[96:127]}"(acc.t2), "+{v[128:159]}"(acc.t3),
+              "+{v[160:191]}"(acc.t4), "+{v[192:223]}"(acc.t5), "+{v[224:255]}"(acc.t6)
+            : [iters] "s"(iters), [val] "v"(value), [rows] "v"(rows), [off] "v"(off), [l16] "v"(l16)
+            : "m0", "scc", "memory", "v20", "v21", "v22", "v23", "v24", "v25", "v26", "v27", "v28", "v29", "v30", "v31", "v32", "v33",
+              "v34", "v35", "v36", "v37", "v38", "v39", "v40", "v41", "v42", "v46", "v48", "s70", "s73", "s74", "s86");
+    } else if constexpr (MODE == 2) {
+        asm volatile(
+            "v_mov_b32 v40, %[val]\n\t"
+            "v_mov_b32 v41, %[rows]\n\t"
+            "v_mov_b32 v42, %[off]\n\t"
+            "v_mov_b32 v46, %[off]\n\t"
+            "v_mov_b32 v48, %[l16]\n\t"
+            "v_mov_b32 v20, 1.0\n\tv_mov_b32 v21, 1.0\n\tv_mov_b32 v22, 1.0\n\tv_mov_b32 v23, 1.0\n\t"
+            "s_mov_b32 s74, %[iters]\n"
+            ".Lq_loop_%=:\n\t"
+            SH_ROWS(s70, 0)
+            SH_FMAC_SET0(0, s70) SH_FMAC_SET0(1, s70) SH_FMAC_SET0(2, s70) SH_FMAC_SET0(3, s70)
+            SH_OFF
+            SH_ROWS(s70, 4)
+            SH_FMAC_SET0(4, s70) SH_FMAC_SET0(5, s70) SH_FMAC_SET0(6, s70) SH_FMAC_SET0(7, s70)
+            SH_OFF
+            SH_ROWS(s70, 8)
+            SH_FMAC_SET0(8, s70) SH_FMAC_SET0(9, s70) SH_FMAC_SET0(10, s70) SH_FMAC_SET0(11, s70)
+            SH_OFF
+            SH_ROWS(s70, 12)
+            SH_FMAC_SET0(12, s70) SH_FMAC_SET0(13, s70) SH_FMAC_SET0(14, s70) SH_FMAC_SET0(15, s70)
+            SH_OFF
+            "s_sub_u32 s74, s74, 1\n\t"
+            "s_cmp_lg_u32 s74, 0\n\t"
+            "s_cbranch_scc1 .Lq_loop_%=\n\t"
+            : "+{v[60:63]}"(acc.t0), "+{v[64:95]}"(acc.t1), "+{v[96:127]}"(acc.t2), "+{v[128:159]}"(acc.t3),
+              "+{v[160:191]}"(acc.t4), "+{v[192:223]}"(acc.t5), "+{v[224:255]}"(acc.t6)
+            : [iters] "s"(iters), [val] "v"(value), [rows] "v"(rows), [off] "v"(off), [l16] "v"(l16)
+            : "m0", "scc", "memory", "v20", "v21", "v22", "v23", "v40", "v41", "v42", "v46", "v48", "s70", "s73", "s74", "s86");
+    } else {
+        asm volatile(
+            "v_mov_b32 v40, %[val]\n\t"
+            "v_mov_b32 v20, 1.0\n\tv_mov_b32 v21, 1.0\n\tv_mov_b32 v22, 1.0\n\tv_mov_b32 v23, 1.0\n\t"
+            "s_mov_b32 s74, %[iters]\n"
+            ".Lq_loop_%=:\n\t"
+            "v_fmac_f32 v60, v40, v20\n\tv_fmac_f32 v109, v40, v21\n\tv_fmac_f32 v158, v40, v22\n\tv_fmac_f32 v207, v40, v23\n\t"
+            "v_fmac_f32 v61, v40, v20\n\tv_fmac_f32 v110, v40, v21\n\tv_fmac_f32 v159, v40, v22\n\tv_fmac_f32 v208, v40, v23\n\t"
+            "v_fmac_f32 v62, v40, v20\n\tv_fmac_f32 v111, v40, v21\n\tv_fmac_f32 v160, v40, v22\n\tv_fmac_f32 v209, v40, v23\n\t"
+            "v_fmac_f32 v63, v40, v20\n\tv_fmac_f32 v112, v40, v21\n\tv_fmac_f32 v161, v40, v22\n\tv_fmac_f32 v210, v40, v23\n\t"
+            "v_fmac_f32 v64, v40, v20\n\tv_fmac_f32 v113, v40, v21\n\tv_fmac_f32 v162, v40, v22\n\tv_fmac_f32 v211, v40, v23\n\t"
+            "v_fmac_f32 v65, v40, v20\n\tv_fmac_f32 v114, v40, v21\n\tv_fmac_f32 v163, v40, v22\n\tv_fmac_f32 v212, v40, v23\n\t"
+            "v_fmac_f32 v66, v40, v20\n\tv_fmac_f32 v115, v40, v21\n\tv_fmac_f32 v164, v40, v22\n\tv_fmac_f32 v213, v40, v23\n\t"
+            "v_fmac_f32 v67, v40, v20\n\tv_fmac_f32 v116, v40, v21\n\tv_fmac_f32 v165, v40, v22\n\tv_fmac_f32 v214, v40, v23\n\t"
+            "v_fmac_f32 v68, v40, v20\n\tv_fmac_f32 v117, v40, v21\n\tv_fmac_f32 v166, v40, v22\n\tv_fmac_f32 v215, v40, v23\n\t"
+            "v_fmac_f32 v69, v40, v20\n\tv_fmac_f32 v118, v40, v21\n\tv_fmac_f32 v167, v40, v22\n\tv_fmac_f32 v216, v40, v23\n\t"
+            "v_fmac_f32 v70, v40, v20\n\tv_fmac_f32 v119, v40, v21\n\tv_fmac_f32 v168, v40, v22\n\tv_fmac_f32 v217, v40, v23\n\t"
+            "v_fmac_f32 v71, v40, v20\n\tv_fmac_f32 v120, v40, v21\n\tv_fmac_f32 v169, v40, v22\n\tv_fmac_f32 v218, v40, v23\n\t"
+            "v_fmac_f32 v72, v40, v20\n\tv_fmac_f32 v121, v40, v21\n\tv_fmac_f32 v170, v40, v22\n\tv_fmac_f32 v219, v40, v23\n\t"
+            "v_fmac_f32 v73, v40, v20\n\tv_fmac_f32 v122, v40, v21\n\tv_fmac_f32 v171, v40, v22\n\tv_fmac_f32 v220, v40, v23\n\t"
+            "v_fmac_f32 v74, v40, v20\n\tv_fmac_f32 v123, v40, v21\n\tv_fmac_f32 v172, v40, v22\n\tv_fmac_f32 v221, v40, v23\n\t"
+            "v_fmac_f32 v75, v40, v20\n\tv_fmac_f32 v124, v40, v21\n\tv_fmac_f32 v173, v40, v22\n\tv_fmac_f32 v222, v40, v23\n\t"
+            "s_sub_u32 s74, s74, 1\n\t"
+            "s_cmp_lg_u32 s74, 0\n\t"
+            "s_cbranch_scc1 .Lq_loop_%=\n\t"
+            : "+{v[60:63]}"(acc.t0), "+{v[64:95]}"(acc.t1), "+{v[96:127]}"(acc.t2), "+{v[128:159]}"(acc.t3),
+              "+{v[160:191]}"(acc.t4), "+{v[192:223]}"(acc.t5), "+{v[224:255]}"(acc.t6)
+            : [iters] "s"(iters), [val] "v"(value)
+            : "scc", "memory", "v20", "v21", "v22", "v23", "v40", "s74");
+    }
+    float s = 0.0f;
+    for (int r = 0; r < 4; ++r) s += gcoo::share_acc_get(acc, gcoo::kShareAccFirst + r);
+    if (s == 123.456f) out[0] = s;
+}
+
+// ---------------------------------------------------------------- 3. bands of a B tile straight to LDS
+// Workgroup = 8 waves; band b = 48 rows picked in ascending order from the tile's k rows (stride `gap` on
+// average), six rows per wave, to buffer b % 3; one barrier per band in front of which the loads of the band
+// after next may still be in flight.
+__global__ __launch_bounds__(512) void fill(const float* __restrict__ B, int k, int ldb, int bands, int gap, int nq, float* out)
+{
+    extern __shared__ __attribute__((aligned(16))) float lds[];
+    const int lane = threadIdx.x & 63, wv = threadIdx.x >> 6;
+    const unsigned bid = blockIdx.x, per = gridDim.x >> 3;
+    const unsigned item = (bid & 7u) * per + (bid >> 3);
+    const unsigned tile = item / nq;                       // tile-major, like the kernel (the last tile reaches into the row pitch)
+    const float* bt = B + (size_t)tile * 256 + lane * 4;
+    unsigned seed = item * 2654435761u + 99u;
+    auto request = [&](int band) {
+        for (int t = 0; t < 6; ++t) {
+            seed = seed * 1664525u + 1013904223u;
+            long row = ((long)band * 48 + wv * 6 + t) * gap + (seed >> 10) % gap;
+            if (row >= k) row = row % k;
+            __builtin_amdgcn_global_load_lds((__attribute__((address_space(1))) const void*)(bt + row * ldb),
+                                             (__attribute__((address_space(3))) void*)(lds + (band % 3) * 12288 + (wv * 6 + t) * 256), 16, 0, 0);
+        }
+    };
+    request(0);
+    request(1);
+    for (int b = 0; b < bands; ++b) {
+        if (b + 2 < bands) {
+            request(b + 2);
+            asm volatile("s_waitcnt vmcnt(6)\n\ts_barrier" ::: "memory");
+        } else {
+            asm volatile("s_waitcnt vmcnt(0)\n\ts_barrier" ::: "memory");
+        }
+    }
+    if (lds[threadIdx.x] == 123.456f) out[0] = 1.0f;
+}
+
+// ---------------------------------------------------------------- 4. the register kernel's fetch pattern
+__device__ __forceinline__ void ld16(f32x4& t, unsigned off, const char* base)
+{
+    asm volatile("global_load_dwordx4 %0, %1, %2" : "=v"(t) : "v"(off), "s"(base));
+}
+__global__ __launch_bounds__(64) void sweep(const char* __restrict__ B, unsigned rows, unsigned pitch, unsigned gap, float* out, int groups)
+{
+    const int lane = threadIdx.x;
+    const unsigned bid = blockIdx.x, per = gridDim.x >> 3;
+    const unsigned w = (bid & 7u) * per + (bid >> 3);
+    const unsigned tile = w / groups;
+    unsigned s = __builtin_amdgcn_readfirstlane(w * 2654435761u + 12345u);
+    const char* base = B + (size_t)tile * 1024;
+    const unsigned off = lane * 16;
+    f32x4 bq[4][4];
+    f32x4 acc = {0, 0, 0, 0};
+    unsigned row = 0;
+    auto issue4 = [&](f32x4(&d)[4]) {
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            s = s * 1664525u + 1013904223u;
+            row += 1 + (s >> 8) % gap;
+            const unsigned r = row < rows ? row : rows - 1;
+            ld16(d[j], off, base + (size_t)r * pitch);
+        }
+    };
+    issue4(bq[0]);
+    issue4(bq[1]);
+    issue4(bq[2]);
+    while (row < rows) {
+#pragma unroll
+        for (int st = 0; st < 4; ++st) {
+            issue4(bq[(st + 3) % 4]);
+            asm volatile("s_waitcnt vmcnt(12)");
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                asm volatile("v_add_f32 %0, %0, %1" : "+v"(acc.x) : "v"(bq[st][j].x));
+                asm volatile("v_add_f32 %0, %0, %1" : "+v"(acc.y) : "v"(bq[st][j].w));
+            }
+        }
+    }
+    asm volatile("s_waitcnt vmcnt(0)");
+    if (acc.x == 123.456f) out[0] = acc.y;
+}
+
+template <typename F>
+static float timed(F launch, int reps)
+{
+    hipEvent_t e0, e1;
+    CK(hipEventCreate(&e0));
+    CK(hipEventCreate(&e1));
+    launch();
+    CK(hipDeviceSynchronize());
+    CK(hipEventRecord(e0));
+    for (int r = 0; r < reps; ++r) launch();
+    CK(hipEventRecord(e1));
+    CK(hipEventSynchronize(e1));
+    float ms;
+    CK(hipEventElapsedTime(&ms, e0, e1));
+    CK(hipGetLastError());
+    return ms / reps;
+}
+
+int main()
+{
+    CK(hipSetDevice(0));
+    float* out;
+    CK(hipMalloc(&out, 4096));
+    unsigned* sink = reinterpret_cast<unsigned*>(out);
+
+    // 1
+    CK(hipFuncSetAttribute((const void*)lds_read, hipFuncAttributeMaxDynamicSharedMemorySize, 131072));
+    {
+        const int iters = 4000;
+        const float ms = timed([&] { lds_read<<<kCUs, 512, 131072>>>(iters, sink); }, 3);
+        const double bytes = (double)kCUs * 8 * 64 * 16 * 8.0 * iters;
+        printf("lds    ds_read_b128, 8 waves per CU: %.3f ms, %.1f TB/s chip; one 1 KB row per entry and tile -> %.0f us for the headline workload\n",
+               ms, bytes / ms * 1e-9, kEntryTiles * 1024.0 / (bytes / ms * 1e3) * 1e6);
+        fflush(stdout);
+    }
+    // 2
+    CK(hipFuncSetAttribute((const void*)issue<0>, hipFuncAttributeMaxDynamicSharedMemorySize, 3 * 49152));
+    CK(hipFuncSetAttribute((const void*)issue<1>, hipFuncAttributeMaxDynamicSharedMemorySize, 3 * 49152));
+    CK(hipFuncSetAttribute((const void*)issue<2>, hipFuncAttributeMaxDynamicSharedMemorySize, 3 * 49152));
+    CK(hipFuncSetAttribute((const void*)issue<3>, hipFuncAttributeMaxDynamicSharedMemorySize, 3 * 49152));
+    {
+        const int iters = 4000;
+        const char* names[4] = {"16 singles (address, LDS read, index mode, 4 multiply-adds each)", "4 quads (one LDS read per four entries)",
+                                "multiply-adds and index mode only", "plain v_fmac_f32 only"};
+        const double instr[4] = {172, 119, 107, 67};      // instructions of one turn of each loop (16 entries)
+        for (int mode = 0; mode < 4; ++mode) {
+            const float ms = timed([&] {
+                if (mode == 0) issue<0><<<kCUs, 512, 3 * 49152>>>(iters, out);
+                else if (mode == 1) issue<1><<<kCUs, 512, 3 * 49152>>>(iters, out);
+                else if (mode == 2) issue<2><<<kCUs, 512, 3 * 49152>>>(iters, out);
+                else issue<3><<<kCUs, 512, 3 * 49152>>>(iters, out);
+            }, 3);
+            const double entries = (double)kCUs * 8 * 16.0 * iters;       // 16 entries per wave and turn
+            const double per_entry_ns = ms * 1e6 / ((double)16 * iters);   // per wave
+            printf("issue  %-66s %.3f ms: %.2f ns per entry and wave, about %.1f instructions per entry -> %.0f us for the headline workload\n",
+                   names[mode], ms, per_entry_ns, instr[mode] / 16.0, kEntryTiles / (entries / ms) * 1e3);
+            fflush(stdout);
+        }
+    }
+    // 3 and 4 read a B of 8000 x 8000 floats
+    const int k = 8000, ldb = 8000;
+    float* B;
+    CK(hipMalloc(&B, (size_t)k * ldb * 4 + 65536));
+    CK(hipMemset(B, 0, (size_t)k * ldb * 4 + 65536));
+    CK(hipFuncSetAttribute((const void*)fill, hipFuncAttributeMaxDynamicSharedMemorySize, 3 * 49152));
+    {
+        // the headline workload at 42 rows per group: 24 super-groups x 32 tiles, 136 bands each (6515 distinct columns of 8000)
+        const int grid = 24 * 32, bands = 136;
+        const float ms = timed([&] { fill<<<grid, 512, 3 * 49152>>>(B, k, ldb, bands, 1, 24, out); }, 5);
+        const double bytes = (double)grid * bands * 48 * 1024.0;
+        printf("fill   %d workgroups x %d bands x 48 rows of 1 KB straight to LDS, one barrier per band: %.3f ms, %.1f TB/s (%.1f GB: what the "
+               "workgroup-shared kernel fetches for the headline workload at 42 rows per group)\n", grid, bands, ms, bytes / ms * 1e-9, bytes * 1e-9);
+        fflush(stdout);
+    }
+    {
+        // the headline workload at 32 rows per group: 250 groups x 32 tiles, each wave loads about 1/7 of the 8000 rows
+        const int groups = 250, tiles = 32, grid = groups * tiles;
+        for (unsigned gap : {13u, 1u}) {
+            const float ms = timed([&] { sweep<<<grid, 64>>>(reinterpret_cast<const char*>(B), (unsigned)k, (unsigned)ldb * 4u, gap, out, groups); }, 5);
+            const double loads = (double)grid * (k / ((gap + 1) / 2.0));
+            printf("sweep  %d waves, every %s row of a tile, 1 KB per load, 12 loads in flight: %.3f ms, %.1f TB/s through the vector cache (%.1f GB%s)\n",
+                   grid, gap == 1 ? "" : "7th (on average)", ms, loads * 1024.0 / ms * 1e-9, loads * 1024.0 * 1e-9,
+                   gap == 1 ? "" : ": what the register kernel fetches for the headline workload");
+            fflush(stdout);
+        }
+    }
+    return 0;
+}
