@@ -58,6 +58,10 @@ def parse():
     ap.add_argument("--eo-kc", action="store_true",
                     help="instead of the headline run: dense A on the device -> GCOO (Algorithm 1) -> SpDM at n = 4000 and "
                          "14000, sparsity 0.95..0.99: the split of Section 4.3 into extra overhead (conversion) and kernel")
+    ap.add_argument("--kernels", action="store_true",
+                    help="instead of the headline run: the register kernel (p = 32, 38) against the workgroup-shared kernel "
+                         "(p = 32, 42, 48) on uniform random square matrices, kernel and conversion times: the grid behind "
+                         "the library's choice between the two")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="only run a plain 256 MiB device copy a few times: the reference launch against which the "
                          "FETCH_SIZE / WRITE_SIZE counters of rocprofv3 --pmc are scaled")
@@ -324,6 +328,46 @@ def sweep(torch, binding, workloads, args, dev):
             "rows": rows}
 
 
+def kernels_compared(torch, binding, workloads, args, dev):
+    """Register kernel against workgroup-shared kernel on the same matrices (uniform random, N = n)."""
+    rows = []
+    plan = [(4000, 0.98), (4000, 0.995), (8000, 0.9), (8000, 0.95), (8000, 0.98), (8000, 0.99), (8000, 0.995), (8000, 0.999),
+            (14000, 0.98), (14000, 0.995)]
+    cur_n, Bd, Cd = None, None, None
+    binding.gcoo_set_share_policy(binding.SHARE_ALWAYS)
+    try:
+        for n, sp in plan:
+            if n != cur_n:
+                del Bd, Cd
+                g = torch.Generator(device=dev)
+                g.manual_seed(workloads.BASE_SEED + n)
+                Bd = torch.randn((n, n), generator=g, device=dev, dtype=torch.float32)
+                Cd = torch.empty((n, n), device=dev, dtype=torch.float32)
+                cur_n = n
+            w = workloads.uniform_random(n, n, 1, sp, workloads.BASE_SEED + n + int(round(sp * 10000)), name="kernels")
+            rp, ci, va = [torch.from_numpy(x).to(dev) for x in (w.row_ptr, w.col_idx, w.vals)]
+            row = dict(n=n, sparsity=sp, nnz=w.nnz)
+            for name, variant, p in (("reg32", binding.VARIANT_REG, 32), ("reg38", binding.VARIANT_REG, 38),
+                                     ("share32", binding.VARIANT_SHARE, 32), ("share42", binding.VARIANT_SHARE, 42),
+                                     ("share48", binding.VARIANT_SHARE, 48)):
+                holder = {}
+
+                def convert():
+                    holder["A"] = binding.gcoo_from_csr(n, n, rp, ci, va, p)
+
+                t_conv = _event_ms(torch, convert, 3)
+                A = holder["A"]
+                row[name + "_ms"] = _event_ms(torch, lambda: binding.gcoo_spdm(A, Bd, Cd, variant=variant), 5)
+                row[name + "_convert_ms"] = t_conv      # with both schedules built (the policy above)
+                A.free()
+            print("kernels " + " ".join(f"{k}={v:.3f}" if isinstance(v, float) else f"{k}={v}" for k, v in row.items()),
+                  file=sys.stderr, flush=True)
+            rows.append(row)
+    finally:
+        binding.gcoo_set_share_policy(binding.SHARE_AUTO)
+    return {"metric": "register kernel against workgroup-shared kernel, uniform random square A, N = n, fp32, ms", "rows": rows}
+
+
 def eo_kc(torch, binding, workloads, args, dev):
     """Dense device matrix -> GCOO -> product: conversion time against kernel time (Section 4.3)."""
     rows = []
@@ -390,6 +434,9 @@ def main():
         return
     if args.eo_kc:
         print(json.dumps(eo_kc(torch, binding, workloads, args, dev)))
+        return
+    if args.kernels:
+        print(json.dumps(kernels_compared(torch, binding, workloads, args, dev)))
         return
     if args.sweep:
         print(json.dumps(sweep(torch, binding, workloads, args, dev)))

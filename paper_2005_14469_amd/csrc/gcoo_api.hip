@@ -126,7 +126,7 @@ int dense_vec_width(const float* A, int64_t lda, int64_t k)
 // the workgroup-shared kernel is the one gcoo_spdm() will pick.  Measured on MI355X with uniform random square
 // matrices (n = 4000 .. 14000, density 0.1 % .. 10 %, N = n), against the register kernel at its best group height:
 // the workgroup-shared kernel wins from 3500 columns on at 0.8 % density or more (n = 8000: by 10 .. 30 % between
-// 1 % and 5 %; n = 4000, 2 %: 12 %) and from 12000 columns on already at 0.4 % (n = 14000: 1.7 .. 2.3x between 0.5 %
+// 1 % and 5 %; n = 4000, 2 %: 12 %) and from 9000 columns on already at 0.4 % (n = 10000, 0.5 %: 1.0 against 1.23 ms; n = 14000: 1.7 .. 2.3x between 0.5 %
 // and 2 %); at n = 8000 and 0.5 % the two kernels are level and the schedule's cost decides for the register
 // kernel.  The B tile of a column tile then no longer stays in L2 between the groups that need it, and what
 // the register kernel pays per run (a 1 KB segment through the vector cache) costs more than the per-band steps
@@ -146,7 +146,7 @@ bool share_shape_preferred(int64_t m, int64_t k, int64_t nnz)
     if (m <= 0 || k <= 0 || nnz <= 0 || k > gcoo::kShareMaxK) return false;
     const double density = (double)nnz / ((double)m * (double)k);
     if (density > 0.06) return false;
-    return (k >= 12000 && density >= 0.004) || (k >= 3500 && density >= 0.008);
+    return (k >= 9000 && density >= 0.004) || (k >= 3500 && density >= 0.008);
 }
 
 bool share_kernel_preferred(int64_t m, int64_t k, int64_t nnz, int32_t p)
@@ -331,18 +331,21 @@ int launch_build_schedule(const gcoo_matrix* h, char* scratch, hipStream_t s)
 {
     uint32_t* share_alloc = reinterpret_cast<uint32_t*>(scratch + h->L.share_alloc);
     if (h->g > 0 && h->has_sched) {
-        const dim3 grid((unsigned)(h->g * h->nw));
-        if (h->nnz / (h->g * h->nw) <= 1024)
+        // the groups by falling size, where the matrix has few of them: a workgroup more of the small-workgroup
+        // instance, a launch of its own beside the large-workgroup instance
+        int32_t* order = h->has_order() ? h->order() : nullptr;
+        if (h->nnz / (h->g * h->nw) <= 1024) {
+            const dim3 grid((unsigned)(h->g * h->nw + (order ? 1 : 0)));
             gcoo::build_schedule<256><<<grid, dim3(256), 0, s>>>(h->gIdxes(), h->rows(), h->cols(), h->values(), h->p, h->g, h->nw,
-                                                                 h->window_cols, h->sched_hdr(), h->sched());
-        else
+                                                                 h->window_cols, h->sched_hdr(), h->sched(), order, order ? order + h->g : nullptr);
+        } else {
+            const dim3 grid((unsigned)(h->g * h->nw));
             gcoo::build_schedule<1024><<<grid, dim3(1024), 0, s>>>(h->gIdxes(), h->rows(), h->cols(), h->values(), h->p, h->g, h->nw,
-                                                                   h->window_cols, h->sched_hdr(), h->sched());
-        HIP_TRY(hipGetLastError());
-        if (h->has_order()) {
-            gcoo::group_order_by_size<<<dim3(1), dim3(1024), 0, s>>>(h->gIdxes(), (int32_t)h->g, h->order(), h->order() + h->g);
+                                                                   h->window_cols, h->sched_hdr(), h->sched(), nullptr, nullptr);
             HIP_TRY(hipGetLastError());
+            if (order) gcoo::group_order_by_size<<<dim3(1), dim3(1024), 0, s>>>(h->gIdxes(), (int32_t)h->g, order, order + h->g);
         }
+        HIP_TRY(hipGetLastError());
     }
     if (h->g > 0 && h->has_share) {
         const size_t bitmap_bytes = (size_t)((h->k + 31) / 32) * 4;

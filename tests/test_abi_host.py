@@ -150,7 +150,7 @@ def test_default_p_rule(L):
         return L.gcoo_default_p(m, n, int(m * n * (1 - s)), n if N is None else N)
     assert dp(8000, 0.995) == 32            # the headline workload: 8000 columns at 0.5 %, the kernels are level
     assert dp(8000, 0.98) == 42 and dp(8000, 0.99) == 42 and dp(8000, 0.95) == 42      # 24 super-groups x 32 tiles = 3 rounds of 256
-    assert dp(14000, 0.995) == 48 and dp(12000, 0.997) == 32
+    assert dp(14000, 0.995) == 48 and dp(12000, 0.997) == 32 and dp(10000, 0.995) != 32
     assert dp(14000, 0.98) == 48 and dp(4000, 0.98) == 32
     for n in (4000, 5000, 7000, 8000, 10000, 14000):
         assert dp(n, 0.98) == _share_height(n, n), n
