@@ -112,6 +112,7 @@ __global__ __launch_bounds__(kBuildThreads) void build_schedule(const int32_t* _
     (void)order;
     (void)osize;
     __shared__ __attribute__((aligned(16))) int32_t stage[kStage];
+    __shared__ uint8_t piece_s[kStage];           // staged window: place in its piece (3 bits) and length of the piece - 1 (3 bits) of every entry
     const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
     const int64_t q = blockIdx.x / nw;
     const int32_t w = (int32_t)(blockIdx.x - q * nw);
@@ -176,10 +177,51 @@ __global__ __launch_bounds__(kBuildThreads) void build_schedule(const int32_t* _
             return len;
         };
 
-        for (int32_t e = wb + tid; e < we; e += kBuildThreads) {
-            int pos;
-            const int L = natural_piece(e, pos);
-            if (pos == 0) atomicAdd(&cnt[L - 1], 1);      // a count: the order of the adds is irrelevant
+        // The same for a staged window, without a chain of dependent reads per entry: the entries of a wave
+        // (64 in a row) mark where a run starts, a ballot gives every lane the start and the end of its run inside
+        // the wave, lane 0 alone walks back to the start of a run that began before the wave, and eight lanes look
+        // at the eight entries behind the wave (a piece ends at most seven entries after one of its entries).
+        // ew = the wave's first entry.  Every lane of the wave must call it.
+        auto staged_piece = [&](int32_t e, int32_t ew, int& pos) -> int {
+            const bool valid = e < we;
+            const int32_t c = valid ? stage[e - wb] : 0;
+            const bool start = !valid || e == wb || stage[e - 1 - wb] != c;
+            const uint64_t b1 = __ballot(start);
+            const int32_t e2 = ew + 64 + lane;
+            const bool start2 = lane < 8 && (e2 >= we || stage[e2 - wb] != stage[e2 - 1 - wb]);
+            const uint64_t b2 = __ballot(start2);
+            int32_t carry = 0;                           // entries of the wave's first run in front of the wave
+            if ((b1 & 1ull) == 0) {                      // (then ew < we and ew > wb)
+                if (lane == 0) {
+                    while (ew - 1 - carry >= wb && stage[ew - 1 - carry - wb] == c) ++carry;
+                }
+                carry = __shfl(carry, 0, 64);
+            }
+            const uint64_t upto = b1 & (lane == 63 ? ~0ull : ((2ull << lane) - 1ull));
+            const int32_t d = upto ? lane - (63 - __clzll(upto)) : lane + carry;      // entries of the run in front of e
+            pos = d % kMaxRun;
+            const uint64_t after = lane == 63 ? 0ull : (b1 & ~((2ull << lane) - 1ull));
+            const int32_t run_end = after ? __ffsll((long long)after) - 1 : (b2 ? 64 + __ffsll((long long)b2) - 1 : 72);
+            const int32_t len = run_end - (lane - pos);
+            return len < kMaxRun ? len : kMaxRun;
+        };
+
+        if (staged) {
+            for (int32_t t0 = wb; t0 < we; t0 += kBuildThreads) {
+                const int32_t e = t0 + tid;
+                int pos;
+                const int L = staged_piece(e, t0 + wv * 64, pos);
+                if (e < we) {
+                    piece_s[e - wb] = (uint8_t)(pos | ((L - 1) << 3));
+                    if (pos == 0) atomicAdd(&cnt[L - 1], 1);      // a count: the order of the adds is irrelevant
+                }
+            }
+        } else {
+            for (int32_t e = wb + tid; e < we; e += kBuildThreads) {
+                int pos;
+                const int L = natural_piece(e, pos);
+                if (pos == 0) atomicAdd(&cnt[L - 1], 1);
+            }
         }
         __syncthreads();
         if (tid == 0) {
@@ -204,8 +246,14 @@ __global__ __launch_bounds__(kBuildThreads) void build_schedule(const int32_t* _
             const int32_t e = t0 + tid;
             int L = 0;                                    // class of the piece that starts at e (0: none)
             if (e < we) {
-                int pos;
-                const int nat = natural_piece(e, pos);
+                int pos, nat;
+                if (staged) {
+                    const int pl = piece_s[e - wb];
+                    pos = pl & 7;
+                    nat = (pl >> 3) + 1;
+                } else {
+                    nat = natural_piece(e, pos);
+                }
                 if (demote[nat - 1]) L = 1;
                 else if (pos == 0) L = nat;
             }
