@@ -349,8 +349,16 @@ int launch_build_schedule(const gcoo_matrix* h, char* scratch, hipStream_t s)
     }
     if (h->g > 0 && h->has_share) {
         const size_t bitmap_bytes = (size_t)((h->k + 31) / 32) * 4;
+        // the bitmaps of the groups, one workgroup each, where they fit the second sort buffer (free by now: 12 bytes
+        // per entry); otherwise one workgroup per super-group marks all its entries itself
+        uint32_t* parts = nullptr;
+        if ((uint64_t)h->g * bitmap_bytes <= (uint64_t)h->nnz * 12u) {
+            parts = reinterpret_cast<uint32_t*>(scratch + h->L.tmp_cols);
+            gcoo::share_mark_groups<<<dim3((unsigned)h->g), dim3(gcoo::kShareBuildThreads), bitmap_bytes, s>>>(h->gIdxes(), h->cols(), h->k, parts);
+            HIP_TRY(hipGetLastError());
+        }
         gcoo::share_union<<<dim3((unsigned)h->share_nq()), dim3(gcoo::kShareBuildThreads), bitmap_bytes, s>>>(
-            h->gIdxes(), h->cols(), h->g, h->k, gcoo::kShareW, h->share_ucols(), h->share_ucount(), share_alloc);
+            h->gIdxes(), h->cols(), h->g, h->k, gcoo::kShareW, h->share_ucols(), h->share_ucount(), share_alloc, parts);
         HIP_TRY(hipGetLastError());
         // LDS of share_fill: its per-band tables and room for the columns of a group of up to twice the mean size
         // (between 8 K and 28 K entries: two workgroups share a compute unit up to 80 KB each)

@@ -39,20 +39,9 @@ __device__ __forceinline__ int32_t share_block_scan(int32_t mine, int32_t* wsum,
 // `ucols` that starts at the super-group's first entry (it cannot be longer than its entries).
 // Dynamic LDS: ceil(k/32) words.
 // ---------------------------------------------------------------------------------------------
-__global__ __launch_bounds__(kShareBuildThreads) void share_union(const int32_t* __restrict__ gIdxes, const int32_t* __restrict__ cols,
-                                                               int64_t g, int64_t k, int32_t W,
-                                                               int32_t* __restrict__ ucols, int32_t* __restrict__ ucount,
-                                                               uint32_t* __restrict__ zeroed = nullptr)
+// Marks the columns of the entries [e0, e1) in the bitmap `bits` (LDS, nbw words, cleared here).
+__device__ __forceinline__ void share_mark(const int32_t* __restrict__ cols, int32_t e0, int32_t e1, uint32_t* bits, int32_t nbw)
 {
-    if (zeroed && blockIdx.x == 0 && threadIdx.x == 0) *zeroed = 0u;   // a counter of the kernel that runs next
-    extern __shared__ uint32_t share_union_lds[];
-    __shared__ int32_t wsum[kShareBuildWaves];
-    __shared__ int32_t total_s;
-    const int32_t nbw = (int32_t)((k + 31) / 32);
-    uint32_t* bits = share_union_lds;
-    const int64_t Q = blockIdx.x;
-    const int64_t q0 = Q * W, q1 = (q0 + W < g) ? q0 + W : g;
-    const int32_t e0 = gIdxes[q0], e1 = gIdxes[q1];
     for (int32_t i = threadIdx.x; i < nbw; i += kShareBuildThreads) bits[i] = 0u;
     __syncthreads();
     // A thread takes eight consecutive entries at a time and collects the bits of one bitmap word in a register
@@ -78,6 +67,48 @@ __global__ __launch_bounds__(kShareBuildThreads) void share_union(const int32_t*
         if (acc) atomicOr(&bits[word], acc);
     }
     __syncthreads();
+}
+
+// First half of share_union spread over the machine: one workgroup per group writes the bitmap of the group's
+// columns to parts[q * nbw ..] (whole, zero words included, so the array needs no clearing).  A super-group of
+// 50 000 entries keeps one workgroup busy for 30 us; its eight groups side by side take a fifth of that.
+__global__ __launch_bounds__(kShareBuildThreads) void share_mark_groups(const int32_t* __restrict__ gIdxes, const int32_t* __restrict__ cols,
+                                                                       int64_t k, uint32_t* __restrict__ parts)
+{
+    extern __shared__ uint32_t share_union_lds[];
+    const int32_t nbw = (int32_t)((k + 31) / 32);
+    const int64_t q = blockIdx.x;
+    share_mark(cols, gIdxes[q], gIdxes[q + 1], share_union_lds, nbw);
+    uint32_t* out = parts + q * nbw;
+    for (int32_t i = threadIdx.x; i < nbw; i += kShareBuildThreads) out[i] = share_union_lds[i];
+}
+
+// `parts` != nullptr: the bitmaps of the groups are there (share_mark_groups) and are ORed together instead of
+// marking the entries here.
+__global__ __launch_bounds__(kShareBuildThreads) void share_union(const int32_t* __restrict__ gIdxes, const int32_t* __restrict__ cols,
+                                                               int64_t g, int64_t k, int32_t W,
+                                                               int32_t* __restrict__ ucols, int32_t* __restrict__ ucount,
+                                                               uint32_t* __restrict__ zeroed, const uint32_t* __restrict__ parts)
+{
+    if (zeroed && blockIdx.x == 0 && threadIdx.x == 0) *zeroed = 0u;   // a counter of the kernel that runs next
+    extern __shared__ uint32_t share_union_lds[];
+    __shared__ int32_t wsum[kShareBuildWaves];
+    __shared__ int32_t total_s;
+    const int32_t nbw = (int32_t)((k + 31) / 32);
+    uint32_t* bits = share_union_lds;
+    const int64_t Q = blockIdx.x;
+    const int64_t q0 = Q * W, q1 = (q0 + W < g) ? q0 + W : g;
+    const int32_t e0 = gIdxes[q0], e1 = gIdxes[q1];
+    if (parts) {
+        for (int32_t i = threadIdx.x; i < nbw; i += kShareBuildThreads) {
+            uint32_t b = 0u;
+            for (int64_t q = q0; q < q1; ++q) b |= parts[q * nbw + i];
+            bits[i] = b;
+        }
+        __syncthreads();
+    } else {
+        share_mark(cols, e0, e1, bits, nbw);
+    }
     // thread t owns the words [t*per, (t+1)*per)
     const int32_t per = (nbw + kShareBuildThreads - 1) / kShareBuildThreads;
     const int32_t w0 = (int32_t)threadIdx.x * per, w1 = (w0 + per < nbw) ? w0 + per : nbw;
@@ -96,21 +127,40 @@ __global__ __launch_bounds__(kShareBuildThreads) void share_union(const int32_t*
 }
 
 
-// Where entry i of a (group, band) that spans [s, e) stands in its run.  A run is a maximal stretch of one
-// column, cut into stretches of kShareRunCap from its first entry.  Writes the entry's place in its stretch
-// and the stretch's length.
-// `col_at(i)` = column of entry i.
+// Where the entries of a (group, band) that spans [s, e) stand in their runs.  A run is a maximal stretch of one
+// column, cut into stretches of kShareRunCap from its first entry; *x = the entry's place in its stretch, *len = the
+// stretch's length.  `col_at(i)` = column of entry i.
+// share_place_wave does it for the 64 entries cur .. cur+63 of the band at once (lane l: entry cur + l; every lane of the wave must
+// call it), without a walk along the run per entry: the lanes mark where a run starts, a ballot gives every lane the
+// start and the end of its run inside the 64, lane 0 alone walks back to the start of a run that began before them,
+// and 32 lanes look at the 32 entries behind (a stretch ends at most kShareRunCap - 1 entries after one of its entries).
 template <typename ColAt>
-__device__ __forceinline__ void share_place(ColAt col_at, int32_t s, int32_t e, int32_t i, int32_t* x, int32_t* len)
+__device__ __forceinline__ void share_place_wave(ColAt col_at, int32_t s, int32_t e, int32_t cur, int lane, int32_t* x, int32_t* len)
 {
-    const int32_t c = col_at(i);
-    int32_t rs = i;
-    while (rs > s && col_at(rs - 1) == c) --rs;
-    rs += (i - rs) / kShareRunCap * kShareRunCap;
-    int32_t re = i + 1;
-    while (re < e && re < rs + kShareRunCap && col_at(re) == c) ++re;
-    *x = i - rs;
-    *len = re - rs;
+    static_assert(kShareRunCap == 32, "the look-ahead below is 32 entries");
+    const int32_t i = cur + lane;
+    const bool valid = i < e;
+    const int32_t c = valid ? col_at(i) : 0;
+    const bool start = !valid || i == s || col_at(i - 1) != c;
+    const uint64_t b1 = __ballot(start);
+    const int32_t i2 = cur + 64 + lane;
+    const bool start2 = lane < 32 && (i2 >= e || col_at(i2) != col_at(i2 - 1));
+    const uint64_t b2 = __ballot(start2);
+    int32_t carry = 0;                                // entries of the first run in front of cur
+    if ((b1 & 1ull) == 0) {                           // (then cur < e and cur > s)
+        if (lane == 0) {
+            while (cur - 1 - carry >= s && col_at(cur - 1 - carry) == c) ++carry;
+        }
+        carry = __shfl(carry, 0, 64);
+    }
+    const uint64_t upto = b1 & (lane == 63 ? ~0ull : ((2ull << lane) - 1ull));
+    const int32_t d = upto ? lane - (63 - __clzll(upto)) : lane + carry;     // entries of the run in front of entry i
+    const int32_t pos = d % kShareRunCap;
+    const uint64_t after = lane == 63 ? 0ull : (b1 & ~((2ull << lane) - 1ull));
+    const int32_t run_end = after ? __ffsll((long long)after) - 1 : (b2 ? 64 + __ffsll((long long)b2) - 1 : 96);
+    const int32_t n = run_end - (lane - pos);
+    *x = pos;
+    *len = n < kShareRunCap ? n : kShareRunCap;
 }
 
 typedef uint32_t share_u32x4 __attribute__((ext_vector_type(4)));
@@ -182,10 +232,12 @@ __global__ __launch_bounds__(kShareBuildThreads) void share_fill(const int32_t* 
     for (int32_t b = wv; b < NB; b += kShareBuildWaves) {
         const int32_t s = bstart[b], e = bstart[b + 1];
         int32_t members = 0, singles = 0;
-        for (int32_t i = s + lane; i < e; i += 64) {
+        for (int32_t cur = s; cur < e; cur += 64) {
             int32_t x, len;
-            share_place(col_at, s, e, i, &x, &len);
-            if (x < (len & ~3)) ++members; else ++singles;
+            share_place_wave(col_at, s, e, cur, lane, &x, &len);
+            if (cur + lane < e) {
+                if (x < (len & ~3)) ++members; else ++singles;
+            }
         }
 #pragma unroll
         for (int d = 32; d >= 1; d >>= 1) {
@@ -240,10 +292,8 @@ __global__ __launch_bounds__(kShareBuildThreads) void share_fill(const int32_t* 
             const int32_t i = cur + lane;
             const bool live = i < e;
             int32_t x = 0, len = 0, col = 0;
-            if (live) {
-                share_place(col_at, s, e, i, &x, &len);
-                col = col_at(i);
-            }
+            share_place_wave(col_at, s, e, cur, lane, &x, &len);
+            if (live) col = col_at(i);
             const bool member = live && x < (len & ~3);
             const bool single = live && !member;
             const uint64_t mm = __ballot(member), sm = __ballot(single);

@@ -425,6 +425,20 @@ def test_share_variant_skewed_rows_and_diagonal(share_always, p):
     assert err < 2e-6
 
 
+def test_share_schedule_of_a_very_sparse_matrix(share_always):
+    """So few entries that the per-group column bitmaps of the conversion do not fit its scratch area: the column
+    lists are then made by one workgroup per super-group.  Schedule against the model, product against the oracle."""
+    m, k, p = 3000, 40000, 24
+    w = workloads.uniform_random(m, k, 64, 1.0 - 300.0 / (m * k), seed=77)
+    assert ((m + p - 1) // p) * ((k + 31) // 32) * 4 > 12 * w.nnz
+    _say(f"share variant, very sparse: nnz={w.nnz}")
+    A = binding.gcoo_from_csr(w.m, w.k, w.row_ptr, w.col_idx, w.vals, p, device=DEV)
+    G = orc.gcoo_from_csr(w.m, w.k, w.row_ptr, w.col_idx, w.vals, p)
+    _check_share_schedule(A, m, k, p, G)
+    err, _, _ = _check_product(w, p, binding.VARIANT_SHARE, A=A)
+    assert err < 2e-6
+
+
 def test_share_variant_repeated_coordinates_and_strides(share_always):
     from tests.test_share_model import repeated_coordinates_workload
     m, k, N, row_ptr, col_idx, vals, B = repeated_coordinates_workload()
