@@ -174,8 +174,16 @@ __global__ __launch_bounds__(WAVES * kWave) void sort_groups_by_col_digit(
 
     for (int i = tid; i < WAVES * 256; i += WAVES * kWave) (&slot_of[0][0])[i] = 0;
     __syncthreads();
-    for (int32_t e = pb + lane; e < pe; e += kWave)
-        atomicAdd(&slot_of[wv][((uint32_t)in_range(src_cols[e]) >> shift) & 255u], 1);   // counts only: order-free
+    // (four loads in flight per lane: a wave's part is some thirty tiles, and one load at a time made the pass a chain
+    // of memory latencies)
+    for (int32_t e = pb + lane; e < pe; e += 4 * kWave) {
+        int32_t c[4];
+#pragma unroll
+        for (int u = 0; u < 4; ++u) c[u] = e + u * kWave < pe ? src_cols[e + u * kWave] : 0;
+#pragma unroll
+        for (int u = 0; u < 4; ++u)
+            if (e + u * kWave < pe) atomicAdd(&slot_of[wv][((uint32_t)in_range(c[u]) >> shift) & 255u], 1);   // counts only: order-free
+    }
     __syncthreads();
     if (tid < 256) {
         int32_t run = 0;
@@ -213,14 +221,25 @@ __global__ __launch_bounds__(WAVES * kWave) void sort_groups_by_col_digit(
     const int64_t r_lo = q * p;
     const int64_t r_hi = (r_lo + p < m) ? r_lo + p : m;
     const uint64_t lt = lanemask_lt();
+    // the loads of the next tile are issued before this tile is ranked and stored
+    int32_t col_next = 0, row_next = 0;
+    float val_next = 0.0f;
+    auto request = [&](int32_t t) {
+        const int32_t e = t + lane;
+        if (e < pe) {
+            col_next = src_cols[e];
+            val_next = src_vals[e];
+            if (!FIRST) row_next = src_rows[e];
+        }
+    };
+    request(pb);
     for (int32_t t0 = pb; t0 < pe; t0 += kWave) {
         const int32_t e = t0 + lane;
         const bool act = e < pe;
-        int32_t col = 0, row = 0;
-        float val = 0.0f;
+        int32_t col = col_next, row = row_next;
+        float val = val_next;
+        if (t0 + kWave < pe) request(t0 + kWave);
         if (act) {
-            col = src_cols[e];
-            val = src_vals[e];
             if (FIRST) {
                 const int32_t c = in_range(col);
                 if (c != col) { *bad_col = 1u; col = c; }
@@ -231,8 +250,6 @@ __global__ __launch_bounds__(WAVES * kWave) void sort_groups_by_col_digit(
                     if (rp_s[mid] <= e) lo = mid; else hi = mid;
                 }
                 row = (int32_t)r_lo + lo;
-            } else {
-                row = src_rows[e];
             }
         }
         const uint32_t d = ((uint32_t)col >> shift) & 255u;
