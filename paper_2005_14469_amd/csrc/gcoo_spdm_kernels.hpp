@@ -5,8 +5,8 @@
 // wave-uniform data: the wave streams them from global memory into LDS with coalesced loads, far
 // ahead of their use, and reads them back with broadcast reads (the staging in shared memory of
 // Algorithm 2); the B row segment of a run of entries is one coalesced vector load per lane, and
-// all entries of the run multiply out of those registers (Section 3.3, "high
-// computation-to-memory ratio").  The entries are read from the run
+// all entries of the run multiply out of those registers (the reuse of a fetched value of B that
+// Section 3.3 builds the kernel around).  The entries are read from the run
 // schedule (gcoo_sched.hpp), in which runs are sorted by length, so the code for a run of L
 // entries is straight-line: no "is the next column the same" test at run time.
 #pragma once
