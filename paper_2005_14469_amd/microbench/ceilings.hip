@@ -201,6 +201,84 @@ __global__ __launch_bounds__(512) void issue(int iters, float* out)
     if (s == 123.456f) out[0] = s;
 }
 
+#define VALU_BODY_0 \
+        "v_fmac_f32 v8, v5, v2\n\tv_fmac_f32 v9, v6, v3\n\tv_fmac_f32 v10, v7, v0\n\tv_fmac_f32 v11, v4, v1\n\t" \
+        "v_fmac_f32 v12, v5, v2\n\tv_fmac_f32 v13, v6, v3\n\tv_fmac_f32 v14, v7, v0\n\tv_fmac_f32 v15, v4, v1\n\t" \
+        "v_fmac_f32 v16, v5, v2\n\tv_fmac_f32 v17, v6, v3\n\tv_fmac_f32 v18, v7, v0\n\tv_fmac_f32 v19, v4, v1\n\t" \
+        "v_fmac_f32 v20, v5, v2\n\tv_fmac_f32 v21, v6, v3\n\tv_fmac_f32 v22, v7, v0\n\tv_fmac_f32 v23, v4, v1\n\t" \
+        "v_fmac_f32 v24, v5, v2\n\tv_fmac_f32 v25, v6, v3\n\tv_fmac_f32 v26, v7, v0\n\tv_fmac_f32 v27, v4, v1\n\t" \
+        "v_fmac_f32 v28, v5, v2\n\tv_fmac_f32 v29, v6, v3\n\tv_fmac_f32 v30, v7, v0\n\tv_fmac_f32 v31, v4, v1\n\t" \
+        "v_fmac_f32 v32, v5, v2\n\tv_fmac_f32 v33, v6, v3\n\tv_fmac_f32 v34, v7, v0\n\tv_fmac_f32 v35, v4, v1\n\t" \
+        "v_fmac_f32 v36, v5, v2\n\tv_fmac_f32 v37, v6, v3\n\tv_fmac_f32 v38, v7, v0\n\tv_fmac_f32 v39, v4, v1\n\t" \
+        "v_fmac_f32 v40, v5, v2\n\tv_fmac_f32 v41, v6, v3\n\tv_fmac_f32 v42, v7, v0\n\tv_fmac_f32 v43, v4, v1\n\t" \
+        "v_fmac_f32 v44, v5, v2\n\tv_fmac_f32 v45, v6, v3\n\tv_fmac_f32 v46, v7, v0\n\tv_fmac_f32 v47, v4, v1\n\t" \
+        "v_fmac_f32 v48, v5, v2\n\tv_fmac_f32 v49, v6, v3\n\tv_fmac_f32 v50, v7, v0\n\tv_fmac_f32 v51, v4, v1\n\t" \
+        "v_fmac_f32 v52, v5, v2\n\tv_fmac_f32 v53, v6, v3\n\tv_fmac_f32 v54, v7, v0\n\tv_fmac_f32 v55, v4, v1\n\t" \
+        "v_fmac_f32 v56, v5, v2\n\tv_fmac_f32 v57, v6, v3\n\tv_fmac_f32 v58, v7, v0\n\tv_fmac_f32 v59, v4, v1\n\t" \
+        "v_fmac_f32 v60, v5, v2\n\tv_fmac_f32 v61, v6, v3\n\tv_fmac_f32 v62, v7, v0\n\tv_fmac_f32 v63, v4, v1\n\t" \
+        "v_fmac_f32 v64, v5, v2\n\tv_fmac_f32 v65, v6, v3\n\tv_fmac_f32 v66, v7, v0\n\tv_fmac_f32 v67, v4, v1\n\t" \
+        "v_fmac_f32 v68, v5, v2\n\tv_fmac_f32 v69, v6, v3\n\tv_fmac_f32 v70, v7, v0\n\tv_fmac_f32 v71, v4, v1\n\t"
+#define VALU_BODY_1 \
+        "v_fmac_f32 v8, v4, v0\n\tv_fmac_f32 v9, v5, v1\n\tv_fmac_f32 v10, v6, v2\n\tv_fmac_f32 v11, v7, v3\n\t" \
+        "v_fmac_f32 v12, v4, v0\n\tv_fmac_f32 v13, v5, v1\n\tv_fmac_f32 v14, v6, v2\n\tv_fmac_f32 v15, v7, v3\n\t" \
+        "v_fmac_f32 v16, v4, v0\n\tv_fmac_f32 v17, v5, v1\n\tv_fmac_f32 v18, v6, v2\n\tv_fmac_f32 v19, v7, v3\n\t" \
+        "v_fmac_f32 v20, v4, v0\n\tv_fmac_f32 v21, v5, v1\n\tv_fmac_f32 v22, v6, v2\n\tv_fmac_f32 v23, v7, v3\n\t" \
+        "v_fmac_f32 v24, v4, v0\n\tv_fmac_f32 v25, v5, v1\n\tv_fmac_f32 v26, v6, v2\n\tv_fmac_f32 v27, v7, v3\n\t" \
+        "v_fmac_f32 v28, v4, v0\n\tv_fmac_f32 v29, v5, v1\n\tv_fmac_f32 v30, v6, v2\n\tv_fmac_f32 v31, v7, v3\n\t" \
+        "v_fmac_f32 v32, v4, v0\n\tv_fmac_f32 v33, v5, v1\n\tv_fmac_f32 v34, v6, v2\n\tv_fmac_f32 v35, v7, v3\n\t" \
+        "v_fmac_f32 v36, v4, v0\n\tv_fmac_f32 v37, v5, v1\n\tv_fmac_f32 v38, v6, v2\n\tv_fmac_f32 v39, v7, v3\n\t" \
+        "v_fmac_f32 v40, v4, v0\n\tv_fmac_f32 v41, v5, v1\n\tv_fmac_f32 v42, v6, v2\n\tv_fmac_f32 v43, v7, v3\n\t" \
+        "v_fmac_f32 v44, v4, v0\n\tv_fmac_f32 v45, v5, v1\n\tv_fmac_f32 v46, v6, v2\n\tv_fmac_f32 v47, v7, v3\n\t" \
+        "v_fmac_f32 v48, v4, v0\n\tv_fmac_f32 v49, v5, v1\n\tv_fmac_f32 v50, v6, v2\n\tv_fmac_f32 v51, v7, v3\n\t" \
+        "v_fmac_f32 v52, v4, v0\n\tv_fmac_f32 v53, v5, v1\n\tv_fmac_f32 v54, v6, v2\n\tv_fmac_f32 v55, v7, v3\n\t" \
+        "v_fmac_f32 v56, v4, v0\n\tv_fmac_f32 v57, v5, v1\n\tv_fmac_f32 v58, v6, v2\n\tv_fmac_f32 v59, v7, v3\n\t" \
+        "v_fmac_f32 v60, v4, v0\n\tv_fmac_f32 v61, v5, v1\n\tv_fmac_f32 v62, v6, v2\n\tv_fmac_f32 v63, v7, v3\n\t" \
+        "v_fmac_f32 v64, v4, v0\n\tv_fmac_f32 v65, v5, v1\n\tv_fmac_f32 v66, v6, v2\n\tv_fmac_f32 v67, v7, v3\n\t" \
+        "v_fmac_f32 v68, v4, v0\n\tv_fmac_f32 v69, v5, v1\n\tv_fmac_f32 v70, v6, v2\n\tv_fmac_f32 v71, v7, v3\n\t"
+#define VALU_BODY_2 \
+        "v_fmac_f32 v8, v5, v1\n\tv_fmac_f32 v9, v6, v2\n\tv_fmac_f32 v10, v7, v3\n\tv_fmac_f32 v11, v4, v0\n\t" \
+        "v_fmac_f32 v12, v5, v1\n\tv_fmac_f32 v13, v6, v2\n\tv_fmac_f32 v14, v7, v3\n\tv_fmac_f32 v15, v4, v0\n\t" \
+        "v_fmac_f32 v16, v5, v1\n\tv_fmac_f32 v17, v6, v2\n\tv_fmac_f32 v18, v7, v3\n\tv_fmac_f32 v19, v4, v0\n\t" \
+        "v_fmac_f32 v20, v5, v1\n\tv_fmac_f32 v21, v6, v2\n\tv_fmac_f32 v22, v7, v3\n\tv_fmac_f32 v23, v4, v0\n\t" \
+        "v_fmac_f32 v24, v5, v1\n\tv_fmac_f32 v25, v6, v2\n\tv_fmac_f32 v26, v7, v3\n\tv_fmac_f32 v27, v4, v0\n\t" \
+        "v_fmac_f32 v28, v5, v1\n\tv_fmac_f32 v29, v6, v2\n\tv_fmac_f32 v30, v7, v3\n\tv_fmac_f32 v31, v4, v0\n\t" \
+        "v_fmac_f32 v32, v5, v1\n\tv_fmac_f32 v33, v6, v2\n\tv_fmac_f32 v34, v7, v3\n\tv_fmac_f32 v35, v4, v0\n\t" \
+        "v_fmac_f32 v36, v5, v1\n\tv_fmac_f32 v37, v6, v2\n\tv_fmac_f32 v38, v7, v3\n\tv_fmac_f32 v39, v4, v0\n\t" \
+        "v_fmac_f32 v40, v5, v1\n\tv_fmac_f32 v41, v6, v2\n\tv_fmac_f32 v42, v7, v3\n\tv_fmac_f32 v43, v4, v0\n\t" \
+        "v_fmac_f32 v44, v5, v1\n\tv_fmac_f32 v45, v6, v2\n\tv_fmac_f32 v46, v7, v3\n\tv_fmac_f32 v47, v4, v0\n\t" \
+        "v_fmac_f32 v48, v5, v1\n\tv_fmac_f32 v49, v6, v2\n\tv_fmac_f32 v50, v7, v3\n\tv_fmac_f32 v51, v4, v0\n\t" \
+        "v_fmac_f32 v52, v5, v1\n\tv_fmac_f32 v53, v6, v2\n\tv_fmac_f32 v54, v7, v3\n\tv_fmac_f32 v55, v4, v0\n\t" \
+        "v_fmac_f32 v56, v5, v1\n\tv_fmac_f32 v57, v6, v2\n\tv_fmac_f32 v58, v7, v3\n\tv_fmac_f32 v59, v4, v0\n\t" \
+        "v_fmac_f32 v60, v5, v1\n\tv_fmac_f32 v61, v6, v2\n\tv_fmac_f32 v62, v7, v3\n\tv_fmac_f32 v63, v4, v0\n\t" \
+        "v_fmac_f32 v64, v5, v1\n\tv_fmac_f32 v65, v6, v2\n\tv_fmac_f32 v66, v7, v3\n\tv_fmac_f32 v67, v4, v0\n\t" \
+        "v_fmac_f32 v68, v5, v1\n\tv_fmac_f32 v69, v6, v2\n\tv_fmac_f32 v70, v7, v3\n\tv_fmac_f32 v71, v4, v0\n\t"
+// ---------------------------------------------------------------- 2b. VALU issue rate against waves per SIMD and register banks
+// 64 independent v_fmac_f32 per turn in 72 registers; workgroups of four waves (one per SIMD), W of them per compute
+// unit (the launch asks for 1/W of the LDS), so W waves share a SIMD.  The vector registers sit in four banks
+// (register number mod 4).  KIND 0: the three operands of every instruction in three banks; 1: all in one bank;
+// 2: the two sources in one bank, the destination in another.
+#define VALU_KERNEL(KIND)                                                                                       \
+    __global__ __launch_bounds__(256) void valu##KIND(int iters, float* out)                                    \
+    {                                                                                                           \
+        float r = 0.0f;                                                                                         \
+        asm volatile(                                                                                           \
+            "v_mov_b32 v0, 1.0\n\tv_mov_b32 v1, 1.0\n\tv_mov_b32 v2, 1.0\n\tv_mov_b32 v3, 1.0\n\t"                   \
+            "v_mov_b32 v4, 0.5\n\tv_mov_b32 v5, 0.5\n\tv_mov_b32 v6, 0.5\n\tv_mov_b32 v7, 0.5\n\t"                   \
+            "s_mov_b32 s20, %[iters]\n"                                                                         \
+            ".Lv_loop_%=:\n\t" VALU_BODY_##KIND                                                                 \
+            "s_sub_u32 s20, s20, 1\n\t"                                                                         \
+            "s_cmp_lg_u32 s20, 0\n\t"                                                                           \
+            "s_cbranch_scc1 .Lv_loop_%=\n\t"                                                                    \
+            "v_mov_b32 %[r], v8\n\t"                                                                            \
+            : [r] "=v"(r)                                                                                       \
+            : [iters] "s"(iters)                                                                                \
+            : "scc", "s20", "v0", "v1", "v2", "v3", "v4", "v5", "v6", "v7", "v8", "v9", "v10", "v11", "v12", "v13", "v14", "v15", "v16", "v17", "v18", "v19", "v20", "v21", "v22", "v23", "v24", "v25", "v26", "v27", "v28", "v29", "v30", "v31", "v32", "v33", "v34", "v35", "v36", "v37", "v38", "v39", "v40", "v41", "v42", "v43", "v44", "v45", "v46", "v47", "v48", "v49", "v50", "v51", "v52", "v53", "v54", "v55", "v56", "v57", "v58", "v59", "v60", "v61", "v62", "v63", "v64", "v65", "v66", "v67", "v68", "v69", "v70", "v71");                                                   \
+        if (r == 123.456f) out[0] = r;                                                                          \
+    }
+VALU_KERNEL(0)
+VALU_KERNEL(1)
+VALU_KERNEL(2)
+
 // ---------------------------------------------------------------- 3. bands of a B tile straight to LDS
 // Workgroup = 8 waves; band b = 48 rows picked in ascending order from the tile's k rows (stride `gap` on
 // average), six rows per wave, to buffer b % 3; one barrier per band in front of which the loads of the band
@@ -340,6 +418,25 @@ int main()
             fflush(stdout);
         }
     }
+    // 2b
+    CK(hipFuncSetAttribute((const void*)valu0, hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024));
+    CK(hipFuncSetAttribute((const void*)valu1, hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024));
+    CK(hipFuncSetAttribute((const void*)valu2, hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024));
+    for (int kind = 0; kind < 3; ++kind)
+        for (int waves : {1, 2, 4}) {
+            const int iters = 4000;
+            const size_t lds = (size_t)(156 * 1024) / waves;        // so that exactly `waves` workgroups fit a compute unit
+            const float ms = timed([&] {
+                if (kind == 0) valu0<<<kCUs * waves, 256, lds>>>(iters, out);
+                else if (kind == 1) valu1<<<kCUs * waves, 256, lds>>>(iters, out);
+                else valu2<<<kCUs * waves, 256, lds>>>(iters, out);
+            }, 3);
+            const double per_simd = (double)waves * 64.0 * iters / (ms * 1e6);       // v_fmac_f32 per ns and SIMD
+            const char* names[3] = {"operands in three register banks", "all three operands in one bank", "both sources in one bank"};
+            printf("valu   %d waves per SIMD, independent v_fmac_f32, %s: %.3f ms, %.2f instructions per ns and SIMD, %.1f TFLOP/s for the chip\n",
+                   waves, names[kind], ms, per_simd, per_simd * 1024 * 128.0 * 1e-3);
+            fflush(stdout);
+        }
     // 3 and 4 read a B of 8000 x 8000 floats
     const int k = 8000, ldb = 8000;
     float* B;
