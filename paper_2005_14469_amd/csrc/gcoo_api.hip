@@ -122,7 +122,7 @@ int dense_vec_width(const float* A, int64_t lda, int64_t k)
     return (k % 4 == 0 && lda % 4 == 0 && reinterpret_cast<uintptr_t>(A) % 16 == 0) ? 4 : 1;
 }
 
-// The share schedule costs conversion time (0.05 ms at 320 000 entries) and memory, so it is built only where
+// The share schedule costs conversion time (0.04 ms at 320 000 entries) and memory, so it is built only where
 // the workgroup-shared kernel is the one gcoo_spdm() will pick.  Measured on MI355X with uniform random square
 // matrices (n = 4000 .. 14000, density 0.1 % .. 10 %, N = n), against the register kernel at its best group height:
 // the workgroup-shared kernel wins from 3500 columns on at 0.8 % density or more (n = 8000: by 10 .. 30 % between
