@@ -201,6 +201,72 @@ __global__ __launch_bounds__(512) void issue(int iters, float* out)
     if (s == 123.456f) out[0] = s;
 }
 
+// ---------------------------------------------------------------- 2a. the singles sequence with 128 registers per wave
+// The same per-entry instructions as issue<0>, with the partial sums of 20 rows (+ the sink row) x 4 columns in
+// v[44:127] and the working registers below them, so that four waves fit a SIMD (workgroups of 8 waves, two per compute
+// unit, or one): does the sequence issue faster when a SIMD has four waves to choose from instead of two?
+#define S16_DPP(i) " row_newbcast:" #i " row_mask:0xf bank_mask:0xf\n\t"
+#define S16_ADDR(dst, src, i) "v_add_u32_dpp " #dst ", " #src ", v28" S16_DPP(i)
+#define S16_ROWS(reg, i) "v_readlane_b32 " #reg ", v25, " #i "\n\t"
+#define S16_FMAC(i, rows, b0, b1, b2, b3)                   \
+    "s_set_gpr_idx_on " #rows ", gpr_idx(SRC2,DST)\n\t"      \
+    "v_fmac_f32_dpp v44, v24, " #b0 S16_DPP(i)               \
+    "v_fmac_f32_dpp v65, v24, " #b1 S16_DPP(i)               \
+    "v_fmac_f32_dpp v86, v24, " #b2 S16_DPP(i)               \
+    "v_fmac_f32_dpp v107, v24, " #b3 S16_DPP(i)              \
+    "s_lshr_b32 " #rows ", " #rows ", 8\n\t"
+#define S16_STEP(i, rows, set, b0, b1, b2, b3, ad)           \
+    "s_waitcnt lgkmcnt(3)\n\t" S16_FMAC(i, rows, b0, b1, b2, b3) "ds_read_b128 v[" #b0 ":" #b3 "], " #ad "\n\t"
+#define S16_GROUP(src, n0, n1, n2, n3, nextrows, i0, i1, i2, i3, rows)                                        \
+    S16_ADDR(v20, src, n0) S16_ADDR(v21, src, n1) S16_ADDR(v22, src, n2) S16_ADDR(v23, src, n3) nextrows      \
+    "s_waitcnt lgkmcnt(3)\n\t" S16_FMAC(i0, rows, v4, v5, v6, v7) "ds_read_b128 v[4:7], v20\n\t"             \
+    "s_waitcnt lgkmcnt(3)\n\t" S16_FMAC(i1, rows, v8, v9, v10, v11) "ds_read_b128 v[8:11], v21\n\t"          \
+    "s_waitcnt lgkmcnt(3)\n\t" S16_FMAC(i2, rows, v12, v13, v14, v15) "ds_read_b128 v[12:15], v22\n\t"       \
+    "s_waitcnt lgkmcnt(3)\n\t" S16_FMAC(i3, rows, v16, v17, v18, v19) "ds_read_b128 v[16:19], v23\n\t"       \
+    "s_set_gpr_idx_off\n\t"
+__global__ __launch_bounds__(512) void issue128(int iters, float* out)
+{
+    extern __shared__ __attribute__((aligned(16))) float lds[];
+    const int lane = threadIdx.x & 63;
+    for (int i = threadIdx.x; i < 12288; i += 512) lds[i] = 1.0f + (float)(i & 7);
+    __syncthreads();
+    const unsigned rec = lane & 15;
+    const float value = 0.5f;
+    const unsigned g4 = rec & ~3u;
+    const unsigned rows = ((g4 * 3) % 20) | (((g4 * 3 + 7) % 20) << 8) | (((g4 * 3 + 11) % 20) << 16) | (((g4 * 3 + 17) % 20) << 24);
+    const unsigned off = ((rec * 11) % 48) * 1024u;
+    const unsigned l16 = lane * 16u;
+    float r = 0.0f;
+    asm volatile(
+        "v_mov_b32 v24, %[val]\n\t"
+        "v_mov_b32 v25, %[rows]\n\t"
+        "v_mov_b32 v26, %[off]\n\t"
+        "v_mov_b32 v27, %[off]\n\t"
+        "v_mov_b32 v28, %[l16]\n\t"
+        "s_mov_b32 s74, %[iters]\n"
+        ".Lq_loop_%=:\n\t"
+        S16_ROWS(s70, 0)
+        S16_ADDR(v20, v26, 0) S16_ADDR(v21, v26, 1) S16_ADDR(v22, v26, 2) S16_ADDR(v23, v26, 3)
+        "ds_read_b128 v[4:7], v20\n\tds_read_b128 v[8:11], v21\n\tds_read_b128 v[12:15], v22\n\tds_read_b128 v[16:19], v23\n\t"
+        "s_sub_u32 s73, s73, 1\n\ts_nop 0\n\t"
+        S16_GROUP(v26, 4, 5, 6, 7, S16_ROWS(s86, 4), 0, 1, 2, 3, s70)
+        "s_sub_u32 s73, s73, 1\n\ts_nop 0\n\t"
+        S16_GROUP(v26, 8, 9, 10, 11, S16_ROWS(s70, 8), 4, 5, 6, 7, s86)
+        "s_sub_u32 s73, s73, 1\n\ts_nop 0\n\t"
+        S16_GROUP(v26, 12, 13, 14, 15, S16_ROWS(s86, 12), 8, 9, 10, 11, s70)
+        "s_sub_u32 s73, s73, 1\n\ts_nop 0\n\t"
+        S16_GROUP(v27, 0, 1, 2, 3, "", 12, 13, 14, 15, s86)
+        "s_waitcnt lgkmcnt(0)\n\t"
+        "s_sub_u32 s74, s74, 1\n\t"
+        "s_cmp_lg_u32 s74, 0\n\t"
+        "s_cbranch_scc1 .Lq_loop_%=\n\t"
+        "v_mov_b32 %[r], v44\n\t"
+        : [r] "=v"(r)
+        : [iters] "s"(iters), [val] "v"(value), [rows] "v"(rows), [off] "v"(off), [l16] "v"(l16)
+        : "m0", "scc", "memory", "s70", "s73", "s74", "s86", "v4", "v5", "v6", "v7", "v8", "v9", "v10", "v11", "v12", "v13", "v14", "v15", "v16", "v17", "v18", "v19", "v20", "v21", "v22", "v23", "v24", "v25", "v26", "v27", "v28", "v29", "v30", "v31", "v32", "v33", "v34", "v35", "v36", "v37", "v38", "v39", "v40", "v41", "v42", "v43", "v44", "v45", "v46", "v47", "v48", "v49", "v50", "v51", "v52", "v53", "v54", "v55", "v56", "v57", "v58", "v59", "v60", "v61", "v62", "v63", "v64", "v65", "v66", "v67", "v68", "v69", "v70", "v71", "v72", "v73", "v74", "v75", "v76", "v77", "v78", "v79", "v80", "v81", "v82", "v83", "v84", "v85", "v86", "v87", "v88", "v89", "v90", "v91", "v92", "v93", "v94", "v95", "v96", "v97", "v98", "v99", "v100", "v101", "v102", "v103", "v104", "v105", "v106", "v107", "v108", "v109", "v110", "v111", "v112", "v113", "v114", "v115", "v116", "v117", "v118", "v119", "v120", "v121", "v122", "v123", "v124", "v125", "v126", "v127");
+    if (r == 123.456f) out[0] = r;
+}
+
 #define VALU_BODY_0 \
         "v_fmac_f32 v8, v5, v2\n\tv_fmac_f32 v9, v6, v3\n\tv_fmac_f32 v10, v7, v0\n\tv_fmac_f32 v11, v4, v1\n\t" \
         "v_fmac_f32 v12, v5, v2\n\tv_fmac_f32 v13, v6, v3\n\tv_fmac_f32 v14, v7, v0\n\tv_fmac_f32 v15, v4, v1\n\t" \
@@ -417,6 +483,17 @@ int main()
                    names[mode], ms, per_entry_ns, instr[mode] / 16.0, kEntryTiles / (entries / ms) * 1e3);
             fflush(stdout);
         }
+    }
+    // 2a
+    CK(hipFuncSetAttribute((const void*)issue128, hipFuncAttributeMaxDynamicSharedMemorySize, 156 * 1024));
+    for (int wgs : {1, 2}) {
+        const int iters = 4000;
+        const size_t lds = (size_t)(156 * 1024) / wgs;
+        const float ms = timed([&] { issue128<<<kCUs * wgs, 512, lds>>>(iters, out); }, 3);
+        const double entries = (double)kCUs * wgs * 8 * 16.0 * iters;
+        printf("issue  16 singles with 128 registers per wave, %d waves per SIMD: %.3f ms, %.2f ns per entry and wave -> %.0f us for the headline workload\n",
+               2 * wgs, ms, ms * 1e6 / (16.0 * iters), kEntryTiles / (entries / ms) * 1e3);
+        fflush(stdout);
     }
     // 2b
     CK(hipFuncSetAttribute((const void*)valu0, hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024));
