@@ -85,7 +85,9 @@ int32_t gcoo_default_p(int64_t m, int64_t k, int64_t nnz, int64_t N);
  * 3*nnz + 2*g elements, plus one sentinel), the kernel-private schedules derived from them (the run
  * schedule of the register kernel, at most 3*nnz + 2048*g + 128 words; where gcoo_set_share_policy()
  * asks for it the share schedule of the workgroup-shared kernel) and the scratch space the
- * conversion kernels use.  Returns 0 for invalid arguments.  Pure host arithmetic.
+ * conversion kernels use; for p > 64 also a second copy of the matrix regrouped at 32 rows with its
+ * schedules, which is what the fast kernels multiply with (they hold at most 64 rows of partial sums).
+ * Returns 0 for invalid arguments.  Pure host arithmetic.
  */
 size_t gcoo_device_bytes(int64_t m, int64_t k, int64_t nnz, int32_t p);
 
@@ -185,8 +187,10 @@ int gcoo_spdm(const gcoo_matrix* A, const float* B_dev, int64_t ldb, int64_t N,
  */
 #define GCOO_VARIANT_AUTO 0
 #define GCOO_VARIANT_LDS  1  /* partial sums in LDS, reads the five arrays directly; any p, any alignment */
-/* partial sums in VGPRs, reads the run schedule built at conversion; needs p <= 64 and N >= 4 (p <= 38:
- * four columns per lane) or N >= 2 (39 <= p <= 64: two), else GCOO_EINVAL.  Any N, ldb, ldc and base
+/* partial sums in VGPRs, reads the run schedule built at conversion; needs N >= 4 (p <= 38 and p > 64:
+ * four columns per lane) or N >= 2 (39 <= p <= 64: two), else GCOO_EINVAL.  A matrix of groups taller than
+ * 64 rows is multiplied through a second, kernel-private copy regrouped at 32 rows that the conversion keeps
+ * behind the five arrays (gcoo_device_bytes() counts it); GCOO_VARIANT_SHARE works on that copy too.  Any N, ldb, ldc and base
  * addresses: where N is not a multiple of the columns per lane, the lane at the end of a row computes the
  * last columns of the row instead of reaching beyond N, and rows aligned to 4 bytes only are read and
  * written with unaligned 16-byte accesses (a few per cent slower than aligned ones).  No access leaves

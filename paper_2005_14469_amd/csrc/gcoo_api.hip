@@ -242,6 +242,17 @@ Layout make_layout(int64_t m, int64_t k, int64_t nnz, int64_t g, int32_t p, bool
     return L;
 }
 
+// Groups taller than the fast kernels serve (p > 64) get a second, kernel-private copy of the matrix regrouped at
+// kInnerP rows: the buffer of such a handle is its own layout followed by that of the inner handle.
+constexpr int32_t kInnerP = 32;
+bool wants_inner(int32_t p) { return p > gcoo::kSchedMaxP; }
+size_t total_bytes(int64_t m, int64_t k, int64_t nnz, int32_t p, bool scratch_inside)
+{
+    const size_t own = make_layout(m, k, nnz, (m + p - 1) / p, p, scratch_inside).total;
+    if (!wants_inner(p)) return own;
+    return al(own) + make_layout(m, k, nnz, (m + kInnerP - 1) / kInnerP, kInnerP, scratch_inside).total;
+}
+
 bool dims_ok(int64_t m, int64_t k, int64_t nnz, int32_t p)
 {
     return m >= 0 && k >= 0 && nnz >= 0 && p >= 1 && p <= GCOO_MAX_P && m <= INT32_MAX && k <= INT32_MAX &&
@@ -269,6 +280,10 @@ struct gcoo_matrix {
     int device;
     char* base;
     Layout L;
+    // p > 64: the same matrix regrouped at kInnerP rows per group, with the schedules of the fast kernels, in the
+    // part of the caller's buffer behind this handle's own; gcoo_spdm() multiplies with it.  Owned.
+    gcoo_matrix* inner = nullptr;
+    ~gcoo_matrix() { delete inner; }
     float* values() const { return reinterpret_cast<float*>(base + L.values); }
     int32_t* rows() const { return reinterpret_cast<int32_t*>(base + L.rows); }
     int32_t* cols() const { return reinterpret_cast<int32_t*>(base + L.cols); }
@@ -409,7 +424,7 @@ int32_t gcoo_default_p(int64_t m, int64_t k, int64_t nnz, int64_t N)
 size_t gcoo_device_bytes(int64_t m, int64_t k, int64_t nnz, int32_t p)
 {
     if (!dims_ok(m, k, nnz, p)) return 0;
-    return make_layout(m, k, nnz, (m + p - 1) / p, p).total;
+    return total_bytes(m, k, nnz, p, true);
 }
 
 }  // extern "C"
@@ -434,7 +449,7 @@ int from_csr(int64_t m, int64_t k, const int32_t* row_ptr, const int32_t* col_id
     int64_t nnz;
     if (src_on_device && nnz_known >= 0) {          // everything the host can check, before the first launch
         if (nnz_known > 0 && (!col_idx || !vals)) return GCOO_EINVAL;
-        if (dev_buf_bytes < make_layout(m, k, nnz_known, g, p, inside).total) return GCOO_ENOMEM;
+        if (dev_buf_bytes < total_bytes(m, k, nnz_known, p, inside)) return GCOO_ENOMEM;
     }
     // nnz and the size of the largest group are computed on the device and stay there (the counters
     // sit at an offset of the buffer that does not depend on nnz); the launches that need the
@@ -466,7 +481,7 @@ int from_csr(int64_t m, int64_t k, const int32_t* row_ptr, const int32_t* col_id
     }
     if (nnz > 0 && (!col_idx || !vals)) return GCOO_EINVAL;
     const Layout L = make_layout(m, k, nnz, g, p, inside);
-    if (dev_buf_bytes < L.total) return GCOO_ENOMEM;
+    if (dev_buf_bytes < total_bytes(m, k, nnz, p, inside)) return GCOO_ENOMEM;
 
     gcoo_matrix* h = nullptr;
     int rc = new_handle(m, k, nnz, p, dev_buf, &h, inside);
@@ -533,6 +548,14 @@ int from_csr(int64_t m, int64_t k, const int32_t* row_ptr, const int32_t* col_id
     }
     rc = launch_build_schedule(h, scratch, s);
     if (rc != GCOO_OK) { delete h; return rc; }
+    if (wants_inner(p)) {
+        // the same entries once more, regrouped at kInnerP rows, from the CSR arrays on the device (a host input's
+        // staged copy is still in this handle's scratch area, which the inner conversion does not touch)
+        const size_t own = al(L.total);
+        rc = from_csr(m, k, d_row_ptr, d_cols, d_vals, 1, nnz, kInnerP, base + own, dev_buf_bytes - own, stream, &h->inner,
+                      static_scratch_ptr);
+        if (rc != GCOO_OK) { delete h; return rc; }
+    }
     *out = h;
     return GCOO_OK;
 }
@@ -544,7 +567,7 @@ extern "C" {
 size_t gcoo_static_handle_bytes(int64_t m, int64_t k, int64_t nnz, int32_t p)
 {
     if (!dims_ok(m, k, nnz, p) || nnz > kStaticMaxNnz) return 0;
-    return make_layout(m, k, nnz, (m + p - 1) / p, p, false).total;
+    return total_bytes(m, k, nnz, p, false);
 }
 
 int gcoo_from_csr_device_static(int64_t m, int64_t k, int64_t nnz, const int32_t* row_ptr_dev, const int32_t* col_idx_dev,
@@ -644,7 +667,7 @@ int gcoo_from_dense(int64_t m, int64_t k, const float* A_dev, int64_t lda, int32
     if (total > (unsigned long long)INT32_MAX) return GCOO_EINVAL;
     const int64_t nnz = (int64_t)total;
     const Layout L = make_layout(m, k, nnz, g, p);
-    if (dev_buf_bytes < L.total) return GCOO_ENOMEM;
+    if (dev_buf_bytes < total_bytes(m, k, nnz, p, true)) return GCOO_ENOMEM;
     gcoo_matrix* h = nullptr;
     int rc = new_handle(m, k, nnz, p, dev_buf, &h);
     if (rc != GCOO_OK) return rc;
@@ -659,6 +682,11 @@ int gcoo_from_dense(int64_t m, int64_t k, const float* A_dev, int64_t lda, int32
     }
     rc = launch_build_schedule(h, h->base + h->L.persistent, s);
     if (rc != GCOO_OK) { delete h; return rc; }
+    if (wants_inner(p)) {
+        const size_t own = al(L.total);
+        rc = gcoo_from_dense(m, k, A_dev, lda, kInnerP, base + own, dev_buf_bytes - own, stream, &h->inner);
+        if (rc != GCOO_OK) { delete h; return rc; }
+    }
     *out = h;
     return GCOO_OK;
 }
@@ -737,6 +765,7 @@ int gcoo_spdm_pick(const gcoo_matrix* A, const float* B_dev, int64_t ldb, int64_
 {
     int rc = check_spdm_args(A, B_dev, ldb, N, C_dev, ldc);
     if (rc != GCOO_OK) return rc;
+    if (A->inner) A = A->inner;        // groups taller than 64 rows: the fast kernels run on the regrouped copy
     const Shape sh = shape_of(B_dev, ldb, N, C_dev, ldc);
     // the workgroup-shared kernel wants enough workgroups to occupy the chip (one per 8p rows and 256 columns),
     // and below 9000 columns its margin does not survive a last round that is mostly idle
@@ -766,6 +795,7 @@ int gcoo_spdm_variant(const gcoo_matrix* A, const float* B_dev, int64_t ldb, int
         HIP_TRY(hipGetLastError());
         return GCOO_OK;
     }
+    if (A->inner) A = A->inner;        // the schedules of the kernels below belong to the regrouped copy
     if (variant == GCOO_VARIANT_SHARE) {
         const Shape sh = shape_of(B_dev, ldb, N, C_dev, ldc);
         if (!A->has_share || !share_operands_ok(A, sh, ldb)) return GCOO_EINVAL;

@@ -62,6 +62,8 @@ def _variants_for(p, N):
     v = [binding.VARIANT_LDS]
     if (p <= 38 and N >= 4) or (p <= REG_MAX_P and N >= 2):       # four columns per lane, or two
         v += [binding.VARIANT_REG]
+    if p > REG_MAX_P and N >= 4:      # groups taller than 64 rows: the register kernel runs on the copy regrouped at 32 rows
+        v += [binding.VARIANT_REG]
     return v
 
 
@@ -194,10 +196,10 @@ def test_ragged_shapes_all_variants(m, k, N, p):
 
 
 def test_register_kernel_refuses_what_it_does_not_serve():
-    _say("REG variant: p > 64 and a single column are refused, AUTO falls back to the LDS kernel")
+    _say("REG variant: a single column is refused, AUTO falls back to the LDS kernel")
     w = workloads.uniform_random(256, 256, 64, 0.9, seed=5)
     Bt = torch.from_numpy(w.B).to(DEV)
-    for p, N in [(128, 64), (65, 64), (32, 1), (48, 1)]:
+    for p, N in [(128, 1), (32, 1), (48, 1)]:
         A = binding.gcoo_from_csr(w.m, w.k, w.row_ptr, w.col_idx, w.vals, p, device=DEV)
         Bv = Bt[:, :N].contiguous()
         Cv = torch.empty((w.m, N), device=DEV)
@@ -205,6 +207,36 @@ def test_register_kernel_refuses_what_it_does_not_serve():
         with pytest.raises(binding.GcooError):
             binding.gcoo_spdm(A, Bv, Cv, variant=binding.VARIANT_REG)
         torch.cuda.synchronize()
+
+
+@pytest.mark.parametrize("p", [65, 100, 128, 256])
+def test_groups_taller_than_64_rows_run_the_fast_kernels(p):
+    """p > 64: the conversion keeps a second copy of the matrix regrouped at 32 rows and the product runs on it, through
+    every route into the library; the exported arrays are those of the caller's p."""
+    w = workloads.uniform_random(700, 900, 260, 0.93, seed=p)
+    _say(f"tall groups p={p}: CSR from the host, CSR on the device, dense, the entry point that allocates nothing")
+    G = orc.gcoo_from_csr(w.m, w.k, w.row_ptr, w.col_idx, w.vals, p)
+    Bt = torch.from_numpy(w.B).to(DEV)
+    dev = [torch.from_numpy(x).to(DEV) for x in (w.row_ptr, w.col_idx, w.vals)]
+    Ah = np.zeros((w.m, w.k), np.float32)
+    Ah[np.repeat(np.arange(w.m), np.diff(w.row_ptr)), w.col_idx] = w.vals
+    handles = [binding.gcoo_from_csr(w.m, w.k, w.row_ptr, w.col_idx, w.vals, p, device=DEV),
+               binding.gcoo_from_csr(w.m, w.k, *dev, p, device=DEV, known_nnz=True),
+               binding.gcoo_from_csr_device_static(w.m, w.k, *dev, p),
+               binding.gcoo_from_dense(torch.from_numpy(Ah).to(DEV), p)]
+    C64, D64 = orc.spdm_csr(w.k, w.N, w.row_ptr, w.col_idx, w.vals, w.B)
+    for A in handles:
+        Cg = torch.full((w.m, w.N), float("nan"), device=DEV)
+        assert binding.gcoo_spdm_pick(A, Bt, Cg) == binding.VARIANT_REG
+        for variant in (binding.VARIANT_AUTO, binding.VARIANT_REG, binding.VARIANT_LDS):
+            Cg.fill_(float("nan"))
+            binding.gcoo_spdm(A, Bt, Cg, variant=variant)
+            torch.cuda.synchronize()
+            err, bad = orc.max_scaled_error(Cg.cpu().numpy(), C64, D64)
+            assert bad == 0 and err <= TOL, (variant, err, bad)
+        E = A.export()
+        assert np.array_equal(E["gIdxes"], G.gIdxes) and np.array_equal(E["cols"], G.cols) and np.array_equal(E["rows"], G.rows)
+        assert np.array_equal(E["values"].view(np.uint32), G.values.view(np.uint32))
 
 
 @pytest.mark.skip(reason="the one-column-per-lane register kernel (65 <= p <= 128) is not part of the library any more: "
