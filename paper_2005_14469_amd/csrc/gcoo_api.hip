@@ -350,7 +350,7 @@ int launch_build_schedule(const gcoo_matrix* h, char* scratch, hipStream_t s)
         // instance, a launch of its own beside the large-workgroup instance
         int32_t* order = h->has_order() ? h->order() : nullptr;
         if (h->nnz / (h->g * h->nw) <= 1024) {
-            const dim3 grid((unsigned)(h->g * h->nw + (order ? 1 : 0)));
+            const dim3 grid((unsigned)(h->g * h->nw + (order ? (h->g + 255) / 256 : 0)));
             gcoo::build_schedule<256><<<grid, dim3(256), 0, s>>>(h->gIdxes(), h->rows(), h->cols(), h->values(), h->p, h->g, h->nw,
                                                                  h->window_cols, h->sched_hdr(), h->sched(), order, order ? order + h->g : nullptr);
         } else {
@@ -358,7 +358,7 @@ int launch_build_schedule(const gcoo_matrix* h, char* scratch, hipStream_t s)
             gcoo::build_schedule<1024><<<grid, dim3(1024), 0, s>>>(h->gIdxes(), h->rows(), h->cols(), h->values(), h->p, h->g, h->nw,
                                                                    h->window_cols, h->sched_hdr(), h->sched(), nullptr, nullptr);
             HIP_TRY(hipGetLastError());
-            if (order) gcoo::group_order_by_size<<<dim3(1), dim3(1024), 0, s>>>(h->gIdxes(), (int32_t)h->g, order, order + h->g);
+            if (order) gcoo::group_order_by_size<<<dim3((unsigned)((h->g + 1023) / 1024)), dim3(1024), 0, s>>>(h->gIdxes(), (int32_t)h->g, order, order + h->g);
         }
         HIP_TRY(hipGetLastError());
     }
