@@ -106,9 +106,18 @@ __host__ __device__ inline int32_t sched_heavy_min(int64_t nnz, int64_t g, int64
     if (!sched_heavy_possible(nnz, g, tiles)) return 0x7fffffff;
     const int64_t items = g * tiles;
     const int64_t mean_group = nnz / g;
-    if (largest < 4 * mean_group && items * 8 > kHeavyWaveSlots) return 0x7fffffff;
+    const bool skewed = largest >= 4 * mean_group;
+    const bool empty = items * 8 <= kHeavyWaveSlots;       // plain waves would fill an eighth of the machine at most
+    if (!skewed && !empty) return 0x7fffffff;
+    // Split what carries more than one and a half times the mean load of a wave of this launch (a wave per item
+    // while the items do not outnumber the wave slots, a slot's share of all entries beyond that): a workgroup of
+    // eight waves for a group costs its compute unit the seven other groups that would run beside it, so a lower
+    // bar loses more than it gains, and a higher one leaves single waves with the long groups.  On the power-law
+    // workload (16384 rows, 512 columns of B) at 32 rows per group (1024 items) the bar is 2544 entries: 0.161 ms
+    // against 0.185 at 1272 and 0.186 at 3392; at 16 rows per group (2048 items) it is 1272: 0.20 ms against 0.26 at 2544.
     const int64_t mean_per_slot = nnz * tiles / kHeavyWaveSlots;
-    int64_t t = mean_per_slot + mean_per_slot / 2;
+    const int64_t mean_wave = mean_group > mean_per_slot ? mean_group : mean_per_slot;
+    int64_t t = mean_wave + mean_wave / 2;
     if (t < kHeavyMin) t = kHeavyMin;
     return t >= 0x7fffffff ? 0x7fffffff : (int32_t)t;
 }
