@@ -32,8 +32,8 @@
  * gcoo_spdm*, gcoo_info and gcoo_export* only read it, so any number of host threads may use one
  * handle at once, on any streams (each caller orders its own streams behind the conversion).
  * Distinct handles are independent.  gcoo_free() must not run while another call still uses the
- * handle.  The process-wide setting gcoo_set_share_policy() is the one function that is not
- * thread-safe.
+ * handle.  gcoo_set_share_policy() is process-wide; it may be called from any thread at any time, and a
+ * conversion uses, for all of its work, the value it finds when it starts.
  */
 #ifndef GCOO_H
 #define GCOO_H

@@ -133,7 +133,16 @@ int dense_vec_width(const float* A, int64_t lda, int64_t k)
 // of the workgroup-shared kernel.  Above 6 % the register kernel, which reuses a fetched segment along runs of
 // up to eight entries, is ahead (10 %: 2.9 against 3.2 ms at n = 8000); at 0.1 % and at n <= 3000 too.
 // gcoo_set_share_policy() overrides the choice.
-int g_share_policy = GCOO_SHARE_AUTO;
+std::atomic<int> g_share_policy{GCOO_SHARE_AUTO};
+// A conversion lays its buffer out more than once (size check, handle, inner handle): it reads the policy once, when
+// it starts, and every layout of that call uses that value, whatever another thread sets meanwhile.
+thread_local int t_policy_of_call = -1;
+struct PolicyOfCall {
+    bool outermost;
+    PolicyOfCall() : outermost(t_policy_of_call < 0) { if (outermost) t_policy_of_call = g_share_policy.load(std::memory_order_relaxed); }
+    ~PolicyOfCall() { if (outermost) t_policy_of_call = -1; }
+};
+int share_policy_now() { return t_policy_of_call >= 0 ? t_policy_of_call : g_share_policy.load(std::memory_order_relaxed); }
 
 bool share_schedule_possible(int64_t m, int64_t k, int64_t nnz, int32_t p)
 {
@@ -156,8 +165,9 @@ bool share_kernel_preferred(int64_t m, int64_t k, int64_t nnz, int32_t p)
 
 bool share_schedule_wanted(int64_t m, int64_t k, int64_t nnz, int32_t p)
 {
-    if (g_share_policy == GCOO_SHARE_NEVER || !share_schedule_possible(m, k, nnz, p)) return false;
-    return g_share_policy == GCOO_SHARE_ALWAYS || share_kernel_preferred(m, k, nnz, p);
+    const int policy = share_policy_now();
+    if (policy == GCOO_SHARE_NEVER || !share_schedule_possible(m, k, nnz, p)) return false;
+    return policy == GCOO_SHARE_ALWAYS || share_kernel_preferred(m, k, nnz, p);
 }
 
 // A workgroup of that kernel runs for a whole (super-group, column tile): how well `items` of them fill
@@ -398,7 +408,7 @@ extern "C" {
 int gcoo_set_share_policy(int policy)
 {
     if (policy < GCOO_SHARE_AUTO || policy > GCOO_SHARE_NEVER) return GCOO_EINVAL;
-    g_share_policy = policy;
+    g_share_policy.store(policy, std::memory_order_relaxed);
     return GCOO_OK;
 }
 
@@ -438,6 +448,7 @@ int from_csr(int64_t m, int64_t k, const int32_t* row_ptr, const int32_t* col_id
              int64_t nnz_known, int32_t p, void* dev_buf, size_t dev_buf_bytes, void* stream, gcoo_matrix** out,
              unsigned char* static_scratch_ptr = nullptr)
 {
+    const PolicyOfCall policy_of_call;
     const bool inside = static_scratch_ptr == nullptr;
     if (!out) return GCOO_EINVAL;
     *out = nullptr;
@@ -622,6 +633,7 @@ int gcoo_dense_nnz(int64_t m, int64_t k, const float* A_dev, int64_t lda, void* 
 int gcoo_from_dense(int64_t m, int64_t k, const float* A_dev, int64_t lda, int32_t p, void* dev_buf, size_t dev_buf_bytes,
                     void* stream, gcoo_matrix** out)
 {
+    const PolicyOfCall policy_of_call;
     if (!out) return GCOO_EINVAL;
     *out = nullptr;
     if (!dev_buf || !dims_ok(m, k, 0, p) || lda < k || (m > 0 && k > 0 && !A_dev)) return GCOO_EINVAL;
