@@ -50,7 +50,7 @@ def parse():
     ap.add_argument("--secondary", default="config2", help="second workload reported in the same line ('' = none)")
     ap.add_argument("--crossover", action="store_true",
                     help="instead of the headline run: sweep the sparsity of an 8000^2 uniform random A and report where "
-                         "the path overtakes the dense SGEMM (Section 4.2 of the paper, 'time vs. sparsity')")
+                         "the path overtakes the dense SGEMM (the time-against-sparsity comparison of Section 4.2 of the paper)")
     ap.add_argument("--sweep", choices=["sparsity", "size"], default=None,
                     help="instead of the headline run, one of the paper's sweeps on uniform random square matrices: "
                          "'sparsity' = time against sparsity at n = 4000 and 14000 with the dense SGEMM beside it "
