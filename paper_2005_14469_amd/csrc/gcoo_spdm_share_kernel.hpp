@@ -68,7 +68,10 @@ __device__ __forceinline__ float share_acc_get(const ShareAcc& a, int reg)
 
 // ---- asm text -----------------------------------------------------------------------------------
 // Fixed registers of the main loop (all named in the clobber list):
-//   v[20:35]  four sets of B values        v[36:39]  four LDS addresses
+//   v[20:35]  four sets of B values (sets 0..3)   v[4:19]  four more (sets 4..7: the singles of a band alternate between the two)
+//   v[36:39]  four LDS addresses
+//   v3 v43 v53 v58 v59  inputs that stay as they are: the lane's place in a vector of columns, the shift that packs a
+//             record's row, the lane's place in the wave's ring, lane*16 (0 for lanes beyond N) and lane*16
 //   v40 v41 v42  values, packed rows (the four rows of a record's group of four, one byte each), offsets of this block
 //   v[44:47]  records of the next block    v48 lane*16 + band buffer
 //   v49  byte offsets of the rows to fetch, ten bands     v50 v51 scratch     v52 columns of the ten bands after those
@@ -82,7 +85,39 @@ __device__ __forceinline__ float share_acc_get(const ShareAcc& a, int reg)
 #define SH_DPP(i) " row_newbcast:" #i " row_mask:0xf bank_mask:0xf\n\t"
 #define SH_ADDR(dst, src, i) "v_add_u32_dpp " #dst ", " #src ", v48" SH_DPP(i)
 #define SH_ROWS(reg, i) "v_readlane_b32 " #reg ", v41, " #i "\n\t"
+// Timing ablations (GCOO_SHARE_ABLATE, a set of bits): the kernel with one of its parts taken out, to see what that
+// part costs.  Such a build computes WRONG products; every address it forms is one the whole kernel forms too.
+// Only the micro-benchmark builds them, into libraries of their own; libgcoo.so is always built with 0.
+//   1 no row of B is requested (the bands in LDS hold whatever was there)      2 no multiply-adds, no index mode
+//   4 no barrier between bands      8 the singles read no B values from LDS    16 the wait in front of the barrier
+//   leaves the rows of two bands in flight instead of one
+#ifndef GCOO_SHARE_ABLATE
+#define GCOO_SHARE_ABLATE 0
+#endif
+#if GCOO_SHARE_ABLATE & 1
+#define SH_FILL_LOAD ""
+#else
+#define SH_FILL_LOAD "global_load_lds_dwordx4 v50, %[bt]\n\t"
+#endif
+#if GCOO_SHARE_ABLATE & 4
+#define SH_BAND_BARRIER ""
+#else
+#define SH_BAND_BARRIER "s_barrier\n\t"
+#endif
+#if GCOO_SHARE_ABLATE & 8
+#define SH_GROUP_READS(x) ""
+#else
+#define SH_GROUP_READS(x) x
+#endif
+#if GCOO_SHARE_ABLATE & 16
+#define SH_WAIT_FILLS "s_waitcnt vmcnt(12)\n\t"
+#else
+#define SH_WAIT_FILLS "s_waitcnt vmcnt(6)\n\t"
+#endif
 // one entry: record i of this block, its row in the low byte of `rows`, its B values in b0..b3
+#if GCOO_SHARE_ABLATE & 2
+#define SH_FMAC(i, rows, b0, b1, b2, b3) "s_lshr_b32 " #rows ", " #rows ", 8\n\t"
+#else
 #define SH_FMAC(i, rows, b0, b1, b2, b3)                    \
     "s_set_gpr_idx_on " #rows ", gpr_idx(SRC2,DST)\n\t"      \
     "v_fmac_f32_dpp v60, v40, " #b0 SH_DPP(i)                \
@@ -90,14 +125,23 @@ __device__ __forceinline__ float share_acc_get(const ShareAcc& a, int reg)
     "v_fmac_f32_dpp v158, v40, " #b2 SH_DPP(i)               \
     "v_fmac_f32_dpp v207, v40, " #b3 SH_DPP(i)               \
     "s_lshr_b32 " #rows ", " #rows ", 8\n\t"
+#endif
 #define SH_FMAC_SET0(i, rows) SH_FMAC(i, rows, v20, v21, v22, v23)
 #define SH_FMAC_SET1(i, rows) SH_FMAC(i, rows, v24, v25, v26, v27)
 #define SH_FMAC_SET2(i, rows) SH_FMAC(i, rows, v28, v29, v30, v31)
 #define SH_FMAC_SET3(i, rows) SH_FMAC(i, rows, v32, v33, v34, v35)
+#define SH_FMAC_SET4(i, rows) SH_FMAC(i, rows, v4, v5, v6, v7)
+#define SH_FMAC_SET5(i, rows) SH_FMAC(i, rows, v8, v9, v10, v11)
+#define SH_FMAC_SET6(i, rows) SH_FMAC(i, rows, v12, v13, v14, v15)
+#define SH_FMAC_SET7(i, rows) SH_FMAC(i, rows, v16, v17, v18, v19)
 #define SH_READ_SET0 "ds_read_b128 v[20:23], v36\n\t"
 #define SH_READ_SET1 "ds_read_b128 v[24:27], v37\n\t"
 #define SH_READ_SET2 "ds_read_b128 v[28:31], v38\n\t"
 #define SH_READ_SET3 "ds_read_b128 v[32:35], v39\n\t"
+#define SH_READ_SET4 "ds_read_b128 v[4:7], v36\n\t"
+#define SH_READ_SET5 "ds_read_b128 v[8:11], v37\n\t"
+#define SH_READ_SET6 "ds_read_b128 v[12:15], v38\n\t"
+#define SH_READ_SET7 "ds_read_b128 v[16:19], v39\n\t"
 #define SH_WAIT3 "s_waitcnt lgkmcnt(3)\n\t"
 #define SH_OFF "s_set_gpr_idx_off\n\t"
 
@@ -110,7 +154,7 @@ __device__ __forceinline__ float share_acc_get(const ShareAcc& a, int reg)
 // Index mode must be off.  L = a number unique to the expansion (local labels).
 #define SH_ADVANCE(L)                                                                         \
     "v_mov_b32 v40, v44\n\t"                                                                  \
-    "v_lshlrev_b32 v41, %[sh8], v45\n\t"                                                      \
+    "v_lshlrev_b32 v41, v43, v45\n\t"                                                      \
     "v_mov_b32 v42, v46\n\t"                                                                  \
     "s_add_u32 s68, s68, 1\n\t"                                                               \
     "v_or_b32_dpp v50, v41, v41 quad_perm:[1,0,3,2] row_mask:0xf bank_mask:0xf\n\t"           \
@@ -129,13 +173,13 @@ __device__ __forceinline__ float share_acc_get(const ShareAcc& a, int reg)
     "s_xor_b32 s71, s71, 0x400\n\t"                                                           \
     "s_add_u32 m0, s71, %[ring]\n\t"                                                          \
     "s_add_u32 s69, s69, 1\n\t"                                                               \
-    "global_load_lds_dwordx4 %[l16], s[76:77]\n\t"                                            \
+    "global_load_lds_dwordx4 v59, s[76:77]\n\t"                                            \
     "s_add_u32 s76, s76, 0x400\n\t"                                                           \
     "s_addc_u32 s77, s77, 0\n"                                                                \
     ".Lsh_adv_read" #L "_%=:\n\t"                                                             \
     "s_lshl_b32 s71, s68, 8\n\t"                                                              \
     "s_and_b32 s71, s71, 0x700\n\t"                                                           \
-    "v_add_u32 v50, s71, %[rl]\n\t"                                                           \
+    "v_add_u32 v50, s71, v53\n\t"                                                           \
     "ds_read_b128 v[44:47], v50\n\t"
 
 // One row of B to LDS: row t of the wave's six in the buffer at s72; its byte offset in B is lane s81 of v49.
@@ -143,8 +187,8 @@ __device__ __forceinline__ float share_acc_get(const ShareAcc& a, int reg)
     "s_add_u32 m0, s72, " #t "*1024\n\t"                              \
     "v_readlane_b32 s71, v49, s81\n\t"                                \
     "s_add_u32 s81, s81, 1\n\t"                                       \
-    "v_add_u32 v50, s71, %[l16g]\n\t"                                 \
-    "global_load_lds_dwordx4 v50, %[bt]\n\t"
+    "v_add_u32 v50, s71, v58\n\t"                                 \
+    SH_FILL_LOAD
 // The six rows of the next band to fetch, to the buffer at s89 (which then moves on by one buffer).  When the
 // lanes of v49 are used up, the next ten bands' offsets are made from v52 and the columns of the ten
 // bands after those are requested.
@@ -153,7 +197,7 @@ __device__ __forceinline__ float share_acc_get(const ShareAcc& a, int reg)
     "s_cbranch_scc1 .Lsh_fill_go" #L "_%=\n\t"                        \
     "v_mul_lo_u32 v49, v52, %[ldb4]\n\t"                              \
     "s_mul_i32 s71, s80, 48\n\t"                                      \
-    "v_add_u32 v50, s71, %[cidx]\n\t"                                 \
+    "v_add_u32 v50, s71, v3\n\t"                                 \
     "v_min_u32 v50, v50, %[last]\n\t"                                 \
     "v_lshlrev_b32 v50, 2, v50\n\t"                                   \
     "global_load_dword v52, v50, s[78:79]\n\t"                        \
@@ -200,7 +244,6 @@ __global__ __launch_bounds__(64 * kShareW) void spdm_share(ShareArgs a, int64_t 
         const uint32_t ldb4 = (uint32_t)a.ldb * 4u;                // the launcher checks that every row offset fits 32 bits
         const uint32_t l16 = (uint32_t)lane * 16u;
         const uint32_t l16g = in ? l16 : 0u;                       // lanes beyond N fetch the first columns of the tile
-        const uint32_t l8 = (uint32_t)lane * 8u;
         const uint32_t sh8 = (uint32_t)(lane & 3) * 8u;
         // lane 6i + t of a column vector: row t of the wave's six in band (first band of the vector) + i
         const int li = lane < 60 ? lane : 59;
@@ -225,22 +268,23 @@ __global__ __launch_bounds__(64 * kShareW) void spdm_share(ShareArgs a, int64_t 
             "s_mov_b32 s80, 20\n\t"
             "s_mov_b32 m0, %[ring]\n\t"
             "s_nop 0\n\t"
-            "global_load_lds_dwordx4 %[l16], s[76:77]\n\t"
+            "global_load_lds_dwordx4 v59, s[76:77]\n\t"
             "s_add_u32 s76, s76, 0x400\n\t"
             "s_addc_u32 s77, s77, 0\n\t"
             "s_add_u32 m0, %[ring], 0x400\n\t"
             "s_nop 0\n\t"
-            "global_load_lds_dwordx4 %[l16], s[76:77]\n\t"
+            "global_load_lds_dwordx4 v59, s[76:77]\n\t"
             "s_add_u32 s76, s76, 0x400\n\t"
             "s_addc_u32 s77, s77, 0\n\t"
-            "global_load_dwordx2 v[54:55], %[l8], s[74:75]\n\t"
-            "global_load_dwordx2 v[56:57], %[l8], s[74:75] offset:512\n\t"
+            "v_lshrrev_b32 v50, 1, v59\n\t"
+            "global_load_dwordx2 v[54:55], v50, s[74:75]\n\t"
+            "global_load_dwordx2 v[56:57], v50, s[74:75] offset:512\n\t"
             "s_add_u32 s74, s74, 0x400\n\t"
             "s_addc_u32 s75, s75, 0\n\t"
-            "v_min_u32 v50, %[cidx], %[last]\n\t"
+            "v_min_u32 v50, v3, %[last]\n\t"
             "v_lshlrev_b32 v50, 2, v50\n\t"
             "global_load_dword v51, v50, s[78:79]\n\t"
-            "v_add_u32 v50, 480, %[cidx]\n\t"
+            "v_add_u32 v50, 480, v3\n\t"
             "v_min_u32 v50, v50, %[last]\n\t"
             "v_lshlrev_b32 v50, 2, v50\n\t"
             "global_load_dword v52, v50, s[78:79]\n\t"
@@ -248,7 +292,7 @@ __global__ __launch_bounds__(64 * kShareW) void spdm_share(ShareArgs a, int64_t 
             "v_mul_lo_u32 v49, v51, %[ldb4]\n\t"
             "v_readlane_b32 s66, v54, 0\n\t"
             "v_readlane_b32 s67, v55, 0\n\t"
-            "ds_read_b128 v[44:47], %[rl]\n\t"
+            "ds_read_b128 v[44:47], v53\n\t"
             SH_FILL_BAND(0)
             "s_cmp_lt_u32 s65, 2\n\t"
             "s_cbranch_scc1 .Lsh_one_band_%=\n\t"
@@ -263,7 +307,7 @@ __global__ __launch_bounds__(64 * kShareW) void spdm_share(ShareArgs a, int64_t 
             SH_ADVANCE(0)
             // ---- one band
             ".Lsh_band_%=:\n\t"
-            "v_add_u32 v48, s88, %[l16]\n\t"
+            "v_add_u32 v48, s88, v59\n\t"
             "s_mov_b32 s83, s69\n\t"
             "s_mov_b32 s92, 0\n\t"
             // the first B rows of the band's first part are read while the requests below are issued
@@ -347,22 +391,26 @@ __global__ __launch_bounds__(64 * kShareW) void spdm_share(ShareArgs a, int64_t 
             "s_cbranch_scc1 .Lsh_nos_%=\n"
             ".Lsh_sblk_%=:\n\t"
             SH_ROWS(s70, 0)
-// a group of four singles: records i0..i3 with their rows in `rows`; the addresses of the four after them
-// (records n0..n3 of `src`) and, where there is one, the rows of the next group are fetched first
-#define SH_GROUP(src, n0, n1, n2, n3, nextrows, i0, i1, i2, i3, rows)                     \
+// a group of four singles: its B values were requested a whole group ahead into one bank of four sets (sets 0..3 or
+// 4..7: the groups of a band alternate), so that one wait covers them: first the addresses of the four records
+// after them (records n0..n3 of `src`) and their reads into the other bank (R0..R3), where there is one the rows of
+// the next group, then the wait that leaves only those four reads outstanding, then the multiply-adds (F0..F3)
+#define SH_GROUP(src, n0, n1, n2, n3, R0, R1, R2, R3, nextrows, F0, F1, F2, F3)           \
             "s_sub_u32 s73, s73, 1\n\t"                                               \
             "s_cbranch_scc1 .Lsh_send_%=\n\t"                                         \
-            SH_ADDR(v36, src, n0) SH_ADDR(v37, src, n1) SH_ADDR(v38, src, n2) SH_ADDR(v39, src, n3) \
+            SH_GROUP_READS(SH_ADDR(v36, src, n0) SH_ADDR(v37, src, n1) SH_ADDR(v38, src, n2) SH_ADDR(v39, src, n3) R0 R1 R2 R3) \
             nextrows                                                                  \
-            SH_WAIT3 SH_FMAC_SET0(i0, rows) SH_READ_SET0                              \
-            SH_WAIT3 SH_FMAC_SET1(i1, rows) SH_READ_SET1                              \
-            SH_WAIT3 SH_FMAC_SET2(i2, rows) SH_READ_SET2                              \
-            SH_WAIT3 SH_FMAC_SET3(i3, rows) SH_READ_SET3                              \
+            "s_waitcnt lgkmcnt(4)\n\t"                                                \
+            F0 F1 F2 F3                                                               \
             SH_OFF
-            SH_GROUP(v42, 4, 5, 6, 7, SH_ROWS(s86, 4), 0, 1, 2, 3, s70)
-            SH_GROUP(v42, 8, 9, 10, 11, SH_ROWS(s70, 8), 4, 5, 6, 7, s86)
-            SH_GROUP(v42, 12, 13, 14, 15, SH_ROWS(s86, 12), 8, 9, 10, 11, s70)
-            SH_GROUP(v46, 0, 1, 2, 3, "", 12, 13, 14, 15, s86)
+            SH_GROUP(v42, 4, 5, 6, 7, SH_READ_SET4, SH_READ_SET5, SH_READ_SET6, SH_READ_SET7, SH_ROWS(s86, 4),
+                     SH_FMAC_SET0(0, s70), SH_FMAC_SET1(1, s70), SH_FMAC_SET2(2, s70), SH_FMAC_SET3(3, s70))
+            SH_GROUP(v42, 8, 9, 10, 11, SH_READ_SET0, SH_READ_SET1, SH_READ_SET2, SH_READ_SET3, SH_ROWS(s70, 8),
+                     SH_FMAC_SET4(4, s86), SH_FMAC_SET5(5, s86), SH_FMAC_SET6(6, s86), SH_FMAC_SET7(7, s86))
+            SH_GROUP(v42, 12, 13, 14, 15, SH_READ_SET4, SH_READ_SET5, SH_READ_SET6, SH_READ_SET7, SH_ROWS(s86, 12),
+                     SH_FMAC_SET0(8, s70), SH_FMAC_SET1(9, s70), SH_FMAC_SET2(10, s70), SH_FMAC_SET3(11, s70))
+            SH_GROUP(v46, 0, 1, 2, 3, SH_READ_SET0, SH_READ_SET1, SH_READ_SET2, SH_READ_SET3, "",
+                     SH_FMAC_SET4(12, s86), SH_FMAC_SET5(13, s86), SH_FMAC_SET6(14, s86), SH_FMAC_SET7(15, s86))
             "s_cmp_eq_u32 s73, 0\n\t"
             "s_cbranch_scc1 .Lsh_send_%=\n\t"
             SH_ADVANCE(3)
@@ -376,7 +424,8 @@ __global__ __launch_bounds__(64 * kShareW) void spdm_share(ShareArgs a, int64_t 
             "s_cbranch_scc1 .Lsh_samehdr_%=\n\t"
             "v_mov_b32 v54, v56\n\t"
             "v_mov_b32 v55, v57\n\t"
-            "global_load_dwordx2 v[56:57], %[l8], s[74:75]\n\t"
+            "v_lshrrev_b32 v50, 1, v59\n\t"
+            "global_load_dwordx2 v[56:57], v50, s[74:75]\n\t"
             "s_add_u32 s74, s74, 0x200\n\t"
             "s_addc_u32 s75, s75, 0\n"
             ".Lsh_samehdr_%=:\n\t"
@@ -386,13 +435,13 @@ __global__ __launch_bounds__(64 * kShareW) void spdm_share(ShareArgs a, int64_t 
             // their way) and so has everything requested before this band began; all waves are done with band b
             "s_cmp_eq_u32 s92, 0\n\t"
             "s_cbranch_scc1 .Lsh_drain_%=\n\t"
-            "s_waitcnt vmcnt(6)\n\t"
-            "s_barrier\n\t"
+            SH_WAIT_FILLS
+            SH_BAND_BARRIER
             "s_max_u32 s82, s82, s83\n\t"
             "s_branch .Lsh_sync_%=\n"
             ".Lsh_drain_%=:\n\t"
             "s_waitcnt vmcnt(0)\n\t"
-            "s_barrier\n\t"
+            SH_BAND_BARRIER
             "s_mov_b32 s82, s69\n"
             ".Lsh_sync_%=:\n\t"
             "s_mov_b64 s[66:67], s[90:91]\n\t"
@@ -405,18 +454,23 @@ __global__ __launch_bounds__(64 * kShareW) void spdm_share(ShareArgs a, int64_t 
             : "+{v[60:63]}"(acc.t0), "+{v[64:95]}"(acc.t1), "+{v[96:127]}"(acc.t2), "+{v[128:159]}"(acc.t3),
               "+{v[160:191]}"(acc.t4), "+{v[192:223]}"(acc.t5), "+{v[224:255]}"(acc.t6)
             : [hdr] "s"(hdr), [strm] "s"(strm), [uc] "s"(uc), [bt] "s"(bt), [nb] "s"(nb), [ldb4] "s"(ldb4), [ring] "s"(ring),
-              [fillw] "s"(fillw), [last] "s"(last), [l16] "v"(l16), [l16g] "v"(l16g), [l8] "v"(l8), [sh8] "v"(sh8), [cidx] "v"(cidx),
-              [rl] "v"(rl)
+              [fillw] "s"(fillw), [last] "s"(last), "{v59}"(l16), "{v58}"(l16g), "{v43}"(sh8), "{v3}"(cidx), "{v53}"(rl)
             : "m0", "scc", "memory", "v20", "v21", "v22", "v23", "v24", "v25", "v26", "v27", "v28", "v29", "v30", "v31", "v32", "v33",
-              "v34", "v35", "v36", "v37", "v38", "v39", "v40", "v41", "v42", "v43", "v44", "v45", "v46", "v47", "v48", "v49", "v50",
-              "v51", "v52", "v53", "v54", "v55", "v56", "v57", "s64", "s65", "s66", "s67", "s68", "s69", "s70", "s71", "s72", "s73",
+              "v34", "v35", "v36", "v37", "v38", "v39", "v40", "v41", "v42", "v44", "v45", "v46", "v47", "v48", "v49", "v50",
+              "v51", "v52", "v54", "v55", "v56", "v57", "v4", "v5", "v6", "v7", "v8", "v9", "v10", "v11", "v12", "v13", "v14", "v15",
+              "v16", "v17", "v18", "v19", "s64", "s65", "s66", "s67", "s68", "s69", "s70", "s71", "s72", "s73",
               "s74", "s75", "s76", "s77", "s78", "s79", "s80", "s81", "s82", "s83", "s84", "s85", "s86", "s87", "s88", "s89", "s90",
               "s91", "s92");
     }
 
-    if (q < a.g && in) {
+    // The lane's columns once more, from a thread index the compiler cannot connect with the one above: the loop
+    // leaves it three registers, too few to carry the lane's place in C across it.
+    uint32_t tid = threadIdx.x;
+    asm volatile("" : "+v"(tid));
+    const int64_t jc = tile * 256 + (int64_t)(tid & 63u) * 4;
+    if (q < a.g && jc < a.N) {
         const int64_t row0 = q * a.p;
-        float* __restrict__ Cl = a.C + j0;
+        float* __restrict__ Cl = a.C + jc;
 #pragma unroll
         for (int r = 0; r < kShareMaxP; ++r) {
             if (r < a.p && row0 + r < a.m) {

@@ -57,7 +57,8 @@ __global__ __launch_bounds__(512) void lds_read(int iters, unsigned* sink)
 
 // ---------------------------------------------------------------- 2. issue rate of the per-entry sequence
 // MODE 0: sixteen singles (SH_GROUP x 4), 1: four quads, 2: the multiply-adds of sixteen entries with their
-// index-mode switches and nothing else, 3: 64 plain v_fmac_f32 (no index mode, no LDS)
+// index-mode switches and nothing else, 3: 64 plain v_fmac_f32 (no index mode, no LDS), 4: sixteen singles the
+// way the kernel did them before (four sets of B values, a wait before every entry)
 template <int MODE>
 __global__ __launch_bounds__(512) void issue(int iters, float* out)
 {
@@ -75,23 +76,27 @@ __global__ __launch_bounds__(512) void issue(int iters, float* out)
     const unsigned off = ((rec * 11) % 48) * 1024u;
     const unsigned l16 = lane * 16u;
     if constexpr (MODE == 0) {
+        // the kernel's own macros: eight sets of B values, the reads of a group of four issued a whole group ahead
         asm volatile(
             "v_mov_b32 v40, %[val]\n\t"
             "v_mov_b32 v41, %[rows]\n\t"
             "v_mov_b32 v42, %[off]\n\t"
             "v_mov_b32 v46, %[off]\n\t"
             "v_mov_b32 v48, %[l16]\n\t"
-            "s_mov_b32 s74, %[iters]\n"
+            "s_mov_b32 s74, %[iters]\n\t"
+            SH_ADDR(v36, v42, 0) SH_ADDR(v37, v42, 1) SH_ADDR(v38, v42, 2) SH_ADDR(v39, v42, 3)
+            SH_READ_SET0 SH_READ_SET1 SH_READ_SET2 SH_READ_SET3
             ".Lq_loop_%=:\n\t"
             "s_mov_b32 s73, 1000\n\t"
             SH_ROWS(s70, 0)
-            SH_ADDR(v36, v42, 0) SH_ADDR(v37, v42, 1) SH_ADDR(v38, v42, 2) SH_ADDR(v39, v42, 3)
-            SH_READ_SET0 SH_READ_SET1 SH_READ_SET2 SH_READ_SET3
-            SH_GROUP(v42, 4, 5, 6, 7, SH_ROWS(s86, 4), 0, 1, 2, 3, s70)
-            SH_GROUP(v42, 8, 9, 10, 11, SH_ROWS(s70, 8), 4, 5, 6, 7, s86)
-            SH_GROUP(v42, 12, 13, 14, 15, SH_ROWS(s86, 12), 8, 9, 10, 11, s70)
-            SH_GROUP(v46, 0, 1, 2, 3, "", 12, 13, 14, 15, s86)
-            "s_waitcnt lgkmcnt(0)\n\t"
+            SH_GROUP(v42, 4, 5, 6, 7, SH_READ_SET4, SH_READ_SET5, SH_READ_SET6, SH_READ_SET7, SH_ROWS(s86, 4),
+                     SH_FMAC_SET0(0, s70), SH_FMAC_SET1(1, s70), SH_FMAC_SET2(2, s70), SH_FMAC_SET3(3, s70))
+            SH_GROUP(v42, 8, 9, 10, 11, SH_READ_SET0, SH_READ_SET1, SH_READ_SET2, SH_READ_SET3, SH_ROWS(s70, 8),
+                     SH_FMAC_SET4(4, s86), SH_FMAC_SET5(5, s86), SH_FMAC_SET6(6, s86), SH_FMAC_SET7(7, s86))
+            SH_GROUP(v42, 12, 13, 14, 15, SH_READ_SET4, SH_READ_SET5, SH_READ_SET6, SH_READ_SET7, SH_ROWS(s86, 12),
+                     SH_FMAC_SET0(8, s70), SH_FMAC_SET1(9, s70), SH_FMAC_SET2(10, s70), SH_FMAC_SET3(11, s70))
+            SH_GROUP(v46, 0, 1, 2, 3, SH_READ_SET0, SH_READ_SET1, SH_READ_SET2, SH_READ_SET3, "",
+                     SH_FMAC_SET4(12, s86), SH_FMAC_SET5(13, s86), SH_FMAC_SET6(14, s86), SH_FMAC_SET7(15, s86))
             "s_sub_u32 s74, s74, 1\n\t"
             "s_cmp_lg_u32 s74, 0\n\t"
             "s_cbranch_scc1 .Lq_loop_%=\n"
@@ -100,7 +105,8 @@ __global__ __launch_bounds__(512) void issue(int iters, float* out)
             : "+{v[60:63]}"(acc.t0), "+{v[64:95]}"(acc.t1), "+{v[96:127]}"(acc.t2), "+{v[128:159]}"(acc.t3),
               "+{v[160:191]}"(acc.t4), "+{v[192:223]}"(acc.t5), "+{v[224:255]}"(acc.t6)
             : [iters] "s"(iters), [val] "v"(value), [rows] "v"(rows), [off] "v"(off), [l16] "v"(l16)
-            : "m0", "scc", "memory", "v20", "v21", "v22", "v23", "v24", "v25", "v26", "v27", "v28", "v29", "v30", "v31", "v32", "v33",
+            : "m0", "scc", "memory", "v4", "v5", "v6", "v7", "v8", "v9", "v10", "v11", "v12", "v13", "v14", "v15", "v16", "v17", "v18", "v19",
+              "v20", "v21", "v22", "v23", "v24", "v25", "v26", "v27", "v28", "v29", "v30", "v31", "v32", "v33",
               "v34", "v35", "v36", "v37", "v38", "v39", "v40", "v41", "v42", "v46", "v48", "s70", "s73", "s74", "s86");
     } else if constexpr (MODE == 1) {
         asm volatile(
@@ -137,6 +143,47 @@ __global__ __launch_bounds__(512) void issue(int iters, float* out)
             : [iters] "s"(iters), [val] "v"(value), [rows] "v"(rows), [off] "v"(off), [l16] "v"(l16)
             : "m0", "scc", "memory", "v20", "v21", "v22", "v23", "v24", "v25", "v26", "v27", "v28", "v29", "v30", "v31", "v32", "v33",
               "v34", "v35", "v36", "v37", "v38", "v39", "v40", "v41", "v42", "v46", "v48", "s70", "s73", "s74", "s86");
+    } else if constexpr (MODE == 4) {
+        // the sequence the kernel used before: four sets of B values, each read issued right after the multiply-adds
+        // that free its set (three entries ahead), a wait before every entry
+#define OLD_GROUP(src, n0, n1, n2, n3, nextrows, i0, i1, i2, i3, rows)                    \
+            "s_sub_u32 s73, s73, 1\n\t"                                               \
+            "s_cbranch_scc1 .Lsh_send_%=\n\t"                                         \
+            SH_ADDR(v36, src, n0) SH_ADDR(v37, src, n1) SH_ADDR(v38, src, n2) SH_ADDR(v39, src, n3) \
+            nextrows                                                                  \
+            SH_WAIT3 SH_FMAC_SET0(i0, rows) SH_READ_SET0                              \
+            SH_WAIT3 SH_FMAC_SET1(i1, rows) SH_READ_SET1                              \
+            SH_WAIT3 SH_FMAC_SET2(i2, rows) SH_READ_SET2                              \
+            SH_WAIT3 SH_FMAC_SET3(i3, rows) SH_READ_SET3                              \
+            SH_OFF
+        asm volatile(
+            "v_mov_b32 v40, %[val]\n\t"
+            "v_mov_b32 v41, %[rows]\n\t"
+            "v_mov_b32 v42, %[off]\n\t"
+            "v_mov_b32 v46, %[off]\n\t"
+            "v_mov_b32 v48, %[l16]\n\t"
+            "s_mov_b32 s74, %[iters]\n"
+            ".Lq_loop_%=:\n\t"
+            "s_mov_b32 s73, 1000\n\t"
+            SH_ROWS(s70, 0)
+            SH_ADDR(v36, v42, 0) SH_ADDR(v37, v42, 1) SH_ADDR(v38, v42, 2) SH_ADDR(v39, v42, 3)
+            SH_READ_SET0 SH_READ_SET1 SH_READ_SET2 SH_READ_SET3
+            OLD_GROUP(v42, 4, 5, 6, 7, SH_ROWS(s86, 4), 0, 1, 2, 3, s70)
+            OLD_GROUP(v42, 8, 9, 10, 11, SH_ROWS(s70, 8), 4, 5, 6, 7, s86)
+            OLD_GROUP(v42, 12, 13, 14, 15, SH_ROWS(s86, 12), 8, 9, 10, 11, s70)
+            OLD_GROUP(v46, 0, 1, 2, 3, "", 12, 13, 14, 15, s86)
+            "s_waitcnt lgkmcnt(0)\n\t"
+            "s_sub_u32 s74, s74, 1\n\t"
+            "s_cmp_lg_u32 s74, 0\n\t"
+            "s_cbranch_scc1 .Lq_loop_%=\n"
+            ".Lsh_send_%=:\n\t"
+            "s_waitcnt lgkmcnt(0)\n\t"
+            : "+{v[60:63]}"(acc.t0), "+{v[64:95]}"(acc.t1), "+{v[96:127]}"(acc.t2), "+{v[128:159]}"(acc.t3),
+              "+{v[160:191]}"(acc.t4), "+{v[192:223]}"(acc.t5), "+{v[224:255]}"(acc.t6)
+            : [iters] "s"(iters), [val] "v"(value), [rows] "v"(rows), [off] "v"(off), [l16] "v"(l16)
+            : "m0", "scc", "memory", "v20", "v21", "v22", "v23", "v24", "v25", "v26", "v27", "v28", "v29", "v30", "v31", "v32", "v33",
+              "v34", "v35", "v36", "v37", "v38", "v39", "v40", "v41", "v42", "v46", "v48", "s70", "s73", "s74", "s86");
+#undef OLD_GROUP
     } else if constexpr (MODE == 2) {
         asm volatile(
             "v_mov_b32 v40, %[val]\n\t"
@@ -465,17 +512,20 @@ int main()
     CK(hipFuncSetAttribute((const void*)issue<1>, hipFuncAttributeMaxDynamicSharedMemorySize, 3 * 49152));
     CK(hipFuncSetAttribute((const void*)issue<2>, hipFuncAttributeMaxDynamicSharedMemorySize, 3 * 49152));
     CK(hipFuncSetAttribute((const void*)issue<3>, hipFuncAttributeMaxDynamicSharedMemorySize, 3 * 49152));
+    CK(hipFuncSetAttribute((const void*)issue<4>, hipFuncAttributeMaxDynamicSharedMemorySize, 3 * 49152));
     {
         const int iters = 4000;
-        const char* names[4] = {"16 singles (address, LDS read, index mode, 4 multiply-adds each)", "4 quads (one LDS read per four entries)",
-                                "multiply-adds and index mode only", "plain v_fmac_f32 only"};
-        const double instr[4] = {172, 119, 107, 67};      // instructions of one turn of each loop (16 entries)
-        for (int mode = 0; mode < 4; ++mode) {
+        const char* names[5] = {"16 singles (address, LDS read, index mode, 4 multiply-adds each)  ", "4 quads (one LDS read per four entries)",
+                                "multiply-adds and index mode only", "plain v_fmac_f32 only",
+                                "16 singles the former way: four sets of B values, a wait per entry"};
+        const double instr[5] = {4 * (2 + 8 + 1 + 1 + 24 + 1) - 1 + 4, 119, 107, 67, 172};      // instructions of one turn of each loop (16 entries)
+        for (int mode = 0; mode < 5; ++mode) {
             const float ms = timed([&] {
                 if (mode == 0) issue<0><<<kCUs, 512, 3 * 49152>>>(iters, out);
                 else if (mode == 1) issue<1><<<kCUs, 512, 3 * 49152>>>(iters, out);
                 else if (mode == 2) issue<2><<<kCUs, 512, 3 * 49152>>>(iters, out);
-                else issue<3><<<kCUs, 512, 3 * 49152>>>(iters, out);
+                else if (mode == 3) issue<3><<<kCUs, 512, 3 * 49152>>>(iters, out);
+                else issue<4><<<kCUs, 512, 3 * 49152>>>(iters, out);
             }, 3);
             const double entries = (double)kCUs * 8 * 16.0 * iters;       // 16 entries per wave and turn
             const double per_entry_ns = ms * 1e6 / ((double)16 * iters);   // per wave
