@@ -81,7 +81,7 @@ __device__ __forceinline__ float share_acc_get(const ShareAcc& a, int reg)
 //   s70 s86 packed rows  s71 s72 scratch  s73 loop count
 //   s[74:75] header pointer (next 64 bands)  s[76:77] stream pointer (next piece)  s[78:79] ucols of the super-group
 //   s80 first band of the column vector after v52  s81 lane of v49 that holds the next row to fetch
-//   s88 LDS address of this band's buffer  s89 of the buffer that the next rows go to  s92 rows were requested in this band
+//   s88 LDS address of this band's buffer  s89 of the buffer that the next rows go to
 #define SH_DPP(i) " row_newbcast:" #i " row_mask:0xf bank_mask:0xf\n\t"
 #define SH_ADDR(dst, src, i) "v_add_u32_dpp " #dst ", " #src ", v48" SH_DPP(i)
 #define SH_ROWS(reg, i) "v_readlane_b32 " #reg ", v41, " #i "\n\t"
@@ -293,45 +293,26 @@ __global__ __launch_bounds__(64 * kShareW) void spdm_share(ShareArgs a, int64_t 
             "v_readlane_b32 s66, v54, 0\n\t"
             "v_readlane_b32 s67, v55, 0\n\t"
             "ds_read_b128 v[44:47], v53\n\t"
+            // (bands beyond the last one are requested like any other: their columns are clamped to the last
+            // column of the super-group, their rows go to a buffer that nobody reads)
             SH_FILL_BAND(0)
-            "s_cmp_lt_u32 s65, 2\n\t"
-            "s_cbranch_scc1 .Lsh_one_band_%=\n\t"
             SH_FILL_BAND(1)
             "s_waitcnt vmcnt(6) lgkmcnt(0)\n\t"
             "s_barrier\n\t"
-            "s_branch .Lsh_started_%=\n"
-            ".Lsh_one_band_%=:\n\t"
-            "s_waitcnt vmcnt(0) lgkmcnt(0)\n\t"
-            "s_barrier\n"
-            ".Lsh_started_%=:\n\t"
             SH_ADVANCE(0)
             // ---- one band
             ".Lsh_band_%=:\n\t"
             "v_add_u32 v48, s88, v59\n\t"
             "s_mov_b32 s83, s69\n\t"
-            "s_mov_b32 s92, 0\n\t"
-            // the first B rows of the band's first part are read while the requests below are issued
+            // One decision per band: quads first, singles only, or nothing for this wave.  In each case the first B
+            // rows of the band's first part are read while the rows of the band after next are requested.
             "s_cmp_eq_u32 s66, 0\n\t"
-            "s_cbranch_scc1 .Lsh_first_s_%=\n\t"
+            "s_cbranch_scc1 .Lsh_noq_%=\n\t"
             SH_ADDR(v36, v42, 0) SH_ADDR(v37, v42, 4) SH_ADDR(v38, v42, 8) SH_ADDR(v39, v42, 12)
             SH_READ_SET0 SH_READ_SET1 SH_READ_SET2 SH_READ_SET3
-            "s_branch .Lsh_first_done_%=\n"
-            ".Lsh_first_s_%=:\n\t"
-            "s_cmp_eq_u32 s67, 0\n\t"
-            "s_cbranch_scc1 .Lsh_first_done_%=\n\t"
-            SH_ADDR(v36, v42, 0) SH_ADDR(v37, v42, 1) SH_ADDR(v38, v42, 2) SH_ADDR(v39, v42, 3)
-            SH_READ_SET0 SH_READ_SET1 SH_READ_SET2 SH_READ_SET3
-            ".Lsh_first_done_%=:\n\t"
-            "s_add_u32 s72, s64, 2\n\t"
-            "s_cmp_ge_u32 s72, s65\n\t"
-            "s_cbranch_scc1 .Lsh_nofill_%=\n\t"
-            "s_mov_b32 s92, 1\n\t"
             SH_FILL_BAND(2)
-            ".Lsh_nofill_%=:\n\t"
             // ---- quads
-            "s_mov_b32 s73, s66\n\t"
-            "s_cmp_eq_u32 s66, 0\n\t"
-            "s_cbranch_scc1 .Lsh_noq_%=\n"
+            "s_mov_b32 s73, s66\n"
             ".Lsh_qblk_%=:\n\t"
             SH_ROWS(s70, 0)
             // quad 0; after it everything read from LDS so far has arrived, the records of the next block included
@@ -385,10 +366,13 @@ __global__ __launch_bounds__(64 * kShareW) void spdm_share(ShareArgs a, int64_t 
             SH_READ_SET0 SH_READ_SET1 SH_READ_SET2 SH_READ_SET3
             "s_branch .Lsh_sblk_%=\n"
             ".Lsh_noq_%=:\n\t"
-            // ---- singles, four at a time
-            "s_mov_b32 s73, s67\n\t"
             "s_cmp_eq_u32 s67, 0\n\t"
-            "s_cbranch_scc1 .Lsh_nos_%=\n"
+            "s_cbranch_scc1 .Lsh_empty_%=\n\t"
+            SH_ADDR(v36, v42, 0) SH_ADDR(v37, v42, 1) SH_ADDR(v38, v42, 2) SH_ADDR(v39, v42, 3)
+            SH_READ_SET0 SH_READ_SET1 SH_READ_SET2 SH_READ_SET3
+            SH_FILL_BAND(3)
+            // ---- singles, four at a time
+            "s_mov_b32 s73, s67\n"
             ".Lsh_sblk_%=:\n\t"
             SH_ROWS(s70, 0)
 // a group of four singles: its B values were requested a whole group ahead into one bank of four sets (sets 0..3 or
@@ -433,17 +417,9 @@ __global__ __launch_bounds__(64 * kShareW) void spdm_share(ShareArgs a, int64_t 
             "v_readlane_b32 s91, v55, s71\n\t"
             // ---- the rows of band b+1 have landed (those of band b+2, requested in this band, may still be on
             // their way) and so has everything requested before this band began; all waves are done with band b
-            "s_cmp_eq_u32 s92, 0\n\t"
-            "s_cbranch_scc1 .Lsh_drain_%=\n\t"
             SH_WAIT_FILLS
             SH_BAND_BARRIER
             "s_max_u32 s82, s82, s83\n\t"
-            "s_branch .Lsh_sync_%=\n"
-            ".Lsh_drain_%=:\n\t"
-            "s_waitcnt vmcnt(0)\n\t"
-            SH_BAND_BARRIER
-            "s_mov_b32 s82, s69\n"
-            ".Lsh_sync_%=:\n\t"
             "s_mov_b64 s[66:67], s[90:91]\n\t"
             "s_add_u32 s88, s88, 0xC000\n\t"
             "s_cmp_lt_u32 s88, 0x24000\n\t"
@@ -451,6 +427,14 @@ __global__ __launch_bounds__(64 * kShareW) void spdm_share(ShareArgs a, int64_t 
             "s_add_u32 s64, s64, 1\n\t"
             "s_cmp_lt_u32 s64, s65\n\t"
             "s_cbranch_scc1 .Lsh_band_%=\n\t"
+            "s_branch .Lsh_done_%=\n"
+            // a band in which this wave has no entry
+            ".Lsh_empty_%=:\n\t"
+            SH_FILL_BAND(5)
+            "s_branch .Lsh_nos_%=\n"
+            // the rows requested for the bands beyond the last one arrive before the wave gives up its LDS
+            ".Lsh_done_%=:\n\t"
+            "s_waitcnt vmcnt(0)\n\t"
             : "+{v[60:63]}"(acc.t0), "+{v[64:95]}"(acc.t1), "+{v[96:127]}"(acc.t2), "+{v[128:159]}"(acc.t3),
               "+{v[160:191]}"(acc.t4), "+{v[192:223]}"(acc.t5), "+{v[224:255]}"(acc.t6)
             : [hdr] "s"(hdr), [strm] "s"(strm), [uc] "s"(uc), [bt] "s"(bt), [nb] "s"(nb), [ldb4] "s"(ldb4), [ring] "s"(ring),
@@ -460,7 +444,7 @@ __global__ __launch_bounds__(64 * kShareW) void spdm_share(ShareArgs a, int64_t 
               "v51", "v52", "v54", "v55", "v56", "v57", "v4", "v5", "v6", "v7", "v8", "v9", "v10", "v11", "v12", "v13", "v14", "v15",
               "v16", "v17", "v18", "v19", "s64", "s65", "s66", "s67", "s68", "s69", "s70", "s71", "s72", "s73",
               "s74", "s75", "s76", "s77", "s78", "s79", "s80", "s81", "s82", "s83", "s84", "s85", "s86", "s87", "s88", "s89", "s90",
-              "s91", "s92");
+              "s91");
     }
 
     // The lane's columns once more, from a thread index the compiler cannot connect with the one above: the loop
