@@ -758,7 +758,8 @@ namespace {
 
 bool share_operands_ok(const gcoo_matrix* A, const Shape& sh, int64_t ldb)
 {
-    return sh.al4 && (uint64_t)A->k * (uint64_t)ldb * 4u <= 0xffffffffull;
+    // (the kernel keeps byte offsets into B in 32 bits, each up to 3072 above the place it stands for)
+    return sh.al4 && (uint64_t)A->k * (uint64_t)ldb * 4u <= 0xffffffffull - 4096u;
 }
 
 int check_spdm_args(const gcoo_matrix* A, const float* B, int64_t ldb, int64_t N, const float* C, int64_t ldc)

@@ -70,17 +70,18 @@ __device__ __forceinline__ float share_acc_get(const ShareAcc& a, int reg)
 // Fixed registers of the main loop (all named in the clobber list):
 //   v[20:35]  four sets of B values (sets 0..3)   v[4:19]  four more (sets 4..7: the singles of a band alternate between the two)
 //   v[36:39]  four LDS addresses
-//   v3 v43 v53 v58 v59  inputs that stay as they are: the lane's place in a vector of columns, the shift that packs a
+//   v3 v43 v51 v53 v58 v59  inputs that stay as they are: the lane's place in a vector of columns, the shift that packs a
 //             record's row, the lane's place in the wave's ring, lane*16 (0 for lanes beyond N) and lane*16
 //   v40 v41 v42  values, packed rows (the four rows of a record's group of four, one byte each), offsets of this block
 //   v[44:47]  records of the next block    v48 lane*16 + band buffer
-//   v49  byte offsets of the rows to fetch, ten bands     v50 v51 scratch     v52 columns of the ten bands after those
+//   v49  byte offsets of the rows to fetch, two bands     v50 scratch     v52 columns of the two bands after those
+//   v51  (input) what every offset in v49 carries beside the row's place in B
 //   v[54:55]  (quads, singles) of 64 bands  v[56:57] of the 64 bands after those
 //   s64 band  s65 bands  s66 s67 quads and groups of four singles of this band  s[90:91] of the next
 //   s68 blocks read from the ring  s69 pieces of the stream requested  s82 of which known to have landed  s83 s69 at the start of the band
-//   s70 s86 packed rows  s71 s72 scratch  s73 loop count
+//   s70 s86 packed rows  s71 scratch  s73 loop count
 //   s[74:75] header pointer (next 64 bands)  s[76:77] stream pointer (next piece)  s[78:79] ucols of the super-group
-//   s80 first band of the column vector after v52  s81 lane of v49 that holds the next row to fetch
+//   s80 the pair of bands whose columns are requested next
 //   s88 LDS address of this band's buffer  s89 of the buffer that the next rows go to
 #define SH_DPP(i) " row_newbcast:" #i " row_mask:0xf bank_mask:0xf\n\t"
 #define SH_ADDR(dst, src, i) "v_add_u32_dpp " #dst ", " #src ", v48" SH_DPP(i)
@@ -95,9 +96,9 @@ __device__ __forceinline__ float share_acc_get(const ShareAcc& a, int reg)
 #define GCOO_SHARE_ABLATE 0
 #endif
 #if GCOO_SHARE_ABLATE & 1
-#define SH_FILL_LOAD ""
+#define SH_FILL_LOAD(off) ""
 #else
-#define SH_FILL_LOAD "global_load_lds_dwordx4 v50, %[bt]\n\t"
+#define SH_FILL_LOAD(off) "global_load_lds_dwordx4 v50, %[bt] offset:" #off "\n\t"
 #endif
 #if GCOO_SHARE_ABLATE & 4
 #define SH_BAND_BARRIER ""
@@ -115,17 +116,18 @@ __device__ __forceinline__ float share_acc_get(const ShareAcc& a, int reg)
 #define SH_WAIT_FILLS "s_waitcnt vmcnt(6)\n\t"
 #endif
 // one entry: record i of this block, its row in the low byte of `rows`, its B values in b0..b3
+// (SH_FMACL: the last entry of its group of four, after which the packed rows are not needed any more)
 #if GCOO_SHARE_ABLATE & 2
-#define SH_FMAC(i, rows, b0, b1, b2, b3) "s_lshr_b32 " #rows ", " #rows ", 8\n\t"
+#define SH_FMACL(i, rows, b0, b1, b2, b3) ""
 #else
-#define SH_FMAC(i, rows, b0, b1, b2, b3)                    \
+#define SH_FMACL(i, rows, b0, b1, b2, b3)                   \
     "s_set_gpr_idx_on " #rows ", gpr_idx(SRC2,DST)\n\t"      \
     "v_fmac_f32_dpp v60, v40, " #b0 SH_DPP(i)                \
     "v_fmac_f32_dpp v109, v40, " #b1 SH_DPP(i)               \
     "v_fmac_f32_dpp v158, v40, " #b2 SH_DPP(i)               \
-    "v_fmac_f32_dpp v207, v40, " #b3 SH_DPP(i)               \
-    "s_lshr_b32 " #rows ", " #rows ", 8\n\t"
+    "v_fmac_f32_dpp v207, v40, " #b3 SH_DPP(i)
 #endif
+#define SH_FMAC(i, rows, b0, b1, b2, b3) SH_FMACL(i, rows, b0, b1, b2, b3) "s_lshr_b32 " #rows ", " #rows ", 8\n\t"
 #define SH_FMAC_SET0(i, rows) SH_FMAC(i, rows, v20, v21, v22, v23)
 #define SH_FMAC_SET1(i, rows) SH_FMAC(i, rows, v24, v25, v26, v27)
 #define SH_FMAC_SET2(i, rows) SH_FMAC(i, rows, v28, v29, v30, v31)
@@ -134,6 +136,14 @@ __device__ __forceinline__ float share_acc_get(const ShareAcc& a, int reg)
 #define SH_FMAC_SET5(i, rows) SH_FMAC(i, rows, v8, v9, v10, v11)
 #define SH_FMAC_SET6(i, rows) SH_FMAC(i, rows, v12, v13, v14, v15)
 #define SH_FMAC_SET7(i, rows) SH_FMAC(i, rows, v16, v17, v18, v19)
+#define SH_FMACL_SET0(i, rows) SH_FMACL(i, rows, v20, v21, v22, v23)
+#define SH_FMACL_SET1(i, rows) SH_FMACL(i, rows, v24, v25, v26, v27)
+#define SH_FMACL_SET2(i, rows) SH_FMACL(i, rows, v28, v29, v30, v31)
+#define SH_FMACL_SET3(i, rows) SH_FMACL(i, rows, v32, v33, v34, v35)
+#define SH_FMACL_SET4(i, rows) SH_FMACL(i, rows, v4, v5, v6, v7)
+#define SH_FMACL_SET5(i, rows) SH_FMACL(i, rows, v8, v9, v10, v11)
+#define SH_FMACL_SET6(i, rows) SH_FMACL(i, rows, v12, v13, v14, v15)
+#define SH_FMACL_SET7(i, rows) SH_FMACL(i, rows, v16, v17, v18, v19)
 #define SH_READ_SET0 "ds_read_b128 v[20:23], v36\n\t"
 #define SH_READ_SET1 "ds_read_b128 v[24:27], v37\n\t"
 #define SH_READ_SET2 "ds_read_b128 v[28:31], v38\n\t"
@@ -182,33 +192,41 @@ __device__ __forceinline__ float share_acc_get(const ShareAcc& a, int reg)
     "v_add_u32 v50, s71, v53\n\t"                                                           \
     "ds_read_b128 v[44:47], v50\n\t"
 
-// One row of B to LDS: row t of the wave's six in the buffer at s72; its byte offset in B is lane s81 of v49.
-#define SH_FILL(t)                                                    \
-    "s_add_u32 m0, s72, " #t "*1024\n\t"                              \
-    "v_readlane_b32 s71, v49, s81\n\t"                                \
-    "s_add_u32 s81, s81, 1\n\t"                                       \
-    "v_add_u32 v50, s71, v58\n\t"                                 \
-    SH_FILL_LOAD
-// The six rows of the next band to fetch, to the buffer at s89 (which then moves on by one buffer).  When the
-// lanes of v49 are used up, the next ten bands' offsets are made from v52 and the columns of the ten
-// bands after those are requested.
-#define SH_FILL_BAND(L)                                               \
-    "s_cmp_lg_u32 s81, 60\n\t"                                        \
-    "s_cbranch_scc1 .Lsh_fill_go" #L "_%=\n\t"                        \
+// The byte offsets in B of the rows this wave fetches sit in v49 as a ring of 16 per row of 16 lanes (all four rows
+// of lanes hold the same 16): positions 0..5 = the wave's six rows of an even band, 6..11 = of the odd band after it,
+// so that a DPP row broadcast puts a row's offset in front of every lane's column offset in one instruction.
+// Every offset carries +3072 - 1024 * (t & 3), t = the row's place among the six, and the base pointer -3072: the
+// loads of rows 0..3 and 4..5 then differ only in their immediate offsets, which also move the LDS address, and
+// M0 is written twice per band instead of once per row.
+#define SH_FILL_ROW(r, off) "v_add_u32_dpp v50, v49, v58 row_newbcast:" #r " row_mask:0xf bank_mask:0xf\n\t" SH_FILL_LOAD(off)
+#define SH_FILL_SIX(r0, r1, r2, r3, r4, r5)                                                         \
+    "s_add_u32 m0, s89, %[fillw]\n\t"                                                               \
+    SH_FILL_ROW(r0, 0) SH_FILL_ROW(r1, 1024) SH_FILL_ROW(r2, 2048) SH_FILL_ROW(r3, 3072)            \
+    "s_add_u32 m0, m0, 0x1000\n\t"                                                                  \
+    SH_FILL_ROW(r4, 0) SH_FILL_ROW(r5, 1024)
+// A new pair of bands: their offsets from the columns in v52, and the columns of the pair after them (pair s80)
+// requested; lanes past the last column of the super-group repeat it.
+#define SH_FILL_NEW_PAIR                                              \
     "v_mul_lo_u32 v49, v52, %[ldb4]\n\t"                              \
-    "s_mul_i32 s71, s80, 48\n\t"                                      \
-    "v_add_u32 v50, s71, v3\n\t"                                 \
+    "s_mul_i32 s71, s80, 96\n\t"                                      \
+    "v_add_u32 v49, v49, v51\n\t"                                     \
+    "v_add_u32 v50, s71, v3\n\t"                                      \
     "v_min_u32 v50, v50, %[last]\n\t"                                 \
     "v_lshlrev_b32 v50, 2, v50\n\t"                                   \
     "global_load_dword v52, v50, s[78:79]\n\t"                        \
-    "s_add_u32 s80, s80, 10\n\t"                                      \
-    "s_mov_b32 s81, 0\n"                                              \
-    ".Lsh_fill_go" #L "_%=:\n\t"                                      \
-    "s_add_u32 s72, s89, %[fillw]\n\t"                                \
-    SH_FILL(0) SH_FILL(1) SH_FILL(2) SH_FILL(3) SH_FILL(4) SH_FILL(5) \
-    "s_add_u32 s89, s89, 0xC000\n\t"                                  \
-    "s_cmp_lt_u32 s89, 0x24000\n\t"                                   \
-    "s_cselect_b32 s89, s89, 0\n\t"
+    "s_add_u32 s80, s80, 1\n\t"
+// The six rows of the band after next (band s64 + 2), to the buffer before this band's.
+#define SH_FILL_BAND(L)                                               \
+    "s_sub_u32 s89, s88, 0xC000\n\t"                                  \
+    "s_cselect_b32 s89, 0x18000, s89\n\t"                             \
+    "s_bitcmp1_b32 s64, 0\n\t"                                        \
+    "s_cbranch_scc1 .Lsh_fill_odd" #L "_%=\n\t"                       \
+    SH_FILL_NEW_PAIR                                                  \
+    SH_FILL_SIX(0, 1, 2, 3, 4, 5)                                     \
+    "s_branch .Lsh_fill_end" #L "_%=\n"                               \
+    ".Lsh_fill_odd" #L "_%=:\n\t"                                     \
+    SH_FILL_SIX(6, 7, 8, 9, 10, 11)                                   \
+    ".Lsh_fill_end" #L "_%=:\n\t"
 
 __global__ __launch_bounds__(64 * kShareW) void spdm_share(ShareArgs a, int64_t total)
 {
@@ -240,14 +258,16 @@ __global__ __launch_bounds__(64 * kShareW) void spdm_share(ShareArgs a, int64_t 
         const uint32_t* hdr = a.hdr + 2 * (hb * kShareW + wv * cap);
         const uint32_t* strm = a.blocks + (int64_t)__builtin_amdgcn_readfirstlane(a.sbase[q]) * kShareBlockWords;
         const int32_t* uc = a.ucols + first;
-        const char* bt = reinterpret_cast<const char*>(a.B + tile * 256);
+        const char* bt = reinterpret_cast<const char*>(a.B + tile * 256) - 3072;   // see SH_FILL_SIX
         const uint32_t ldb4 = (uint32_t)a.ldb * 4u;                // the launcher checks that every row offset fits 32 bits
         const uint32_t l16 = (uint32_t)lane * 16u;
         const uint32_t l16g = in ? l16 : 0u;                       // lanes beyond N fetch the first columns of the tile
         const uint32_t sh8 = (uint32_t)(lane & 3) * 8u;
-        // lane 6i + t of a column vector: row t of the wave's six in band (first band of the vector) + i
-        const int li = lane < 60 ? lane : 59;
+        // place 6i + t of the ring of 16 (lane & 15; the last four places repeat the twelfth): row t of the wave's
+        // six in band i of a pair of bands
+        const int li = (lane & 15) < 12 ? (lane & 15) : 11;
         const uint32_t cidx = (uint32_t)((li / 6) * kShareBandRows + wv * 6 + li % 6);
+        const uint32_t fbias = 3072u - (uint32_t)((li % 6) & 3) * 1024u;
         const uint32_t ring = (uint32_t)(3 * kShareBandBytes + wv * kShareRingBytes);
         const uint32_t rl = ring + (uint32_t)(lane & 15) * 16u;
         const uint32_t fillw = (uint32_t)wv * 6144u;               // the wave's six rows inside a band buffer
@@ -263,9 +283,7 @@ __global__ __launch_bounds__(64 * kShareW) void spdm_share(ShareArgs a, int64_t 
             "s_mov_b32 s69, 2\n\t"
             "s_mov_b32 s82, 2\n\t"
             "s_mov_b32 s88, 0\n\t"
-            "s_mov_b32 s89, 0\n\t"
-            "s_mov_b32 s81, 0\n\t"
-            "s_mov_b32 s80, 20\n\t"
+            "s_mov_b32 s80, 1\n\t"
             "s_mov_b32 m0, %[ring]\n\t"
             "s_nop 0\n\t"
             "global_load_lds_dwordx4 v59, s[76:77]\n\t"
@@ -283,20 +301,18 @@ __global__ __launch_bounds__(64 * kShareW) void spdm_share(ShareArgs a, int64_t 
             "s_addc_u32 s75, s75, 0\n\t"
             "v_min_u32 v50, v3, %[last]\n\t"
             "v_lshlrev_b32 v50, 2, v50\n\t"
-            "global_load_dword v51, v50, s[78:79]\n\t"
-            "v_add_u32 v50, 480, v3\n\t"
-            "v_min_u32 v50, v50, %[last]\n\t"
-            "v_lshlrev_b32 v50, 2, v50\n\t"
             "global_load_dword v52, v50, s[78:79]\n\t"
             "s_waitcnt vmcnt(0)\n\t"
-            "v_mul_lo_u32 v49, v51, %[ldb4]\n\t"
             "v_readlane_b32 s66, v54, 0\n\t"
             "v_readlane_b32 s67, v55, 0\n\t"
             "ds_read_b128 v[44:47], v53\n\t"
             // (bands beyond the last one are requested like any other: their columns are clamped to the last
             // column of the super-group, their rows go to a buffer that nobody reads)
-            SH_FILL_BAND(0)
-            SH_FILL_BAND(1)
+            "s_mov_b32 s89, 0\n\t"
+            SH_FILL_NEW_PAIR
+            SH_FILL_SIX(0, 1, 2, 3, 4, 5)
+            "s_mov_b32 s89, 0xC000\n\t"
+            SH_FILL_SIX(6, 7, 8, 9, 10, 11)
             "s_waitcnt vmcnt(6) lgkmcnt(0)\n\t"
             "s_barrier\n\t"
             SH_ADVANCE(0)
@@ -320,7 +336,7 @@ __global__ __launch_bounds__(64 * kShareW) void spdm_share(ShareArgs a, int64_t 
             "s_cbranch_scc1 .Lsh_qend_%=\n\t"
             SH_ROWS(s86, 4)
             SH_WAIT3
-            SH_FMAC_SET0(0, s70) SH_FMAC_SET0(1, s70) SH_FMAC_SET0(2, s70) SH_FMAC_SET0(3, s70)
+            SH_FMAC_SET0(0, s70) SH_FMAC_SET0(1, s70) SH_FMAC_SET0(2, s70) SH_FMACL_SET0(3, s70)
             SH_OFF
             "s_waitcnt lgkmcnt(0)\n\t"
             SH_ADDR(v36, v46, 0)
@@ -331,7 +347,7 @@ __global__ __launch_bounds__(64 * kShareW) void spdm_share(ShareArgs a, int64_t 
             SH_ROWS(s70, 8)
             SH_ADDR(v37, v46, 4)
             "s_waitcnt lgkmcnt(1)\n\t"
-            SH_FMAC_SET1(4, s86) SH_FMAC_SET1(5, s86) SH_FMAC_SET1(6, s86) SH_FMAC_SET1(7, s86)
+            SH_FMAC_SET1(4, s86) SH_FMAC_SET1(5, s86) SH_FMAC_SET1(6, s86) SH_FMACL_SET1(7, s86)
             SH_READ_SET1
             SH_OFF
             // quad 2
@@ -340,7 +356,7 @@ __global__ __launch_bounds__(64 * kShareW) void spdm_share(ShareArgs a, int64_t 
             SH_ROWS(s86, 12)
             SH_ADDR(v38, v46, 8)
             "s_waitcnt lgkmcnt(2)\n\t"
-            SH_FMAC_SET2(8, s70) SH_FMAC_SET2(9, s70) SH_FMAC_SET2(10, s70) SH_FMAC_SET2(11, s70)
+            SH_FMAC_SET2(8, s70) SH_FMAC_SET2(9, s70) SH_FMAC_SET2(10, s70) SH_FMACL_SET2(11, s70)
             SH_READ_SET2
             SH_OFF
             // quad 3
@@ -348,7 +364,7 @@ __global__ __launch_bounds__(64 * kShareW) void spdm_share(ShareArgs a, int64_t 
             "s_cbranch_scc1 .Lsh_qend_%=\n\t"
             SH_ADDR(v39, v46, 12)
             SH_WAIT3
-            SH_FMAC_SET3(12, s86) SH_FMAC_SET3(13, s86) SH_FMAC_SET3(14, s86) SH_FMAC_SET3(15, s86)
+            SH_FMAC_SET3(12, s86) SH_FMAC_SET3(13, s86) SH_FMAC_SET3(14, s86) SH_FMACL_SET3(15, s86)
             SH_READ_SET3
             SH_OFF
             "s_cmp_eq_u32 s73, 0\n\t"
@@ -388,13 +404,13 @@ __global__ __launch_bounds__(64 * kShareW) void spdm_share(ShareArgs a, int64_t 
             F0 F1 F2 F3                                                               \
             SH_OFF
             SH_GROUP(v42, 4, 5, 6, 7, SH_READ_SET4, SH_READ_SET5, SH_READ_SET6, SH_READ_SET7, SH_ROWS(s86, 4),
-                     SH_FMAC_SET0(0, s70), SH_FMAC_SET1(1, s70), SH_FMAC_SET2(2, s70), SH_FMAC_SET3(3, s70))
+                     SH_FMAC_SET0(0, s70), SH_FMAC_SET1(1, s70), SH_FMAC_SET2(2, s70), SH_FMACL_SET3(3, s70))
             SH_GROUP(v42, 8, 9, 10, 11, SH_READ_SET0, SH_READ_SET1, SH_READ_SET2, SH_READ_SET3, SH_ROWS(s70, 8),
-                     SH_FMAC_SET4(4, s86), SH_FMAC_SET5(5, s86), SH_FMAC_SET6(6, s86), SH_FMAC_SET7(7, s86))
+                     SH_FMAC_SET4(4, s86), SH_FMAC_SET5(5, s86), SH_FMAC_SET6(6, s86), SH_FMACL_SET7(7, s86))
             SH_GROUP(v42, 12, 13, 14, 15, SH_READ_SET4, SH_READ_SET5, SH_READ_SET6, SH_READ_SET7, SH_ROWS(s86, 12),
-                     SH_FMAC_SET0(8, s70), SH_FMAC_SET1(9, s70), SH_FMAC_SET2(10, s70), SH_FMAC_SET3(11, s70))
+                     SH_FMAC_SET0(8, s70), SH_FMAC_SET1(9, s70), SH_FMAC_SET2(10, s70), SH_FMACL_SET3(11, s70))
             SH_GROUP(v46, 0, 1, 2, 3, SH_READ_SET0, SH_READ_SET1, SH_READ_SET2, SH_READ_SET3, "",
-                     SH_FMAC_SET4(12, s86), SH_FMAC_SET5(13, s86), SH_FMAC_SET6(14, s86), SH_FMAC_SET7(15, s86))
+                     SH_FMAC_SET4(12, s86), SH_FMAC_SET5(13, s86), SH_FMAC_SET6(14, s86), SH_FMACL_SET7(15, s86))
             "s_cmp_eq_u32 s73, 0\n\t"
             "s_cbranch_scc1 .Lsh_send_%=\n\t"
             SH_ADVANCE(3)
@@ -438,12 +454,12 @@ __global__ __launch_bounds__(64 * kShareW) void spdm_share(ShareArgs a, int64_t 
             : "+{v[60:63]}"(acc.t0), "+{v[64:95]}"(acc.t1), "+{v[96:127]}"(acc.t2), "+{v[128:159]}"(acc.t3),
               "+{v[160:191]}"(acc.t4), "+{v[192:223]}"(acc.t5), "+{v[224:255]}"(acc.t6)
             : [hdr] "s"(hdr), [strm] "s"(strm), [uc] "s"(uc), [bt] "s"(bt), [nb] "s"(nb), [ldb4] "s"(ldb4), [ring] "s"(ring),
-              [fillw] "s"(fillw), [last] "s"(last), "{v59}"(l16), "{v58}"(l16g), "{v43}"(sh8), "{v3}"(cidx), "{v53}"(rl)
+              [fillw] "s"(fillw), [last] "s"(last), "{v59}"(l16), "{v58}"(l16g), "{v43}"(sh8), "{v3}"(cidx), "{v53}"(rl), "{v51}"(fbias)
             : "m0", "scc", "memory", "v20", "v21", "v22", "v23", "v24", "v25", "v26", "v27", "v28", "v29", "v30", "v31", "v32", "v33",
               "v34", "v35", "v36", "v37", "v38", "v39", "v40", "v41", "v42", "v44", "v45", "v46", "v47", "v48", "v49", "v50",
-              "v51", "v52", "v54", "v55", "v56", "v57", "v4", "v5", "v6", "v7", "v8", "v9", "v10", "v11", "v12", "v13", "v14", "v15",
-              "v16", "v17", "v18", "v19", "s64", "s65", "s66", "s67", "s68", "s69", "s70", "s71", "s72", "s73",
-              "s74", "s75", "s76", "s77", "s78", "s79", "s80", "s81", "s82", "s83", "s84", "s85", "s86", "s87", "s88", "s89", "s90",
+              "v52", "v54", "v55", "v56", "v57", "v4", "v5", "v6", "v7", "v8", "v9", "v10", "v11", "v12", "v13", "v14", "v15",
+              "v16", "v17", "v18", "v19", "s64", "s65", "s66", "s67", "s68", "s69", "s70", "s71", "s73",
+              "s74", "s75", "s76", "s77", "s78", "s79", "s80", "s82", "s83", "s84", "s85", "s86", "s87", "s88", "s89", "s90",
               "s91");
     }
 

@@ -192,7 +192,8 @@ def check_lds_loads(asm_text: str, mangled_prefix: str, in_flight: int = 0):
     Such a load takes the LDS address of lane 0 from M0, and `s_set_gpr_idx_on/idx` overwrite M0.
     Returns (number of such loads, list of problems).  Proved on the text, block by block:
       * walking back from every such load, an instruction that writes M0 as a plain destination
-        (`s_mov_b32 m0`, `s_add_i32 m0`, ...) comes before any label, branch or index-mode instruction;
+        (`s_mov_b32 m0`, `s_add_i32 m0`, ...) comes before any label, branch or index-mode instruction
+        (other loads to LDS in between are passed over: they leave M0 as it is);
       * walking back from every `s_barrier`, an `s_waitcnt` that names vmcnt(n), n <= in_flight, comes before
         any such load (what a wave has sent to LDS has arrived before the other waves are let past the
         barrier, except the youngest in_flight loads, which a kernel may keep on their way on purpose).
@@ -209,7 +210,7 @@ def check_lds_loads(asm_text: str, mangled_prefix: str, in_flight: int = 0):
                 t = body[j]
                 if re.match(r"^s_\w+\s+m0\b", t):
                     break
-                if _LABEL.match(t) or _BRANCH.match(t) or t.startswith("s_set_gpr_idx") or t.startswith("global_load_lds"):
+                if _LABEL.match(t) or _BRANCH.match(t) or t.startswith("s_set_gpr_idx"):
                     problems.append(f"line {i}: '{line}' has no M0 write of its own (stopped at '{t}')")
                     break
                 j -= 1

@@ -90,13 +90,13 @@ __global__ __launch_bounds__(512) void issue(int iters, float* out)
             "s_mov_b32 s73, 1000\n\t"
             SH_ROWS(s70, 0)
             SH_GROUP(v42, 4, 5, 6, 7, SH_READ_SET4, SH_READ_SET5, SH_READ_SET6, SH_READ_SET7, SH_ROWS(s86, 4),
-                     SH_FMAC_SET0(0, s70), SH_FMAC_SET1(1, s70), SH_FMAC_SET2(2, s70), SH_FMAC_SET3(3, s70))
+                     SH_FMAC_SET0(0, s70), SH_FMAC_SET1(1, s70), SH_FMAC_SET2(2, s70), SH_FMACL_SET3(3, s70))
             SH_GROUP(v42, 8, 9, 10, 11, SH_READ_SET0, SH_READ_SET1, SH_READ_SET2, SH_READ_SET3, SH_ROWS(s70, 8),
-                     SH_FMAC_SET4(4, s86), SH_FMAC_SET5(5, s86), SH_FMAC_SET6(6, s86), SH_FMAC_SET7(7, s86))
+                     SH_FMAC_SET4(4, s86), SH_FMAC_SET5(5, s86), SH_FMAC_SET6(6, s86), SH_FMACL_SET7(7, s86))
             SH_GROUP(v42, 12, 13, 14, 15, SH_READ_SET4, SH_READ_SET5, SH_READ_SET6, SH_READ_SET7, SH_ROWS(s86, 12),
-                     SH_FMAC_SET0(8, s70), SH_FMAC_SET1(9, s70), SH_FMAC_SET2(10, s70), SH_FMAC_SET3(11, s70))
+                     SH_FMAC_SET0(8, s70), SH_FMAC_SET1(9, s70), SH_FMAC_SET2(10, s70), SH_FMACL_SET3(11, s70))
             SH_GROUP(v46, 0, 1, 2, 3, SH_READ_SET0, SH_READ_SET1, SH_READ_SET2, SH_READ_SET3, "",
-                     SH_FMAC_SET4(12, s86), SH_FMAC_SET5(13, s86), SH_FMAC_SET6(14, s86), SH_FMAC_SET7(15, s86))
+                     SH_FMAC_SET4(12, s86), SH_FMAC_SET5(13, s86), SH_FMAC_SET6(14, s86), SH_FMACL_SET7(15, s86))
             "s_sub_u32 s74, s74, 1\n\t"
             "s_cmp_lg_u32 s74, 0\n\t"
             "s_cbranch_scc1 .Lq_loop_%=\n"
@@ -122,18 +122,18 @@ __global__ __launch_bounds__(512) void issue(int iters, float* out)
             SH_ADDR(v36, v42, 0) SH_ADDR(v37, v42, 4) SH_ADDR(v38, v42, 8) SH_ADDR(v39, v42, 12)
             SH_READ_SET0 SH_READ_SET1 SH_READ_SET2 SH_READ_SET3
             SH_WAIT3
-            SH_FMAC_SET0(0, s70) SH_FMAC_SET0(1, s70) SH_FMAC_SET0(2, s70) SH_FMAC_SET0(3, s70)
+            SH_FMAC_SET0(0, s70) SH_FMAC_SET0(1, s70) SH_FMAC_SET0(2, s70) SH_FMACL_SET0(3, s70)
             SH_OFF
             SH_ROWS(s70, 8)
             "s_waitcnt lgkmcnt(2)\n\t"
-            SH_FMAC_SET1(4, s86) SH_FMAC_SET1(5, s86) SH_FMAC_SET1(6, s86) SH_FMAC_SET1(7, s86)
+            SH_FMAC_SET1(4, s86) SH_FMAC_SET1(5, s86) SH_FMAC_SET1(6, s86) SH_FMACL_SET1(7, s86)
             SH_OFF
             SH_ROWS(s86, 12)
             "s_waitcnt lgkmcnt(1)\n\t"
-            SH_FMAC_SET2(8, s70) SH_FMAC_SET2(9, s70) SH_FMAC_SET2(10, s70) SH_FMAC_SET2(11, s70)
+            SH_FMAC_SET2(8, s70) SH_FMAC_SET2(9, s70) SH_FMAC_SET2(10, s70) SH_FMACL_SET2(11, s70)
             SH_OFF
             "s_waitcnt lgkmcnt(0)\n\t"
-            SH_FMAC_SET3(12, s86) SH_FMAC_SET3(13, s86) SH_FMAC_SET3(14, s86) SH_FMAC_SET3(15, s86)
+            SH_FMAC_SET3(12, s86) SH_FMAC_SET3(13, s86) SH_FMAC_SET3(14, s86) SH_FMACL_SET3(15, s86)
             SH_OFF
             "s_sub_u32 s74, s74, 1\n\t"
             "s_cmp_lg_u32 s74, 0\n\t"
@@ -392,6 +392,63 @@ VALU_KERNEL(0)
 VALU_KERNEL(1)
 VALU_KERNEL(2)
 
+// ---------------------------------------------------------------- 2c. what scalar instructions and branches cost a wave
+// 8 waves per workgroup, one workgroup per compute unit (two waves per SIMD, as in the kernels).  One turn of the
+// loop is 16 instructions of one kind: 0 independent s_add_u32; 1 eight compare-and-branch pairs, never taken;
+// 2 eight pairs, always taken (to the next instruction); 3 eight pairs of a v_readlane_b32 and a scalar add that
+// uses its result; 4 sixteen dependent v_add_u32.
+#define REP8(x) x x x x x x x x
+template <int KIND>
+__global__ __launch_bounds__(512) void scalar_cost(int iters, unsigned* sink)
+{
+    unsigned v = threadIdx.x, r = 0;
+    if constexpr (KIND == 0) {
+        asm volatile("s_mov_b32 s74, %[iters]\n"
+                     ".Lsc_loop_%=:\n\t"
+                     REP8("s_add_u32 s70, s70, 1\n\ts_add_u32 s71, s71, 3\n\t")
+                     "s_sub_u32 s74, s74, 1\n\ts_cmp_lg_u32 s74, 0\n\ts_cbranch_scc1 .Lsc_loop_%=\n\t"
+                     "v_mov_b32 %[r], s70\n\t"
+                     : [r] "=v"(r) : [iters] "s"(iters) : "scc", "s70", "s71", "s74");
+    } else if constexpr (KIND == 1) {
+        asm volatile("s_mov_b32 s74, %[iters]\n\ts_mov_b32 s70, 0\n"
+                     ".Lsc_loop_%=:\n\t"
+                     REP8("s_cmp_eq_u32 s70, 12345\n\ts_cbranch_scc1 .Lsc_out_%=\n\t")
+                     "s_sub_u32 s74, s74, 1\n\ts_cmp_lg_u32 s74, 0\n\ts_cbranch_scc1 .Lsc_loop_%=\n"
+                     ".Lsc_out_%=:\n\t"
+                     "v_mov_b32 %[r], s70\n\t"
+                     : [r] "=v"(r) : [iters] "s"(iters) : "scc", "s70", "s71", "s74");
+    } else if constexpr (KIND == 2) {
+        asm volatile("s_mov_b32 s74, %[iters]\n\ts_mov_b32 s70, 0\n"
+                     ".Lsc_loop_%=:\n\t"
+                     "s_cmp_eq_u32 s70, 0\n\ts_cbranch_scc1 .Lsc_a_%=\n.Lsc_a_%=:\n\t"
+                     "s_cmp_eq_u32 s70, 0\n\ts_cbranch_scc1 .Lsc_b_%=\n.Lsc_b_%=:\n\t"
+                     "s_cmp_eq_u32 s70, 0\n\ts_cbranch_scc1 .Lsc_c_%=\n.Lsc_c_%=:\n\t"
+                     "s_cmp_eq_u32 s70, 0\n\ts_cbranch_scc1 .Lsc_d_%=\n.Lsc_d_%=:\n\t"
+                     "s_cmp_eq_u32 s70, 0\n\ts_cbranch_scc1 .Lsc_e_%=\n.Lsc_e_%=:\n\t"
+                     "s_cmp_eq_u32 s70, 0\n\ts_cbranch_scc1 .Lsc_f_%=\n.Lsc_f_%=:\n\t"
+                     "s_cmp_eq_u32 s70, 0\n\ts_cbranch_scc1 .Lsc_g_%=\n.Lsc_g_%=:\n\t"
+                     "s_cmp_eq_u32 s70, 0\n\ts_cbranch_scc1 .Lsc_h_%=\n.Lsc_h_%=:\n\t"
+                     "s_sub_u32 s74, s74, 1\n\ts_cmp_lg_u32 s74, 0\n\ts_cbranch_scc1 .Lsc_loop_%=\n\t"
+                     "v_mov_b32 %[r], s70\n\t"
+                     : [r] "=v"(r) : [iters] "s"(iters) : "scc", "s70", "s71", "s74");
+    } else if constexpr (KIND == 3) {
+        asm volatile("s_mov_b32 s74, %[iters]\n\ts_mov_b32 s72, 0\n"
+                     ".Lsc_loop_%=:\n\t"
+                     REP8("v_readlane_b32 s71, %[v], 3\n\ts_add_u32 s72, s72, s71\n\t")
+                     "s_sub_u32 s74, s74, 1\n\ts_cmp_lg_u32 s74, 0\n\ts_cbranch_scc1 .Lsc_loop_%=\n\t"
+                     "v_mov_b32 %[r], s72\n\t"
+                     : [r] "=v"(r) : [iters] "s"(iters), [v] "v"(v) : "scc", "s70", "s71", "s72", "s74");
+    } else {
+        asm volatile("s_mov_b32 s74, %[iters]\n"
+                     ".Lsc_loop_%=:\n\t"
+                     REP8("v_add_u32 %[v], 1, %[v]\n\tv_add_u32 %[v], 3, %[v]\n\t")
+                     "s_sub_u32 s74, s74, 1\n\ts_cmp_lg_u32 s74, 0\n\ts_cbranch_scc1 .Lsc_loop_%=\n\t"
+                     "v_mov_b32 %[r], %[v]\n\t"
+                     : [r] "=v"(r), [v] "+v"(v) : [iters] "s"(iters) : "scc", "s74");
+    }
+    if (r == 0x7fffffffu) sink[0] = r;
+}
+
 // ---------------------------------------------------------------- 3. bands of a B tile straight to LDS
 // Workgroup = 8 waves; band b = 48 rows picked in ascending order from the tile's k rows (stride `gap` on
 // average), six rows per wave, to buffer b % 3; one barrier per band in front of which the loads of the band
@@ -518,7 +575,7 @@ int main()
         const char* names[5] = {"16 singles (address, LDS read, index mode, 4 multiply-adds each)  ", "4 quads (one LDS read per four entries)",
                                 "multiply-adds and index mode only", "plain v_fmac_f32 only",
                                 "16 singles the former way: four sets of B values, a wait per entry"};
-        const double instr[5] = {4 * (2 + 8 + 1 + 1 + 24 + 1) - 1 + 4, 119, 107, 67, 172};      // instructions of one turn of each loop (16 entries)
+        const double instr[5] = {4 * (2 + 8 + 1 + 1 + 23 + 1) - 1 + 4, 115, 107, 67, 172};      // instructions of one turn of each loop (16 entries)
         for (int mode = 0; mode < 5; ++mode) {
             const float ms = timed([&] {
                 if (mode == 0) issue<0><<<kCUs, 512, 3 * 49152>>>(iters, out);
@@ -544,6 +601,24 @@ int main()
         printf("issue  16 singles with 128 registers per wave, %d waves per SIMD: %.3f ms, %.2f ns per entry and wave -> %.0f us for the headline workload\n",
                2 * wgs, ms, ms * 1e6 / (16.0 * iters), kEntryTiles / (entries / ms) * 1e3);
         fflush(stdout);
+    }
+    // 2c
+    {
+        const int iters = 20000;
+        const char* names[5] = {"16 independent s_add_u32", "8 x (s_cmp, s_cbranch not taken)", "8 x (s_cmp, s_cbranch taken)",
+                                "8 x (v_readlane_b32, s_add_u32 of its result)", "16 dependent v_add_u32"};
+        for (int kind = 0; kind < 5; ++kind) {
+            const float ms = timed([&] {
+                if (kind == 0) scalar_cost<0><<<kCUs, 512>>>(iters, sink);
+                else if (kind == 1) scalar_cost<1><<<kCUs, 512>>>(iters, sink);
+                else if (kind == 2) scalar_cost<2><<<kCUs, 512>>>(iters, sink);
+                else if (kind == 3) scalar_cost<3><<<kCUs, 512>>>(iters, sink);
+                else scalar_cost<4><<<kCUs, 512>>>(iters, sink);
+            }, 3);
+            printf("scalar %-48s %.3f ms: %.2f ns per instruction and wave (two waves per SIMD, 19 instructions a turn)\n", names[kind], ms,
+                   ms * 1e6 / (19.0 * iters));
+            fflush(stdout);
+        }
     }
     // 2b
     CK(hipFuncSetAttribute((const void*)valu0, hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024));
