@@ -77,8 +77,8 @@ __device__ __forceinline__ float share_acc_get(const ShareAcc& a, int reg)
 //   v49  byte offsets of the rows to fetch, two bands     v50 scratch     v52 columns of the two bands after those
 //   v51  (input) what every offset in v49 carries beside the row's place in B
 //   v[54:55]  (quads, singles) of 64 bands  v[56:57] of the 64 bands after those
-//   s64 band  s65 bands  s66 s67 quads and groups of four singles of this band  s[90:91] of the next
-//   s68 blocks read from the ring  s69 pieces of the stream requested  s82 of which known to have landed  s83 s69 at the start of the band
+//   s64 band  s65 bands  s66 s67 quads and groups of four singles of this band (of the next one from the band's end on)
+//   s68 blocks read from the ring x 0x100  s69 pieces of the stream requested  s82 of which known to have landed  s83 s69 at the start of the band
 //   s70 s86 packed rows  s71 scratch  s73 loop count
 //   s[74:75] header pointer (next 64 bands)  s[76:77] stream pointer (next piece)  s[78:79] ucols of the super-group
 //   s80 the pair of bands whose columns are requested next
@@ -161,36 +161,37 @@ __device__ __forceinline__ float share_acc_get(const ShareAcc& a, int reg)
 // wave enters a new 1 KB piece of the stream: it has landed if it was requested before the band before
 // this one began (s82), otherwise all loads are awaited here; and the piece after it is requested for the
 // half of the ring whose blocks have all been read.
-// Index mode must be off.  L = a number unique to the expansion (local labels).
+// Index mode must be off.  L = a number unique to the expansion (local labels).  s68 counts blocks in steps of
+// 0x100, their size in bytes; the rare part (SH_ADVANCE_PIECE) stands out of line, behind the loop.
 #define SH_ADVANCE(L)                                                                         \
+    "v_lshlrev_b32 v41, v43, v45\n\t"                                                         \
     "v_mov_b32 v40, v44\n\t"                                                                  \
-    "v_lshlrev_b32 v41, v43, v45\n\t"                                                      \
     "v_mov_b32 v42, v46\n\t"                                                                  \
-    "s_add_u32 s68, s68, 1\n\t"                                                               \
     "v_or_b32_dpp v50, v41, v41 quad_perm:[1,0,3,2] row_mask:0xf bank_mask:0xf\n\t"           \
-    "s_and_b32 s71, s68, 3\n\t"                                                               \
-    "s_nop 0\n\t"                                                                             \
+    "s_add_u32 s68, s68, 0x100\n\t"                                                           \
+    "s_and_b32 s71, s68, 0x300\n\t"                                                           \
     "v_or_b32_dpp v41, v50, v50 quad_perm:[2,3,0,1] row_mask:0xf bank_mask:0xf\n\t"           \
-    "s_cbranch_scc1 .Lsh_adv_read" #L "_%=\n\t"                                               \
-    "s_lshr_b32 s71, s68, 2\n\t"                                                              \
+    "s_cbranch_scc0 .Lsh_adv_piece" #L "_%=\n"                                                \
+    ".Lsh_adv_read" #L "_%=:\n\t"                                                             \
+    "s_and_b32 s71, s68, 0x700\n\t"                                                           \
+    "v_add_u32 v50, s71, v53\n\t"                                                             \
+    "ds_read_b128 v[44:47], v50\n\t"
+#define SH_ADVANCE_PIECE(L)                                                                   \
+    ".Lsh_adv_piece" #L "_%=:\n\t"                                                            \
+    "s_lshr_b32 s71, s68, 10\n\t"                                                             \
     "s_cmp_lt_u32 s71, s82\n\t"                                                               \
     "s_cbranch_scc1 .Lsh_adv_req" #L "_%=\n\t"                                                \
     "s_waitcnt vmcnt(0)\n\t"                                                                  \
     "s_mov_b32 s82, s69\n"                                                                    \
     ".Lsh_adv_req" #L "_%=:\n\t"                                                              \
-    "s_lshl_b32 s71, s68, 8\n\t"                                                              \
-    "s_and_b32 s71, s71, 0x400\n\t"                                                           \
+    "s_and_b32 s71, s68, 0x400\n\t"                                                           \
     "s_xor_b32 s71, s71, 0x400\n\t"                                                           \
     "s_add_u32 m0, s71, %[ring]\n\t"                                                          \
     "s_add_u32 s69, s69, 1\n\t"                                                               \
-    "global_load_lds_dwordx4 v59, s[76:77]\n\t"                                            \
+    "global_load_lds_dwordx4 v59, s[76:77]\n\t"                                               \
     "s_add_u32 s76, s76, 0x400\n\t"                                                           \
-    "s_addc_u32 s77, s77, 0\n"                                                                \
-    ".Lsh_adv_read" #L "_%=:\n\t"                                                             \
-    "s_lshl_b32 s71, s68, 8\n\t"                                                              \
-    "s_and_b32 s71, s71, 0x700\n\t"                                                           \
-    "v_add_u32 v50, s71, v53\n\t"                                                           \
-    "ds_read_b128 v[44:47], v50\n\t"
+    "s_addc_u32 s77, s77, 0\n\t"                                                              \
+    "s_branch .Lsh_adv_read" #L "_%=\n"
 
 // The byte offsets in B of the rows this wave fetches sit in v49 as a ring of 16 per row of 16 lanes (all four rows
 // of lanes hold the same 16): positions 0..5 = the wave's six rows of an even band, 6..11 = of the odd band after it,
@@ -215,10 +216,8 @@ __device__ __forceinline__ float share_acc_get(const ShareAcc& a, int reg)
     "v_lshlrev_b32 v50, 2, v50\n\t"                                   \
     "global_load_dword v52, v50, s[78:79]\n\t"                        \
     "s_add_u32 s80, s80, 1\n\t"
-// The six rows of the band after next (band s64 + 2), to the buffer before this band's.
+// The six rows of the band after next (band s64 + 2), to the buffer at s89.
 #define SH_FILL_BAND(L)                                               \
-    "s_sub_u32 s89, s88, 0xC000\n\t"                                  \
-    "s_cselect_b32 s89, 0x18000, s89\n\t"                             \
     "s_bitcmp1_b32 s64, 0\n\t"                                        \
     "s_cbranch_scc1 .Lsh_fill_odd" #L "_%=\n\t"                       \
     SH_FILL_NEW_PAIR                                                  \
@@ -311,8 +310,9 @@ __global__ __launch_bounds__(64 * kShareW) void spdm_share(ShareArgs a, int64_t 
             "s_mov_b32 s89, 0\n\t"
             SH_FILL_NEW_PAIR
             SH_FILL_SIX(0, 1, 2, 3, 4, 5)
-            "s_mov_b32 s89, 0xC000\n\t"
+            "s_mov_b32 s89, 0x18000\n\t"
             SH_FILL_SIX(6, 7, 8, 9, 10, 11)
+            "s_mov_b32 s89, 0xC000\n\t"
             "s_waitcnt vmcnt(6) lgkmcnt(0)\n\t"
             "s_barrier\n\t"
             SH_ADVANCE(0)
@@ -419,28 +419,23 @@ __global__ __launch_bounds__(64 * kShareW) void spdm_share(ShareArgs a, int64_t 
             SH_ADVANCE(4)
             ".Lsh_nos_%=:\n\t"
             // ---- (quads, singles) of the next band; every 64 bands the pairs of the following 64 take over
-            "s_add_u32 s71, s64, 1\n\t"
-            "s_and_b32 s71, s71, 63\n\t"
-            "s_cbranch_scc1 .Lsh_samehdr_%=\n\t"
-            "v_mov_b32 v54, v56\n\t"
-            "v_mov_b32 v55, v57\n\t"
-            "v_lshrrev_b32 v50, 1, v59\n\t"
-            "global_load_dwordx2 v[56:57], v50, s[74:75]\n\t"
-            "s_add_u32 s74, s74, 0x200\n\t"
-            "s_addc_u32 s75, s75, 0\n"
+            // (out of line, behind the loop).  The buffers turn on meanwhile: band b lives in buffer -b mod 3, so
+            // the rows of band b + 3 go where band b was.
+            "s_add_u32 s64, s64, 1\n\t"
+            "s_and_b32 s71, s64, 63\n\t"
+            "s_cbranch_scc0 .Lsh_newhdr_%=\n"
             ".Lsh_samehdr_%=:\n\t"
-            "v_readlane_b32 s90, v54, s71\n\t"
-            "v_readlane_b32 s91, v55, s71\n\t"
+            "s_mov_b32 s89, s88\n\t"
+            "s_sub_u32 s88, s88, 0xC000\n\t"
+            "s_cselect_b32 s88, 0x18000, s88\n\t"
+            "s_nop 0\n\t"
+            "v_readlane_b32 s66, v54, s71\n\t"
+            "v_readlane_b32 s67, v55, s71\n\t"
             // ---- the rows of band b+1 have landed (those of band b+2, requested in this band, may still be on
             // their way) and so has everything requested before this band began; all waves are done with band b
             SH_WAIT_FILLS
             SH_BAND_BARRIER
             "s_max_u32 s82, s82, s83\n\t"
-            "s_mov_b64 s[66:67], s[90:91]\n\t"
-            "s_add_u32 s88, s88, 0xC000\n\t"
-            "s_cmp_lt_u32 s88, 0x24000\n\t"
-            "s_cselect_b32 s88, s88, 0\n\t"
-            "s_add_u32 s64, s64, 1\n\t"
             "s_cmp_lt_u32 s64, s65\n\t"
             "s_cbranch_scc1 .Lsh_band_%=\n\t"
             "s_branch .Lsh_done_%=\n"
@@ -448,6 +443,15 @@ __global__ __launch_bounds__(64 * kShareW) void spdm_share(ShareArgs a, int64_t 
             ".Lsh_empty_%=:\n\t"
             SH_FILL_BAND(5)
             "s_branch .Lsh_nos_%=\n"
+            ".Lsh_newhdr_%=:\n\t"
+            "v_mov_b32 v54, v56\n\t"
+            "v_mov_b32 v55, v57\n\t"
+            "v_lshrrev_b32 v50, 1, v59\n\t"
+            "global_load_dwordx2 v[56:57], v50, s[74:75]\n\t"
+            "s_add_u32 s74, s74, 0x200\n\t"
+            "s_addc_u32 s75, s75, 0\n\t"
+            "s_branch .Lsh_samehdr_%=\n"
+            SH_ADVANCE_PIECE(0) SH_ADVANCE_PIECE(1) SH_ADVANCE_PIECE(2) SH_ADVANCE_PIECE(3) SH_ADVANCE_PIECE(4)
             // the rows requested for the bands beyond the last one arrive before the wave gives up its LDS
             ".Lsh_done_%=:\n\t"
             "s_waitcnt vmcnt(0)\n\t"
@@ -459,8 +463,7 @@ __global__ __launch_bounds__(64 * kShareW) void spdm_share(ShareArgs a, int64_t 
               "v34", "v35", "v36", "v37", "v38", "v39", "v40", "v41", "v42", "v44", "v45", "v46", "v47", "v48", "v49", "v50",
               "v52", "v54", "v55", "v56", "v57", "v4", "v5", "v6", "v7", "v8", "v9", "v10", "v11", "v12", "v13", "v14", "v15",
               "v16", "v17", "v18", "v19", "s64", "s65", "s66", "s67", "s68", "s69", "s70", "s71", "s73",
-              "s74", "s75", "s76", "s77", "s78", "s79", "s80", "s82", "s83", "s84", "s85", "s86", "s87", "s88", "s89", "s90",
-              "s91");
+              "s74", "s75", "s76", "s77", "s78", "s79", "s80", "s82", "s83", "s84", "s85", "s86", "s87", "s88", "s89");
     }
 
     // The lane's columns once more, from a thread index the compiler cannot connect with the one above: the loop
