@@ -217,14 +217,52 @@ __device__ __forceinline__ float share_acc_get(const ShareAcc& a, int reg)
     "global_load_dword v52, v50, s[78:79]\n\t"                        \
     "s_add_u32 s80, s80, 1\n\t"
 // The six rows of the band after next (band s64 + 2), to the buffer at s89.
+#ifndef SH_SPLIT
+#define SH_SPLIT 2
+#endif
+#if SH_SPLIT == 3
+#define SH_FILL_HEAD(r0, r1, r2, r3, r4, r5)                                                        \
+    "s_add_u32 m0, s89, %[fillw]\n\t"                                                               \
+    SH_FILL_ROW(r0, 0) SH_FILL_ROW(r1, 1024) SH_FILL_ROW(r2, 2048)
+#define SH_FILL_TAIL(r0, r1, r2, r3, r4, r5)                                                        \
+    "s_add_u32 m0, s89, %[fillw]\n\t"                                                               \
+    SH_FILL_ROW(r3, 3072)                                                                           \
+    "s_add_u32 m0, m0, 0x1000\n\t"                                                                  \
+    SH_FILL_ROW(r4, 0) SH_FILL_ROW(r5, 1024)
+#elif SH_SPLIT == 2
+#define SH_FILL_HEAD(r0, r1, r2, r3, r4, r5)                                                        \
+    "s_add_u32 m0, s89, %[fillw]\n\t"                                                               \
+    SH_FILL_ROW(r0, 0) SH_FILL_ROW(r1, 1024)
+#define SH_FILL_TAIL(r0, r1, r2, r3, r4, r5)                                                        \
+    "s_add_u32 m0, s89, %[fillw]\n\t"                                                               \
+    SH_FILL_ROW(r2, 2048) SH_FILL_ROW(r3, 3072)                                                     \
+    "s_add_u32 m0, m0, 0x1000\n\t"                                                                  \
+    SH_FILL_ROW(r4, 0) SH_FILL_ROW(r5, 1024)
+#elif SH_SPLIT == 4
+#define SH_FILL_HEAD(r0, r1, r2, r3, r4, r5)                                                        \
+    "s_add_u32 m0, s89, %[fillw]\n\t"                                                               \
+    SH_FILL_ROW(r0, 0) SH_FILL_ROW(r1, 1024) SH_FILL_ROW(r2, 2048) SH_FILL_ROW(r3, 3072)
+#define SH_FILL_TAIL(r0, r1, r2, r3, r4, r5)                                                        \
+    "s_add_u32 m0, s89, %[fillw]\n\t"                                                               \
+    "s_add_u32 m0, m0, 0x1000\n\t"                                                                  \
+    SH_FILL_ROW(r4, 0) SH_FILL_ROW(r5, 1024)
+#endif
 #define SH_FILL_BAND(L)                                               \
     "s_bitcmp1_b32 s64, 0\n\t"                                        \
     "s_cbranch_scc1 .Lsh_fill_odd" #L "_%=\n\t"                       \
     SH_FILL_NEW_PAIR                                                  \
-    SH_FILL_SIX(0, 1, 2, 3, 4, 5)                                     \
+    SH_FILL_HEAD(0, 1, 2, 3, 4, 5)                                    \
     "s_branch .Lsh_fill_end" #L "_%=\n"                               \
     ".Lsh_fill_odd" #L "_%=:\n\t"                                     \
-    SH_FILL_SIX(6, 7, 8, 9, 10, 11)                                   \
+    SH_FILL_HEAD(6, 7, 8, 9, 10, 11)                                  \
+    ".Lsh_fill_end" #L "_%=:\n\t"
+#define SH_FILL_BAND_REST(L)                                          \
+    "s_bitcmp1_b32 s64, 0\n\t"                                        \
+    "s_cbranch_scc1 .Lsh_fill_odd" #L "_%=\n\t"                       \
+    SH_FILL_TAIL(0, 1, 2, 3, 4, 5)                                    \
+    "s_branch .Lsh_fill_end" #L "_%=\n"                               \
+    ".Lsh_fill_odd" #L "_%=:\n\t"                                     \
+    SH_FILL_TAIL(6, 7, 8, 9, 10, 11)                                  \
     ".Lsh_fill_end" #L "_%=:\n\t"
 
 __global__ __launch_bounds__(64 * kShareW) void spdm_share(ShareArgs a, int64_t total)
@@ -421,6 +459,7 @@ __global__ __launch_bounds__(64 * kShareW) void spdm_share(ShareArgs a, int64_t 
             // ---- (quads, singles) of the next band; every 64 bands the pairs of the following 64 take over
             // (out of line, behind the loop).  The buffers turn on meanwhile: band b lives in buffer -b mod 3, so
             // the rows of band b + 3 go where band b was.
+            SH_FILL_BAND_REST(6)
             "s_add_u32 s64, s64, 1\n\t"
             "s_and_b32 s71, s64, 63\n\t"
             "s_cbranch_scc0 .Lsh_newhdr_%=\n"
