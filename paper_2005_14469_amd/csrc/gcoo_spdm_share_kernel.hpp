@@ -74,14 +74,14 @@ __device__ __forceinline__ float share_acc_get(const ShareAcc& a, int reg)
 //             record's row, the lane's place in the wave's ring, lane*16 (0 for lanes beyond N) and lane*16
 //   v40 v41 v42  values, packed rows (the four rows of a record's group of four, one byte each), offsets of this block
 //   v[44:47]  records of the next block    v48 lane*16 + band buffer
-//   v49  byte offsets of the rows to fetch, two bands     v50 scratch     v52 columns of the two bands after those
+//   v49  byte offsets of the rows to fetch for the band after next     v50 scratch     v52 columns of the band after that
 //   v51  (input) what every offset in v49 carries beside the row's place in B
 //   v[54:55]  (quads, singles) of 64 bands  v[56:57] of the 64 bands after those
 //   s64 band  s65 bands  s66 s67 quads and groups of four singles of this band (of the next one from the band's end on)
 //   s68 blocks read from the ring x 0x100  s69 pieces of the stream requested  s82 of which known to have landed  s83 s69 at the start of the band
-//   s70 s86 packed rows  s71 scratch  s73 loop count
+//   s70 s86 packed rows  s71 scratch  s72 where this wave's rows of the band after next go in LDS  s73 loop count
 //   s[74:75] header pointer (next 64 bands)  s[76:77] stream pointer (next piece)  s[78:79] ucols of the super-group
-//   s80 the pair of bands whose columns are requested next
+//   s80 first place in ucols of the band whose columns are requested next
 //   s88 LDS address of this band's buffer  s89 of the buffer that the next rows go to
 #define SH_DPP(i) " row_newbcast:" #i " row_mask:0xf bank_mask:0xf\n\t"
 #define SH_ADDR(dst, src, i) "v_add_u32_dpp " #dst ", " #src ", v48" SH_DPP(i)
@@ -193,77 +193,36 @@ __device__ __forceinline__ float share_acc_get(const ShareAcc& a, int reg)
     "s_addc_u32 s77, s77, 0\n\t"                                                              \
     "s_branch .Lsh_adv_read" #L "_%=\n"
 
-// The byte offsets in B of the rows this wave fetches sit in v49 as a ring of 16 per row of 16 lanes (all four rows
-// of lanes hold the same 16): positions 0..5 = the wave's six rows of an even band, 6..11 = of the odd band after it,
-// so that a DPP row broadcast puts a row's offset in front of every lane's column offset in one instruction.
-// Every offset carries +3072 - 1024 * (t & 3), t = the row's place among the six, and the base pointer -3072: the
-// loads of rows 0..3 and 4..5 then differ only in their immediate offsets, which also move the LDS address, and
-// M0 is written twice per band instead of once per row.
+// The byte offsets in B of the six rows this wave fetches for a band sit in v49 at places 0..5 of every row of 16
+// lanes (the other places repeat the sixth), so that a DPP row broadcast puts a row's offset in front of every
+// lane's column offset in one instruction.  Every offset carries +3072 - 1024 * (t & 3), t = the row's place among
+// the six, and the base pointer -3072: the loads of rows 0..3 and 4..5 then differ only in their immediate offsets,
+// which also move the LDS address, and M0 is written once per part instead of once per row.
+// The six rows of the band after next (band s64 + 2) go to the buffer at s89 in three parts, spread over the band
+// (all eight waves asking for all their rows at once right behind the barrier holds every one of them up at the
+// compute unit's one address path): HEAD at the band's start, which also makes the offsets from the columns in v52
+// and requests the columns of the band after (s80 = its first place in ucols; places past the last column of the
+// super-group repeat it), MID behind the first entries, TAIL at the band's end.
 #define SH_FILL_ROW(r, off) "v_add_u32_dpp v50, v49, v58 row_newbcast:" #r " row_mask:0xf bank_mask:0xf\n\t" SH_FILL_LOAD(off)
-#define SH_FILL_SIX(r0, r1, r2, r3, r4, r5)                                                         \
-    "s_add_u32 m0, s89, %[fillw]\n\t"                                                               \
-    SH_FILL_ROW(r0, 0) SH_FILL_ROW(r1, 1024) SH_FILL_ROW(r2, 2048) SH_FILL_ROW(r3, 3072)            \
-    "s_add_u32 m0, m0, 0x1000\n\t"                                                                  \
-    SH_FILL_ROW(r4, 0) SH_FILL_ROW(r5, 1024)
-// A new pair of bands: their offsets from the columns in v52, and the columns of the pair after them (pair s80)
-// requested; lanes past the last column of the super-group repeat it.
-#define SH_FILL_NEW_PAIR                                              \
-    "v_mul_lo_u32 v49, v52, %[ldb4]\n\t"                              \
-    "s_mul_i32 s71, s80, 96\n\t"                                      \
-    "v_add_u32 v49, v49, v51\n\t"                                     \
-    "v_add_u32 v50, s71, v3\n\t"                                      \
+#define SH_FILL_OFFSETS(cols)                                         \
+    "v_mul_lo_u32 v49, " #cols ", %[ldb4]\n\t"                        \
+    "s_add_u32 s72, s89, %[fillw]\n\t"                                \
+    "v_add_u32 v49, v49, v51\n\t"
+#define SH_FILL_HEAD                                                  \
+    SH_FILL_OFFSETS(v52)                                              \
+    "v_add_u32 v50, s80, v3\n\t"                                      \
     "v_min_u32 v50, v50, %[last]\n\t"                                 \
     "v_lshlrev_b32 v50, 2, v50\n\t"                                   \
     "global_load_dword v52, v50, s[78:79]\n\t"                        \
-    "s_add_u32 s80, s80, 1\n\t"
-// The six rows of the band after next (band s64 + 2), to the buffer at s89.
-#ifndef SH_SPLIT
-#define SH_SPLIT 2
-#endif
-#if SH_SPLIT == 3
-#define SH_FILL_HEAD(r0, r1, r2, r3, r4, r5)                                                        \
-    "s_add_u32 m0, s89, %[fillw]\n\t"                                                               \
-    SH_FILL_ROW(r0, 0) SH_FILL_ROW(r1, 1024) SH_FILL_ROW(r2, 2048)
-#define SH_FILL_TAIL(r0, r1, r2, r3, r4, r5)                                                        \
-    "s_add_u32 m0, s89, %[fillw]\n\t"                                                               \
-    SH_FILL_ROW(r3, 3072)                                                                           \
-    "s_add_u32 m0, m0, 0x1000\n\t"                                                                  \
-    SH_FILL_ROW(r4, 0) SH_FILL_ROW(r5, 1024)
-#elif SH_SPLIT == 2
-#define SH_FILL_HEAD(r0, r1, r2, r3, r4, r5)                                                        \
-    "s_add_u32 m0, s89, %[fillw]\n\t"                                                               \
-    SH_FILL_ROW(r0, 0) SH_FILL_ROW(r1, 1024)
-#define SH_FILL_TAIL(r0, r1, r2, r3, r4, r5)                                                        \
-    "s_add_u32 m0, s89, %[fillw]\n\t"                                                               \
-    SH_FILL_ROW(r2, 2048) SH_FILL_ROW(r3, 3072)                                                     \
-    "s_add_u32 m0, m0, 0x1000\n\t"                                                                  \
-    SH_FILL_ROW(r4, 0) SH_FILL_ROW(r5, 1024)
-#elif SH_SPLIT == 4
-#define SH_FILL_HEAD(r0, r1, r2, r3, r4, r5)                                                        \
-    "s_add_u32 m0, s89, %[fillw]\n\t"                                                               \
-    SH_FILL_ROW(r0, 0) SH_FILL_ROW(r1, 1024) SH_FILL_ROW(r2, 2048) SH_FILL_ROW(r3, 3072)
-#define SH_FILL_TAIL(r0, r1, r2, r3, r4, r5)                                                        \
-    "s_add_u32 m0, s89, %[fillw]\n\t"                                                               \
-    "s_add_u32 m0, m0, 0x1000\n\t"                                                                  \
-    SH_FILL_ROW(r4, 0) SH_FILL_ROW(r5, 1024)
-#endif
-#define SH_FILL_BAND(L)                                               \
-    "s_bitcmp1_b32 s64, 0\n\t"                                        \
-    "s_cbranch_scc1 .Lsh_fill_odd" #L "_%=\n\t"                       \
-    SH_FILL_NEW_PAIR                                                  \
-    SH_FILL_HEAD(0, 1, 2, 3, 4, 5)                                    \
-    "s_branch .Lsh_fill_end" #L "_%=\n"                               \
-    ".Lsh_fill_odd" #L "_%=:\n\t"                                     \
-    SH_FILL_HEAD(6, 7, 8, 9, 10, 11)                                  \
-    ".Lsh_fill_end" #L "_%=:\n\t"
-#define SH_FILL_BAND_REST(L)                                          \
-    "s_bitcmp1_b32 s64, 0\n\t"                                        \
-    "s_cbranch_scc1 .Lsh_fill_odd" #L "_%=\n\t"                       \
-    SH_FILL_TAIL(0, 1, 2, 3, 4, 5)                                    \
-    "s_branch .Lsh_fill_end" #L "_%=\n"                               \
-    ".Lsh_fill_odd" #L "_%=:\n\t"                                     \
-    SH_FILL_TAIL(6, 7, 8, 9, 10, 11)                                  \
-    ".Lsh_fill_end" #L "_%=:\n\t"
+    "s_add_u32 s80, s80, 48\n\t"                                      \
+    "s_mov_b32 m0, s72\n\t"                                           \
+    SH_FILL_ROW(0, 0) SH_FILL_ROW(1, 1024)
+#define SH_FILL_MID                                                   \
+    "s_mov_b32 m0, s72\n\t"                                           \
+    SH_FILL_ROW(2, 2048) SH_FILL_ROW(3, 3072)
+#define SH_FILL_TAIL                                                  \
+    "s_add_u32 m0, s72, 0x1000\n\t"                                   \
+    SH_FILL_ROW(4, 0) SH_FILL_ROW(5, 1024)
 
 __global__ __launch_bounds__(64 * kShareW) void spdm_share(ShareArgs a, int64_t total)
 {
@@ -300,11 +259,10 @@ __global__ __launch_bounds__(64 * kShareW) void spdm_share(ShareArgs a, int64_t 
         const uint32_t l16 = (uint32_t)lane * 16u;
         const uint32_t l16g = in ? l16 : 0u;                       // lanes beyond N fetch the first columns of the tile
         const uint32_t sh8 = (uint32_t)(lane & 3) * 8u;
-        // place 6i + t of the ring of 16 (lane & 15; the last four places repeat the twelfth): row t of the wave's
-        // six in band i of a pair of bands
-        const int li = (lane & 15) < 12 ? (lane & 15) : 11;
-        const uint32_t cidx = (uint32_t)((li / 6) * kShareBandRows + wv * 6 + li % 6);
-        const uint32_t fbias = 3072u - (uint32_t)((li % 6) & 3) * 1024u;
+        // place t of every row of 16 lanes (the places from the sixth on repeat it): row t of the wave's six in a band
+        const int li = (lane & 15) < 6 ? (lane & 15) : 5;
+        const uint32_t cidx = (uint32_t)(wv * 6 + li);
+        const uint32_t fbias = 3072u - (uint32_t)(li & 3) * 1024u;
         const uint32_t ring = (uint32_t)(3 * kShareBandBytes + wv * kShareRingBytes);
         const uint32_t rl = ring + (uint32_t)(lane & 15) * 16u;
         const uint32_t fillw = (uint32_t)wv * 6144u;               // the wave's six rows inside a band buffer
@@ -320,7 +278,7 @@ __global__ __launch_bounds__(64 * kShareW) void spdm_share(ShareArgs a, int64_t 
             "s_mov_b32 s69, 2\n\t"
             "s_mov_b32 s82, 2\n\t"
             "s_mov_b32 s88, 0\n\t"
-            "s_mov_b32 s80, 1\n\t"
+            "s_mov_b32 s80, 3 * 48\n\t"
             "s_mov_b32 m0, %[ring]\n\t"
             "s_nop 0\n\t"
             "global_load_lds_dwordx4 v59, s[76:77]\n\t"
@@ -336,7 +294,16 @@ __global__ __launch_bounds__(64 * kShareW) void spdm_share(ShareArgs a, int64_t 
             "global_load_dwordx2 v[56:57], v50, s[74:75] offset:512\n\t"
             "s_add_u32 s74, s74, 0x400\n\t"
             "s_addc_u32 s75, s75, 0\n\t"
+            // the columns of bands 0, 1 and 2
             "v_min_u32 v50, v3, %[last]\n\t"
+            "v_lshlrev_b32 v50, 2, v50\n\t"
+            "global_load_dword v40, v50, s[78:79]\n\t"
+            "v_add_u32 v50, 48, v3\n\t"
+            "v_min_u32 v50, v50, %[last]\n\t"
+            "v_lshlrev_b32 v50, 2, v50\n\t"
+            "global_load_dword v42, v50, s[78:79]\n\t"
+            "v_add_u32 v50, 96, v3\n\t"
+            "v_min_u32 v50, v50, %[last]\n\t"
             "v_lshlrev_b32 v50, 2, v50\n\t"
             "global_load_dword v52, v50, s[78:79]\n\t"
             "s_waitcnt vmcnt(0)\n\t"
@@ -346,10 +313,15 @@ __global__ __launch_bounds__(64 * kShareW) void spdm_share(ShareArgs a, int64_t 
             // (bands beyond the last one are requested like any other: their columns are clamped to the last
             // column of the super-group, their rows go to a buffer that nobody reads)
             "s_mov_b32 s89, 0\n\t"
-            SH_FILL_NEW_PAIR
-            SH_FILL_SIX(0, 1, 2, 3, 4, 5)
+            SH_FILL_OFFSETS(v40)
+            "s_mov_b32 m0, s72\n\t"
+            SH_FILL_ROW(0, 0) SH_FILL_ROW(1, 1024) SH_FILL_ROW(2, 2048) SH_FILL_ROW(3, 3072)
+            SH_FILL_TAIL
             "s_mov_b32 s89, 0x18000\n\t"
-            SH_FILL_SIX(6, 7, 8, 9, 10, 11)
+            SH_FILL_OFFSETS(v42)
+            "s_mov_b32 m0, s72\n\t"
+            SH_FILL_ROW(0, 0) SH_FILL_ROW(1, 1024) SH_FILL_ROW(2, 2048) SH_FILL_ROW(3, 3072)
+            SH_FILL_TAIL
             "s_mov_b32 s89, 0xC000\n\t"
             "s_waitcnt vmcnt(6) lgkmcnt(0)\n\t"
             "s_barrier\n\t"
@@ -364,7 +336,7 @@ __global__ __launch_bounds__(64 * kShareW) void spdm_share(ShareArgs a, int64_t 
             "s_cbranch_scc1 .Lsh_noq_%=\n\t"
             SH_ADDR(v36, v42, 0) SH_ADDR(v37, v42, 4) SH_ADDR(v38, v42, 8) SH_ADDR(v39, v42, 12)
             SH_READ_SET0 SH_READ_SET1 SH_READ_SET2 SH_READ_SET3
-            SH_FILL_BAND(2)
+            SH_FILL_HEAD
             // ---- quads
             "s_mov_b32 s73, s66\n"
             ".Lsh_qblk_%=:\n\t"
@@ -412,6 +384,7 @@ __global__ __launch_bounds__(64 * kShareW) void spdm_share(ShareArgs a, int64_t 
             // (reads issued for a block that is not of this part stay in flight: LDS answers in order, their
             // values are never used)
             ".Lsh_qend_%=:\n\t"
+            SH_FILL_MID
             SH_ADVANCE(2)
             "s_mov_b32 s73, s67\n\t"
             "s_cmp_eq_u32 s67, 0\n\t"
@@ -424,11 +397,7 @@ __global__ __launch_bounds__(64 * kShareW) void spdm_share(ShareArgs a, int64_t 
             "s_cbranch_scc1 .Lsh_empty_%=\n\t"
             SH_ADDR(v36, v42, 0) SH_ADDR(v37, v42, 1) SH_ADDR(v38, v42, 2) SH_ADDR(v39, v42, 3)
             SH_READ_SET0 SH_READ_SET1 SH_READ_SET2 SH_READ_SET3
-            SH_FILL_BAND(3)
-            // ---- singles, four at a time
-            "s_mov_b32 s73, s67\n"
-            ".Lsh_sblk_%=:\n\t"
-            SH_ROWS(s70, 0)
+            SH_FILL_HEAD
 // a group of four singles: its B values were requested a whole group ahead into one bank of four sets (sets 0..3 or
 // 4..7: the groups of a band alternate), so that one wait covers them: first the addresses of the four records
 // after them (records n0..n3 of `src`) and their reads into the other bank (R0..R3), where there is one the rows of
@@ -441,14 +410,28 @@ __global__ __launch_bounds__(64 * kShareW) void spdm_share(ShareArgs a, int64_t 
             "s_waitcnt lgkmcnt(4)\n\t"                                                \
             F0 F1 F2 F3                                                               \
             SH_OFF
-            SH_GROUP(v42, 4, 5, 6, 7, SH_READ_SET4, SH_READ_SET5, SH_READ_SET6, SH_READ_SET7, SH_ROWS(s86, 4),
+#define SH_GROUP_0 SH_ROWS(s70, 0)                                                                                      \
+            SH_GROUP(v42, 4, 5, 6, 7, SH_READ_SET4, SH_READ_SET5, SH_READ_SET6, SH_READ_SET7, SH_ROWS(s86, 4),         \
                      SH_FMAC_SET0(0, s70), SH_FMAC_SET1(1, s70), SH_FMAC_SET2(2, s70), SH_FMACL_SET3(3, s70))
-            SH_GROUP(v42, 8, 9, 10, 11, SH_READ_SET0, SH_READ_SET1, SH_READ_SET2, SH_READ_SET3, SH_ROWS(s70, 8),
+#define SH_GROUP_1                                                                                                      \
+            SH_GROUP(v42, 8, 9, 10, 11, SH_READ_SET0, SH_READ_SET1, SH_READ_SET2, SH_READ_SET3, SH_ROWS(s70, 8),       \
                      SH_FMAC_SET4(4, s86), SH_FMAC_SET5(5, s86), SH_FMAC_SET6(6, s86), SH_FMACL_SET7(7, s86))
-            SH_GROUP(v42, 12, 13, 14, 15, SH_READ_SET4, SH_READ_SET5, SH_READ_SET6, SH_READ_SET7, SH_ROWS(s86, 12),
+#define SH_GROUP_2                                                                                                      \
+            SH_GROUP(v42, 12, 13, 14, 15, SH_READ_SET4, SH_READ_SET5, SH_READ_SET6, SH_READ_SET7, SH_ROWS(s86, 12),    \
                      SH_FMAC_SET0(8, s70), SH_FMAC_SET1(9, s70), SH_FMAC_SET2(10, s70), SH_FMACL_SET3(11, s70))
-            SH_GROUP(v46, 0, 1, 2, 3, SH_READ_SET0, SH_READ_SET1, SH_READ_SET2, SH_READ_SET3, "",
+#define SH_GROUP_3                                                                                                      \
+            SH_GROUP(v46, 0, 1, 2, 3, SH_READ_SET0, SH_READ_SET1, SH_READ_SET2, SH_READ_SET3, "",                      \
                      SH_FMAC_SET4(12, s86), SH_FMAC_SET5(13, s86), SH_FMAC_SET6(14, s86), SH_FMACL_SET7(15, s86))
+            // ---- singles, four at a time; in a band without quads the second part of the rows is requested behind
+            // the first group
+            "s_mov_b32 s73, s67\n\t"
+            SH_GROUP_0
+            SH_FILL_MID
+            "s_branch .Lsh_sgroup1_%=\n"
+            ".Lsh_sblk_%=:\n\t"
+            SH_GROUP_0
+            ".Lsh_sgroup1_%=:\n\t"
+            SH_GROUP_1 SH_GROUP_2 SH_GROUP_3
             "s_cmp_eq_u32 s73, 0\n\t"
             "s_cbranch_scc1 .Lsh_send_%=\n\t"
             SH_ADVANCE(3)
@@ -459,7 +442,7 @@ __global__ __launch_bounds__(64 * kShareW) void spdm_share(ShareArgs a, int64_t 
             // ---- (quads, singles) of the next band; every 64 bands the pairs of the following 64 take over
             // (out of line, behind the loop).  The buffers turn on meanwhile: band b lives in buffer -b mod 3, so
             // the rows of band b + 3 go where band b was.
-            SH_FILL_BAND_REST(6)
+            SH_FILL_TAIL
             "s_add_u32 s64, s64, 1\n\t"
             "s_and_b32 s71, s64, 63\n\t"
             "s_cbranch_scc0 .Lsh_newhdr_%=\n"
@@ -480,7 +463,8 @@ __global__ __launch_bounds__(64 * kShareW) void spdm_share(ShareArgs a, int64_t 
             "s_branch .Lsh_done_%=\n"
             // a band in which this wave has no entry
             ".Lsh_empty_%=:\n\t"
-            SH_FILL_BAND(5)
+            SH_FILL_HEAD
+            SH_FILL_MID
             "s_branch .Lsh_nos_%=\n"
             ".Lsh_newhdr_%=:\n\t"
             "v_mov_b32 v54, v56\n\t"
