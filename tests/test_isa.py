@@ -116,8 +116,8 @@ def test_lds_load_checker_sees_planted_mistakes(share_asm):
     i = share_asm.index(SHARE)
     head, body = share_asm[:i], share_asm[i:]
     # an M0 write taken away: the load behind it would use what the one before left (or the index mode's row)
-    # (one that opens a block: the walk back from its loads then ends at the label)
-    m = re.search(r"(Lsh_fill_odd\w+:\n\s*)(s_add_u32 m0, s89, s\d+)", body)
+    # (one right behind the index mode: the walk back from its loads then ends there)
+    m = re.search(r"(s_set_gpr_idx_off\n\s*)(s_mov_b32 m0, s72)", body)
     _, problems = isa_check.check_lds_loads(head + body.replace(m.group(0), m.group(1) + "s_nop 0", 1), SHARE, in_flight=6)
     assert problems and "M0" in problems[0]
     # an index-mode instruction between the M0 write and the load
