@@ -155,7 +155,13 @@ bool share_shape_preferred(int64_t m, int64_t k, int64_t nnz)
     if (m <= 0 || k <= 0 || nnz <= 0 || k > gcoo::kShareMaxK) return false;
     const double density = (double)nnz / ((double)m * (double)k);
     if (density > 0.06) return false;
-    return (k >= 9000 && density >= 0.004) || (k >= 3500 && density >= 0.008);
+    // Whole steps (conversion + product) measured on uniform random square matrices, n = 2000 .. 14000: the wider A, the
+    // less of a column tile of B stays in an XCD's L2 between the groups that read it, and the sooner fetching each
+    // row once per 8 groups pays for the second schedule that the conversion then builds.
+    if (k >= 9000) return density >= 0.0004;
+    if (k >= 7000) return density >= 0.003;
+    if (k >= 5500) return density >= 0.008;
+    return k >= 3500 && density >= 0.015;
 }
 
 bool share_kernel_preferred(int64_t m, int64_t k, int64_t nnz, int32_t p)

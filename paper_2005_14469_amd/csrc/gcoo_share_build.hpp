@@ -235,14 +235,10 @@ __global__ __launch_bounds__(kShareBuildThreads) void share_fill(const int32_t* 
         for (int32_t cur = s; cur < e; cur += 64) {
             int32_t x, len;
             share_place_wave(col_at, s, e, cur, lane, &x, &len);
-            if (cur + lane < e) {
-                if (x < (len & ~3)) ++members; else ++singles;
-            }
-        }
-#pragma unroll
-        for (int d = 32; d >= 1; d >>= 1) {
-            members += __shfl_xor(members, d, 64);
-            singles += __shfl_xor(singles, d, 64);
+            const bool live = cur + lane < e;
+            const bool member = live && x < (len & ~3);
+            members += __popcll(__ballot(member));
+            singles += __popcll(__ballot(live && !member));
         }
         const int32_t nq = members / 4, ns4 = (singles + 3) / 4;
         if (lane == 0) {
@@ -264,6 +260,24 @@ __global__ __launch_bounds__(kShareBuildThreads) void share_fill(const int32_t* 
         if (threadIdx.x == 0) carry_s += total_s;
         __syncthreads();
     }
+    // What pass 2 reads from global memory for a band (the band's columns, one per lane, ascending, lanes past the
+    // end holding a column no entry has; value and row of the first 64 entries) is requested a band ahead: a wave
+    // walks its bands one after another, and a memory latency per band would be most of its time.
+    struct Ahead { int32_t band_col; float value; int32_t row; };
+    auto fetch = [&](int32_t b) -> Ahead {
+        Ahead a = {INT32_MAX, 0.0f, 0};
+        if (b < NB) {
+            const int32_t nc = (nU - b * kShareBandRows < kShareBandRows) ? nU - b * kShareBandRows : kShareBandRows;
+            if (lane < nc) a.band_col = uc[b * kShareBandRows + lane];
+            const int32_t i = bstart[b] + lane;
+            if (i < bstart[b + 1]) {
+                a.value = values[i];
+                a.row = rows[i];
+            }
+        }
+        return a;
+    };
+    Ahead ahead = fetch(wv);
     if (threadIdx.x == 0) {
         const int32_t base = (int32_t)atomicAdd(alloc, (uint32_t)carry_s);
         base_s = base;
@@ -275,12 +289,12 @@ __global__ __launch_bounds__(kShareBuildThreads) void share_fill(const int32_t* 
 
     // pass 2
     for (int32_t b = wv; b < NB; b += kShareBuildWaves) {
+        const Ahead now = ahead;
+        ahead = fetch(b + kShareBuildWaves);
         const int32_t s = bstart[b], e = bstart[b + 1];
         if (s >= e) continue;
-        const int32_t nc = (nU - b * kShareBandRows < kShareBandRows) ? nU - b * kShareBandRows : kShareBandRows;
-        // the band's columns, one per lane (ascending; lanes past the end hold a column no entry has): an
-        // entry's slot is then a lower bound over the lanes, six exchanges
-        const int32_t band_col_of_lane = lane < nc ? uc[b * kShareBandRows + lane] : INT32_MAX;
+        // an entry's slot is a lower bound over the lanes' columns, six exchanges
+        const int32_t band_col_of_lane = now.band_col;
         share_u32x4* qblk = out + (int64_t)boff[b] * 16;
         int32_t members_before = 0, singles_before = 0;         // in the tiles before this one
         int32_t nq_blocks = 0;                                    // known after the walk: S blocks sit behind the Q blocks
@@ -294,6 +308,12 @@ __global__ __launch_bounds__(kShareBuildThreads) void share_fill(const int32_t* 
             int32_t x = 0, len = 0, col = 0;
             share_place_wave(col_at, s, e, cur, lane, &x, &len);
             if (live) col = col_at(i);
+            float value = now.value;
+            int32_t row = now.row;
+            if (cur != s && live) {
+                value = values[i];
+                row = rows[i];
+            }
             const bool member = live && x < (len & ~3);
             const bool single = live && !member;
             const uint64_t mm = __ballot(member), sm = __ballot(single);
@@ -305,7 +325,7 @@ __global__ __launch_bounds__(kShareBuildThreads) void share_fill(const int32_t* 
                 if (probe < col) slot += step;
             }
             if (live) {
-                const share_u32x4 rec = {__float_as_uint(values[i]), (uint32_t)(rows[i] - row0), (uint32_t)slot * 1024u, 0u};
+                const share_u32x4 rec = {__float_as_uint(value), (uint32_t)(row - row0), (uint32_t)slot * 1024u, 0u};
                 if (member) {
                     const int32_t u = x & 3;
                     const int32_t rank = (members_before + __popcll(mm & below) - u) / 4;
