@@ -158,8 +158,10 @@ bool share_shape_preferred(int64_t m, int64_t k, int64_t nnz)
     // Whole steps (conversion + product) measured on uniform random square matrices, n = 2000 .. 14000: the wider A, the
     // less of a column tile of B stays in an XCD's L2 between the groups that read it, and the sooner fetching each
     // row once per 8 groups pays for the second schedule that the conversion then builds.
-    if (k >= 9000) return density >= 0.0004;
-    if (k >= 7000) return density >= 0.003;
+    // (From 9000 columns on it is ahead down to 0.05 % - 8 to 16 % of the step at n = 10000 .. 14000 - but a conversion
+    // sees neither the width of B nor how even the rows are, and a second schedule built for nothing costs a matrix
+    // with few long rows a third of its step: the limit stays where the gain is large.)
+    if (k >= 7000) return density >= 0.0035;
     if (k >= 5500) return density >= 0.008;
     return k >= 3500 && density >= 0.015;
 }

@@ -150,11 +150,11 @@ def test_default_p_rule(L):
         return L.gcoo_default_p(m, n, int(m * n * (1 - s)), n if N is None else N)
     assert dp(8000, 0.995) == 42            # the headline workload: 8000 columns at 0.5 %
     assert dp(8000, 0.98) == 42 and dp(8000, 0.99) == 42 and dp(8000, 0.95) == 42      # 24 super-groups x 32 tiles = 3 rounds of 256
-    assert dp(8000, 0.997) == 42 and dp(8000, 0.998) == 32          # from 7000 columns on: 0.3 % and more
+    assert dp(8000, 0.996) == 42 and dp(8000, 0.997) == 32          # from 7000 columns on: 0.35 % and more
     assert dp(6000, 0.99) == _share_height(6000, 6000) and dp(6000, 0.995) == 32    # from 5500 on: 0.8 % and more
     assert dp(5000, 0.98) == _share_height(5000, 5000) and dp(5000, 0.99) == 32     # from 3500 on: 1.5 % and more
-    assert dp(14000, 0.9995) == _share_height(14000, 14000) and dp(14000, 0.9997) == 32     # from 9000 on: 0.04 % and more
-    assert dp(14000, 0.995) == 48 and dp(12000, 0.997) == _share_height(12000, 12000) and dp(10000, 0.995) != 32
+    assert dp(14000, 0.995) == 48 and dp(12000, 0.997) == 32 and dp(10000, 0.995) != 32
+    assert dp(16384, 1 - 868447 / 16384 ** 2, N=512) == 32 and dp(16384, 1 - 868447 / 16384 ** 2) == 32   # the skewed workload's shape
     assert dp(14000, 0.98) == 48 and dp(4000, 0.98) == 32
     for n in (4000, 5000, 7000, 8000, 10000, 14000):
         assert dp(n, 0.98) == _share_height(n, n), n
