@@ -67,7 +67,8 @@ typedef struct gcoo_matrix gcoo_matrix;
  * per lane); on MI355X it was the fastest of {4, 8, 16, 32, 64} for that kernel for uniform random
  * matrices of density 0.001 .. 0.5, for a power-law row-length matrix and for a diagonal one.
  * Where gcoo_spdm() will run the workgroup-shared kernel (GCOO_VARIANT_SHARE: N a multiple of 4,
- * density at most 6 %, and at least 1.5 % from 3500 columns on, 0.8 % from 5500, 0.35 % from 7000), a height between
+ * density at most 6 %, and at least 1.5 % from 3500 columns on, 0.8 % from 5500, 0.35 % from 7000; never while
+ * the policy is GCOO_SHARE_NEVER), a height between
  * 24 and 48 is returned that makes the workgroups of that kernel (one per 8p rows x 256 columns of C)
  * fill whole rounds over the 256 compute units: the p that minimises
  * ceil(workgroups / 256) x (p + 24).

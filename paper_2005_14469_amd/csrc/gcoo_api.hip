@@ -423,7 +423,7 @@ int gcoo_set_share_policy(int policy)
 int32_t gcoo_default_p(int64_t m, int64_t k, int64_t nnz, int64_t N)
 {
     if (m < 0 || k < 0 || nnz < 0 || N < 0) return 0;
-    if (N > 0 && N % 4 == 0 && share_shape_preferred(m, k, nnz)) {
+    if (N > 0 && N % 4 == 0 && share_policy_now() != GCOO_SHARE_NEVER && share_shape_preferred(m, k, nnz)) {
         const int32_t p = share_best_p(m, N);
         const int64_t items = share_items(m, p, N);
         if (items >= 192 && (k >= 9000 || fill_of_rounds(items) >= 0.8)) return p;

@@ -167,5 +167,11 @@ def test_default_p_rule(L):
     assert dp(12000, 0.98, N=12002) == 32   # rows of B not 16-byte aligned
     for m, k, nnz, n in [(0, 0, 0, 0), (1, 1, 1, 1), (256, 256, 6000, 256)]:
         assert L.gcoo_default_p(m, k, nnz, n) == 32
+    # no height for a kernel that the policy rules out
+    assert L.gcoo_set_share_policy(binding.SHARE_NEVER) == 0
+    try:
+        assert dp(8000, 0.995) == 32 and dp(14000, 0.98) == 32 and dp(8000, 0.9) == 38
+    finally:
+        assert L.gcoo_set_share_policy(binding.SHARE_AUTO) == 0
     assert L.gcoo_default_p(-1, 1, 1, 1) == 0
     assert L.gcoo_default_p(1, 1, -1, 1) == 0
