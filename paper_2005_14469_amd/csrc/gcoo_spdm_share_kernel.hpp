@@ -6,12 +6,13 @@
 // plus the sink row of the padding records).  The workgroup walks the bands of Q.  LDS holds three
 // band buffers of 48 KB (48 rows of B x 256 columns): while band b is multiplied, band b+1 has
 // landed or is landing and the rows of band b+2 are requested, by global->LDS loads (no registers
-// in between), six rows per wave.  One barrier per band; the wait in front of it lets the loads
-// of band b+2 stay in flight, so the path from L2 to LDS never drains.
+// in between), six rows per wave in three parts spread over the band.  One barrier per band; the
+// wait in front of it lets the loads of band b+2 stay in flight, so the path from L2 to LDS never
+// drains.
 //
 // Per entry the wave issues
 //     v_add_u32_dpp   address = record.offset (broadcast inside each row of 16 lanes) + lane * 16
-//     ds_read_b128    the lane's four columns of the B row, four entries ahead of their use
+//     ds_read_b128    the lane's four columns of the B row, a group of four entries ahead of their use
 //     s_set_gpr_idx_on + s_lshr_b32   the entry's row selects the partial sums (index mode); the rows
 //                     of four entries travel in one scalar register
 //     4 x v_fmac_f32_dpp   sum[row][c] += record.value (broadcast the same way) * b[c]
@@ -22,9 +23,10 @@
 // entries in shared memory and their broadcast to all threads of Algorithm 2, and the reuse of
 // the fetched B value along a run of equal columns (Section 3.3).
 //
-// What a wave needs of the schedule beside the records comes in vectors, far ahead of its use:
-// the columns of the rows it fetches, ten bands per load (lane 6i + t = row t of band 10j + i); the
-// (quads, singles) pairs of its bands, 64 bands per load.  v_readlane picks the lane.
+// What a wave needs of the schedule beside the records comes in vectors, ahead of its use: the
+// columns of the six rows it fetches for a band, one load per band, two bands before the rows are
+// requested (a DPP row broadcast picks the row); the (quads, singles) pairs of its bands, 64 bands
+// per load (v_readlane picks the lane).
 // The stream of blocks reaches LDS through a ring of eight blocks per wave, filled 1 KB at a time
 // by global->LDS loads one piece ahead.
 //
