@@ -423,6 +423,9 @@ def _check_share_schedule(A, m, k, p, G):
     (100, 300, 8, 32, 0.9), (257, 1000, 260, 42, 0.99), (70, 200, 4, 16, 0.3), (64, 64, 64, 48, 0.0), (33, 50, 4, 8, 0.95),
     (300, 70, 12, 32, 0.6), (1, 1, 4, 1, 0.0), (20, 130, 4, 32, 1.0), (700, 500, 516, 48, 0.5), (530, 2000, 300, 12, 0.98),
     (1000, 3000, 1024, 42, 0.995), (3000, 900, 64, 16, 0.95), (64, 4000, 256, 32, 0.999), (100, 300, 8, 2, 0.95),
+    # one, two and three bands, full and with one column over (the kernel asks for the rows of two bands beyond the last
+    # one as for any other: their columns repeat the last one)
+    (336, 48, 256, 42, 0.5), (336, 49, 256, 42, 0.5), (400, 96, 260, 42, 0.7), (400, 97, 512, 48, 0.7), (336, 145, 256, 42, 0.9),
 ])
 def test_share_schedule_and_variant(share_always, m, k, N, p, s):
     """The kernel whose eight waves share the rows of B through LDS: its schedule against the model, its product
