@@ -69,15 +69,15 @@ __device__ __forceinline__ float share_acc_get(const ShareAcc& a, int reg)
 }
 
 // ---- asm text -----------------------------------------------------------------------------------
-// Fixed registers of the main loop (all named in the clobber list):
+// Fixed registers of the main loop (named in the clobber list, but for the inputs, which are pinned to theirs):
 //   v[20:35]  four sets of B values (sets 0..3)   v[4:19]  four more (sets 4..7: the singles of a band alternate between the two)
 //   v[36:39]  four LDS addresses
-//   v3 v43 v51 v53 v58 v59  inputs that stay as they are: the lane's place in a vector of columns, the shift that packs a
-//             record's row, the lane's place in the wave's ring, lane*16 (0 for lanes beyond N) and lane*16
+//   inputs that stay as they are: v3 the place in ucols, inside a band, of the row whose offset the lane holds in v49;
+//             v43 the shift that packs a record's row; v51 what that offset carries beside the row's place in B;
+//             v53 the lane's place in the wave's ring; v58 lane*16 (0 for lanes beyond N); v59 lane*16
 //   v40 v41 v42  values, packed rows (the four rows of a record's group of four, one byte each), offsets of this block
 //   v[44:47]  records of the next block    v48 lane*16 + band buffer
 //   v49  byte offsets of the rows to fetch for the band after next     v50 scratch     v52 columns of the band after that
-//   v51  (input) what every offset in v49 carries beside the row's place in B
 //   v[54:55]  (quads, singles) of 64 bands  v[56:57] of the 64 bands after those
 //   s64 band  s65 bands  s66 s67 quads and groups of four singles of this band (of the next one from the band's end on)
 //   s68 blocks read from the ring x 0x100  s69 pieces of the stream requested  s82 of which known to have landed  s83 s69 at the start of the band
